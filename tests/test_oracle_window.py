@@ -1,0 +1,112 @@
+"""Pins for the oracle's window partition and window attention (Sec. 3.2.2)."""
+import itertools
+
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2605_26636_amd import synth
+
+
+def test_hand_map(golden):
+    g = golden("window_map_3x3_win2x2.txt")
+    assert oracle.window_geometry(3, 3, 2, 2) == tuple(int(x) for x in g["padded"])
+    ti, pm, wt = oracle.window_maps(3, 3, 2, 2)
+    assert ti.dtype == np.int32 and pm.dtype == np.uint8 and wt.dtype == np.int32
+    assert ti.reshape(-1).tolist() == [int(x) for x in g["token_index"]]
+    assert pm.reshape(-1).tolist() == [int(x) for x in g["pad_mask"]]
+    assert wt.tolist() == [int(x) for x in g["window_of_token"]]
+
+
+def test_geometry_of_the_padded_37x37_grid(golden):
+    g = golden("window_geometry_37x37_win8x8.txt")
+    assert oracle.window_geometry(37, 37, 8, 8) == tuple(int(x) for x in g["padded"])
+    _, pm, _ = oracle.window_maps(37, 37, 8, 8)
+    counts = pm.sum(axis=1).tolist()
+    assert counts.count(64) == g["count_64"][0]
+    assert counts.count(40) == g["count_40"][0]
+    assert counts.count(25) == g["count_25"][0]
+    assert sum(counts) == g["total"][0]
+
+
+def test_maps_exhaustively_on_small_grids():
+    # properties that fix the maps uniquely, checked for every geometry up to 9
+    for H, W, wh, ww in itertools.product(range(1, 10), range(1, 10), range(1, 10), range(1, 10)):
+        Hp, Wp, nw = oracle.window_geometry(H, W, wh, ww)
+        assert Hp % wh == 0 and Wp % ww == 0 and H <= Hp < H + wh and W <= Wp < W + ww
+        assert nw == (Hp // wh) * (Wp // ww)
+        ti, pm, wt = oracle.window_maps(H, W, wh, ww)
+        assert np.array_equal(pm, (ti >= 0).astype(np.uint8))
+        real = ti[ti >= 0]
+        assert np.array_equal(np.sort(real), np.arange(H * W))          # each token exactly once
+        for win in range(nw):
+            wr, wc = divmod(win, Wp // ww)
+            for slot in range(wh * ww):
+                sr, sc = divmod(slot, ww)
+                r, c = wr * wh + sr, wc * ww + sc                        # the cell this slot covers
+                if r < H and c < W:
+                    assert ti[win, slot] == r * W + c and wt[r * W + c] == win
+                else:
+                    assert ti[win, slot] == -1
+        assert pm.sum(axis=1).min() >= 1                                 # no window is all pad
+
+
+def _qkv(seed, B, h, N, d):
+    return [synth.normal((B, h, N, d), seed + i) for i in range(3)]
+
+
+def test_window_attention_is_block_masked_full_attention():
+    for (H, W, wh, ww) in [(8, 8, 4, 4), (7, 9, 4, 4), (5, 5, 2, 3), (37, 37, 8, 8)]:
+        B, h, d = (1, 1, 8) if H == 37 else (2, 2, 8)
+        q, k, v = _qkv(200 + H, B, h, H * W, d)
+        _, _, wt = oracle.window_maps(H, W, wh, ww)
+        allow = (wt[:, None] == wt[None, :]).astype(np.uint8)
+        want = oracle.masked_attn(q, k, v, allow)
+        got = oracle.window_attn(q, k, v, H, W, wh, ww)
+        assert np.abs(got - want).max() < 1e-13
+
+
+def test_whole_grid_window_is_full_attention():
+    H, W = 6, 7
+    q, k, v = _qkv(300, 2, 2, H * W, 8)
+    assert np.abs(oracle.window_attn(q, k, v, H, W, H, W) - oracle.full_attn(q, k, v)).max() < 1e-14
+    # a window larger than the grid pads only; still full attention
+    assert np.abs(oracle.window_attn(q, k, v, H, W, 8, 8) - oracle.full_attn(q, k, v)).max() < 1e-14
+
+
+def test_one_by_one_windows_return_the_values():
+    H, W = 4, 5
+    q, k, v = _qkv(310, 1, 2, H * W, 8)
+    assert np.array_equal(oracle.window_attn(q, k, v, H, W, 1, 1), v.astype(np.float64))
+
+
+def _torch_window_attention(q, k, v, H, W, wh, ww):
+    """Reshape-based partition + library attention with a key padding mask."""
+    B, h, N, d = q.shape
+    Hp, Wp = -(-H // wh) * wh, -(-W // ww) * ww
+
+    def part(x):
+        x = torch.from_numpy(x).double().reshape(B, h, H, W, d)
+        x = F.pad(x, (0, 0, 0, Wp - W, 0, Hp - H))
+        x = x.reshape(B, h, Hp // wh, wh, Wp // ww, ww, d).permute(0, 1, 2, 4, 3, 5, 6)
+        return x.reshape(B, h, -1, wh * ww, d)
+
+    valid = torch.zeros(Hp, Wp, dtype=torch.bool)
+    valid[:H, :W] = True
+    valid = valid.reshape(Hp // wh, wh, Wp // ww, ww).permute(0, 2, 1, 3).reshape(-1, 1, wh * ww)
+    o = F.scaled_dot_product_attention(part(q), part(k), part(v),
+                                       attn_mask=valid[None, None].expand(B, h, -1, wh * ww, wh * ww))
+    o = o.reshape(B, h, Hp // wh, Wp // ww, wh, ww, d).permute(0, 1, 2, 4, 3, 5, 6)
+    return o.reshape(B, h, Hp, Wp, d)[:, :, :H, :W].reshape(B, h, N, d).numpy()
+
+
+def test_against_reshape_partition_and_library_attention():
+    for (H, W, wh, ww) in [(8, 12, 4, 4), (9, 7, 4, 4), (37, 37, 8, 8)]:
+        q, k, v = _qkv(400 + H, 1, 2, H * W, 16)
+        want = _torch_window_attention(q, k, v, H, W, wh, ww)
+        got = oracle.window_attn(q, k, v, H, W, wh, ww)
+        assert np.abs(got - want).max() < 1e-13
+        rows = synth.sample_rows(1, 2, H * W, 7, seed=H)
+        got_rows = oracle.window_attn_rows(q, k, v, H, W, wh, ww, rows)
+        assert np.array_equal(got_rows, np.stack([got[b, hh, i] for b, hh, i in rows]))
