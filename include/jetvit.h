@@ -1,0 +1,146 @@
+/*
+ * jetvit.h -- C ABI of the MI355X (gfx950) token-mixer library for JetViT's
+ * hybrid-attention Vision Transformer.
+ *
+ * The library computes the forward pass of the three token mixers that the
+ * paper's Post-Training Attention Search assigns per layer -- ReLU-kernel
+ * linear attention, non-overlapping 2-D window attention, and the retained
+ * full softmax attention -- on caller-owned device buffers.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Pointers named q, k, v, o, workspace and every pointer documented as
+ *    "device" are DEVICE pointers (HBM, current HIP device).  Pointers
+ *    documented as "host" are host pointers.  Descriptor structs are host
+ *    memory and are read before the call returns.
+ *  - Ownership: the caller owns every buffer and the stream.  The library never
+ *    allocates or frees device memory, never synchronises, and launches only on
+ *    the stream it is given (hip_stream is a hipStream_t; NULL is the default
+ *    stream).  Scratch memory comes in through `workspace`.
+ *  - Tensors Q, K, V, O are logically [batch, heads, N, head_dim] with
+ *    N = grid_h * grid_w tokens in row-major raster order (token n = r*grid_w+c).
+ *    The head_dim axis is contiguous; the other three axes have the element
+ *    strides given in jv_strides, so a fused QKV projection output laid out
+ *    [batch, N, 3, heads, head_dim] can be consumed without a transpose.
+ *    Base pointers and all strides must keep every (b, h, n) row 16-byte aligned.
+ *  - head_dim must be 64.
+ *  - Inputs are never written.  O must not alias Q, K or V.
+ *  - Arithmetic: JV_F32 tensors are processed in fp32 throughout.  JV_BF16
+ *    tensors feed bf16 matrix instructions with fp32 accumulation; softmax,
+ *    normalisers and divisions are fp32.  O is rounded to `o_dtype` once, at the
+ *    final store (round to nearest even).
+ *  - Errors: every call validates its arguments on the host before any launch
+ *    and returns a jv_status.  On any status other than JV_OK nothing was
+ *    launched and no buffer was touched (JV_ERR_HIP excepted: a launch was
+ *    attempted and the HIP runtime refused it).  No call aborts, throws or
+ *    prints.  jv_last_error() returns a thread-local description of the last
+ *    failure on the calling thread.
+ *  - Thread safety: no mutable global state; concurrent calls are safe as long
+ *    as their output and workspace buffers do not overlap.
+ */
+#ifndef JETVIT_H
+#define JETVIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    JV_OK = 0,
+    JV_ERR_INVALID_ARG = 1,         /* null pointer, non-positive size, bad stride/alignment */
+    JV_ERR_UNSUPPORTED = 2,         /* valid request this build does not implement */
+    JV_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below the *_workspace_bytes query */
+    JV_ERR_HIP = 4                  /* the HIP runtime rejected a launch */
+} jv_status;
+
+typedef enum { JV_F32 = 0, JV_BF16 = 1 } jv_dtype;
+
+/* Element strides of one [batch, heads, N, head_dim] tensor; head_dim stride is 1. */
+typedef struct {
+    int64_t stride_b, stride_h, stride_n;
+} jv_strides;
+
+typedef struct {
+    int32_t batch, heads;
+    int32_t grid_h, grid_w; /* token grid; N = grid_h * grid_w */
+    int32_t head_dim;       /* 64 */
+    jv_dtype dtype;         /* element type of Q, K, V */
+    jv_dtype o_dtype;       /* element type of O: equal to dtype, or JV_F32 with JV_BF16 inputs */
+    jv_strides q, k, v, o;
+} jv_attn_desc;
+
+const char *jv_version(void);
+const char *jv_status_string(jv_status status);
+const char *jv_last_error(void);
+
+/* ---------------------------------------------------------------------------
+ * Linear attention (Sec. 3.2.1, Eq. 2 with the ReLU feature map the block keeps;
+ * the output is normalised by the key sum):
+ *     S = sum_j relu(k_j)^T v_j   (head_dim x head_dim, per batch and head)
+ *     z = sum_j relu(k_j)
+ *     o_i = relu(q_i) S / (relu(q_i) . z + eps)
+ * Two passes: a streaming reduction of K and V into partial (S, z) states held
+ * in `workspace`, then a pass over Q that sums the partials and applies them.
+ * No 1/sqrt(d) scaling is applied.  eps is added to the denominator; eps < 0
+ * or NaN is JV_ERR_INVALID_ARG.
+ *
+ * workspace: device, at least jv_linear_attn_workspace_bytes(desc) bytes,
+ * 256-byte aligned; contents on entry are ignored, contents on return are
+ * unspecified.  The query returns 0 for an invalid descriptor.
+ * ------------------------------------------------------------------------- */
+size_t jv_linear_attn_workspace_bytes(const jv_attn_desc *desc);
+jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                             const void *v, void *o, float eps, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Window partition (Sec. 3.2.2: the feature map is split into non-overlapping
+ * windows).  The grid is extended at the bottom and right to multiples of the
+ * window (padded_h x padded_w); windows are anchored at (0, 0) and numbered
+ * row-major; the win_h*win_w slots of a window are numbered row-major.
+ *
+ * jv_window_geometry: host computation; the three outputs are host pointers.
+ *
+ * jv_window_maps_host / jv_window_maps_device fill (any output may be NULL):
+ *   token_index     int32 [n_windows * win_h*win_w]  token r*grid_w+c of the slot, -1 for padding
+ *   pad_mask        uint8 [n_windows * win_h*win_w]  1 for a real token, 0 for padding
+ *   window_of_token int32 [grid_h*grid_w]            window that holds each token
+ * The _host variant takes host pointers and runs on the CPU; the _device
+ * variant takes device pointers and runs one kernel on hip_stream.  Both give
+ * identical bytes.
+ * ------------------------------------------------------------------------- */
+jv_status jv_window_geometry(int32_t grid_h, int32_t grid_w, int32_t win_h, int32_t win_w,
+                             int32_t *padded_h, int32_t *padded_w, int32_t *n_windows);
+jv_status jv_window_maps_host(int32_t grid_h, int32_t grid_w, int32_t win_h, int32_t win_w,
+                              int32_t *token_index, uint8_t *pad_mask, int32_t *window_of_token);
+jv_status jv_window_maps_device(int32_t grid_h, int32_t grid_w, int32_t win_h, int32_t win_w,
+                                int32_t *token_index, uint8_t *pad_mask,
+                                int32_t *window_of_token, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Window attention (Sec. 3.2.2): every token attends, with the softmax
+ * attention of Eq. 1, to the real tokens of its own win_h x win_w window only.
+ * Padding is virtual: Q, K, V, O hold the grid_h*grid_w real tokens; padded key
+ * slots are excluded from the softmax (not merely zero-valued) and padded query
+ * slots produce no output.  scale multiplies the logits; scale <= 0 or NaN
+ * selects 1/sqrt(head_dim).
+ * ------------------------------------------------------------------------- */
+jv_status jv_window_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                             const void *v, void *o, int32_t win_h, int32_t win_w, float scale,
+                             void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Full softmax attention (Eq. 1): o_i = sum_j softmax_j(scale * q_i . k_j) v_j
+ * over all N tokens, computed tile by tile with a running maximum and sum.
+ * scale <= 0 or NaN selects 1/sqrt(head_dim).
+ * ------------------------------------------------------------------------- */
+jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                           const void *v, void *o, float scale, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JETVIT_H */

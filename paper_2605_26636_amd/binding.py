@@ -1,0 +1,179 @@
+"""Thin ctypes binding of libjetvit.so (include/jetvit.h).
+
+Argument marshalling only: every computation runs inside the library's HIP
+kernels.  Tensors are torch tensors on the GPU (torch is used for device memory
+and streams); the functions carry the names of the C entry points.  There is no
+CPU fallback: a missing library or a non-OK status raises.
+"""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libjetvit.so")
+
+JV_OK, JV_ERR_INVALID_ARG, JV_ERR_UNSUPPORTED, JV_ERR_WORKSPACE_TOO_SMALL, JV_ERR_HIP = range(5)
+JV_F32, JV_BF16 = 0, 1
+
+EXPORTS = [
+    "jv_version", "jv_status_string", "jv_last_error",
+    "jv_linear_attn_workspace_bytes", "jv_linear_attn_fwd",
+    "jv_window_geometry", "jv_window_maps_host", "jv_window_maps_device",
+    "jv_window_attn_fwd", "jv_full_attn_fwd",
+]
+
+
+class JvStrides(ctypes.Structure):
+    _fields_ = [("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+                ("stride_n", ctypes.c_int64)]
+
+
+class JvAttnDesc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int), ("o_dtype", ctypes.c_int),
+                ("q", JvStrides), ("k", JvStrides), ("v", JvStrides), ("o", JvStrides)]
+
+
+class JvError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"jetvit status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Load libjetvit.so (built in-tree by build.py); fails loudly when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2605_26636_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.jv_version.restype = ctypes.c_char_p
+        L.jv_status_string.restype = ctypes.c_char_p
+        L.jv_last_error.restype = ctypes.c_char_p
+        L.jv_linear_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.jv_linear_attn_workspace_bytes.argtypes = [ctypes.POINTER(JvAttnDesc)]
+        vp = ctypes.c_void_p
+        L.jv_linear_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
+                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
+        L.jv_window_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
+                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp]
+        L.jv_full_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
+                                       ctypes.c_float, vp]
+        i32 = ctypes.c_int32
+        L.jv_window_geometry.argtypes = [i32, i32, i32, i32, vp, vp, vp]
+        L.jv_window_maps_host.argtypes = [i32, i32, i32, i32, vp, vp, vp]
+        L.jv_window_maps_device.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != JV_OK:
+        raise JvError(status, lib().jv_last_error().decode() or
+                      lib().jv_status_string(status).decode())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return JV_F32
+    if t.dtype == torch.bfloat16:
+        return JV_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _strides(t):
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("tensors must be [batch, heads, N, head_dim] views with a contiguous last axis")
+    return JvStrides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def make_desc(q, k, v, o, grid):
+    """Descriptor for [B, heads, N, d] tensor views q, k, v, o on an H x W grid."""
+    B, heads, N, d = q.shape
+    H, W = grid
+    if H * W != N:
+        raise ValueError("grid does not match the token count")
+    for t in (k, v, o):
+        if tuple(t.shape) != (B, heads, N, d):
+            raise ValueError("q, k, v, o must share one shape")
+    if not (q.dtype == k.dtype == v.dtype):
+        raise TypeError("q, k, v must share one dtype")
+    for t in (q, k, v, o):
+        if not t.is_cuda:
+            raise ValueError("tensors must live on the GPU")
+    return JvAttnDesc(B, heads, H, W, d, _dtype_code(q), _dtype_code(o),
+                      _strides(q), _strides(k), _strides(v), _strides(o))
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def jv_version():
+    return lib().jv_version().decode()
+
+
+def jv_linear_attn_workspace_bytes(desc):
+    return int(lib().jv_linear_attn_workspace_bytes(ctypes.byref(desc)))
+
+
+def jv_linear_attn_fwd(q, k, v, o, grid, eps=1e-6, workspace=None, stream=None):
+    """o <- ReLU linear attention of (q, k, v); returns the workspace tensor used."""
+    desc = make_desc(q, k, v, o, grid)
+    need = jv_linear_attn_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib().jv_linear_attn_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                    o.data_ptr(), eps, workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+    return workspace
+
+
+def jv_window_attn_fwd(q, k, v, o, grid, window, scale=0.0, stream=None):
+    desc = make_desc(q, k, v, o, grid)
+    _check(lib().jv_window_attn_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                    o.data_ptr(), window[0], window[1], scale, _stream(stream)))
+
+
+def jv_full_attn_fwd(q, k, v, o, grid, scale=0.0, stream=None):
+    desc = make_desc(q, k, v, o, grid)
+    _check(lib().jv_full_attn_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                  o.data_ptr(), scale, _stream(stream)))
+
+
+def jv_window_geometry(grid_h, grid_w, win_h, win_w):
+    """(padded_h, padded_w, n_windows); host computation."""
+    out = (ctypes.c_int32 * 3)()
+    base = ctypes.addressof(out)
+    _check(lib().jv_window_geometry(grid_h, grid_w, win_h, win_w, base, base + 4, base + 8))
+    return out[0], out[1], out[2]
+
+
+def jv_window_maps_host(grid_h, grid_w, win_h, win_w):
+    """(token_index, pad_mask, window_of_token) as numpy arrays, computed on the host."""
+    import numpy as np
+    _, _, nw = jv_window_geometry(grid_h, grid_w, win_h, win_w)
+    ti = np.empty((nw, win_h * win_w), dtype=np.int32)
+    pm = np.empty((nw, win_h * win_w), dtype=np.uint8)
+    wt = np.empty(grid_h * grid_w, dtype=np.int32)
+    _check(lib().jv_window_maps_host(grid_h, grid_w, win_h, win_w, ti.ctypes.data, pm.ctypes.data,
+                                     wt.ctypes.data))
+    return ti, pm, wt
+
+
+def jv_window_maps_device(grid_h, grid_w, win_h, win_w, device="cuda", stream=None):
+    """(token_index, pad_mask, window_of_token) as device tensors, computed by a kernel."""
+    _, _, nw = jv_window_geometry(grid_h, grid_w, win_h, win_w)
+    ti = torch.empty((nw, win_h * win_w), dtype=torch.int32, device=device)
+    pm = torch.empty((nw, win_h * win_w), dtype=torch.uint8, device=device)
+    wt = torch.empty(grid_h * grid_w, dtype=torch.int32, device=device)
+    _check(lib().jv_window_maps_device(grid_h, grid_w, win_h, win_w, ti.data_ptr(), pm.data_ptr(),
+                                       wt.data_ptr(), _stream(stream)))
+    return ti, pm, wt

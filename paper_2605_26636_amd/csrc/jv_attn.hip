@@ -1,0 +1,127 @@
+// Softmax attention over windows of the token grid (Sec. 3.2.2 of the paper) and over the whole
+// grid (Eq. 1).  Full attention is the one-window case of the same kernels: a window that
+// spans the grid.  Queries and keys are addressed by (window, slot); slot -> token is the
+// row-major position inside the window, and slots that fall outside the H x W grid are
+// padding: excluded as keys, skipped as queries.
+#include <math.h>
+
+#include "jv_common.h"
+
+namespace jv {
+
+// slot of window (wy, wx) -> token index, or -1 for padding / past the window.
+__device__ inline int slot_token(const WindowGeom &g, int wy, int wx, int slot) {
+    if (slot >= g.slots) return -1;
+    int r = wy * g.wh + slot / g.ww, c = wx * g.ww + slot % g.ww;
+    return (r < g.H && c < g.W) ? r * g.W + c : -1;
+}
+
+__device__ inline float wave_max(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    return x;
+}
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 path.  One wavefront per query slot; a workgroup holds four consecutive slots of one
+// window.  Key tiles of 64 slots: lane j scores key j (dot product over 64 channels), the
+// tile joins the running softmax, then lane c accumulates channel c of the output.
+// grid (ceil(slots/4), n_win, B*heads), 256 threads.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+attn_f32(TensorArg qt, TensorArg kt, TensorArg vt, TensorArg ot, WindowGeom g, int heads,
+         float scale) {
+    __shared__ float qs[4][kHeadDim];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int bh = blockIdx.z, b = bh / heads, h = bh % heads;
+    const int win = blockIdx.y, wy = win / g.wins_x, wx = win % g.wins_x;
+    const int qslot = blockIdx.x * 4 + wave;
+    const int qtok = slot_token(g, wy, wx, qslot);
+    if (qtok < 0) return;  // wave-uniform: padded query slots produce nothing
+    const float *qp = (const float *)qt.ptr + b * qt.sb + h * qt.sh + (long long)qtok * qt.sn;
+    const float *kp = (const float *)kt.ptr + b * kt.sb + h * kt.sh;
+    const float *vp = (const float *)vt.ptr + b * vt.sb + h * vt.sh;
+    float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)qtok * ot.sn;
+    qs[wave][lane] = qp[lane];  // read back by the same wave only
+    float m = -INFINITY, l = 0.f, acc = 0.f;
+    for (int s0 = 0; s0 < g.slots; s0 += 64) {
+        const int tok = slot_token(g, wy, wx, s0 + lane);
+        float s = -INFINITY;
+        if (tok >= 0) {
+            const float4 *krow = (const float4 *)(kp + (long long)tok * kt.sn);
+            float dot = 0.f;
+#pragma unroll
+            for (int c4 = 0; c4 < 16; ++c4) {
+                float4 kk = krow[c4];
+                dot = fmaf(qs[wave][4 * c4 + 0], kk.x, dot);
+                dot = fmaf(qs[wave][4 * c4 + 1], kk.y, dot);
+                dot = fmaf(qs[wave][4 * c4 + 2], kk.z, dot);
+                dot = fmaf(qs[wave][4 * c4 + 3], kk.w, dot);
+            }
+            s = dot * scale;
+        }
+        const float tile_max = wave_max(s);
+        if (tile_max == -INFINITY) continue;  // a tile of padding only
+        const float m_new = fmaxf(m, tile_max);
+        const float alpha = expf(m - m_new);  // exp(-inf) = 0 on the first live tile
+        const float p = (tok >= 0) ? expf(s - m_new) : 0.f;
+        l = l * alpha + wave_sum(p);
+        acc *= alpha;
+        for (int j = 0; j < 64; ++j) {
+            const int tj = __shfl(tok, j, 64);
+            if (tj < 0) continue;  // wave-uniform
+            const float pj = __shfl(p, j, 64);
+            acc = fmaf(pj, vp[(long long)tj * vt.sn + lane], acc);
+        }
+        m = m_new;
+    }
+    op[lane] = acc / l;
+}
+
+jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStream_t stream);
+
+static jv_status attn_dispatch(const Problem &pr, const WindowGeom &g, float scale,
+                               hipStream_t stream) {
+    if (pr.bf16) return attn_bf16(pr, g, scale, stream);
+    const long long qblocks = (g.slots + 3) / 4;
+    if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
+    hipLaunchKernelGGL(attn_f32, dim3((unsigned)qblocks, g.n_win, pr.B * pr.heads), dim3(256), 0,
+                       stream, pr.q, pr.k, pr.v, pr.o, g, pr.heads, scale);
+    return launch_status("attn_f32");
+}
+
+}  // namespace jv
+
+extern "C" {
+
+jv_status jv_window_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                             const void *v, void *o, int32_t win_h, int32_t win_w, float scale,
+                             void *hip_stream) {
+    jv::clear_error();
+    jv::Problem pr;
+    jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
+    if (st != JV_OK) return st;
+    jv::WindowGeom g;
+    if ((st = jv::make_window_geom(pr.H, pr.W, win_h, win_w, &g)) != JV_OK) return st;
+    return jv::attn_dispatch(pr, g, jv::resolve_scale(scale), (hipStream_t)hip_stream);
+}
+
+jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                           const void *v, void *o, float scale, void *hip_stream) {
+    jv::clear_error();
+    jv::Problem pr;
+    jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
+    if (st != JV_OK) return st;
+    // One window that spans the grid; the token order inside it is the raster order.
+    jv::WindowGeom g;
+    g.H = pr.H; g.W = pr.W; g.wh = pr.H; g.ww = pr.W;
+    g.Hp = pr.H; g.Wp = pr.W; g.wins_x = 1; g.wins_y = 1; g.n_win = 1; g.slots = pr.N;
+    return jv::attn_dispatch(pr, g, jv::resolve_scale(scale), (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

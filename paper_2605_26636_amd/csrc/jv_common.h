@@ -1,0 +1,55 @@
+// Shared host-side plumbing of the JetViT mixer library: error reporting,
+// descriptor validation, kernel-argument structs.  No kernel code lives here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "jetvit.h"
+
+namespace jv {
+
+constexpr int kHeadDim = 64;
+
+// Thread-local description of the last failure; returns `st` for tail calls.
+jv_status fail(jv_status st, const char *fmt, ...);
+void clear_error();
+
+// One [batch, heads, N, 64] tensor as a kernel sees it (element strides).
+struct TensorArg {
+    const void *ptr;
+    long long sb, sh, sn;
+};
+
+// Everything a mixer kernel needs to know about the problem.
+struct Problem {
+    int B, heads, H, W, N;
+    bool bf16;      // element type of Q, K, V
+    bool o_bf16;    // element type of O
+    TensorArg q, k, v, o;
+};
+
+// Validates the descriptor and the four base pointers; fills `out`.
+jv_status make_problem(const jv_attn_desc *desc, const void *q, const void *k, const void *v,
+                       void *o, Problem *out);
+// Descriptor-only part of the validation (no pointers).
+jv_status check_desc(const jv_attn_desc *desc);
+
+inline jv_status launch_status(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(JV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return JV_OK;
+}
+
+inline float resolve_scale(float scale) {
+    return (scale > 0.0f) ? scale : 0.125f;  // 1/sqrt(64); NaN fails the comparison too
+}
+
+// Window partition of an H x W grid (bottom/right padding, windows anchored at (0,0)).
+struct WindowGeom {
+    int H, W, wh, ww;
+    int Hp, Wp, wins_x, wins_y, n_win, slots;  // slots = wh*ww
+};
+jv_status make_window_geom(int H, int W, int wh, int ww, WindowGeom *g);
+
+}  // namespace jv

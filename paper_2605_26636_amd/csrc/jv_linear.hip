@@ -1,0 +1,176 @@
+// ReLU linear attention (Eq. 2 of the paper with phi = ReLU, key-sum normaliser):
+//   pass 1  la_state_*  : S_p = sum_j relu(k_j)^T v_j, z_p = sum_j relu(k_j) over one token chunk
+//   pass 2  la_apply_*  : S = sum_p S_p, z = sum_p z_p;  o_i = relu(q_i) S / (relu(q_i).z + eps)
+//
+// Workspace layout (fp32): partial p of (batch b, head h) starts at
+//   ((p * B*heads) + b*heads + h) * kStateFloats
+// and holds S transposed, St[c2][c1] (c2 = value channel, c1 = key channel), then z[c1].
+#include "jv_common.h"
+
+namespace jv {
+
+constexpr int kStateFloats = kHeadDim * kHeadDim + kHeadDim;
+
+struct LinearPlan {
+    int n_split;       // token chunks per (batch, head)
+    int chunk;         // tokens per chunk (multiple of 64)
+    int apply_tokens;  // tokens per apply workgroup
+};
+
+static LinearPlan plan_linear(int B, int heads, int N) {
+    LinearPlan p;
+    const long long bh = (long long)B * heads;
+    // Aim for about two workgroups per compute unit, chunks of at least 256 tokens.
+    long long want = (512 + bh - 1) / bh;
+    long long max_split = (N + 255) / 256;
+    if (want > max_split) want = max_split;
+    if (want < 1) want = 1;
+    if (want > 64) want = 64;
+    long long chunk = (N + want - 1) / want;
+    chunk = ((chunk + 63) / 64) * 64;
+    p.chunk = (int)chunk;
+    p.n_split = (int)((N + chunk - 1) / chunk);
+    p.apply_tokens = 256;
+    return p;
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 path: plain FMA arithmetic, used for fp32 tensors.
+// ---------------------------------------------------------------------------------------
+
+// grid (n_split, B*heads), 256 threads.  Thread t owns S[16*(t/64) .. +15][t%64].
+__global__ void __launch_bounds__(256)
+la_state_f32(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int N, int chunk) {
+    __shared__ float Ks[32][kHeadDim];
+    __shared__ float Vs[32][kHeadDim];
+    const int bh = blockIdx.y, b = bh / heads, h = bh % heads, p = blockIdx.x;
+    const int BH = gridDim.y;
+    const float *kp = (const float *)kt.ptr + b * kt.sb + h * kt.sh;
+    const float *vp = (const float *)vt.ptr + b * vt.sb + h * vt.sh;
+    const int t = threadIdx.x, c2 = t & 63, rb = t >> 6;
+    float acc[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    float zacc = 0.f;
+    const int n0 = p * chunk, n1 = min(N, n0 + chunk);
+    for (int base = n0; base < n1; base += 32) {
+        // 32 tokens x 64 channels = 512 float4; two per thread per tensor
+        for (int e = t; e < 512; e += 256) {
+            int j = e >> 4, c4 = (e & 15) * 4, n = base + j;
+            float4 kk = make_float4(0.f, 0.f, 0.f, 0.f), vv = kk;
+            if (n < n1) {
+                kk = *(const float4 *)(kp + (long long)n * kt.sn + c4);
+                vv = *(const float4 *)(vp + (long long)n * vt.sn + c4);
+            }
+            Ks[j][c4 + 0] = fmaxf(kk.x, 0.f);
+            Ks[j][c4 + 1] = fmaxf(kk.y, 0.f);
+            Ks[j][c4 + 2] = fmaxf(kk.z, 0.f);
+            Ks[j][c4 + 3] = fmaxf(kk.w, 0.f);
+            *(float4 *)&Vs[j][c4] = vv;
+        }
+        __syncthreads();
+        for (int j = 0; j < 32; ++j) {
+            float vj = Vs[j][c2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = fmaf(Ks[j][rb * 16 + r], vj, acc[r]);
+            if (rb == 0) zacc += Ks[j][c2];
+        }
+        __syncthreads();
+    }
+    float *out = ws + ((size_t)p * BH + bh) * kStateFloats;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) out[c2 * kHeadDim + rb * 16 + r] = acc[r];
+    if (rb == 0) out[kHeadDim * kHeadDim + c2] = zacc;
+}
+
+// grid (ceil(N/256), B*heads), 256 threads.
+__global__ void __launch_bounds__(256)
+la_apply_f32(TensorArg qt, TensorArg ot, const float *__restrict__ ws, int heads, int N,
+             int n_split, float eps) {
+    __shared__ float S[kHeadDim][kHeadDim + 1];  // S[c1][c2]
+    __shared__ float z[kHeadDim];
+    __shared__ float Qs[64][kHeadDim];
+    const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
+    const int BH = gridDim.y;
+    const float *qp = (const float *)qt.ptr + b * qt.sb + h * qt.sh;
+    float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh;
+    const int t = threadIdx.x;
+    for (int e = t; e < kStateFloats; e += 256) {
+        float s = 0.f;
+        for (int p = 0; p < n_split; ++p) s += ws[((size_t)p * BH + bh) * kStateFloats + e];
+        if (e < kHeadDim * kHeadDim) S[e & 63][e >> 6] = s;  // stored transposed in the workspace
+        else z[e - kHeadDim * kHeadDim] = s;
+    }
+    const int c2 = t & 63, tg = t >> 6;
+    const int n0 = blockIdx.x * 256, n1 = min(N, n0 + 256);
+    for (int base = n0; base < n1; base += 64) {
+        __syncthreads();
+        for (int e = t; e < 1024; e += 256) {
+            int j = e >> 4, c4 = (e & 15) * 4, n = base + j;
+            float4 qq = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n < n1) qq = *(const float4 *)(qp + (long long)n * qt.sn + c4);
+            Qs[j][c4 + 0] = fmaxf(qq.x, 0.f);
+            Qs[j][c4 + 1] = fmaxf(qq.y, 0.f);
+            Qs[j][c4 + 2] = fmaxf(qq.z, 0.f);
+            Qs[j][c4 + 3] = fmaxf(qq.w, 0.f);
+        }
+        __syncthreads();
+        for (int jj = 0; jj < 16; ++jj) {
+            int j = tg * 16 + jj, n = base + j;
+            if (n >= n1) break;
+            float num = 0.f, den = 0.f;
+#pragma unroll 8
+            for (int c1 = 0; c1 < kHeadDim; ++c1) {
+                float qv = Qs[j][c1];
+                num = fmaf(qv, S[c1][c2], num);
+                den = fmaf(qv, z[c1], den);
+            }
+            op[(long long)n * ot.sn + c2] = num / (den + eps);
+        }
+    }
+}
+
+jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
+                      hipStream_t stream);
+
+}  // namespace jv
+
+extern "C" {
+
+size_t jv_linear_attn_workspace_bytes(const jv_attn_desc *desc) {
+    jv::clear_error();
+    if (jv::check_desc(desc) != JV_OK) return 0;
+    jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
+    return (size_t)plan.n_split * desc->batch * desc->heads * jv::kStateFloats * sizeof(float);
+}
+
+jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                             const void *v, void *o, float eps, void *workspace,
+                             size_t workspace_bytes, void *hip_stream) {
+    jv::clear_error();
+    jv::Problem pr;
+    jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
+    if (st != JV_OK) return st;
+    if (!(eps >= 0.0f)) return jv::fail(JV_ERR_INVALID_ARG, "eps must be >= 0");
+    if (!workspace) return jv::fail(JV_ERR_INVALID_ARG, "workspace is null");
+    if ((uintptr_t)workspace & 255)
+        return jv::fail(JV_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    const size_t need = jv_linear_attn_workspace_bytes(desc);
+    if (workspace_bytes < need)
+        return jv::fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed",
+                        workspace_bytes, need);
+    jv::LinearPlan plan = jv::plan_linear(pr.B, pr.heads, pr.N);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *ws = (float *)workspace;
+    if (pr.bf16) return jv::linear_bf16(pr, plan, eps, ws, stream);
+
+    const int BH = pr.B * pr.heads;
+    hipLaunchKernelGGL(jv::la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v,
+                       ws, pr.heads, pr.N, plan.chunk);
+    if ((st = jv::launch_status("la_state_f32")) != JV_OK) return st;
+    hipLaunchKernelGGL(jv::la_apply_f32, dim3((pr.N + 255) / 256, BH), dim3(256), 0, stream, pr.q,
+                       pr.o, ws, pr.heads, pr.N, plan.n_split, eps);
+    return jv::launch_status("la_apply_f32");
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+"""Host-side checks of the C ABI: the library loads, exports every declared symbol, and its
+host-only entry points (geometry, host maps, argument validation) behave as documented."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_26636_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(jv_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    declared = _declared_symbols()
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(L, name), f"{name} is declared but not exported"
+    assert set(binding.EXPORTS) == declared
+    assert b"gfx950" in L.jv_version()
+
+
+def test_geometry_and_host_maps_match_the_oracle_bit_for_bit():
+    cases = [(3, 3, 2, 2), (37, 37, 8, 8), (64, 64, 16, 16), (16, 16, 8, 8), (5, 9, 4, 2),
+             (7, 7, 7, 7), (7, 7, 9, 3), (1, 1, 1, 1), (128, 128, 16, 16)]
+    for H, W, wh, ww in cases:
+        assert binding.jv_window_geometry(H, W, wh, ww) == oracle.window_geometry(H, W, wh, ww)
+        got = binding.jv_window_maps_host(H, W, wh, ww)
+        want = oracle.window_maps(H, W, wh, ww)
+        for g, w in zip(got, want):
+            assert g.dtype == w.dtype and g.shape == w.shape
+            assert g.tobytes() == w.tobytes()
+
+
+def test_argument_validation_launches_nothing():
+    L = binding.lib()
+    d = binding.JvAttnDesc(1, 2, 4, 4, 64, binding.JV_F32, binding.JV_F32,
+                           binding.JvStrides(2 * 16 * 64, 16 * 64, 64),
+                           binding.JvStrides(2 * 16 * 64, 16 * 64, 64),
+                           binding.JvStrides(2 * 16 * 64, 16 * 64, 64),
+                           binding.JvStrides(2 * 16 * 64, 16 * 64, 64))
+    assert binding.jv_linear_attn_workspace_bytes(d) > 0
+    # null tensors
+    assert L.jv_full_attn_fwd(ctypes.byref(d), None, None, None, None, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert b"non-null" in L.jv_last_error()
+    # head_dim other than 64
+    d2 = binding.JvAttnDesc.from_buffer_copy(d)
+    d2.head_dim = 128
+    assert L.jv_full_attn_fwd(ctypes.byref(d2), 16, 32, 48, 64, 0.0, None) == binding.JV_ERR_UNSUPPORTED
+    assert binding.jv_linear_attn_workspace_bytes(d2) == 0
+    # misaligned pointer, aliasing output, bad window, bad eps, small workspace
+    assert L.jv_full_attn_fwd(ctypes.byref(d), 16, 32, 48, 68, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_full_attn_fwd(ctypes.byref(d), 16, 32, 48, 16, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_window_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, 0, 4, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_linear_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, -1.0, 256, 1 << 30, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_linear_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, 1e-6, 256, 16, None) == binding.JV_ERR_WORKSPACE_TOO_SMALL
+    assert L.jv_linear_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, 1e-6, None, 1 << 30, None) == binding.JV_ERR_INVALID_ARG
+    # stride that breaks row alignment
+    d3 = binding.JvAttnDesc.from_buffer_copy(d)
+    d3.q.stride_n = 66
+    assert L.jv_full_attn_fwd(ctypes.byref(d3), 16, 32, 48, 64, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    with pytest.raises(binding.JvError):
+        binding.jv_window_geometry(4, 4, 0, 2)
+    assert L.jv_status_string(3) == b"workspace too small"
