@@ -5,19 +5,11 @@
 // Workspace layout (fp32): partial p of (batch b, head h) starts at
 //   ((p * B*heads) + b*heads + h) * kStateFloats
 // and holds S transposed, St[c2][c1] (c2 = value channel, c1 = key channel), then z[c1].
-#include "jv_common.h"
+#include "jv_linear.h"
 
 namespace jv {
 
-constexpr int kStateFloats = kHeadDim * kHeadDim + kHeadDim;
-
-struct LinearPlan {
-    int n_split;       // token chunks per (batch, head)
-    int chunk;         // tokens per chunk (multiple of 64)
-    int apply_tokens;  // tokens per apply workgroup
-};
-
-static LinearPlan plan_linear(int B, int heads, int N) {
+LinearPlan plan_linear(int B, int heads, int N) {
     LinearPlan p;
     const long long bh = (long long)B * heads;
     // Aim for about two workgroups per compute unit, chunks of at least 256 tokens.
@@ -27,11 +19,16 @@ static LinearPlan plan_linear(int B, int heads, int N) {
     if (want < 1) want = 1;
     if (want > 64) want = 64;
     long long chunk = (N + want - 1) / want;
-    chunk = ((chunk + 63) / 64) * 64;
+    chunk = ((chunk + 255) / 256) * 256;
     p.chunk = (int)chunk;
     p.n_split = (int)((N + chunk - 1) / chunk);
-    p.apply_tokens = 256;
+    p.apply_tokens = 1024;
+    p.combine = p.n_split > 4;
     return p;
+}
+
+size_t linear_workspace_floats(const LinearPlan &p, int B, int heads) {
+    return (size_t)(p.n_split + (p.combine ? 1 : 0)) * B * heads * kStateFloats;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -130,9 +127,6 @@ la_apply_f32(TensorArg qt, TensorArg ot, const float *__restrict__ ws, int heads
     }
 }
 
-jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
-                      hipStream_t stream);
-
 }  // namespace jv
 
 extern "C" {
@@ -141,7 +135,7 @@ size_t jv_linear_attn_workspace_bytes(const jv_attn_desc *desc) {
     jv::clear_error();
     if (jv::check_desc(desc) != JV_OK) return 0;
     jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
-    return (size_t)plan.n_split * desc->batch * desc->heads * jv::kStateFloats * sizeof(float);
+    return jv::linear_workspace_floats(plan, desc->batch, desc->heads) * sizeof(float);
 }
 
 jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
