@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the JetViT token-mixer hot path on one MI355X.
+
+One "step" = one linear-attention layer + one 16x16 window-attention layer + one full-attention
+layer on the ViT-L attention workload (bf16, batch 8, 64x64 grid = 4096 tokens, 16 heads x 64),
+all inputs resident in HBM.  value = tokens pushed through a mixer layer per second
+(3 layers x 32 768 tokens / step time).  Each mixer is also timed on its own with HIP events on
+the launch stream and priced against its roofline (HBM for linear and window attention, bf16
+MFMA for full attention); the dominant kernel of the step is full attention.
+
+Prints ONE JSON line.  Use --gpus 1 only: the library is a single-GPU path.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="mixer workload (2 = headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--buffers", type=int, default=6, help="rotating input/output sets")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU path (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_26636_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.lib()
+    c = synth.CONFIGS[args.config]
+    B, heads, H, W, d = c["B"], c["heads"], c["H"], c["W"], c["d"]
+    N = H * W
+    window = c["window"]
+    tokens = B * N
+    dt = torch.bfloat16 if c["bf16"] else torch.float32
+    esz = 2 if c["bf16"] else 4
+
+    q, k, v = synth.config_qkv(args.config)
+    base = [torch.from_numpy(x).cuda().to(dt) for x in (q, k, v)]
+    # Rotating buffer sets so that the last-level cache cannot hold the working set.
+    sets = []
+    for i in range(args.buffers):
+        qs, ks, vs = (t.clone() if i else t for t in base)
+        sets.append((qs, ks, vs, torch.empty_like(qs)))
+    ws = torch.empty(max(256, binding.jv_linear_attn_workspace_bytes(
+        binding.make_desc(*sets[0], (H, W)))), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def linear(s):
+        binding.jv_linear_attn_fwd(s[0], s[1], s[2], s[3], (H, W), 1e-6, ws, stream)
+
+    def win(s):
+        binding.jv_window_attn_fwd(s[0], s[1], s[2], s[3], (H, W), window, 0.0, stream)
+
+    def full(s):
+        binding.jv_full_attn_fwd(s[0], s[1], s[2], s[3], (H, W), 0.0, stream)
+
+    mixers = {"linear": linear, "window": win, "full": full}
+
+    def step(i):
+        s = sets[i % len(sets)]
+        linear(s); win(s); full(s)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # Per-mixer timing with events on the launch stream (average over the timed launches).
+    per = {}
+    for name, fn in mixers.items():
+        for i in range(3):
+            fn(sets[i % len(sets)])
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            s = sets[i % len(sets)]
+            a.record(stream); fn(s); b.record(stream)
+        torch.cuda.synchronize()
+        t = np.array([a.elapsed_time(b) for a, b in evs])
+        per[name] = {"ms_avg": float(t.mean()), "ms_min": float(t.min()),
+                     "ms_median": float(np.median(t))}
+
+    bytes_layer = 4 * tokens * heads * d * esz                 # read Q, K, V; write O
+    flops_full = 4.0 * N * N * d * B * heads                   # QK^T and PV
+    flops_window = 4.0 * N * (window[0] * window[1]) * d * B * heads
+    flops_linear = (4.0 * d * d + 2 * d) * tokens * heads
+    for name in per:
+        ms = per[name]["ms_avg"]
+        per[name]["tokens_per_s"] = tokens / (ms * 1e-3)
+        per[name]["hbm_GBs"] = bytes_layer / (ms * 1e-3) / 1e9
+        per[name]["hbm_frac"] = per[name]["hbm_GBs"] / HBM_PEAK_GBS
+    for name, fl in (("full", flops_full), ("window", flops_window), ("linear", flops_linear)):
+        per[name]["TFLOPs"] = fl / (per[name]["ms_avg"] * 1e-3) / 1e12
+        per[name]["mfma_frac"] = per[name]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+
+    roofline = {"kernel": "attn_stream_bf16 (full attention)", "bound": "mfma",
+                "achieved": per["full"]["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"], "traffic": None}
+    rooflines = {
+        "linear": {"bound": "hbm", "achieved": per["linear"]["hbm_GBs"], "peak": HBM_PEAK_GBS,
+                   "unit": "GB/s", "frac": per["linear"]["hbm_frac"]},
+        "window": {"bound": "hbm", "achieved": per["window"]["hbm_GBs"], "peak": HBM_PEAK_GBS,
+                   "unit": "GB/s", "frac": per["window"]["hbm_frac"],
+                   "mfma_frac": per["window"]["mfma_frac"]},
+        "full": {"bound": "mfma", "achieved": per["full"]["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                 "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"]},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(q, k, v, H, W, window)
+
+    out = {
+        "metric": "attention tokens/s per layer at ViT-L 4096 tokens; % of HBM or MFMA peak",
+        "value": 3 * tokens / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if c["bf16"] else "f32", "data": "synthetic",
+        "config": {"workload": f"config{args.config}: B{B} {H}x{W} grid (N={N}) heads{heads} d{d} "
+                               f"{'bf16' if c['bf16'] else 'fp32'}; step = linear + "
+                               f"window{window[0]}x{window[1]} + full attention layer",
+                   "tokens_per_layer": tokens},
+        "per_mixer": per, "roofline": roofline, "rooflines": rooflines, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(q, k, v, H, W, window):
+    """The CPU oracle as it stands on a bounded sample of the same inputs: the whole linear and
+    window layers (all images) and the full-attention layer of batch element 0."""
+    import oracle
+    B, heads, N = q.shape[0], q.shape[1], q.shape[2]
+    cores = len(os.sched_getaffinity(0))
+    t0 = time.perf_counter(); oracle.linear_attn_state(q, k, v, 1e-6); t_lin = time.perf_counter() - t0
+    t0 = time.perf_counter(); oracle.window_attn(q, k, v, H, W, *window); t_win = time.perf_counter() - t0
+    t0 = time.perf_counter(); oracle.full_attn(q[:1], k[:1], v[:1]); t_full = time.perf_counter() - t0
+    per_image = t_lin / B + t_win / B + t_full
+    return {"value": 3 * N / per_image, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"same seeded inputs: linear layer on all {B} images ({t_lin:.2f}s), window "
+                      f"layer on all {B} images ({t_win:.2f}s), full-attention layer on image 0 "
+                      f"({t_full:.2f}s); value = 3 layers x {N} tokens / time per image",
+            "tokens_per_s": {"linear": B * N / t_lin, "window": B * N / t_win, "full": N / t_full}}
+
+
+if __name__ == "__main__":
+    main()

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2605_26636_amd import binding, synth
-from parity import FP32_TOL, err_fp32, to_device, to_host
+from parity import check, FP32_TOL, err_fp32, to_device, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -25,9 +25,9 @@ def test_config1_all_three_mixers():
     c = synth.CONFIGS[1]
     q, k, v = synth.config_qkv(1)
     got = _run_all(q, k, v, c["H"], c["W"], c["window"])
-    assert err_fp32(got["linear"], oracle.linear_attn_quadratic(q, k, v, 1e-6)) <= FP32_TOL
-    assert err_fp32(got["window"], oracle.window_attn(q, k, v, c["H"], c["W"], *c["window"])) <= FP32_TOL
-    assert err_fp32(got["full"], oracle.full_attn(q, k, v)) <= FP32_TOL
+    check(err_fp32(got["linear"], oracle.linear_attn_quadratic(q, k, v, 1e-6)), FP32_TOL)
+    check(err_fp32(got["window"], oracle.window_attn(q, k, v, c["H"], c["W"], *c["window"])), FP32_TOL)
+    check(err_fp32(got["full"], oracle.full_attn(q, k, v)), FP32_TOL)
 
 
 @pytest.mark.parametrize("B,heads,H,W,window", [
@@ -42,9 +42,9 @@ def test_ragged_and_edge_shapes(B, heads, H, W, window):
     N = H * W
     q, k, v = synth.qkv(7, B, heads, N, 64, 1.0, False)
     got = _run_all(q, k, v, H, W, window)
-    assert err_fp32(got["linear"], oracle.linear_attn_quadratic(q, k, v, 1e-6)) <= FP32_TOL
-    assert err_fp32(got["window"], oracle.window_attn(q, k, v, H, W, *window)) <= FP32_TOL
-    assert err_fp32(got["full"], oracle.full_attn(q, k, v)) <= FP32_TOL
+    check(err_fp32(got["linear"], oracle.linear_attn_quadratic(q, k, v, 1e-6)), FP32_TOL)
+    check(err_fp32(got["window"], oracle.window_attn(q, k, v, H, W, *window)), FP32_TOL)
+    check(err_fp32(got["full"], oracle.full_attn(q, k, v)), FP32_TOL)
 
 
 def test_long_sequence_split_reduction_fp32():
@@ -55,7 +55,7 @@ def test_long_sequence_split_reduction_fp32():
     o = torch.empty_like(dq)
     binding.jv_linear_attn_fwd(dq, dk, dv, o, (H, W), 1e-6)
     ref, _, _ = oracle.linear_attn_state(q, k, v, 1e-6)
-    assert err_fp32(to_host(o), ref) <= FP32_TOL
+    check(err_fp32(to_host(o), ref), FP32_TOL)
 
 
 def test_strided_views_of_a_fused_qkv_buffer():
@@ -70,11 +70,11 @@ def test_strided_views_of_a_fused_qkv_buffer():
     obuf = torch.empty(B, N, heads, 64, device="cuda")
     o = obuf.permute(0, 2, 1, 3)
     binding.jv_full_attn_fwd(dq, dk, dv, o, (H, W))
-    assert err_fp32(to_host(o), oracle.full_attn(q, k, v)) <= FP32_TOL
+    check(err_fp32(to_host(o), oracle.full_attn(q, k, v)), FP32_TOL)
     binding.jv_window_attn_fwd(dq, dk, dv, o, (H, W), (4, 4))
-    assert err_fp32(to_host(o), oracle.window_attn(q, k, v, H, W, 4, 4)) <= FP32_TOL
+    check(err_fp32(to_host(o), oracle.window_attn(q, k, v, H, W, 4, 4)), FP32_TOL)
     binding.jv_linear_attn_fwd(dq, dk, dv, o, (H, W))
-    assert err_fp32(to_host(o), oracle.linear_attn_quadratic(q, k, v, 1e-6)) <= FP32_TOL
+    check(err_fp32(to_host(o), oracle.linear_attn_quadratic(q, k, v, 1e-6)), FP32_TOL)
 
 
 def test_non_default_scale_and_eps():
@@ -83,9 +83,9 @@ def test_non_default_scale_and_eps():
     dq, dk, dv = (to_device(x, False) for x in (q, k, v))
     o = torch.empty_like(dq)
     binding.jv_full_attn_fwd(dq, dk, dv, o, (H, W), scale=0.05)
-    assert err_fp32(to_host(o), oracle.full_attn(q, k, v, scale=0.05)) <= FP32_TOL
+    check(err_fp32(to_host(o), oracle.full_attn(q, k, v, scale=0.05)), FP32_TOL)
     binding.jv_linear_attn_fwd(dq, dk, dv, o, (H, W), eps=3.0)
-    assert err_fp32(to_host(o), oracle.linear_attn_quadratic(q, k, v, 3.0)) <= FP32_TOL
+    check(err_fp32(to_host(o), oracle.linear_attn_quadratic(q, k, v, 3.0)), FP32_TOL)
 
 
 def test_all_negative_queries_give_exact_zero():
@@ -119,4 +119,4 @@ def test_padding_never_reaches_the_output():
         views.append(big[i, :, :, 4:4 + N])
     o = torch.empty(B, heads, N, 64, device="cuda")
     binding.jv_window_attn_fwd(*views, o, (H, W), (4, 4))
-    assert err_fp32(to_host(o), oracle.window_attn(q, k, v, H, W, 4, 4)) <= FP32_TOL
+    check(err_fp32(to_host(o), oracle.window_attn(q, k, v, H, W, 4, 4)), FP32_TOL)
