@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="mixer workload (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--buffers", type=int, default=6, help="rotating input/output sets")
+    ap.add_argument("--only", choices=["linear", "window", "full"], default=None,
+                    help="run only this mixer's timing loop (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference point for HBM counters)")
     args = ap.parse_args()
@@ -75,6 +77,13 @@ def main():
         binding.jv_full_attn_fwd(s[0], s[1], s[2], s[3], (H, W), 0.0, stream)
 
     mixers = {"linear": linear, "window": win, "full": full}
+    if args.only:
+        fn = mixers[args.only]
+        for i in range(args.warmup + args.steps):
+            fn(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "launches": args.warmup + args.steps}))
+        return
 
     def step(i):
         s = sets[i % len(sets)]

@@ -12,8 +12,20 @@
 // same reference is used for numerator and denominator.
 #include <math.h>
 
+#include <type_traits>
+
 #include "jv_common.h"
 #include "jv_mfma.h"
+
+#ifndef JV_ATTN_NT
+#define JV_ATTN_NT 2   // blocks of 32 query columns per wavefront
+#endif
+#ifndef JV_ATTN_SKEW
+#define JV_ATTN_SKEW 0  // 1: half-step skew of the two query blocks inside a tile
+#endif
+#ifndef JV_ATTN_MINW
+#define JV_ATTN_MINW 2  // wavefronts per SIMD the register budget is sized for
+#endif
 
 namespace jv {
 
@@ -55,69 +67,96 @@ __device__ inline bf16x8 load_vt_operand(const unsigned char *tile, int key0, in
     return as_bf16x8(r);
 }
 
-// Running softmax state of one wavefront: 64 query columns (2 blocks of 32), 64 channels.
+// Running softmax state of one wavefront: NT blocks of 32 query columns, 64 channels.
+template <int NT>
 struct WaveState {
-    f32x16 acc[2][2];  // [channel block][query block]
-    float m[2], l[2];  // per query block; l is this lane's half of the keys only
+    f32x16 acc[2][NT];  // [channel block][query block]
+    float m[NT], l[NT];  // per query block; l is this lane's half of the keys only
 };
 
-__device__ inline void wave_state_init(WaveState &w) {
+template <int NT>
+__device__ inline void wave_state_init(WaveState<NT> &w) {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
             for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] = 0.f;
-    w.m[0] = w.m[1] = kMinusHuge;
-    w.l[0] = w.l[1] = 0.f;
+        w.m[nt] = kMinusHuge;
+        w.l[nt] = 0.f;
+    }
+}
+
+// Raise the softmax reference of query block nt if the (already masked) scores s exceed it
+// by more than the lazy threshold, rescaling that block's accumulators and row sum.
+template <int NT>
+__device__ inline void update_reference(WaveState<NT> &w, int nt, const f32x16 &s, float c) {
+    float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+    float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+    float t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+    float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
+    t0 = fmaxf(fmaxf(t0, t1), t2);
+    t3 = fmaxf(fmaxf(t3, t4), s[15]);
+    // This lane sees half of the tile's keys; if no lane of the wave exceeds the threshold,
+    // no query column does, and the exchange with the partner lane can be skipped.
+    const float own = fmaxf(t0, t3) * c;
+    if (__builtin_amdgcn_ballot_w64(own > w.m[nt] + kLazyRescale) != 0) {
+        float a, b;
+        pair_values(own, &a, &b);
+        const float m_new = fmaxf(w.m[nt], fmaxf(a, b));
+        const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
+        w.m[nt] = m_new;
+        w.l[nt] *= alpha;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
+    }
+}
+
+__device__ inline void add_key_bias(f32x16 &s, const float *bias, int g) {
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 bv = *(const f32x4 *)(bias + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[4 * q4 + e] += bv[e];
+    }
 }
 
 // One tile of 32 keys.  ktile/vtile point at row 0 of the tile (K rows laid out with
 // tile_off_row, V rows with tile_off_tr; both offsets take tile-relative rows, so tiles must
 // start at a multiple of 8 rows).  bias, if non-null, holds 0 / -inf per key of the tile.
-__device__ inline void attn_tile32(WaveState &w, const bf16x8 (&qreg)[2][4],
+template <int NT>
+__device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4],
                                    const unsigned char *ktile, const unsigned char *vtile,
                                    int krow0, const float *bias, float c, int lane) {
     const int g = lane >> 5, li = lane & 31;
-    f32x16 s[2];
+    f32x16 s[NT];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { s[0][v] = 0.f; s[1][v] = 0.f; }
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         const bf16x8 ka = as_bf16x8(*(const u32x4 *)(ktile + tile_off_row(krow0 + li, 2 * ks + g)));
-        s[0] = mfma32(ka, qreg[0][ks], s[0]);
-        s[1] = mfma32(ka, qreg[1][ks], s[1]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) s[nt] = mfma32(ka, qreg[nt][ks], s[nt]);
     }
     if (bias) {  // wave-uniform
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const f32x4 bv = *(const f32x4 *)(bias + 8 * q4 + 4 * g);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                s[0][4 * q4 + e] += bv[e];
-                s[1][4 * q4 + e] += bv[e];
-            }
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) s[nt][4 * q4 + e] += bv[e];
         }
     }
-    unsigned pk[2][8];
+    unsigned pk[NT][8];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        float tm = s[nt][0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) tm = fmaxf(tm, s[nt][v]);
-        float a, b;
-        pair_values(tm, &a, &b);
-        const float tmy = fmaxf(a, b) * c;
-        if (__builtin_amdgcn_ballot_w64(tmy > w.m[nt] + kLazyRescale) != 0) {
-            const float m_new = fmaxf(w.m[nt], tmy);
-            const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
-            w.m[nt] = m_new;
-            w.l[nt] *= alpha;
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
-        }
+    for (int nt = 0; nt < NT; ++nt) {
+        update_reference<NT>(w, nt, s[nt], c);
         const float neg_m = -w.m[nt];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -129,25 +168,111 @@ __device__ inline void attn_tile32(WaveState &w, const bf16x8 (&qreg)[2][4],
     }
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
-        u32x4 p0 = {pk[0][4 * kk], pk[0][4 * kk + 1], pk[0][4 * kk + 2], pk[0][4 * kk + 3]};
-        u32x4 p1 = {pk[1][4 * kk], pk[1][4 * kk + 1], pk[1][4 * kk + 2], pk[1][4 * kk + 3]};
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) {
             const bf16x8 va = load_vt_operand(vtile, krow0 + 16 * kk, mi, lane);
-            w.acc[mi][0] = mfma32(va, as_bf16x8(p0), w.acc[mi][0]);
-            w.acc[mi][1] = mfma32(va, as_bf16x8(p1), w.acc[mi][1]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
+                w.acc[mi][nt] = mfma32(va, as_bf16x8(pb), w.acc[mi][nt]);
+            }
         }
     }
 }
 
-// Normalise and store the 64 query columns of a wavefront.  `stage` is 4 KB of wave-private
+// One tile of 32 keys for two query blocks, with the two blocks half a step apart so that each
+// wavefront overlaps its own matrix and vector work: the scores of block 1 are formed while
+// block 0 is exponentiated, and the products of block 0 are added while block 1 is
+// exponentiated.  Scheduling fences pin that order.
+__device__ inline void attn_tile32_skewed(WaveState<2> &w, const bf16x8 (&qreg)[2][4],
+                                          const unsigned char *ktile, const unsigned char *vtile,
+                                          int krow0, const float *bias, float c, int lane) {
+    const int g = lane >> 5, li = lane & 31;
+    bf16x8 ka[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+        ka[ks] = as_bf16x8(*(const u32x4 *)(ktile + tile_off_row(krow0 + li, 2 * ks + g)));
+    f32x16 s0, s1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { s0[v] = 0.f; s1[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) s0 = mfma32(ka[ks], qreg[0][ks], s0);
+    if (bias) add_key_bias(s0, bias, g);  // wave-uniform
+    update_reference<2>(w, 0, s0, c);
+
+    unsigned pk0[8], pk1[8];
+    {
+        const float neg_m = -w.m[0];
+        float l = w.l[0];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            s1 = mfma32(ka[ks], qreg[1][ks], s1);
+#pragma unroll
+            for (int j = 2 * ks; j < 2 * ks + 2; ++j) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, neg_m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, neg_m));
+                pk0[j] = pack_bf16x2(p0, p1);
+                l = add_bf16x2(pk0[j], l);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        w.l[0] = l;
+    }
+    bf16x8 va[2][2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) va[kk][mi] = load_vt_operand(vtile, krow0 + 16 * kk, mi, lane);
+    if (bias) add_key_bias(s1, bias, g);
+    update_reference<2>(w, 1, s1, c);
+    {
+        const float neg_m = -w.m[1];
+        float l = w.l[1];
+#pragma unroll
+        for (int idx = 0; idx < 4; ++idx) {
+            const int kk = idx >> 1, mi = idx & 1;
+            u32x4 pb = {pk0[4 * kk], pk0[4 * kk + 1], pk0[4 * kk + 2], pk0[4 * kk + 3]};
+            w.acc[mi][0] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][0]);
+#pragma unroll
+            for (int j = 2 * idx; j < 2 * idx + 2; ++j) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, neg_m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, neg_m));
+                pk1[j] = pack_bf16x2(p0, p1);
+                l = add_bf16x2(pk1[j], l);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        w.l[1] = l;
+    }
+#pragma unroll
+    for (int idx = 0; idx < 4; ++idx) {
+        const int kk = idx >> 1, mi = idx & 1;
+        u32x4 pb = {pk1[4 * kk], pk1[4 * kk + 1], pk1[4 * kk + 2], pk1[4 * kk + 3]};
+        w.acc[mi][1] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][1]);
+    }
+}
+
+template <int NT>
+__device__ inline void attn_tile(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4],
+                                 const unsigned char *ktile, const unsigned char *vtile,
+                                 int krow0, const float *bias, float c, int lane) {
+#if JV_ATTN_SKEW
+    if constexpr (NT == 2) {
+        attn_tile32_skewed(w, qreg, ktile, vtile, krow0, bias, c, lane);
+        return;
+    }
+#endif
+    attn_tile32<NT>(w, qreg, ktile, vtile, krow0, bias, c, lane);
+}
+
+// Normalise and store the 32*NT query columns of a wavefront.  `stage` is 4 KB of wave-private
 // LDS used to turn the channel-major accumulators into token rows for 16-byte stores.
-template <bool O_BF16>
-__device__ inline void wave_store(const WaveState &w, const AttnArgs &a, int wy, int wx,
+template <bool O_BF16, int NT>
+__device__ inline void wave_store(const WaveState<NT> &w, const AttnArgs &a, int wy, int wx,
                                   int q0, long long obase, unsigned char *stage, int lane) {
     const int g = lane >> 5, li = lane & 31, lrow = lane >> 3, lchunk = lane & 7;
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NT; ++nt) {
         float lo, hi;
         pair_values(w.l[nt], &lo, &hi);
         const float inv = __builtin_amdgcn_rcpf(lo + hi);
@@ -188,11 +313,12 @@ __device__ inline void wave_store(const WaveState &w, const AttnArgs &a, int wy,
 }
 
 // Query operands (B of S^T = K Q^T): lane holds channels 16*ks + 8g .. +7 of query li.
-__device__ inline void load_queries(bf16x8 (&qreg)[2][4], const AttnArgs &a, int wy, int wx,
+template <int NT>
+__device__ inline void load_queries(bf16x8 (&qreg)[NT][4], const AttnArgs &a, int wy, int wx,
                                     int q0, long long qbase, int lane) {
     const int g = lane >> 5, li = lane & 31;
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NT; ++nt) {
         const int tok = slot_token(a, wy, wx, q0 + 32 * nt + li);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
@@ -207,47 +333,57 @@ __device__ inline void load_queries(bf16x8 (&qreg)[2][4], const AttnArgs &a, int
 
 // ---------------------------------------------------------------------------------------
 // Streaming kernel: any window size, including the whole grid (full attention).
-// A workgroup holds 256 consecutive query slots of one window (4 waves x 64) and streams the
-// window's keys through LDS in double-buffered stages of 64.
-// grid (ceil(slots/256), n_win, B*heads), 256 threads.
+// A workgroup holds 128*NT consecutive query slots of one window (4 waves x 32*NT) and streams
+// the window's keys through LDS in double-buffered stages of 64.
+// grid (ceil(slots/(128*NT)), n_win, B*heads), 256 threads.
 // ---------------------------------------------------------------------------------------
 constexpr int kStage = 64;
 constexpr int kStageBytes = 2 * kStage * 128;  // K rows then V rows
 
-template <bool O_BF16>
-__global__ void __launch_bounds__(256, 2) attn_stream_bf16(AttnArgs a) {
+template <bool O_BF16, int NT>
+__global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a) {
     __shared__ __align__(16) unsigned char smem[2 * kStageBytes];
     __shared__ __align__(16) float bias[2][kStage];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
     const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
-    const int q0 = blockIdx.x * 256 + wave * 64;
+    const int q0 = blockIdx.x * (128 * NT) + wave * (32 * NT);
     const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
     const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
     const bool wave_live = q0 < a.g.slots;
 
-    bf16x8 qreg[2][4];
-    load_queries(qreg, a, wy, wx, q0, qbase, lane);
-    WaveState w;
-    wave_state_init(w);
+    bf16x8 qreg[NT][4];
+    load_queries<NT>(qreg, a, wy, wx, q0, qbase, lane);
+    WaveState<NT> w;
+    wave_state_init<NT>(w);
 
     // Is any key slot of this window padding?  (Stages past the last slot are handled below.)
     const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
     const int n_stage = (a.g.slots + kStage - 1) / kStage;
     const int lrow = tid >> 3, lchunk = tid & 7;
+    // This thread moves rows lrow and lrow + 32 of every stage.  For windows that span whole
+    // grid rows the token is "first token + slot", so the global pointers just advance by one
+    // stage per step; otherwise the slot is mapped through the window geometry each time.
+    const __bf16 *kptr = (const __bf16 *)a.k.ptr + kbase + lchunk * 8;
+    const __bf16 *vptr = (const __bf16 *)a.v.ptr + vbase + lchunk * 8;
+    const int tok_first = wy * a.g.wh * a.g.W, n_tok = a.g.H * a.g.W;
+    const int tok_limit = min(a.g.slots, n_tok - tok_first);  // contiguous case: live slots
     u32x4 kreg[2], vreg[2];
     bool live[2];
     auto fetch = [&](int stage) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int tok = slot_token(a, wy, wx, stage * kStage + lrow + 32 * i);
+            const int slot = stage * kStage + lrow + 32 * i;
+            int tok;
+            if (a.contig) tok = slot < tok_limit ? tok_first + slot : -1;
+            else tok = slot_token(a, wy, wx, slot);
             u32x4 zero = {0u, 0u, 0u, 0u};
             kreg[i] = zero;
             vreg[i] = zero;
             live[i] = tok >= 0;
             if (tok >= 0) {
-                kreg[i] = *(const u32x4 *)((const __bf16 *)a.k.ptr + kbase + (long long)tok * a.k.sn + lchunk * 8);
-                vreg[i] = *(const u32x4 *)((const __bf16 *)a.v.ptr + vbase + (long long)tok * a.v.sn + lchunk * 8);
+                kreg[i] = *(const u32x4 *)(kptr + (long long)tok * a.k.sn);
+                vreg[i] = *(const u32x4 *)(vptr + (long long)tok * a.v.sn);
             }
         }
     };
@@ -261,12 +397,10 @@ __global__ void __launch_bounds__(256, 2) attn_stream_bf16(AttnArgs a) {
             if (lchunk == 0) bias[buf][row] = live[i] ? 0.f : -INFINITY;
         }
     };
-
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int st = 0; st < n_stage; ++st) {
-        const int buf = st & 1;
+    // One stage: prefetch the next one, run the two tiles of this one, publish the next one.
+    // `buf` is a compile-time constant so that every LDS offset folds into the instruction.
+    auto run_stage = [&](int st, auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
         const bool more = st + 1 < n_stage;
         if (more) fetch(st + 1);
         if (wave_live) {
@@ -274,13 +408,21 @@ __global__ void __launch_bounds__(256, 2) attn_stream_bf16(AttnArgs a) {
             const bool masked = ragged || (st + 1) * kStage > a.g.slots;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
-                attn_tile32(w, qreg, kt, vt, 32 * sub, masked ? &bias[buf][32 * sub] : nullptr,
-                            a.c, lane);
+                attn_tile<NT>(w, qreg, kt, vt, 32 * sub, masked ? &bias[buf][32 * sub] : nullptr,
+                              a.c, lane);
         }
         if (more) stash(buf ^ 1);
         __syncthreads();
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int st = 0; st < n_stage; st += 2) {
+        run_stage(st, std::integral_constant<int, 0>());
+        if (st + 1 < n_stage) run_stage(st + 1, std::integral_constant<int, 1>());
     }
-    if (wave_live) wave_store<O_BF16>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
+    if (wave_live) wave_store<O_BF16, NT>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
 }
 
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStream_t stream) {
@@ -291,11 +433,12 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStre
     a.contig = g.ww == g.W ? 1 : 0;
     a.c = scale * kLog2e;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
-    dim3 grid((g.slots + 255) / 256, g.n_win, pr.B * pr.heads);
+    constexpr int NT = JV_ATTN_NT;
+    dim3 grid((g.slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
     if (pr.o_bf16)
-        hipLaunchKernelGGL(attn_stream_bf16<true>, grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_stream_bf16<true, NT>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL(attn_stream_bf16<false>, grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_stream_bf16<false, NT>), grid, dim3(256), 0, stream, a);
     return launch_status("attn_stream_bf16");
 }
 
