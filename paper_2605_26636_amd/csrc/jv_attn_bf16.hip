@@ -425,6 +425,111 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
     if (wave_live) wave_store<O_BF16, NT>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
 }
 
+// ---------------------------------------------------------------------------------------
+// Window-resident kernel: windows of at most 64*WPW slots (WPW = wavefronts per window).
+// All keys and values of a window are brought into LDS once, then every wavefront runs its 64
+// query slots over the resident tiles with no further synchronisation.  WPW = 4: one
+// workgroup per window (e.g. 16x16 windows); WPW = 1: one wavefront per window, four windows
+// per workgroup (e.g. 8x8 windows).  Window attention moves 4 rows of 128 bytes per token and
+// does little arithmetic on them, so the point of this kernel is to have many bytes in flight:
+// 96 KB of loads per 256 query slots are issued up front.
+// grid (ceil(n_win * WPW / 4), B*heads), 256 threads, kWindowLds bytes of dynamic LDS.
+// ---------------------------------------------------------------------------------------
+constexpr int kWindowLds = 4 * (2 * 64 * 128 + 64 * 4);
+
+template <bool O_BF16, int WPW>
+__global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
+    extern __shared__ __align__(16) unsigned char wsm[];
+    constexpr int R = 64 * WPW;  // LDS rows per window
+    constexpr int T = 64 * WPW;  // threads that load one window
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int bh = blockIdx.y, b = bh / a.heads, h = bh % a.heads;
+    const int win = WPW == 4 ? blockIdx.x : blockIdx.x * 4 + wave;
+    const bool win_live = win < a.g.n_win;  // WPW == 1: the last workgroup may have idle waves
+    const int wy = win_live ? win / a.g.wins_x : 0, wx = win_live ? win % a.g.wins_x : 0;
+    unsigned char *ktile = wsm + (WPW == 4 ? 0 : wave * (2 * 64 * 128));
+    unsigned char *vtile = ktile + R * 128;
+    float *bias = (float *)(wsm + 4 * 2 * 64 * 128) + (WPW == 4 ? 0 : wave * 64);
+    const int t = WPW == 4 ? tid : lane;
+    const int q0 = WPW == 4 ? wave * 64 : 0;
+    const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
+    const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
+    const int n_tile = (a.g.slots + 31) >> 5;
+    const bool wave_live = win_live && q0 < a.g.slots;
+
+    bf16x8 qreg[2][4];
+    if (wave_live) load_queries<2>(qreg, a, wy, wx, q0, qbase, lane);
+
+    if (win_live) {
+        const int lchunk = t & 7;
+        const __bf16 *kptr = (const __bf16 *)a.k.ptr + kbase + lchunk * 8;
+        const __bf16 *vptr = (const __bf16 *)a.v.ptr + vbase + lchunk * 8;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            u32x4 kreg[4], vreg[4];
+            bool live[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (4 * half + i) * (T / 8) + (t >> 3);
+                const int tok = row < 32 * n_tile ? slot_token(a, wy, wx, row) : -1;
+                u32x4 zero = {0u, 0u, 0u, 0u};
+                kreg[i] = zero;
+                vreg[i] = zero;
+                live[i] = tok >= 0;
+                if (tok >= 0) {
+                    kreg[i] = *(const u32x4 *)(kptr + (long long)tok * a.k.sn);
+                    vreg[i] = *(const u32x4 *)(vptr + (long long)tok * a.v.sn);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (4 * half + i) * (T / 8) + (t >> 3);
+                if (row < 32 * n_tile) {
+                    *(u32x4 *)(ktile + tile_off_row(row, lchunk)) = kreg[i];
+                    *(u32x4 *)(vtile + tile_off_tr(row, lchunk)) = vreg[i];
+                    if (lchunk == 0) bias[row] = live[i] ? 0.f : -INFINITY;
+                }
+            }
+        }
+    }
+    if (WPW == 4) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
+
+    WaveState<2> w;
+    wave_state_init<2>(w);
+    if (wave_live) {
+        const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
+        for (int tile = 0; tile < n_tile; ++tile) {
+            const bool masked = ragged || 32 * (tile + 1) > a.g.slots;
+            attn_tile<2>(w, qreg, ktile, vtile, 32 * tile, masked ? bias + 32 * tile : nullptr, a.c,
+                         lane);
+        }
+    }
+    if (WPW == 4) __syncthreads();  // all waves are done with the tiles: reuse them as staging
+    else __builtin_amdgcn_wave_barrier();
+    if (wave_live)
+        wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, ktile + (WPW == 4 ? wave * 4096 : 0), lane);
+}
+
+static jv_status set_lds_limit(const void *fn, int bytes) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    return JV_OK;
+}
+
+template <bool O_BF16, int WPW>
+static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        jv_status st = set_lds_limit((const void *)attn_window_bf16<O_BF16, WPW>, kWindowLds);
+        if (st != JV_OK) return st;
+        attr_set = true;
+    }
+    dim3 grid((a.g.n_win * WPW + 3) / 4, BH);
+    hipLaunchKernelGGL((attn_window_bf16<O_BF16, WPW>), grid, dim3(256), kWindowLds, stream, a);
+    return launch_status("attn_window_bf16");
+}
+
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStream_t stream) {
     AttnArgs a;
     a.q = pr.q; a.k = pr.k; a.v = pr.v; a.o = pr.o;
@@ -433,6 +538,13 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStre
     a.contig = g.ww == g.W ? 1 : 0;
     a.c = scale * kLog2e;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
+    // Windows that fit in LDS whole take the window-resident kernel.
+    if (g.slots <= 64)
+        return pr.o_bf16 ? launch_window<true, 1>(a, pr.B * pr.heads, stream)
+                         : launch_window<false, 1>(a, pr.B * pr.heads, stream);
+    if (g.slots <= 256 && g.n_win > 1)
+        return pr.o_bf16 ? launch_window<true, 4>(a, pr.B * pr.heads, stream)
+                         : launch_window<false, 4>(a, pr.B * pr.heads, stream);
     constexpr int NT = JV_ATTN_NT;
     dim3 grid((g.slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
     if (pr.o_bf16)

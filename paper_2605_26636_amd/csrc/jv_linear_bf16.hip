@@ -160,15 +160,35 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
     int t = n0 + wave * 64;
     if (t < n1) fetch(t);
 
-    const float *src = states + (size_t)bh * kStateFloats;
-    for (int e = tid; e < kStateFloats; e += 256) {
-        float s = 0.f;
-        for (int p = 0; p < n_part; ++p) s += src[(size_t)p * part_stride + e];
-        if (e < kHeadDim * kHeadDim) {
-            const int c2 = e >> 6, c1 = e & 63;
-            St[c2 * 64 + ((((c1 >> 3) ^ (c2 & 7)) << 3) | (c1 & 7))] = s;
-        } else {
-            zs[e - kHeadDim * kHeadDim] = s;
+    // Sum the partial states: 16-byte loads, all of them issued before the first use.
+    {
+        const f32x4 *src = (const f32x4 *)(states + (size_t)bh * kStateFloats);
+        const long long stride4 = part_stride / 4;
+        constexpr int kVec = kStateFloats / 4, kIter = (kVec + 255) / 256;
+        f32x4 part[kIter][4];
+#pragma unroll
+        for (int it = 0; it < kIter; ++it)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int e4 = it * 256 + tid;
+                f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                part[it][p] = (e4 < kVec && p < n_part) ? src[p * stride4 + e4] : zero;
+            }
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int e4 = it * 256 + tid;
+            if (e4 >= kVec) break;
+            f32x4 sum = part[it][0];
+            for (int p = 4; p < n_part; ++p) sum += src[p * stride4 + e4];  // more than 4: rare
+#pragma unroll
+            for (int p = 1; p < 4; ++p) sum += part[it][p];
+            const int e = 4 * e4;
+            if (e < kHeadDim * kHeadDim) {
+                const int c2 = e >> 6, c1 = e & 63;  // 4 consecutive c1 stay inside one group
+                *(f32x4 *)(St + c2 * 64 + ((((c1 >> 3) ^ (c2 & 7)) << 3) | (c1 & 7))) = sum;
+            } else {
+                *(f32x4 *)(zs + e - kHeadDim * kHeadDim) = sum;
+            }
         }
     }
     __syncthreads();
