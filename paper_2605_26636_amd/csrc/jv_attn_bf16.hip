@@ -7,9 +7,10 @@
 // with lane^32), and the exponentiated tile, rounded to bf16, is already laid out as the B
 // operand of O^T += V_tile^T P^T.  K tiles are read from LDS row by row (A operand of the
 // first product); V tiles are read with transposing LDS reads (A operand of the second).
-// The running maximum is only raised when a tile exceeds it by more than 2^8, which keeps the
-// rescaling of the accumulators off the common path; the result is unchanged because the
-// same reference is used for numerator and denominator.
+// The softmax reference (running maximum) is only raised when a tile's probabilities against
+// the current reference come out large (lane sum above 2^8); the common path has no maximum
+// search and no rescaling of the accumulators.  The result is unchanged because numerator and
+// denominator always use the same reference.
 #include <math.h>
 
 #include <type_traits>
@@ -19,9 +20,6 @@
 
 #ifndef JV_ATTN_NT
 #define JV_ATTN_NT 2   // blocks of 32 query columns per wavefront
-#endif
-#ifndef JV_ATTN_SKEW
-#define JV_ATTN_SKEW 0  // 1: half-step skew of the two query blocks inside a tile
 #endif
 #ifndef JV_ATTN_MINW
 #define JV_ATTN_MINW 2  // wavefronts per SIMD the register budget is sized for
@@ -38,7 +36,7 @@ struct AttnArgs {
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLazyRescale = 8.0f;   // log2 units
+constexpr float kLazySum = 256.0f;     // largest lane sum of a tile taken without a max pass
 constexpr float kMinusHuge = -1.0e30f; // finite stand-in for "no maximum yet"
 
 // slot of window (wy, wx) -> token index, or -1 for padding / past the window.
@@ -87,10 +85,10 @@ __device__ inline void wave_state_init(WaveState<NT> &w) {
     }
 }
 
-// Raise the softmax reference of query block nt if the (already masked) scores s exceed it
-// by more than the lazy threshold, rescaling that block's accumulators and row sum.
+// Slow path of the running softmax: find the exact maximum of the (already masked) scores s of
+// query block nt, raise the reference to it and rescale that block's accumulators and row sum.
 template <int NT>
-__device__ inline void update_reference(WaveState<NT> &w, int nt, const f32x16 &s, float c) {
+__device__ inline void raise_reference(WaveState<NT> &w, int nt, const f32x16 &s, float c) {
     float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
     float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
     float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
@@ -98,21 +96,33 @@ __device__ inline void update_reference(WaveState<NT> &w, int nt, const f32x16 &
     float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
     t0 = fmaxf(fmaxf(t0, t1), t2);
     t3 = fmaxf(fmaxf(t3, t4), s[15]);
-    // This lane sees half of the tile's keys; if no lane of the wave exceeds the threshold,
-    // no query column does, and the exchange with the partner lane can be skipped.
-    const float own = fmaxf(t0, t3) * c;
-    if (__builtin_amdgcn_ballot_w64(own > w.m[nt] + kLazyRescale) != 0) {
-        float a, b;
-        pair_values(own, &a, &b);
-        const float m_new = fmaxf(w.m[nt], fmaxf(a, b));
-        const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
-        w.m[nt] = m_new;
-        w.l[nt] *= alpha;
+    float a, b;
+    pair_values(fmaxf(t0, t3) * c, &a, &b);  // this lane and lane^32 share the query column
+    const float m_new = fmaxf(w.m[nt], fmaxf(a, b));
+    const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
+    w.m[nt] = m_new;
+    w.l[nt] *= alpha;
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
+        for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
+}
+
+// Probabilities of one query block's tile against the current reference: rounded to bf16 and
+// packed in score-register order; returns this lane's sum (fp32, before rounding).
+// (Plain adds on purpose: the dot-product instructions share the matrix pipeline and would
+// keep the matrix instructions of the other wavefront from running alongside.)
+__device__ inline float exp_block(const f32x16 &s, unsigned (&pk)[8], float c, float neg_m) {
+    float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[2 * j], c, neg_m));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[2 * j + 1], c, neg_m));
+        pk[j] = pack_bf16x2(p0, p1);
+        sum0 += p0;
+        sum1 += p1;
     }
+    return sum0 + sum1;
 }
 
 __device__ inline void add_key_bias(f32x16 &s, const float *bias, int g) {
@@ -124,145 +134,72 @@ __device__ inline void add_key_bias(f32x16 &s, const float *bias, int g) {
     }
 }
 
-// One tile of 32 keys.  ktile/vtile point at row 0 of the tile (K rows laid out with
-// tile_off_row, V rows with tile_off_tr; both offsets take tile-relative rows, so tiles must
-// start at a multiple of 8 rows).  bias, if non-null, holds 0 / -inf per key of the tile.
-template <int NT>
-__device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4],
-                                   const unsigned char *ktile, const unsigned char *vtile,
-                                   int krow0, const float *bias, float c, int lane) {
+// K operands of one tile of 32 keys (A of S^T = K Q^T): lane holds channels 16*ks + 8g .. +7
+// of key row krow0 + lane%32.
+__device__ inline void load_k_operands(bf16x8 (&ka)[4], const unsigned char *kstage, int krow0,
+                                       int lane) {
     const int g = lane >> 5, li = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+        ka[ks] = as_bf16x8(*(const u32x4 *)(kstage + tile_off_row(krow0 + li, 2 * ks + g)));
+}
+
+// One tile of 32 keys.  kstage/vstage point at row 0 of an LDS stage (K rows laid out with
+// tile_off_row, V rows with tile_off_tr), the tile starts at row krow0 (a multiple of 32).
+// `ka` holds this tile's K operands on entry; if k_next is non-null the K operands of the tile
+// at (k_next, krow_next) are read into it as soon as the scores are issued, so that their LDS
+// latency hides behind the exponentials.  The V operands are read before the scores for the
+// same reason.  bias, if non-null, holds 0 / -inf per key of the tile.
+template <int NT>
+__device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4], bf16x8 (&ka)[4],
+                                   const unsigned char *k_next, int krow_next,
+                                   const unsigned char *vstage, int krow0, const float *bias,
+                                   float c, int lane) {
+    const int g = lane >> 5;
+    bf16x8 va[2][2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) va[kk][mi] = load_vt_operand(vstage, krow0 + 16 * kk, mi, lane);
     f32x16 s[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 ka = as_bf16x8(*(const u32x4 *)(ktile + tile_off_row(krow0 + li, 2 * ks + g)));
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) s[nt] = mfma32(ka, qreg[nt][ks], s[nt]);
-    }
+        for (int nt = 0; nt < NT; ++nt) s[nt] = mfma32(ka[ks], qreg[nt][ks], s[nt]);
+    if (k_next) load_k_operands(ka, k_next, krow_next, lane);  // wave-uniform
     if (bias) {  // wave-uniform
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4 bv = *(const f32x4 *)(bias + 8 * q4 + 4 * g);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) s[nt][4 * q4 + e] += bv[e];
-        }
+        for (int nt = 0; nt < NT; ++nt) add_key_bias(s[nt], bias, g);
     }
+    // Exponentiate against the current reference first; the tile sum tells whether that was
+    // safe.  A lane sum of at most 2^8 means every probability is at most 2^8 (the reference
+    // is at most 8 binary orders stale), which neither overflows nor costs precision.  Larger
+    // sums (or the infinities of the very first tile) take the slow path: raise the reference
+    // to the exact maximum and redo the block.  Numerator and denominator always share one
+    // reference, so the result does not depend on which path ran.
     unsigned pk[NT][8];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        update_reference<NT>(w, nt, s[nt], c);
-        const float neg_m = -w.m[nt];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[nt][2 * j], c, neg_m));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[nt][2 * j + 1], c, neg_m));
-            pk[nt][j] = pack_bf16x2(p0, p1);
-            w.l[nt] = add_bf16x2(pk[nt][j], w.l[nt]);
+        float tile_sum = exp_block(s[nt], pk[nt], c, -w.m[nt]);
+        if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kLazySum)) != 0) {  // also catches inf/NaN
+            raise_reference<NT>(w, nt, s[nt], c);
+            tile_sum = exp_block(s[nt], pk[nt], c, -w.m[nt]);
         }
+        w.l[nt] += tile_sum;
     }
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-            const bf16x8 va = load_vt_operand(vtile, krow0 + 16 * kk, mi, lane);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
-                w.acc[mi][nt] = mfma32(va, as_bf16x8(pb), w.acc[mi][nt]);
-            }
-        }
-    }
-}
-
-// One tile of 32 keys for two query blocks, with the two blocks half a step apart so that each
-// wavefront overlaps its own matrix and vector work: the scores of block 1 are formed while
-// block 0 is exponentiated, and the products of block 0 are added while block 1 is
-// exponentiated.  Scheduling fences pin that order.
-__device__ inline void attn_tile32_skewed(WaveState<2> &w, const bf16x8 (&qreg)[2][4],
-                                          const unsigned char *ktile, const unsigned char *vtile,
-                                          int krow0, const float *bias, float c, int lane) {
-    const int g = lane >> 5, li = lane & 31;
-    bf16x8 ka[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-        ka[ks] = as_bf16x8(*(const u32x4 *)(ktile + tile_off_row(krow0 + li, 2 * ks + g)));
-    f32x16 s0, s1;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { s0[v] = 0.f; s1[v] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) s0 = mfma32(ka[ks], qreg[0][ks], s0);
-    if (bias) add_key_bias(s0, bias, g);  // wave-uniform
-    update_reference<2>(w, 0, s0, c);
-
-    unsigned pk0[8], pk1[8];
-    {
-        const float neg_m = -w.m[0];
-        float l = w.l[0];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            s1 = mfma32(ka[ks], qreg[1][ks], s1);
-#pragma unroll
-            for (int j = 2 * ks; j < 2 * ks + 2; ++j) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, neg_m));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, neg_m));
-                pk0[j] = pack_bf16x2(p0, p1);
-                l = add_bf16x2(pk0[j], l);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        w.l[0] = l;
-    }
-    bf16x8 va[2][2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) va[kk][mi] = load_vt_operand(vtile, krow0 + 16 * kk, mi, lane);
-    if (bias) add_key_bias(s1, bias, g);
-    update_reference<2>(w, 1, s1, c);
-    {
-        const float neg_m = -w.m[1];
-        float l = w.l[1];
+        for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int idx = 0; idx < 4; ++idx) {
-            const int kk = idx >> 1, mi = idx & 1;
-            u32x4 pb = {pk0[4 * kk], pk0[4 * kk + 1], pk0[4 * kk + 2], pk0[4 * kk + 3]};
-            w.acc[mi][0] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][0]);
-#pragma unroll
-            for (int j = 2 * idx; j < 2 * idx + 2; ++j) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, neg_m));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, neg_m));
-                pk1[j] = pack_bf16x2(p0, p1);
-                l = add_bf16x2(pk1[j], l);
+            for (int nt = 0; nt < NT; ++nt) {
+                u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
+                w.acc[mi][nt] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][nt]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        w.l[1] = l;
-    }
-#pragma unroll
-    for (int idx = 0; idx < 4; ++idx) {
-        const int kk = idx >> 1, mi = idx & 1;
-        u32x4 pb = {pk1[4 * kk], pk1[4 * kk + 1], pk1[4 * kk + 2], pk1[4 * kk + 3]};
-        w.acc[mi][1] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][1]);
-    }
-}
-
-template <int NT>
-__device__ inline void attn_tile(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4],
-                                 const unsigned char *ktile, const unsigned char *vtile,
-                                 int krow0, const float *bias, float c, int lane) {
-#if JV_ATTN_SKEW
-    if constexpr (NT == 2) {
-        attn_tile32_skewed(w, qreg, ktile, vtile, krow0, bias, c, lane);
-        return;
-    }
-#endif
-    attn_tile32<NT>(w, qreg, ktile, vtile, krow0, bias, c, lane);
 }
 
 // Normalise and store the 32*NT query columns of a wavefront.  `stage` is 4 KB of wave-private
@@ -340,7 +277,7 @@ __device__ inline void load_queries(bf16x8 (&qreg)[NT][4], const AttnArgs &a, in
 constexpr int kStage = 64;
 constexpr int kStageBytes = 2 * kStage * 128;  // K rows then V rows
 
-template <bool O_BF16, int NT>
+template <bool O_BF16, int NT, bool FAST>
 __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a) {
     __shared__ __align__(16) unsigned char smem[2 * kStageBytes];
     __shared__ __align__(16) float bias[2][kStage];
@@ -361,29 +298,40 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
     const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
     const int n_stage = (a.g.slots + kStage - 1) / kStage;
     const int lrow = tid >> 3, lchunk = tid & 7;
-    // This thread moves rows lrow and lrow + 32 of every stage.  For windows that span whole
-    // grid rows the token is "first token + slot", so the global pointers just advance by one
-    // stage per step; otherwise the slot is mapped through the window geometry each time.
-    const __bf16 *kptr = (const __bf16 *)a.k.ptr + kbase + lchunk * 8;
-    const __bf16 *vptr = (const __bf16 *)a.v.ptr + vbase + lchunk * 8;
+    // This thread moves rows lrow and lrow + 32 of every stage.  FAST: the window spans whole
+    // grid rows (token = first token + slot) and every byte offset inside one (batch, head)
+    // slice fits in 32 bits, so a row's address is a uniform base plus a per-thread constant
+    // plus a per-stage uniform step.  Otherwise the slot goes through the window geometry.
+    const char *kbytes = (const char *)((const __bf16 *)a.k.ptr + kbase);
+    const char *vbytes = (const char *)((const __bf16 *)a.v.ptr + vbase);
     const int tok_first = wy * a.g.wh * a.g.W, n_tok = a.g.H * a.g.W;
-    const int tok_limit = min(a.g.slots, n_tok - tok_first);  // contiguous case: live slots
+    const int tok_limit = min(a.g.slots, n_tok - tok_first);  // FAST: number of live slots
+    unsigned krow_off[2], vrow_off[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        krow_off[i] = 2u * ((unsigned)(tok_first + lrow + 32 * i) * (unsigned)a.k.sn + lchunk * 8);
+        vrow_off[i] = 2u * ((unsigned)(tok_first + lrow + 32 * i) * (unsigned)a.v.sn + lchunk * 8);
+    }
+    const unsigned kstep = 2u * kStage * (unsigned)a.k.sn, vstep = 2u * kStage * (unsigned)a.v.sn;
     u32x4 kreg[2], vreg[2];
     bool live[2];
     auto fetch = [&](int stage) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int slot = stage * kStage + lrow + 32 * i;
-            int tok;
-            if (a.contig) tok = slot < tok_limit ? tok_first + slot : -1;
-            else tok = slot_token(a, wy, wx, slot);
-            u32x4 zero = {0u, 0u, 0u, 0u};
-            kreg[i] = zero;
-            vreg[i] = zero;
-            live[i] = tok >= 0;
-            if (tok >= 0) {
-                kreg[i] = *(const u32x4 *)(kptr + (long long)tok * a.k.sn);
-                vreg[i] = *(const u32x4 *)(vptr + (long long)tok * a.v.sn);
+            if (FAST) {
+                live[i] = slot < tok_limit;
+                if (live[i]) {
+                    kreg[i] = *(const u32x4 *)(kbytes + (krow_off[i] + stage * kstep));
+                    vreg[i] = *(const u32x4 *)(vbytes + (vrow_off[i] + stage * vstep));
+                }
+            } else {
+                const int tok = slot_token(a, wy, wx, slot);
+                live[i] = tok >= 0;
+                if (live[i]) {
+                    kreg[i] = *(const u32x4 *)(kbytes + 2 * ((long long)tok * a.k.sn + lchunk * 8));
+                    vreg[i] = *(const u32x4 *)(vbytes + 2 * ((long long)tok * a.v.sn + lchunk * 8));
+                }
             }
         }
     };
@@ -392,6 +340,11 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = lrow + 32 * i;
+            if (!live[i]) {  // padding rows are zero in LDS and carry a -inf bias
+                u32x4 zero = {0u, 0u, 0u, 0u};
+                kreg[i] = zero;
+                vreg[i] = zero;
+            }
             *(u32x4 *)(kt + tile_off_row(row, lchunk)) = kreg[i];
             *(u32x4 *)(vt + tile_off_tr(row, lchunk)) = vreg[i];
             if (lchunk == 0) bias[buf][row] = live[i] ? 0.f : -INFINITY;
@@ -406,10 +359,11 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
         if (wave_live) {
             const unsigned char *kt = smem + buf * kStageBytes, *vt = kt + kStage * 128;
             const bool masked = ragged || (st + 1) * kStage > a.g.slots;
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-                attn_tile<NT>(w, qreg, kt, vt, 32 * sub, masked ? &bias[buf][32 * sub] : nullptr,
-                              a.c, lane);
+            bf16x8 ka[4];
+            load_k_operands(ka, kt, 0, lane);
+            attn_tile32<NT>(w, qreg, ka, kt, 32, vt, 0, masked ? &bias[buf][0] : nullptr, a.c, lane);
+            attn_tile32<NT>(w, qreg, ka, nullptr, 0, vt, 32, masked ? &bias[buf][32] : nullptr, a.c,
+                            lane);
         }
         if (more) stash(buf ^ 1);
         __syncthreads();
@@ -499,10 +453,12 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     wave_state_init<2>(w);
     if (wave_live) {
         const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
+        bf16x8 ka[4];
+        load_k_operands(ka, ktile, 0, lane);
         for (int tile = 0; tile < n_tile; ++tile) {
             const bool masked = ragged || 32 * (tile + 1) > a.g.slots;
-            attn_tile<2>(w, qreg, ktile, vtile, 32 * tile, masked ? bias + 32 * tile : nullptr, a.c,
-                         lane);
+            attn_tile32<2>(w, qreg, ka, tile + 1 < n_tile ? ktile : nullptr, 32 * (tile + 1), vtile,
+                           32 * tile, masked ? bias + 32 * tile : nullptr, a.c, lane);
         }
     }
     if (WPW == 4) __syncthreads();  // all waves are done with the tiles: reuse them as staging
@@ -547,10 +503,17 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStre
                          : launch_window<false, 4>(a, pr.B * pr.heads, stream);
     constexpr int NT = JV_ATTN_NT;
     dim3 grid((g.slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
-    if (pr.o_bf16)
-        hipLaunchKernelGGL((attn_stream_bf16<true, NT>), grid, dim3(256), 0, stream, a);
+    // 32-bit byte offsets inside one (batch, head) slice?
+    const long long max_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
+    const bool fast = a.contig && ((long long)pr.N + 2 * kStage) * max_sn * 2 + 256 < (1ll << 31);
+    if (pr.o_bf16 && fast)
+        hipLaunchKernelGGL((attn_stream_bf16<true, NT, true>), grid, dim3(256), 0, stream, a);
+    else if (pr.o_bf16)
+        hipLaunchKernelGGL((attn_stream_bf16<true, NT, false>), grid, dim3(256), 0, stream, a);
+    else if (fast)
+        hipLaunchKernelGGL((attn_stream_bf16<false, NT, true>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((attn_stream_bf16<false, NT>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_stream_bf16<false, NT, false>), grid, dim3(256), 0, stream, a);
     return launch_status("attn_stream_bf16");
 }
 
