@@ -102,10 +102,19 @@ __device__ inline void raise_reference(WaveState<NT> &w, int nt, const f32x16 &s
     const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
     w.m[nt] = m_new;
     w.l[nt] *= alpha;
+    // Multiply in place, register by register: written as an opaque instruction so that the
+    // common path (no rescaling) needs no register copies where the two paths meet.  alpha
+    // comes out of a transcendental instruction, whose result may not be read by the very
+    // next vector instruction; the compiler does not pad inline assembly, so pad here.
+    asm volatile("s_nop 1" ::"v"(alpha));
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
+        for (int v = 0; v < 16; ++v) {
+            float x = w.acc[mi][nt][v];
+            asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x) : "v"(alpha));
+            w.acc[mi][nt][v] = x;
+        }
 }
 
 // Probabilities of one query block's tile against the current reference: rounded to bf16 and
