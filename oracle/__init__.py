@@ -174,3 +174,118 @@ def linear_attn_state(q, k, v, eps=1e-6):
                                        z.ctypes.data_as(ctypes.c_void_p), B, h, N, d,
                                        ctypes.c_double(eps)), "linear_attn_state")
     return o, S, z
+
+
+# ---------------------------------------------------------------------------
+# Encoder pieces and the depth-wise-convolution branch of the linear block
+# ---------------------------------------------------------------------------
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def layernorm(x, gamma, beta, eps=1e-6):
+    """LayerNorm over the last axis (population variance); x float64 [..., C]."""
+    x, xp = _f64(x)
+    C = x.shape[-1]
+    gamma, gp = _f32(gamma); beta, bp = _f32(beta)
+    y = np.empty_like(x)
+    _check(lib().jvo_layernorm(xp, gp, bp, y.ctypes.data_as(ctypes.c_void_p),
+                               ctypes.c_int64(x.size // C), C, ctypes.c_double(eps)), "layernorm")
+    return y
+
+
+def linear(a, w, b=None):
+    """y = a W^T + b with a float64 [..., K], W float32 [N, K], b float32 [N] or None."""
+    a, ap = _f64(a)
+    w, wp = _f32(w)
+    N, K = w.shape
+    if a.shape[-1] != K:
+        raise ValueError("inner dimensions differ")
+    bp = None
+    if b is not None:
+        b, bp = _f32(b)
+    y = np.empty(a.shape[:-1] + (N,), dtype=np.float64)
+    _check(lib().jvo_linear(ap, wp, bp, y.ctypes.data_as(ctypes.c_void_p),
+                            ctypes.c_int64(a.size // K), N, K), "linear")
+    return y
+
+
+def gelu(x):
+    """Exact (erf) GELU; returns a new float64 array."""
+    y = np.array(x, dtype=np.float64, order="C", copy=True)
+    _check(lib().jvo_gelu(y.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(y.size)), "gelu")
+    return y
+
+
+def dwc(v, kernel, H, W):
+    """Depth-wise k x k cross-correlation of V [B, heads, H*W, d] with kernel [1 or B, C, k, k]."""
+    v, vp = _f32(v)
+    B, h, N, d = v.shape
+    kernel, kp = _f64(kernel)
+    kb, C, k, k2 = kernel.shape
+    if N != H * W or C != h * d or k != k2:
+        raise ValueError("shape mismatch")
+    out = np.empty(v.shape, dtype=np.float64)
+    _check(lib().jvo_dwc(vp, kp, out.ctypes.data_as(ctypes.c_void_p), B, h, H, W, d, k, kb), "dwc")
+    return out
+
+
+def squeeze_kernel(v, w1, b1, w2, b2, k):
+    """Per-image depth-wise kernels [B, C, k, k] generated from mean_n V by Linear-SiLU-Linear."""
+    v, vp = _f32(v)
+    B, h, N, d = v.shape
+    w1, w1p = _f32(w1); b1, b1p = _f32(b1); w2, w2p = _f32(w2); b2, b2p = _f32(b2)
+    hidden, C = w1.shape
+    if C != h * d or w2.shape != (C * k * k, hidden):
+        raise ValueError("shape mismatch")
+    kappa = np.empty((B, C, k, k), dtype=np.float64)
+    _check(lib().jvo_squeeze_kernel(vp, w1p, b1p, w2p, b2p, kappa.ctypes.data_as(ctypes.c_void_p),
+                                    B, h, N, d, k, hidden), "squeeze_kernel")
+    return kappa
+
+
+def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksize=3):
+    """The paper's linear-attention block output, Eq. 4: normalised ReLU linear attention plus
+    DWC(V).  static_kernel: [C, k, k]; squeeze: (w1, b1, w2, b2) for the dynamic kernel."""
+    o = linear_attn_quadratic(q, k, v, eps)
+    if static_kernel is not None:
+        o = o + dwc(v, np.asarray(static_kernel, dtype=np.float64)[None], H, W)
+    if squeeze is not None:
+        o = o + dwc(v, squeeze_kernel(v, *squeeze, ksize), H, W)
+    return o
+
+
+MIX_LINEAR, MIX_WINDOW, MIX_FULL = 0, 1, 2
+
+
+def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
+    """One pre-LN block:  x += W_O mix(split_heads(W_qkv LN(x))) + b_O;  x += MLP(LN(x)).
+    x float64 [B, N, C]; wts: dict of float32 arrays (ln1_g, ln1_b, w_qkv [3C, C], b_qkv, w_o,
+    b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2).  Q, K, V reach the mixer routines as
+    float32 (their input type): a 2^-24 rounding, far below every tolerance used."""
+    B, N, C = x.shape
+    d = C // heads
+    a = layernorm(x, wts["ln1_g"], wts["ln1_b"], ln_eps)
+    qkv = linear(a, wts["w_qkv"], wts["b_qkv"]).reshape(B, N, 3, heads, d)
+    q, k, v = (np.ascontiguousarray(qkv[:, :, i].transpose(0, 2, 1, 3)).astype(np.float32)
+               for i in range(3))
+    if mixer == MIX_LINEAR:
+        o = linear_attn_quadratic(q, k, v, la_eps)
+    elif mixer == MIX_WINDOW:
+        o = window_attn(q, k, v, H, W, window[0], window[1])
+    else:
+        o = full_attn(q, k, v)
+    o = o.transpose(0, 2, 1, 3).reshape(B, N, C)
+    x = x + linear(o, wts["w_o"], wts["b_o"])
+    m = layernorm(x, wts["ln2_g"], wts["ln2_b"], ln_eps)
+    hmid = gelu(linear(m, wts["w_fc1"], wts["b_fc1"]))
+    return x + linear(hmid, wts["w_fc2"], wts["b_fc2"])
+
+
+def encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
+    """Hybrid encoder: blocks[l] run with mixer pattern[l]; returns the residual stream."""
+    x = np.asarray(x, dtype=np.float64)
+    for wts, mixer in zip(blocks, pattern):
+        x = encoder_block(x, wts, mixer, H, W, heads, window, ln_eps, la_eps)
+    return x

@@ -359,3 +359,122 @@ int jvo_linear_attn_state(const float *q, const float *k, const float *v, double
     }
     return 0;
 }
+
+/* ========================================================================
+ * Encoder pieces (pre-LN transformer block around a token mixer) and the
+ * depth-wise-convolution branch of the linear-attention block.
+ * ====================================================================== */
+
+/* LayerNorm over the last axis: y = (x - mean) / sqrt(var + eps) * gamma + beta,
+ * var = population variance.  x is [rows, cols] float64, gamma/beta float32. */
+int jvo_layernorm(const double *x, const float *gamma, const float *beta, double *y,
+                  int64_t rows, int cols, double eps)
+{
+    if (!x || !gamma || !beta || !y || rows <= 0 || cols <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = x + r * cols;
+        double mean = 0.0;
+        for (int c = 0; c < cols; ++c) mean += xr[c];
+        mean /= cols;
+        double var = 0.0;
+        for (int c = 0; c < cols; ++c) var += (xr[c] - mean) * (xr[c] - mean);
+        var /= cols;
+        double inv = 1.0 / sqrt(var + eps);
+        for (int c = 0; c < cols; ++c)
+            y[r * cols + c] = (xr[c] - mean) * inv * (double)gamma[c] + (double)beta[c];
+    }
+    return 0;
+}
+
+/* Linear layer y = a W^T + b: a [T, K] float64, W [N, K] float32, b [N] float32 or NULL. */
+int jvo_linear(const double *a, const float *w, const float *b, double *y,
+               int64_t T, int N, int K)
+{
+    if (!a || !w || !y || T <= 0 || N <= 0 || K <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k) s += a[t * K + k] * (double)w[(size_t)n * K + k];
+            y[t * N + n] = s + (b ? (double)b[n] : 0.0);
+        }
+    return 0;
+}
+
+/* GELU(x) = x * 0.5 * (1 + erf(x / sqrt 2)), in place. */
+int jvo_gelu(double *x, int64_t n)
+{
+    if (!x || n < 0) return 1;
+    for (int64_t i = 0; i < n; ++i) x[i] = x[i] * 0.5 * (1.0 + erf(x[i] / sqrt(2.0)));
+    return 0;
+}
+
+/* Depth-wise k x k cross-correlation of V on the H x W token grid (Eq. 4 of the paper: the
+ * DWC(V) term), stride 1, zero padding k/2, no bias.  V is [B, heads, N, d] float32 and is
+ * read as C = heads*d channel images, channel = head*d + c.  kernel is [kb, C, k, k]
+ * float64 with kb = 1 (one static kernel) or kb = B (one kernel per image).
+ * out[b, head, r*W + col, c] = sum_{i,j} kernel[.., ch, i, j] * V[b, head, (r+i-k/2)*W + (col+j-k/2), c]. */
+int jvo_dwc(const float *v, const double *kernel, double *out, int B, int heads, int H, int W,
+            int d, int k, int kb)
+{
+    if (!v || !kernel || !out || B <= 0 || heads <= 0 || H <= 0 || W <= 0 || d <= 0 || k <= 0 ||
+        (k & 1) == 0 || (kb != 1 && kb != B))
+        return 1;
+    const int N = H * W, C = heads * d, pad = k / 2;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int hd = 0; hd < heads; ++hd)
+            for (int r = 0; r < H; ++r)
+                for (int col = 0; col < W; ++col)
+                    for (int c = 0; c < d; ++c) {
+                        const int ch = hd * d + c;
+                        const double *kk = kernel + ((size_t)(kb == 1 ? 0 : b) * C + ch) * k * k;
+                        double s = 0.0;
+                        for (int i = 0; i < k; ++i)
+                            for (int j = 0; j < k; ++j) {
+                                int rr = r + i - pad, cc = col + j - pad;
+                                if (rr < 0 || rr >= H || cc < 0 || cc >= W) continue;
+                                s += kk[i * k + j] * (double)v[IDX4(b, hd, rr * W + cc, heads, N, d) + c];
+                            }
+                        out[IDX4(b, hd, r * W + col, heads, N, d) + c] = s;
+                    }
+    return 0;
+}
+
+/* Squeeze Dynamic Convolution kernel generator (Sec. 3.2.1): the depth-wise weights are
+ * produced per image from the average of V over all tokens by a two-layer MLP with SiLU:
+ *   g = mean_n V[b, :, n]  (C values);  u = SiLU(W1 g + b1)  (hidden values);
+ *   kappa[b] = reshape(W2 u + b2, [C, k, k]);   SiLU(x) = x / (1 + exp(-x)).
+ * W1 [hidden, C], b1 [hidden], W2 [C*k*k, hidden], b2 [C*k*k], all float32;
+ * kappa is [B, C, k, k] float64. */
+int jvo_squeeze_kernel(const float *v, const float *w1, const float *b1, const float *w2,
+                       const float *b2, double *kappa, int B, int heads, int N, int d, int k,
+                       int hidden)
+{
+    if (!v || !w1 || !b1 || !w2 || !b2 || !kappa || B <= 0 || heads <= 0 || N <= 0 || d <= 0 ||
+        k <= 0 || hidden <= 0)
+        return 1;
+    const int C = heads * d, KK = C * k * k;
+    for (int b = 0; b < B; ++b) {
+        double *g = (double *)calloc((size_t)C, sizeof(double));
+        double *u = (double *)calloc((size_t)hidden, sizeof(double));
+        for (int hd = 0; hd < heads; ++hd)
+            for (int n = 0; n < N; ++n)
+                for (int c = 0; c < d; ++c) g[hd * d + c] += (double)v[IDX4(b, hd, n, heads, N, d) + c];
+        for (int ch = 0; ch < C; ++ch) g[ch] /= N;
+        for (int j = 0; j < hidden; ++j) {
+            double s = (double)b1[j];
+            for (int ch = 0; ch < C; ++ch) s += (double)w1[(size_t)j * C + ch] * g[ch];
+            u[j] = s / (1.0 + exp(-s));
+        }
+        for (int o = 0; o < KK; ++o) {
+            double s = (double)b2[o];
+            for (int j = 0; j < hidden; ++j) s += (double)w2[(size_t)o * hidden + j] * u[j];
+            kappa[(size_t)b * KK + o] = s;
+        }
+        free(g);
+        free(u);
+    }
+    return 0;
+}

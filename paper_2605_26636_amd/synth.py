@@ -70,3 +70,39 @@ def sample_rows(B, heads, N, count, seed):
     rows[0] = (0, 0, 0)
     rows[-1] = (B - 1, heads - 1, N - 1)
     return rows
+
+
+# ---------------------------------------------------------------------------
+# Encoder workload (config 5): random-init ViT-L weights and the block pattern
+# ---------------------------------------------------------------------------
+MIX_LINEAR, MIX_WINDOW, MIX_FULL = 0, 1, 2
+
+
+def encoder_pattern(n_blocks=24):
+    """Full attention at blocks 5, 11, 17, 23 (every sixth); of the rest, even-indexed blocks
+    take window attention and odd-indexed blocks linear attention."""
+    out = []
+    for i in range(n_blocks):
+        if i % 6 == 5:
+            out.append(MIX_FULL)
+        else:
+            out.append(MIX_WINDOW if i % 2 == 0 else MIX_LINEAR)
+    return out
+
+
+def block_weights(C, hidden, seed, bf16=True):
+    """Xavier-normal weights of one pre-LN block (std = sqrt(2 / (fan_in + fan_out)), Q, K, V
+    drawn as three C x C matrices), zero biases, LayerNorm gamma = 1 and beta = 0; float32
+    arrays, rounded to bf16-representable values when bf16=True."""
+    def xavier(shape, s):
+        w = normal(shape, s, np.sqrt(2.0 / (shape[0] + shape[1])))
+        return round_to_bf16(w) if bf16 else w
+    w_qkv = np.concatenate([xavier((C, C), seed * 16 + i) for i in range(3)], axis=0)
+    return {
+        "ln1_g": np.ones(C, np.float32), "ln1_b": np.zeros(C, np.float32),
+        "w_qkv": w_qkv, "b_qkv": np.zeros(3 * C, np.float32),
+        "w_o": xavier((C, C), seed * 16 + 3), "b_o": np.zeros(C, np.float32),
+        "ln2_g": np.ones(C, np.float32), "ln2_b": np.zeros(C, np.float32),
+        "w_fc1": xavier((hidden, C), seed * 16 + 4), "b_fc1": np.zeros(hidden, np.float32),
+        "w_fc2": xavier((C, hidden), seed * 16 + 5), "b_fc2": np.zeros(C, np.float32),
+    }

@@ -1,0 +1,122 @@
+"""Pins for the oracle's encoder pieces (LayerNorm, linear, GELU, block) and the DWC branch."""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2605_26636_amd import synth
+
+
+def test_layernorm_properties_and_library():
+    x = synth.normal((7, 33), 1).astype(np.float64) * 3 + 2
+    ones, zeros = np.ones(33, np.float32), np.zeros(33, np.float32)
+    y = oracle.layernorm(x, ones, zeros, eps=0.0)
+    assert np.abs(y.mean(-1)).max() < 1e-14 and np.abs(y.var(-1) - 1).max() < 1e-13
+    g, b = synth.normal((33,), 2), synth.normal((33,), 3)
+    ref = F.layer_norm(torch.from_numpy(x), (33,), torch.from_numpy(g).double(),
+                       torch.from_numpy(b).double(), eps=1e-6).numpy()
+    assert np.abs(oracle.layernorm(x, g, b, 1e-6) - ref).max() < 1e-13
+    # constant row: variance 0 -> output = beta exactly (eps keeps the division finite)
+    assert np.array_equal(oracle.layernorm(np.full((1, 33), 4.0), g, b, 1e-6)[0], b.astype(np.float64))
+
+
+def test_linear_against_library_matmul():
+    a = synth.normal((5, 17), 4).astype(np.float64)
+    w, b = synth.normal((9, 17), 5), synth.normal((9,), 6)
+    ref = a @ w.astype(np.float64).T + b
+    assert np.abs(oracle.linear(a, w, b) - ref).max() < 1e-13
+    assert np.abs(oracle.linear(a, w) - (ref - b)).max() < 1e-13
+    # identity weight reproduces the input; a transposed operand would fail on a non-square W
+    assert np.array_equal(oracle.linear(a, np.eye(17, dtype=np.float32)), a)
+
+
+def test_gelu_values(golden):
+    g = golden("gelu_values.txt")
+    assert np.abs(oracle.gelu(np.array(g["x"])) - np.array(g["gelu"])).max() < 1e-15
+    x = synth.normal((100,), 7).astype(np.float64) * 3
+    assert np.abs(oracle.gelu(x) - F.gelu(torch.from_numpy(x)).numpy()).max() < 1e-14
+
+
+def test_dwc_hand_case_and_library(golden):
+    g = golden("dwc_hand_case.txt")
+    v = np.array(g["v"], dtype=np.float32).reshape(1, 1, 9, 1)
+    for name in ("plus", "corner"):
+        kern = np.array(g["kernel_" + name]).reshape(1, 1, 3, 3)
+        assert oracle.dwc(v, kern, 3, 3).reshape(-1).tolist() == g["out_" + name]
+    # against conv2d (a cross-correlation) with groups = C, on a ragged grid, k = 3 and 5
+    B, heads, H, W, d = 2, 2, 5, 7, 4
+    v = synth.normal((B, heads, H * W, d), 8)
+    img = torch.from_numpy(v).double().permute(0, 1, 3, 2).reshape(B, heads * d, H, W)
+    for k in (3, 5):
+        kern = synth.normal((1, heads * d, k, k), 9).astype(np.float64)
+        ref = F.conv2d(img, torch.from_numpy(kern[0])[:, None], padding=k // 2, groups=heads * d)
+        ref = ref.reshape(B, heads, d, H * W).permute(0, 1, 3, 2).numpy()
+        assert np.abs(oracle.dwc(v, kern, H, W) - ref).max() < 1e-13
+        per_image = np.concatenate([kern, 2 * kern])
+        got = oracle.dwc(v, per_image, H, W)
+        assert np.abs(got[0] - ref[0]).max() < 1e-13 and np.abs(got[1] - 2 * ref[1]).max() < 1e-13
+
+
+def test_linear_block_special_kernels():
+    B, heads, H, W, d = 1, 2, 4, 5, 8
+    q, k, v = synth.qkv(50, B, heads, H * W, d, 1.0, False)
+    C = heads * d
+    la = oracle.linear_attn_quadratic(q, k, v, 1e-6)
+    assert np.array_equal(oracle.linear_block(q, k, v, H, W, static_kernel=np.zeros((C, 3, 3))), la)
+    delta = np.zeros((C, 3, 3)); delta[:, 1, 1] = 1
+    assert np.abs(oracle.linear_block(q, k, v, H, W, static_kernel=delta) - (la + v)).max() < 1e-15
+
+
+def test_squeeze_kernel_generator():
+    B, heads, N, d, k, hidden = 2, 2, 12, 4, 3, 5
+    C = heads * d
+    v = synth.normal((B, heads, N, d), 60)
+    w1, b1 = synth.normal((hidden, C), 61), synth.normal((hidden,), 62)
+    w2, b2 = synth.normal((C * k * k, hidden), 63), synth.normal((C * k * k,), 64)
+    kap = oracle.squeeze_kernel(v, w1, b1, w2, b2, k)
+    g = torch.from_numpy(v).double().mean(dim=2).reshape(B, C)          # channel = head*d + c
+    u = F.silu(g @ torch.from_numpy(w1).double().T + torch.from_numpy(b1).double())
+    ref = (u @ torch.from_numpy(w2).double().T + torch.from_numpy(b2).double()).reshape(B, C, k, k)
+    assert np.abs(kap - ref.numpy()).max() < 1e-13
+    # W2 = 0: the dynamic kernel is the static kernel b2, for every image
+    kap0 = oracle.squeeze_kernel(v, w1, b1, np.zeros_like(w2), b2, k)
+    assert np.array_equal(kap0[0], b2.astype(np.float64).reshape(C, k, k)) and np.array_equal(kap0[0], kap0[1])
+    # the kernel depends on V only through its token mean: permuting tokens changes nothing
+    perm = np.random.Generator(np.random.Philox(3)).permutation(N)
+    assert np.abs(oracle.squeeze_kernel(v[:, :, perm], w1, b1, w2, b2, k) - kap).max() < 1e-13
+
+
+def _block_weights(C, hidden, seed):
+    return synth.block_weights(C, hidden, seed, bf16=False)
+
+
+def test_encoder_block_against_torch_modules():
+    B, H, W, C, heads, hidden = 2, 4, 4, 32, 2, 64
+    x = synth.normal((B, H * W, C), 70).astype(np.float64)
+    wts = _block_weights(C, hidden, 71)
+    for key in ("b_qkv", "b_o", "b_fc1", "b_fc2", "ln1_b", "ln2_b"):
+        wts[key] = synth.normal(wts[key].shape, 80 + len(key)) * 0.1        # non-zero biases
+    got = oracle.encoder_block(x, wts, oracle.MIX_FULL, H, W, heads)
+    t = {k: torch.from_numpy(v).double() for k, v in wts.items()}
+    xt = torch.from_numpy(x)
+    a = F.layer_norm(xt, (C,), t["ln1_g"], t["ln1_b"], 1e-6)
+    o, _ = F.multi_head_attention_forward(
+        a.transpose(0, 1), a.transpose(0, 1), a.transpose(0, 1), C, heads, t["w_qkv"], t["b_qkv"],
+        None, None, False, 0.0, t["w_o"], t["b_o"], need_weights=False)
+    xt = xt + o.transpose(0, 1)
+    m = F.layer_norm(xt, (C,), t["ln2_g"], t["ln2_b"], 1e-6)
+    xt = xt + F.linear(F.gelu(F.linear(m, t["w_fc1"], t["b_fc1"])), t["w_fc2"], t["b_fc2"])
+    assert np.abs(got - xt.numpy()).max() < 1e-5       # q, k, v pass through float32 in the oracle
+
+
+def test_encoder_patterns():
+    B, H, W, C, heads, hidden = 1, 4, 4, 32, 2, 64
+    x = synth.normal((B, H * W, C), 90)
+    blocks = [_block_weights(C, hidden, 91 + i) for i in range(3)]
+    full = oracle.encoder_forward(x, blocks, [oracle.MIX_FULL] * 3, H, W, heads)
+    whole = oracle.encoder_forward(x, blocks, [oracle.MIX_WINDOW] * 3, H, W, heads, window=(H, W))
+    assert np.abs(full - whole).max() < 1e-12
+    pattern = synth.encoder_pattern(24)
+    assert pattern.count(oracle.MIX_FULL) == 4 and pattern.count(oracle.MIX_WINDOW) == 12
+    assert pattern.count(oracle.MIX_LINEAR) == 8
+    assert [i for i, p in enumerate(pattern) if p == oracle.MIX_FULL] == [5, 11, 17, 23]
