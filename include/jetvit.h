@@ -140,6 +140,81 @@ jv_status jv_window_attn_fwd(const jv_attn_desc *desc, const void *q, const void
 jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
                            const void *v, void *o, float scale, void *hip_stream);
 
+/* ---------------------------------------------------------------------------
+ * Encoder pieces.  The paper's hybrid encoder keeps the pretrained block around each token
+ * mixer (Sec. 3.2.3: the MLP and the attention projections W_Q, W_K, W_V, W_O are inherited
+ * unchanged); the block is the standard pre-LN transformer block.
+ *
+ * jv_layernorm_fwd: y[r, :] = (x[r, :] - mean) / sqrt(var + eps) * gamma + beta over `cols`
+ * (population variance, fp32 statistics).  x is [rows, cols] of x_dtype, gamma and beta are
+ * fp32 [cols], y is [rows, cols] of y_dtype; all device, rows contiguous, cols % 8 == 0.
+ *
+ * jv_gemm_bias_act: y = epilogue(a w^T + bias), a [M, K] bf16 and w [N, K] bf16 both row-major
+ * (K contiguous), fp32 accumulation on the matrix cores.  bias is fp32 [N] or NULL.
+ *   JV_EPI_NONE      y = acc + bias
+ *   JV_EPI_GELU      y = gelu(acc + bias), the exact (erf) GELU, erf to 3e-5 absolute
+ *   JV_EPI_RESIDUAL  y = acc + bias + residual, residual fp32 [M, N] (may be y itself)
+ * y is [M, N] of y_dtype (JV_BF16 or JV_F32).  K % 64 == 0 and N % 8 == 0 are required
+ * (JV_ERR_UNSUPPORTED otherwise); M is arbitrary.  All pointers device, 16-byte aligned.
+ * ------------------------------------------------------------------------- */
+typedef enum { JV_EPI_NONE = 0, JV_EPI_GELU = 1, JV_EPI_RESIDUAL = 2 } jv_epilogue;
+
+jv_status jv_layernorm_fwd(const void *x, const float *gamma, const float *beta, void *y,
+                           int64_t rows, int32_t cols, float eps, jv_dtype x_dtype,
+                           jv_dtype y_dtype, void *hip_stream);
+jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, const float *residual,
+                           void *y, int64_t M, int32_t N, int32_t K, jv_epilogue epilogue,
+                           jv_dtype y_dtype, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Hybrid encoder forward (Fig. 2 of the paper: per layer, one of the three token mixers;
+ * Sec. 4.4 works with a 24-layer ViT-Large).  For every block l:
+ *     a = LN(x; ln1);  [Q K V] = a W_qkv^T + b_qkv, split into heads of 64;
+ *     x += mix_{pattern[l]}(Q, K, V) W_o^T + b_o;
+ *     x += gelu(LN(x; ln2) W_fc1^T + b_fc1) W_fc2^T + b_fc2.
+ * The residual stream x is fp32; GEMM operands and the tensors between kernels are bf16.
+ * No final norm: the output is the residual stream after the last block.
+ *
+ * jv_encoder_create copies the configuration and the table of weight POINTERS into a host
+ * object; the weights themselves stay where they are (device memory owned by the caller,
+ * which must outlive the object).  pattern is a host array of n_blocks values
+ * (0 linear, 1 window, 2 full).  Weights per block: LayerNorm gamma/beta fp32 [width];
+ * w_qkv bf16 [3*width, width] (rows: Q features, then K, then V), b_qkv fp32 [3*width];
+ * w_o bf16 [width, width], b_o fp32; w_fc1 bf16 [mlp_hidden, width], b_fc1 fp32;
+ * w_fc2 bf16 [width, mlp_hidden], b_fc2 fp32.  width = heads * 64, width and mlp_hidden
+ * multiples of 64.
+ *
+ * jv_encoder_forward: x and y are device fp32 [batch, grid_h*grid_w, width] (y may be x);
+ * workspace is device memory of at least jv_encoder_workspace_bytes(...) bytes, 256-byte
+ * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t n_blocks, width, heads, mlp_hidden;
+    int32_t win_h, win_w;  /* window of the window-attention blocks */
+    float ln_eps, la_eps;  /* LayerNorm epsilon; linear-attention denominator epsilon */
+    const uint8_t *pattern; /* host, n_blocks entries: 0 linear, 1 window, 2 full */
+} jv_encoder_config;
+
+typedef struct {
+    const float *ln1_g, *ln1_b;
+    const void *w_qkv; const float *b_qkv;
+    const void *w_o; const float *b_o;
+    const float *ln2_g, *ln2_b;
+    const void *w_fc1; const float *b_fc1;
+    const void *w_fc2; const float *b_fc2;
+} jv_block_weights;
+
+typedef struct jv_encoder jv_encoder;
+
+jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weights *blocks,
+                            jv_encoder **out);
+size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
+                                  int32_t grid_w);
+jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+                             int32_t grid_h, int32_t grid_w, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+void jv_encoder_destroy(jv_encoder *enc);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,10 @@ EXPORTS = [
     "jv_linear_attn_workspace_bytes", "jv_linear_attn_fwd",
     "jv_window_geometry", "jv_window_maps_host", "jv_window_maps_device",
     "jv_window_attn_fwd", "jv_full_attn_fwd",
+    "jv_layernorm_fwd", "jv_gemm_bias_act",
+    "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_destroy",
 ]
+JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL = 0, 1, 2
 
 
 class JvStrides(ctypes.Structure):
@@ -34,6 +37,21 @@ class JvAttnDesc(ctypes.Structure):
                 ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int), ("o_dtype", ctypes.c_int),
                 ("q", JvStrides), ("k", JvStrides), ("v", JvStrides), ("o", JvStrides)]
+
+
+class JvEncoderConfig(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_int32), ("width", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("mlp_hidden", ctypes.c_int32), ("win_h", ctypes.c_int32), ("win_w", ctypes.c_int32),
+                ("ln_eps", ctypes.c_float), ("la_eps", ctypes.c_float),
+                ("pattern", ctypes.POINTER(ctypes.c_uint8))]
+
+
+BLOCK_FIELDS = ["ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_fc1", "b_fc1",
+                "w_fc2", "b_fc2"]
+
+
+class JvBlockWeights(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in BLOCK_FIELDS]
 
 
 class JvError(RuntimeError):
@@ -69,6 +87,18 @@ def lib():
         L.jv_window_geometry.argtypes = [i32, i32, i32, i32, vp, vp, vp]
         L.jv_window_maps_host.argtypes = [i32, i32, i32, i32, vp, vp, vp]
         L.jv_window_maps_device.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp]
+        i64 = ctypes.c_int64
+        L.jv_layernorm_fwd.argtypes = [vp, vp, vp, vp, i64, i32, ctypes.c_float, ctypes.c_int,
+                                       ctypes.c_int, vp]
+        L.jv_gemm_bias_act.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int,
+                                       ctypes.c_int, vp]
+        L.jv_encoder_create.argtypes = [ctypes.POINTER(JvEncoderConfig),
+                                        ctypes.POINTER(JvBlockWeights), ctypes.POINTER(vp)]
+        L.jv_encoder_workspace_bytes.restype = ctypes.c_size_t
+        L.jv_encoder_workspace_bytes.argtypes = [vp, i32, i32, i32]
+        L.jv_encoder_forward.argtypes = [vp, vp, vp, i32, i32, i32, vp, ctypes.c_size_t, vp]
+        L.jv_encoder_destroy.restype = None
+        L.jv_encoder_destroy.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -177,3 +207,75 @@ def jv_window_maps_device(grid_h, grid_w, win_h, win_w, device="cuda", stream=No
     _check(lib().jv_window_maps_device(grid_h, grid_w, win_h, win_w, ti.data_ptr(), pm.data_ptr(),
                                        wt.data_ptr(), _stream(stream)))
     return ti, pm, wt
+
+
+def jv_layernorm_fwd(x, gamma, beta, y, eps=1e-6, stream=None):
+    """y <- LayerNorm(x) over the last axis; x fp32/bf16 [rows, cols], y bf16/fp32, gamma/beta fp32."""
+    rows, cols = x.shape
+    if not (x.is_contiguous() and y.is_contiguous() and tuple(y.shape) == (rows, cols)):
+        raise ValueError("x and y must be contiguous [rows, cols]")
+    _check(lib().jv_layernorm_fwd(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), y.data_ptr(),
+                                  rows, cols, eps, _dtype_code(x), _dtype_code(y), _stream(stream)))
+
+
+def jv_gemm_bias_act(a, w, bias, residual, y, epilogue=JV_EPI_NONE, stream=None):
+    """y <- epilogue(a w^T + bias); a bf16 [M, K], w bf16 [N, K], bias fp32 [N] or None,
+    residual fp32 [M, N] or None, y bf16 or fp32 [M, N]."""
+    M, K = a.shape
+    N = w.shape[0]
+    if w.shape[1] != K or tuple(y.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    for t in (a, w, y):
+        if not t.is_contiguous():
+            raise ValueError("operands must be contiguous")
+    if a.dtype != torch.bfloat16 or w.dtype != torch.bfloat16:
+        raise TypeError("a and w must be bf16")
+    _check(lib().jv_gemm_bias_act(a.data_ptr(), w.data_ptr(),
+                                  None if bias is None else bias.data_ptr(),
+                                  None if residual is None else residual.data_ptr(), y.data_ptr(),
+                                  M, N, K, epilogue, _dtype_code(y), _stream(stream)))
+
+
+class Encoder:
+    """Handle of a jv_encoder.  `blocks` is a list of dicts of device tensors (BLOCK_FIELDS:
+    weights bf16, biases and LayerNorm parameters fp32); the tensors are kept alive here."""
+
+    def __init__(self, blocks, pattern, heads, mlp_hidden, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
+        self.blocks = blocks
+        self.width = blocks[0]["w_o"].shape[0]
+        n = len(blocks)
+        self._pattern = (ctypes.c_uint8 * n)(*pattern)
+        cfg = JvEncoderConfig(n, self.width, heads, mlp_hidden, window[0], window[1], ln_eps, la_eps,
+                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)))
+        table = (JvBlockWeights * n)()
+        for i, b in enumerate(blocks):
+            for name in BLOCK_FIELDS:
+                setattr(table[i], name, b[name].data_ptr())
+        self._handle = ctypes.c_void_p()
+        _check(lib().jv_encoder_create(ctypes.byref(cfg), table, ctypes.byref(self._handle)))
+
+    def workspace_bytes(self, batch, grid):
+        return int(lib().jv_encoder_workspace_bytes(self._handle, batch, grid[0], grid[1]))
+
+    def forward(self, x, y, grid, workspace=None, stream=None):
+        """y <- encoder(x); x, y fp32 [batch, N, width] on the GPU; returns the workspace used."""
+        batch = x.shape[0]
+        if x.dtype != torch.float32 or y.dtype != torch.float32 or not x.is_contiguous() or not y.is_contiguous():
+            raise ValueError("x and y must be contiguous fp32")
+        if workspace is None:
+            workspace = torch.empty(self.workspace_bytes(batch, grid), dtype=torch.uint8, device=x.device)
+        _check(lib().jv_encoder_forward(self._handle, x.data_ptr(), y.data_ptr(), batch, grid[0],
+                                        grid[1], workspace.data_ptr(), workspace.numel(),
+                                        _stream(stream)))
+        return workspace
+
+    def close(self):
+        if self._handle:
+            lib().jv_encoder_destroy(self._handle)
+            self._handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

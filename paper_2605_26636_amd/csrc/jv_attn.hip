@@ -95,6 +95,21 @@ static jv_status attn_dispatch(const Problem &pr, const WindowGeom &g, float sca
     return launch_status("attn_f32");
 }
 
+jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStream_t stream) {
+    WindowGeom g;
+    jv_status st = make_window_geom(pr.H, pr.W, wh, ww, &g);
+    if (st != JV_OK) return st;
+    return attn_dispatch(pr, g, resolve_scale(scale), stream);
+}
+
+jv_status full_forward(const Problem &pr, float scale, hipStream_t stream) {
+    // One window that spans the grid; the token order inside it is the raster order.
+    WindowGeom g;
+    g.H = pr.H; g.W = pr.W; g.wh = pr.H; g.ww = pr.W;
+    g.Hp = pr.H; g.Wp = pr.W; g.wins_x = 1; g.wins_y = 1; g.n_win = 1; g.slots = pr.N;
+    return attn_dispatch(pr, g, resolve_scale(scale), stream);
+}
+
 }  // namespace jv
 
 extern "C" {
@@ -106,9 +121,7 @@ jv_status jv_window_attn_fwd(const jv_attn_desc *desc, const void *q, const void
     jv::Problem pr;
     jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
     if (st != JV_OK) return st;
-    jv::WindowGeom g;
-    if ((st = jv::make_window_geom(pr.H, pr.W, win_h, win_w, &g)) != JV_OK) return st;
-    return jv::attn_dispatch(pr, g, jv::resolve_scale(scale), (hipStream_t)hip_stream);
+    return jv::window_forward(pr, win_h, win_w, scale, (hipStream_t)hip_stream);
 }
 
 jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
@@ -117,11 +130,7 @@ jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *
     jv::Problem pr;
     jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
     if (st != JV_OK) return st;
-    // One window that spans the grid; the token order inside it is the raster order.
-    jv::WindowGeom g;
-    g.H = pr.H; g.W = pr.W; g.wh = pr.H; g.ww = pr.W;
-    g.Hp = pr.H; g.Wp = pr.W; g.wins_x = 1; g.wins_y = 1; g.n_win = 1; g.slots = pr.N;
-    return jv::attn_dispatch(pr, g, jv::resolve_scale(scale), (hipStream_t)hip_stream);
+    return jv::full_forward(pr, scale, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

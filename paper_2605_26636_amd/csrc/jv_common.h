@@ -52,4 +52,10 @@ struct WindowGeom {
 };
 jv_status make_window_geom(int H, int W, int wh, int ww, WindowGeom *g);
 
+// Mixer launchers on a validated problem (used by the C entry points and by the encoder).
+size_t linear_workspace_bytes(int B, int heads, int N);
+jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStream_t stream);
+jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStream_t stream);
+jv_status full_forward(const Problem &pr, float scale, hipStream_t stream);
+
 }  // namespace jv

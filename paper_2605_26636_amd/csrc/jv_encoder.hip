@@ -1,0 +1,444 @@
+// Encoder pieces around the token mixers (the pre-LN transformer block the paper's hybrid
+// encoder inherits from the pretrained ViT): LayerNorm, the bf16 matrix-core GEMM with fused
+// bias / GELU / residual epilogues, and the host loop that runs the blocks.
+#include <math.h>
+#include <new>
+
+#include "jv_common.h"
+#include "jv_mfma.h"
+
+namespace jv {
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm: one wavefront per row, the row held in registers (16-byte pieces, lane-strided),
+// mean and variance in two register passes, fp32 statistics.
+// grid (ceil(rows / 4)), 256 threads.  NV = 16-byte pieces per lane (cols <= 256 * NV).
+// ---------------------------------------------------------------------------------------
+template <bool IN_BF16, bool OUT_BF16, int NV>
+__global__ void __launch_bounds__(256)
+layernorm_kernel(const void *__restrict__ xin, const float *__restrict__ gamma,
+                 const float *__restrict__ beta, void *__restrict__ yout, long long rows, int cols,
+                 float eps) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + wave;
+    if (row >= rows) return;
+    // piece p of a lane covers columns 4 * (lane + 64 p) .. + 3
+    f32x4 v[NV];
+    float sum = 0.f;
+#pragma unroll
+    for (int p = 0; p < NV; ++p) {
+        const int c = 4 * (lane + 64 * p);
+        f32x4 x = {0.f, 0.f, 0.f, 0.f};
+        if (c < cols) {
+            if (IN_BF16) {
+                const u32x2 raw = *(const u32x2 *)((const __bf16 *)xin + row * cols + c);
+                x[0] = bf16_lo(raw[0]); x[1] = bf16_hi(raw[0]);
+                x[2] = bf16_lo(raw[1]); x[3] = bf16_hi(raw[1]);
+            } else {
+                x = *(const f32x4 *)((const float *)xin + row * cols + c);
+            }
+        }
+        v[p] = x;
+        sum += (x[0] + x[1]) + (x[2] + x[3]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    const float mean = sum / (float)cols;
+    float sq = 0.f;
+#pragma unroll
+    for (int p = 0; p < NV; ++p) {
+        const int c = 4 * (lane + 64 * p);
+        if (c < cols) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float dlt = v[p][e] - mean;
+                sq = fmaf(dlt, dlt, sq);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+    const float inv = 1.0f / sqrtf(sq / (float)cols + eps);
+#pragma unroll
+    for (int p = 0; p < NV; ++p) {
+        const int c = 4 * (lane + 64 * p);
+        if (c < cols) {
+            const f32x4 gm = *(const f32x4 *)(gamma + c), bt = *(const f32x4 *)(beta + c);
+            f32x4 y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = (v[p][e] - mean) * inv * gm[e] + bt[e];
+            if (OUT_BF16) {
+                u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                *(u32x2 *)((__bf16 *)yout + row * cols + c) = pk;
+            } else {
+                *(f32x4 *)((float *)yout + row * cols + c) = y;
+            }
+        }
+    }
+}
+
+template <bool IN_BF16, bool OUT_BF16>
+static void launch_layernorm(const void *x, const float *gamma, const float *beta, void *y,
+                             long long rows, int cols, float eps, hipStream_t stream) {
+    dim3 grid((unsigned)((rows + 3) / 4));
+    const int nv = (cols + 255) / 256;
+    if (nv <= 1)
+        hipLaunchKernelGGL((layernorm_kernel<IN_BF16, OUT_BF16, 1>), grid, dim3(256), 0, stream, x, gamma, beta, y, rows, cols, eps);
+    else if (nv <= 2)
+        hipLaunchKernelGGL((layernorm_kernel<IN_BF16, OUT_BF16, 2>), grid, dim3(256), 0, stream, x, gamma, beta, y, rows, cols, eps);
+    else if (nv <= 4)
+        hipLaunchKernelGGL((layernorm_kernel<IN_BF16, OUT_BF16, 4>), grid, dim3(256), 0, stream, x, gamma, beta, y, rows, cols, eps);
+    else if (nv <= 8)
+        hipLaunchKernelGGL((layernorm_kernel<IN_BF16, OUT_BF16, 8>), grid, dim3(256), 0, stream, x, gamma, beta, y, rows, cols, eps);
+    else
+        hipLaunchKernelGGL((layernorm_kernel<IN_BF16, OUT_BF16, 32>), grid, dim3(256), 0, stream, x, gamma, beta, y, rows, cols, eps);
+}
+
+static jv_status layernorm_forward(const void *x, const float *gamma, const float *beta, void *y,
+                                   long long rows, int cols, float eps, bool in_bf16,
+                                   bool out_bf16, hipStream_t stream) {
+    if (in_bf16 && out_bf16) launch_layernorm<true, true>(x, gamma, beta, y, rows, cols, eps, stream);
+    else if (in_bf16) launch_layernorm<true, false>(x, gamma, beta, y, rows, cols, eps, stream);
+    else if (out_bf16) launch_layernorm<false, true>(x, gamma, beta, y, rows, cols, eps, stream);
+    else launch_layernorm<false, false>(x, gamma, beta, y, rows, cols, eps, stream);
+    return launch_status("layernorm_kernel");
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM  y = epilogue(a w^T + bias):  a [M, K], w [N, K], both bf16 with K contiguous, so both
+// matrix-instruction operands are 16-byte row pieces.  One workgroup (4 wavefronts, one per
+// SIMD, the whole register file each) owns a 256 x 256 tile of y; a wavefront owns 128 x 128 of
+// it (4 x 4 blocks of 32 x 32, 256 accumulator registers).  K is walked in steps of 64: the
+// 256 x 64 tiles of a and w go from global memory straight into LDS (no register staging),
+// double-buffered; rows are 128 bytes in LDS with the 16-byte chunk index rotated by the row
+// so that the row-per-lane operand reads spread over all banks.
+// The product is formed transposed (features x tokens): a lane then holds 4 consecutive output
+// features of one token, which makes the epilogue loads (bias, residual) and stores 8 or 16
+// bytes wide.
+// Tiles are assigned so that the workgroups an XCD receives (every eighth) walk a contiguous
+// range of tiles, feature-tile fastest: they share the a row-tile and keep w in that L2.
+// grid (8 * ceil(tiles / 8)), 256 threads, kGemmLds bytes of dynamic LDS.
+// ---------------------------------------------------------------------------------------
+constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kGemmTileBytes = kBM * kBK * 2;          // one operand tile: 32 KB
+constexpr int kGemmStage = 2 * kGemmTileBytes;         // a tile then w tile
+constexpr int kGemmLds = 2 * kGemmStage;               // two stages: 128 KB
+
+typedef __attribute__((address_space(1))) const void global_cvoid;
+typedef __attribute__((address_space(3))) void lds_void;
+
+// erf(z) by Abramowitz-Stegun 7.1.25 (absolute error below 2.5e-5), exp through exp2.
+__device__ inline float gelu_erf(float x) {
+    const float z = fabsf(x) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.47047f, z, 1.0f));
+    const float poly = t * fmaf(t, fmaf(t, 0.7478556f, -0.0958798f), 0.3480242f);
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
+    const float erf_abs = fmaf(-poly, e, 1.0f);
+    const float erf_x = copysignf(erf_abs, x);
+    return 0.5f * x * (1.0f + erf_x);
+}
+
+template <int EPI, bool OUT_BF16>
+__global__ void __launch_bounds__(256, 1)
+gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
+                 const float *__restrict__ bias, const float *residual, void *Y, int M, int N,
+                 int K, int tiles_n, int n_tiles) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+    const int per_xcd = (n_tiles + 7) / 8;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles) return;  // whole workgroup
+    const int m0 = (tile / tiles_n) * kBM, n0 = (tile % tiles_n) * kBN;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // Global -> LDS: a wavefront moves rows 64*wave .. +63 of both tiles, 8 rows (1 KB) per
+    // instruction; lane = 8 * (row in group) + LDS chunk slot, and it fetches the global chunk
+    // that belongs in that slot under the row rotation.
+    const int lrow = lane >> 3, gchunk = (lane & 7) ^ lrow;
+    unsigned a_off[8], w_off[8];  // byte offsets of this lane's 16 bytes, k = 0
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int r = wave * 64 + j * 8 + lrow;
+        const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);  // edge tiles re-read the last row
+        a_off[j] = 2u * ((unsigned)ar * (unsigned)K + gchunk * 8);
+        w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
+    }
+    auto issue_loads = [&](int k0, int buf) {
+        unsigned char *abase = smem + buf * kGemmStage + wave * 64 * 128;
+        unsigned char *wbase = abase + kGemmTileBytes;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_global_load_lds(
+                (global_cvoid *)((const char *)A + (a_off[j] + 2u * k0)),
+                (lds_void *)(abase + j * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(
+                (global_cvoid *)((const char *)W + (w_off[j] + 2u * k0)),
+                (lds_void *)(wbase + j * 1024), 16, 0, 0);
+        }
+    };
+
+    f32x16 acc[4][4];  // [feature block][token block]
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
+
+    const int n_k = K / kBK;
+    issue_loads(0, 0);
+    __syncthreads();  // the compiler waits for the LDS-bound loads before the barrier
+    for (int kt = 0; kt < n_k; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < n_k) issue_loads((kt + 1) * kBK, buf ^ 1);
+        const unsigned char *at = smem + buf * kGemmStage, *wt = at + kGemmTileBytes;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 aop[4], wop[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                aop[i] = as_bf16x8(*(const u32x4 *)(at + tile_off_row(wm * 128 + i * 32 + li, 2 * ks + g)));
+                wop[i] = as_bf16x8(*(const u32x4 *)(wt + tile_off_row(wn * 128 + i * 32 + li, 2 * ks + g)));
+            }
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[nt], aop[mt], acc[nt][mt]);
+        }
+        __syncthreads();
+    }
+
+    // Epilogue: accumulator register v of block (nt, mt) is output feature
+    // n0 + 128 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int row = m0 + wm * 128 + mt * 32 + li;
+        if (row >= M) continue;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
+                if (col >= N) continue;  // N % 8 == 0: the four features are in or out together
+                f32x4 val = {acc[nt][mt][4 * q4], acc[nt][mt][4 * q4 + 1], acc[nt][mt][4 * q4 + 2],
+                             acc[nt][mt][4 * q4 + 3]};
+                if (bias) val += *(const f32x4 *)(bias + col);
+                const size_t at_out = (size_t)row * N + col;
+                if (EPI == JV_EPI_GELU) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) val[e] = gelu_erf(val[e]);
+                }
+                if (EPI == JV_EPI_RESIDUAL) val += *(const f32x4 *)(residual + at_out);
+                if (OUT_BF16) {
+                    u32x2 pk = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
+                    *(u32x2 *)((__bf16 *)Y + at_out) = pk;
+                } else {
+                    *(f32x4 *)((float *)Y + at_out) = val;
+                }
+            }
+    }
+}
+
+template <int EPI, bool OUT_BF16>
+static jv_status launch_gemm(const void *a, const void *w, const float *bias, const float *residual,
+                             void *y, long long M, int N, int K, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<EPI, OUT_BF16>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+        attr_set = true;
+    }
+    const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (N + kBN - 1) / kBN;
+    const int n_tiles = tiles_m * tiles_n;
+    dim3 grid(8 * ((n_tiles + 7) / 8));
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16>), grid, dim3(256), kGemmLds, stream,
+                       (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K,
+                       tiles_n, n_tiles);
+    return launch_status("gemm_bf16_kernel");
+}
+
+static jv_status gemm_forward(const void *a, const void *w, const float *bias,
+                              const float *residual, void *y, long long M, int N, int K, int epi,
+                              bool out_bf16, hipStream_t stream) {
+    if (M <= 0 || N <= 0 || K <= 0) return fail(JV_ERR_INVALID_ARG, "M, N, K must be positive");
+    if (!a || !w || !y) return fail(JV_ERR_INVALID_ARG, "a, w, y must be non-null");
+    if (((uintptr_t)a | (uintptr_t)w | (uintptr_t)y | (uintptr_t)bias | (uintptr_t)residual) & 15)
+        return fail(JV_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    if (K % kBK) return fail(JV_ERR_UNSUPPORTED, "K must be a multiple of 64");
+    if (N % 8) return fail(JV_ERR_UNSUPPORTED, "N must be a multiple of 8");
+    if (M * (long long)K >= (1ll << 30) || (long long)N * K >= (1ll << 30) || M > (1 << 24))
+        return fail(JV_ERR_UNSUPPORTED, "operand above 2^30 elements");
+    if (epi == JV_EPI_RESIDUAL && !residual)
+        return fail(JV_ERR_INVALID_ARG, "residual epilogue needs a residual tensor");
+    switch (epi) {
+        case JV_EPI_NONE:
+            return out_bf16 ? launch_gemm<JV_EPI_NONE, true>(a, w, bias, residual, y, M, N, K, stream)
+                            : launch_gemm<JV_EPI_NONE, false>(a, w, bias, residual, y, M, N, K, stream);
+        case JV_EPI_GELU:
+            return out_bf16 ? launch_gemm<JV_EPI_GELU, true>(a, w, bias, residual, y, M, N, K, stream)
+                            : launch_gemm<JV_EPI_GELU, false>(a, w, bias, residual, y, M, N, K, stream);
+        case JV_EPI_RESIDUAL:
+            return out_bf16 ? launch_gemm<JV_EPI_RESIDUAL, true>(a, w, bias, residual, y, M, N, K, stream)
+                            : launch_gemm<JV_EPI_RESIDUAL, false>(a, w, bias, residual, y, M, N, K, stream);
+    }
+    return fail(JV_ERR_INVALID_ARG, "unknown epilogue");
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace jv
+
+// The encoder object: configuration and weight pointers, host memory only.
+struct jv_encoder {
+    jv_encoder_config cfg;
+    uint8_t *pattern;
+    jv_block_weights *blocks;
+};
+
+extern "C" {
+
+jv_status jv_layernorm_fwd(const void *x, const float *gamma, const float *beta, void *y,
+                           int64_t rows, int32_t cols, float eps, jv_dtype x_dtype,
+                           jv_dtype y_dtype, void *hip_stream) {
+    jv::clear_error();
+    if (!x || !gamma || !beta || !y) return jv::fail(JV_ERR_INVALID_ARG, "null pointer");
+    if (rows <= 0 || cols <= 0) return jv::fail(JV_ERR_INVALID_ARG, "rows and cols must be positive");
+    if (cols % 8) return jv::fail(JV_ERR_UNSUPPORTED, "cols must be a multiple of 8");
+    if (cols > 8192) return jv::fail(JV_ERR_UNSUPPORTED, "cols above 8192");
+    if (rows > (1ll << 31)) return jv::fail(JV_ERR_UNSUPPORTED, "rows above 2^31");
+    if (!(eps >= 0.f)) return jv::fail(JV_ERR_INVALID_ARG, "eps must be >= 0");
+    if ((x_dtype != JV_F32 && x_dtype != JV_BF16) || (y_dtype != JV_F32 && y_dtype != JV_BF16))
+        return jv::fail(JV_ERR_INVALID_ARG, "unknown dtype");
+    if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta) & 15)
+        return jv::fail(JV_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    return jv::layernorm_forward(x, gamma, beta, y, rows, cols, eps, x_dtype == JV_BF16,
+                                 y_dtype == JV_BF16, (hipStream_t)hip_stream);
+}
+
+jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, const float *residual,
+                           void *y, int64_t M, int32_t N, int32_t K, jv_epilogue epilogue,
+                           jv_dtype y_dtype, void *hip_stream) {
+    jv::clear_error();
+    if (y_dtype != JV_F32 && y_dtype != JV_BF16) return jv::fail(JV_ERR_INVALID_ARG, "unknown dtype");
+    return jv::gemm_forward(a, w, bias, residual, y, M, N, K, (int)epilogue, y_dtype == JV_BF16,
+                            (hipStream_t)hip_stream);
+}
+
+jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weights *blocks,
+                            jv_encoder **out) {
+    jv::clear_error();
+    if (!config || !blocks || !out || !config->pattern)
+        return jv::fail(JV_ERR_INVALID_ARG, "null argument");
+    const jv_encoder_config &c = *config;
+    if (c.n_blocks <= 0 || c.n_blocks > 4096) return jv::fail(JV_ERR_INVALID_ARG, "bad n_blocks");
+    if (c.heads <= 0 || c.width != c.heads * jv::kHeadDim)
+        return jv::fail(JV_ERR_UNSUPPORTED, "width must be heads * 64");
+    if (c.mlp_hidden <= 0 || c.mlp_hidden % 64)
+        return jv::fail(JV_ERR_UNSUPPORTED, "mlp_hidden must be a positive multiple of 64");
+    if (c.win_h <= 0 || c.win_w <= 0) return jv::fail(JV_ERR_INVALID_ARG, "window must be positive");
+    if (!(c.ln_eps >= 0.f) || !(c.la_eps >= 0.f)) return jv::fail(JV_ERR_INVALID_ARG, "bad epsilon");
+    for (int l = 0; l < c.n_blocks; ++l) {
+        if (c.pattern[l] > 2) return jv::fail(JV_ERR_INVALID_ARG, "pattern[%d] is not 0, 1 or 2", l);
+        const jv_block_weights &b = blocks[l];
+        const void *ptrs[] = {b.ln1_g, b.ln1_b, b.w_qkv, b.b_qkv, b.w_o, b.b_o,
+                              b.ln2_g, b.ln2_b, b.w_fc1, b.b_fc1, b.w_fc2, b.b_fc2};
+        for (const void *p : ptrs)
+            if (!p || ((uintptr_t)p & 15))
+                return jv::fail(JV_ERR_INVALID_ARG, "block %d: null or misaligned weight pointer", l);
+    }
+    jv_encoder *e = new (std::nothrow) jv_encoder;
+    if (!e) return jv::fail(JV_ERR_INVALID_ARG, "out of host memory");
+    e->cfg = c;
+    e->pattern = new (std::nothrow) uint8_t[c.n_blocks];
+    e->blocks = new (std::nothrow) jv_block_weights[c.n_blocks];
+    if (!e->pattern || !e->blocks) {
+        delete[] e->pattern;
+        delete[] e->blocks;
+        delete e;
+        return jv::fail(JV_ERR_INVALID_ARG, "out of host memory");
+    }
+    for (int l = 0; l < c.n_blocks; ++l) {
+        e->pattern[l] = c.pattern[l];
+        e->blocks[l] = blocks[l];
+    }
+    e->cfg.pattern = e->pattern;
+    *out = e;
+    return JV_OK;
+}
+
+void jv_encoder_destroy(jv_encoder *enc) {
+    if (!enc) return;
+    delete[] enc->pattern;
+    delete[] enc->blocks;
+    delete enc;
+}
+
+// Workspace: [T, width] bf16 (LayerNorm output, later the mixer output), [T, max(3 width,
+// mlp_hidden)] bf16 (QKV, later the MLP hidden layer), then the linear-attention states.
+size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
+                                  int32_t grid_w) {
+    jv::clear_error();
+    if (!enc || batch <= 0 || grid_h <= 0 || grid_w <= 0) return 0;
+    const size_t T = (size_t)batch * grid_h * grid_w, C = enc->cfg.width;
+    const size_t wide = 3 * C > (size_t)enc->cfg.mlp_hidden ? 3 * C : (size_t)enc->cfg.mlp_hidden;
+    return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
+           jv::align256(jv::linear_workspace_bytes(batch, enc->cfg.heads, grid_h * grid_w));
+}
+
+jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+                             int32_t grid_h, int32_t grid_w, void *workspace,
+                             size_t workspace_bytes, void *hip_stream) {
+    jv::clear_error();
+    if (!enc || !x || !y || !workspace) return jv::fail(JV_ERR_INVALID_ARG, "null argument");
+    if (batch <= 0 || grid_h <= 0 || grid_w <= 0)
+        return jv::fail(JV_ERR_INVALID_ARG, "batch and grid must be positive");
+    if (((uintptr_t)x | (uintptr_t)y) & 15) return jv::fail(JV_ERR_INVALID_ARG, "x, y must be 16-byte aligned");
+    if ((uintptr_t)workspace & 255) return jv::fail(JV_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    const size_t need = jv_encoder_workspace_bytes(enc, batch, grid_h, grid_w);
+    if (workspace_bytes < need)
+        return jv::fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed",
+                        workspace_bytes, need);
+    const jv_encoder_config &c = enc->cfg;
+    const int N = grid_h * grid_w, C = c.width;
+    const long long T = (long long)batch * N;
+    if ((long long)batch * c.heads > 65535) return jv::fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t wide = 3 * (size_t)C > (size_t)c.mlp_hidden ? 3 * (size_t)C : (size_t)c.mlp_hidden;
+    unsigned char *ws = (unsigned char *)workspace;
+    __bf16 *narrow = (__bf16 *)ws;                                  // [T, C]
+    __bf16 *widebuf = (__bf16 *)(ws + jv::align256(T * C * 2));     // [T, 3C] or [T, hidden]
+    void *la_ws = ws + jv::align256(T * C * 2) + jv::align256(T * wide * 2);
+
+    // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
+    jv::Problem pr;
+    pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = N;
+    pr.bf16 = true; pr.o_bf16 = true;
+    const long long sb = (long long)N * 3 * C, sn = 3LL * C;
+    pr.q = {widebuf, sb, jv::kHeadDim, sn};
+    pr.k = {widebuf + C, sb, jv::kHeadDim, sn};
+    pr.v = {widebuf + 2 * C, sb, jv::kHeadDim, sn};
+    pr.o = {narrow, (long long)N * C, jv::kHeadDim, C};
+
+    jv_status st;
+    const float *resid = x;  // the first residual add reads the input and writes y
+    for (int l = 0; l < c.n_blocks; ++l) {
+        const jv_block_weights &b = enc->blocks[l];
+        if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
+        if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
+        switch (enc->pattern[l]) {
+            case 0: st = jv::linear_forward(pr, c.la_eps, la_ws, stream); break;
+            case 1: st = jv::window_forward(pr, c.win_h, c.win_w, 0.f, stream); break;
+            default: st = jv::full_forward(pr, 0.f, stream); break;
+        }
+        if (st != JV_OK) return st;
+        if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
+        resid = y;
+        if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
+        if ((st = jv::gemm_forward(narrow, b.w_fc1, b.b_fc1, nullptr, widebuf, T, c.mlp_hidden, C, JV_EPI_GELU, true, stream)) != JV_OK) return st;
+        if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, y, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
+    }
+    return JV_OK;
+}
+
+}  // extern "C"

@@ -127,6 +127,24 @@ la_apply_f32(TensorArg qt, TensorArg ot, const float *__restrict__ ws, int heads
     }
 }
 
+size_t linear_workspace_bytes(int B, int heads, int N) {
+    return linear_workspace_floats(plan_linear(B, heads, N), B, heads) * sizeof(float);
+}
+
+jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStream_t stream) {
+    LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
+    float *ws = (float *)workspace;
+    if (pr.bf16) return linear_bf16(pr, plan, eps, ws, stream);
+    const int BH = pr.B * pr.heads;
+    jv_status st;
+    hipLaunchKernelGGL(la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v, ws,
+                       pr.heads, pr.N, plan.chunk);
+    if ((st = launch_status("la_state_f32")) != JV_OK) return st;
+    hipLaunchKernelGGL(la_apply_f32, dim3((pr.N + 255) / 256, BH), dim3(256), 0, stream, pr.q, pr.o,
+                       ws, pr.heads, pr.N, plan.n_split, eps);
+    return launch_status("la_apply_f32");
+}
+
 }  // namespace jv
 
 extern "C" {
@@ -134,8 +152,7 @@ extern "C" {
 size_t jv_linear_attn_workspace_bytes(const jv_attn_desc *desc) {
     jv::clear_error();
     if (jv::check_desc(desc) != JV_OK) return 0;
-    jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
-    return jv::linear_workspace_floats(plan, desc->batch, desc->heads) * sizeof(float);
+    return jv::linear_workspace_bytes(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
 }
 
 jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
@@ -153,18 +170,7 @@ jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void
     if (workspace_bytes < need)
         return jv::fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed",
                         workspace_bytes, need);
-    jv::LinearPlan plan = jv::plan_linear(pr.B, pr.heads, pr.N);
-    hipStream_t stream = (hipStream_t)hip_stream;
-    float *ws = (float *)workspace;
-    if (pr.bf16) return jv::linear_bf16(pr, plan, eps, ws, stream);
-
-    const int BH = pr.B * pr.heads;
-    hipLaunchKernelGGL(jv::la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v,
-                       ws, pr.heads, pr.N, plan.chunk);
-    if ((st = jv::launch_status("la_state_f32")) != JV_OK) return st;
-    hipLaunchKernelGGL(jv::la_apply_f32, dim3((pr.N + 255) / 256, BH), dim3(256), 0, stream, pr.q,
-                       pr.o, ws, pr.heads, pr.N, plan.n_split, eps);
-    return jv::launch_status("la_apply_f32");
+    return jv::linear_forward(pr, eps, workspace, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

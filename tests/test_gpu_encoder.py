@@ -1,0 +1,123 @@
+"""GPU parity of the encoder pieces (LayerNorm, GEMM with fused epilogues) and of encoder blocks
+against the CPU oracle.  bf16 operands, fp32 accumulation: max |g - r| / RMS(r) <= 2e-2."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_26636_amd import binding, synth
+from parity import BF16_TOL, check, err_bf16, err_bf16_stored, err_fp32, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("rows,cols", [(37, 1024), (5, 64), (300, 4096), (3, 8), (64, 1000)])
+def test_layernorm(rows, cols):
+    x = synth.normal((rows, cols), 500 + cols) * 2.0 + 0.5
+    g, b = 1.0 + 0.1 * synth.normal((cols,), 501), 0.1 * synth.normal((cols,), 502)
+    ref = oracle.layernorm(x.astype(np.float64), g, b, 1e-6)
+    dx, dg, db = (torch.from_numpy(t).cuda() for t in (x, g, b))
+    y32 = torch.empty(rows, cols, device="cuda")
+    binding.jv_layernorm_fwd(dx, dg, db, y32, 1e-6)
+    check(err_fp32(to_host(y32), ref), 1e-4)
+    y16 = torch.empty(rows, cols, device="cuda", dtype=torch.bfloat16)
+    binding.jv_layernorm_fwd(dx, dg, db, y16, 1e-6)
+    assert torch.equal(y32.to(torch.bfloat16), y16)
+    xb = synth.round_to_bf16(x)
+    binding.jv_layernorm_fwd(torch.from_numpy(xb).cuda().to(torch.bfloat16), dg, db, y32, 1e-6)
+    check(err_fp32(to_host(y32), oracle.layernorm(xb.astype(np.float64), g, b, 1e-6)), 1e-4)
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (256, 256, 64),      # one tile, one K step
+    (300, 520, 192),     # ragged M and N, three K steps
+    (1, 8, 64),          # smallest
+    (1024, 768, 1024),   # several tiles per XCD slot
+    (515, 1024, 4096),   # long K
+])
+def test_gemm_epilogues(M, N, K):
+    a = synth.round_to_bf16(synth.normal((M, K), 600 + M))
+    w = synth.round_to_bf16(synth.normal((N, K), 601 + N, 1.0 / np.sqrt(K)))
+    bias = synth.normal((N,), 602) * 0.5
+    res = synth.normal((M, N), 603)
+    da, dw = (torch.from_numpy(t).cuda().to(torch.bfloat16) for t in (a, w))
+    db, dr = torch.from_numpy(bias).cuda(), torch.from_numpy(res).cuda()
+    plain = oracle.linear(a.astype(np.float64), w, bias)
+    y32 = torch.full((M, N), float("nan"), device="cuda")
+    binding.jv_gemm_bias_act(da, dw, db, None, y32, binding.JV_EPI_NONE)
+    check(err_bf16(to_host(y32), plain), 1e-4)           # exact bf16 products, fp32 accumulation
+    y16 = torch.full((M, N), float("nan"), device="cuda", dtype=torch.bfloat16)
+    binding.jv_gemm_bias_act(da, dw, db, None, y16, binding.JV_EPI_NONE)
+    assert torch.equal(y32.to(torch.bfloat16), y16)
+    binding.jv_gemm_bias_act(da, dw, None, None, y32, binding.JV_EPI_NONE)
+    check(err_bf16(to_host(y32), plain - bias), 1e-4)
+    binding.jv_gemm_bias_act(da, dw, db, None, y32, binding.JV_EPI_GELU)
+    check(err_bf16(to_host(y32), oracle.gelu(plain)), 2e-4)   # erf approximated to 2.5e-5
+    binding.jv_gemm_bias_act(da, dw, db, dr, y32, binding.JV_EPI_RESIDUAL)
+    check(err_bf16(to_host(y32), plain + res), 1e-4)
+    inplace = dr.clone()
+    binding.jv_gemm_bias_act(da, dw, db, inplace, inplace, binding.JV_EPI_RESIDUAL)
+    assert torch.equal(inplace, y32)
+
+
+def test_gemm_rejects_unsupported_shapes():
+    a = torch.zeros(8, 96, device="cuda", dtype=torch.bfloat16)
+    w = torch.zeros(16, 96, device="cuda", dtype=torch.bfloat16)
+    y = torch.zeros(8, 16, device="cuda")
+    with pytest.raises(binding.JvError) as e:
+        binding.jv_gemm_bias_act(a, w, None, None, y)
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
+
+
+def _device_blocks(blocks):
+    out = []
+    for b in blocks:
+        d = {}
+        for k, v in b.items():
+            t = torch.from_numpy(v).cuda()
+            d[k] = t.to(torch.bfloat16) if k.startswith("w_") else t
+        out.append(d)
+    return out
+
+
+def test_small_encoder_each_mixer_and_pattern():
+    B, H, W, heads, hidden = 2, 8, 8, 2, 256
+    C = heads * 64
+    x = synth.normal((B, H * W, C), 700)
+    blocks = [synth.block_weights(C, hidden, 710 + i) for i in range(3)]
+    for b in blocks:                                    # non-trivial biases and LayerNorm parameters
+        for key in ("b_qkv", "b_o", "b_fc1", "b_fc2", "ln1_b", "ln2_b"):
+            b[key] = synth.normal(b[key].shape, 720 + len(key)) * 0.1
+        b["ln1_g"] = 1.0 + 0.1 * synth.normal((C,), 730)
+    dev = _device_blocks(blocks)
+    dx = torch.from_numpy(x).cuda()
+    for pattern in ([0, 0, 0], [1, 1, 1], [2, 2, 2], [0, 1, 2]):
+        enc = binding.Encoder(dev, pattern, heads, hidden, window=(4, 4))
+        y = torch.empty_like(dx)
+        enc.forward(dx, y, (H, W))
+        ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 4))
+        check(err_bf16(to_host(y), ref), BF16_TOL)
+        y2 = dx.clone()
+        enc.forward(y2, y2, (H, W))                     # in place
+        assert torch.equal(y, y2)
+        enc.close()
+
+
+def test_vit_l_blocks_teacher_forced():
+    """One ViT-L block per mixer type at the encoder workload's width (1024, 16 heads, MLP 4096)
+    on a 32 x 32 grid, each fed the same input: per-block parity at full width."""
+    B, H, W, heads, hidden = 1, 32, 32, 16, 4096
+    C = heads * 64
+    x = synth.normal((B, H * W, C), 800)
+    wts = synth.block_weights(C, hidden, 810)
+    dev = _device_blocks([wts])
+    dx = torch.from_numpy(x).cuda()
+    for mixer in (0, 1, 2):
+        enc = binding.Encoder(dev, [mixer], heads, hidden, window=(16, 16))
+        y = torch.empty_like(dx)
+        enc.forward(dx, y, (H, W))
+        ref = oracle.encoder_block(x.astype(np.float64), wts, mixer, H, W, heads, (16, 16))
+        check(err_bf16(to_host(y), ref), BF16_TOL)
+        # the block's own contribution (output minus input) is what the kernels computed
+        check(err_bf16(to_host(y) - x, ref - x), BF16_TOL)
+        enc.close()
