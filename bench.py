@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="mixer workload (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--buffers", type=int, default=6, help="rotating input/output sets")
+    ap.add_argument("--encoder", action="store_true",
+                    help="time the hybrid ViT-L encoder forward (config 5) instead of the mixer step")
     ap.add_argument("--only", choices=["linear", "window", "full"], default=None,
                     help="run only this mixer's timing loop (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -48,6 +50,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.lib()
+    if args.encoder:
+        return bench_encoder(args)
     c = synth.CONFIGS[args.config]
     B, heads, H, W, d = c["B"], c["heads"], c["H"], c["W"], c["d"]
     N = H * W
@@ -165,6 +169,53 @@ def main():
         "per_mixer": per, "roofline": roofline, "rooflines": rooflines, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def bench_encoder(args):
+    """Config 5: 24 pre-LN blocks of width 1024 (16 heads, MLP 4096), batch 4 on a 64x64 grid;
+    full attention at blocks 5, 11, 17, 23, window 16x16 at the other even blocks, linear
+    attention at the rest.  Random-init (Xavier-normal, seeded) bf16 weights, fp32 residual."""
+    import torch
+    from paper_2605_26636_amd import binding, synth
+    B, H, W, heads, hidden, L = 4, 64, 64, 16, 4096, 24
+    C, N = heads * 64, H * W
+    pattern = synth.encoder_pattern(L)
+    blocks = []
+    for l in range(L):
+        wts = synth.block_weights(C, hidden, 5000 + l)
+        blocks.append({k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_")
+                           else torch.from_numpy(v).cuda()) for k, v in wts.items()})
+    enc = binding.Encoder(blocks, pattern, heads, hidden, window=(16, 16))
+    x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda()
+    y = torch.empty_like(x)
+    ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        enc.forward(x, y, (H, W), ws, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        enc.forward(x, y, (H, W), ws, stream)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    T = B * N
+    gemm_flops = 2.0 * T * C * (3 * C + C + 2 * hidden) * L
+    n_full, n_win, n_lin = pattern.count(2), pattern.count(1), pattern.count(0)
+    mix_flops = B * heads * (n_full * 4.0 * N * N * 64 + n_win * 4.0 * N * 256 * 64 +
+                             n_lin * (4.0 * 64 * 64 + 128) * N)
+    flops = gemm_flops + mix_flops
+    tf = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "hybrid ViT-L encoder forward, tokens/s per encoder", "value": T / (ms * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config5: 24-block hybrid ViT-L encoder, B{B} {H}x{W} grid, width {C}, "
+                               f"{n_full} full / {n_win} window16x16 / {n_lin} linear blocks"},
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "flops_per_step": flops, "gemm_flops": gemm_flops},
+        "cpu_baseline": None}))
 
 
 def cpu_baseline(q, k, v, H, W, window):

@@ -108,10 +108,14 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // GEMM  y = epilogue(a w^T + bias):  a [M, K], w [N, K], both bf16 with K contiguous, so both
 // matrix-instruction operands are 16-byte row pieces.  One workgroup (4 wavefronts, one per
 // SIMD, the whole register file each) owns a 256 x 256 tile of y; a wavefront owns 128 x 128 of
-// it (4 x 4 blocks of 32 x 32, 256 accumulator registers).  K is walked in steps of 64: the
-// 256 x 64 tiles of a and w go from global memory straight into LDS (no register staging),
-// double-buffered; rows are 128 bytes in LDS with the 16-byte chunk index rotated by the row
-// so that the row-per-lane operand reads spread over all banks.
+// it (4 x 4 blocks of 32 x 32, 256 accumulator registers).  K is walked in steps of 32: the
+// 256 x 32 tiles of a and w go from global memory straight into LDS (no register staging)
+// through a ring of four stages, three steps ahead of the arithmetic: with 64 KB per step and
+// compute unit, the L2 round trip is longer than one step of arithmetic, so several steps
+// have to be in flight.  The wait before each step is therefore a counted one (the loads of
+// the two later stages may still be outstanding), written by hand next to the barrier.
+// Rows are 64 bytes in LDS; the 16-byte chunk index is rotated by the row pair so that the
+// row-per-lane operand reads spread over all banks.
 // The product is formed transposed (features x tokens): a lane then holds 4 consecutive output
 // features of one token, which makes the epilogue loads (bias, residual) and stores 8 or 16
 // bytes wide.
@@ -119,10 +123,11 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // range of tiles, feature-tile fastest: they share the a row-tile and keep w in that L2.
 // grid (8 * ceil(tiles / 8)), 256 threads, kGemmLds bytes of dynamic LDS.
 // ---------------------------------------------------------------------------------------
-constexpr int kBM = 256, kBN = 256, kBK = 64;
-constexpr int kGemmTileBytes = kBM * kBK * 2;          // one operand tile: 32 KB
-constexpr int kGemmStage = 2 * kGemmTileBytes;         // a tile then w tile
-constexpr int kGemmLds = 2 * kGemmStage;               // two stages: 128 KB
+constexpr int kBM = 256, kBN = 256, kBK = 32;
+constexpr int kGemmTileBytes = kBM * kBK * 2;          // one operand tile: 16 KB
+constexpr int kGemmStage = 2 * kGemmTileBytes;         // a tile then w tile: 32 KB
+constexpr int kGemmStages = 4;
+constexpr int kGemmLds = kGemmStages * kGemmStage;     // 128 KB
 
 typedef __attribute__((address_space(1))) const void global_cvoid;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -138,6 +143,19 @@ __device__ inline float gelu_erf(float x) {
     return 0.5f * x * (1.0f + erf_x);
 }
 
+// Byte offset of 16-byte chunk `chunk` (0..3) of row `row` in a [rows][32] bf16 LDS tile.
+__device__ inline unsigned gemm_tile_off(int row, int chunk) {
+    return (unsigned)(row * 64 + ((chunk ^ ((row >> 1) & 3)) << 4));
+}
+
+// Wait until at most `pending` of this wavefront's vector-memory loads are outstanding, then
+// the workgroup barrier.  "memory" keeps the compiler from moving LDS traffic across it.
+__device__ inline void wait_loads_and_barrier(int pending) {
+    if (pending >= 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (pending >= 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int EPI, bool OUT_BF16>
 __global__ void __launch_bounds__(256, 1)
 gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
@@ -151,28 +169,29 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     const int m0 = (tile / tiles_n) * kBM, n0 = (tile % tiles_n) * kBN;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // Global -> LDS: a wavefront moves rows 64*wave .. +63 of both tiles, 8 rows (1 KB) per
-    // instruction; lane = 8 * (row in group) + LDS chunk slot, and it fetches the global chunk
-    // that belongs in that slot under the row rotation.
-    const int lrow = lane >> 3, gchunk = (lane & 7) ^ lrow;
-    unsigned a_off[8], w_off[8];  // byte offsets of this lane's 16 bytes, k = 0
+    // Global -> LDS: a wavefront moves rows 64*wave .. +63 of both tiles, 16 rows (1 KB) per
+    // instruction; lane = 4 * (row in group) + LDS chunk slot, and it fetches the global chunk
+    // that belongs in that slot under the row rotation.  Eight loads per wavefront and stage.
+    const int lrow = lane >> 2, gchunk = (lane & 3) ^ ((lrow >> 1) & 3);
+    unsigned a_off[4], w_off[4];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int r = wave * 64 + j * 8 + lrow;
+    for (int j = 0; j < 4; ++j) {
+        const int r = wave * 64 + j * 16 + lrow;
         const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);  // edge tiles re-read the last row
         a_off[j] = 2u * ((unsigned)ar * (unsigned)K + gchunk * 8);
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
-    auto issue_loads = [&](int k0, int buf) {
-        unsigned char *abase = smem + buf * kGemmStage + wave * 64 * 128;
+    auto issue_loads = [&](int kt) {
+        unsigned char *abase = smem + (kt & (kGemmStages - 1)) * kGemmStage + wave * 64 * 64;
         unsigned char *wbase = abase + kGemmTileBytes;
+        const unsigned kbytes = 2u * kt * kBK;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < 4; ++j) {
             __builtin_amdgcn_global_load_lds(
-                (global_cvoid *)((const char *)A + (a_off[j] + 2u * k0)),
+                (global_cvoid *)((const char *)A + (a_off[j] + kbytes)),
                 (lds_void *)(abase + j * 1024), 16, 0, 0);
             __builtin_amdgcn_global_load_lds(
-                (global_cvoid *)((const char *)W + (w_off[j] + 2u * k0)),
+                (global_cvoid *)((const char *)W + (w_off[j] + kbytes)),
                 (lds_void *)(wbase + j * 1024), 16, 0, 0);
         }
     };
@@ -186,54 +205,94 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
 
     const int n_k = K / kBK;
-    issue_loads(0, 0);
-    __syncthreads();  // the compiler waits for the LDS-bound loads before the barrier
+    for (int kt = 0; kt < kGemmStages - 1 && kt < n_k; ++kt) issue_loads(kt);
     for (int kt = 0; kt < n_k; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < n_k) issue_loads((kt + 1) * kBK, buf ^ 1);
-        const unsigned char *at = smem + buf * kGemmStage, *wt = at + kGemmTileBytes;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 aop[4], wop[4];
+        // Stage kt has landed once at most the loads of the stages after it are pending; after
+        // the barrier every wavefront is also done with stage kt-1, whose buffer is refilled.
+        const int later = min(n_k - 1 - kt, kGemmStages - 2);
+        wait_loads_and_barrier(8 * later);
+        if (kt + kGemmStages - 1 < n_k) issue_loads(kt + kGemmStages - 1);
+        const unsigned char *at = smem + (kt & (kGemmStages - 1)) * kGemmStage;
+        const unsigned char *wt = at + kGemmTileBytes;
+        // Operand registers are double-buffered across the two k-steps of the stage: the LDS
+        // reads of the second step are issued among the matrix instructions of the first
+        // (one read per two matrix instructions; the scheduling groups below pin that order).
+        bf16x8 aop[2][4], wop[2][4];
+        auto load_ops = [&](int ks, int slot) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                aop[i] = as_bf16x8(*(const u32x4 *)(at + tile_off_row(wm * 128 + i * 32 + li, 2 * ks + g)));
-                wop[i] = as_bf16x8(*(const u32x4 *)(wt + tile_off_row(wn * 128 + i * 32 + li, 2 * ks + g)));
+                aop[slot][i] = as_bf16x8(*(const u32x4 *)(at + gemm_tile_off(wm * 128 + i * 32 + li, 2 * ks + g)));
+                wop[slot][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_tile_off(wn * 128 + i * 32 + li, 2 * ks + g)));
             }
+        };
+        load_ops(0, 0);
+        load_ops(1, 1);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[nt], aop[mt], acc[nt][mt]);
+                for (int mt = 0; mt < 4; ++mt)
+                    acc[nt][mt] = mfma32(wop[ks][nt], aop[ks][mt], acc[nt][mt]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);  // LDS reads of step 0
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {                       // step 0: read, two products
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
-        __syncthreads();
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0); // step 1
     }
 
     // Epilogue: accumulator register v of block (nt, mt) is output feature
     // n0 + 128 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
+    // Loads are batched ahead of their use (all bias pieces once, the residual pieces of a
+    // token block together) so that their latencies overlap instead of adding up.
+    f32x4 bias_reg[4][4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
+            f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            bias_reg[nt][q4] = (bias && col < N) ? *(const f32x4 *)(bias + col) : zero;
+        }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int row = m0 + wm * 128 + mt * 32 + li;
-        if (row >= M) continue;
+        const bool row_ok = row < M;
+        f32x4 res_reg[4][4];
+        if (EPI == JV_EPI_RESIDUAL) {
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
+                    f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    res_reg[nt][q4] = (row_ok && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
+                }
+        }
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
-                if (col >= N) continue;  // N % 8 == 0: the four features are in or out together
+                // N % 8 == 0: the four features of a piece are in or out together
                 f32x4 val = {acc[nt][mt][4 * q4], acc[nt][mt][4 * q4 + 1], acc[nt][mt][4 * q4 + 2],
                              acc[nt][mt][4 * q4 + 3]};
-                if (bias) val += *(const f32x4 *)(bias + col);
-                const size_t at_out = (size_t)row * N + col;
+                val += bias_reg[nt][q4];
                 if (EPI == JV_EPI_GELU) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) val[e] = gelu_erf(val[e]);
                 }
-                if (EPI == JV_EPI_RESIDUAL) val += *(const f32x4 *)(residual + at_out);
-                if (OUT_BF16) {
-                    u32x2 pk = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
-                    *(u32x2 *)((__bf16 *)Y + at_out) = pk;
-                } else {
-                    *(f32x4 *)((float *)Y + at_out) = val;
+                if (EPI == JV_EPI_RESIDUAL) val += res_reg[nt][q4];
+                if (row_ok && col < N) {
+                    const size_t at_out = (size_t)row * N + col;
+                    if (OUT_BF16) {
+                        u32x2 pk = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
+                        *(u32x2 *)((__bf16 *)Y + at_out) = pk;
+                    } else {
+                        *(f32x4 *)((float *)Y + at_out) = val;
+                    }
                 }
             }
     }
@@ -265,7 +324,7 @@ static jv_status gemm_forward(const void *a, const void *w, const float *bias,
     if (!a || !w || !y) return fail(JV_ERR_INVALID_ARG, "a, w, y must be non-null");
     if (((uintptr_t)a | (uintptr_t)w | (uintptr_t)y | (uintptr_t)bias | (uintptr_t)residual) & 15)
         return fail(JV_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
-    if (K % kBK) return fail(JV_ERR_UNSUPPORTED, "K must be a multiple of 64");
+    if (K % 64) return fail(JV_ERR_UNSUPPORTED, "K must be a multiple of 64");
     if (N % 8) return fail(JV_ERR_UNSUPPORTED, "N must be a multiple of 8");
     if (M * (long long)K >= (1ll << 30) || (long long)N * K >= (1ll << 30) || M > (1 << 24))
         return fail(JV_ERR_UNSUPPORTED, "operand above 2^30 elements");

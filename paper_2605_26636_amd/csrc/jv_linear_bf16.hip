@@ -118,15 +118,27 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int
     }
 }
 
-// grid (B*heads), 256 threads: dst[bh] = sum_p ws[p][bh].
+// grid (B*heads, ceil(kStateFloats / 1024)), 256 threads: dst[bh] = sum_p ws[p][bh], one
+// 16-byte piece per thread, the loads of eight partials in flight at a time.
 __global__ void __launch_bounds__(256)
 la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
     const int bh = blockIdx.x, BH = gridDim.x;
-    for (int e = threadIdx.x; e < kStateFloats; e += 256) {
-        float s = 0.f;
-        for (int p = 0; p < n_split; ++p) s += ws[((size_t)p * BH + bh) * kStateFloats + e];
-        dst[(size_t)bh * kStateFloats + e] = s;
+    const int e4 = blockIdx.y * 256 + threadIdx.x;
+    if (e4 >= kStateFloats / 4) return;
+    const f32x4 *src = (const f32x4 *)ws + (size_t)bh * (kStateFloats / 4) + e4;
+    const size_t stride4 = (size_t)BH * (kStateFloats / 4);
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int p0 = 0; p0 < n_split; p0 += 8) {
+        f32x4 part[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            part[i] = p0 + i < n_split ? src[(size_t)(p0 + i) * stride4] : zero;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += part[i];
     }
+    ((f32x4 *)dst)[(size_t)bh * (kStateFloats / 4) + e4] = sum;
 }
 
 // grid (ceil(N / tokens_per_wg), B*heads), 256 threads.
@@ -303,7 +315,8 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
     long long part_stride = (long long)BH * kStateFloats;
     if (plan.combine) {
         float *dst = ws + (size_t)plan.n_split * BH * kStateFloats;
-        hipLaunchKernelGGL(la_combine, dim3(BH), dim3(256), 0, stream, ws, dst, plan.n_split);
+        hipLaunchKernelGGL(la_combine, dim3(BH, (kStateFloats / 4 + 255) / 256), dim3(256), 0, stream, ws, dst,
+                           plan.n_split);
         if ((st = launch_status("la_combine")) != JV_OK) return st;
         states = dst;
         n_part = 1;
