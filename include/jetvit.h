@@ -97,6 +97,40 @@ jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void
                              size_t workspace_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * The paper's linear-attention block (Sec. 3.2.1, Eq. 4): the normalised ReLU linear attention
+ * above plus a depth-wise convolution of V on the token grid,
+ *     O = LA(Q, K, V) + DWC(V).
+ * V is viewed as [batch, C = heads*64, grid_h, grid_w] (channel = head*64 + c); DWC is a
+ * depth-wise (one filter per channel) ksize x ksize cross-correlation, stride 1, zero padding
+ * ksize/2, no bias; its result is added in fp32 before O is rounded.
+ *   JV_DWC_NONE             plain linear attention (same result as jv_linear_attn_fwd).
+ *   JV_DWC_STATIC           one filter bank static_kernel, device fp32 [C, ksize, ksize].
+ *   JV_DWC_SQUEEZE_DYNAMIC  the block the paper proposes ("Squeeze Dynamic Convolution"): the
+ *       filter bank is generated per image from the token average of V by a two-layer MLP
+ *       with SiLU and is shared by all tokens of that image:
+ *           g = mean_n V[b, :, n];  u = silu(w1 g + b1);  kernel[b] = reshape(w2 u + b2, [C, k, k])
+ *       w1 fp32 [hidden, C], b1 fp32 [hidden], w2 fp32 [C*k*k, hidden], b2 fp32 [C*k*k], device.
+ *       The token sum of V is taken in the same pass that reduces K and V into the state.
+ * ksize is 3 or 5; C <= 8192 and hidden <= 1024 (JV_ERR_UNSUPPORTED otherwise).  Pointers the
+ * mode does not use are ignored.  workspace as for jv_linear_attn_fwd, sized by
+ * jv_linear_block_workspace_bytes (0 for an invalid descriptor or parameter block).
+ * ------------------------------------------------------------------------- */
+typedef enum { JV_DWC_NONE = 0, JV_DWC_STATIC = 1, JV_DWC_SQUEEZE_DYNAMIC = 2 } jv_dwc_mode;
+
+typedef struct {
+    jv_dwc_mode mode;
+    int32_t ksize;              /* 3 or 5 */
+    int32_t hidden;             /* hidden width of the generator (squeeze-dynamic only) */
+    const float *static_kernel; /* device, [C, ksize, ksize] (static only) */
+    const float *w1, *b1, *w2, *b2; /* device (squeeze-dynamic only) */
+} jv_dwc_params;
+
+size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_params *dwc);
+jv_status jv_linear_block_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                              const void *v, void *o, float eps, const jv_dwc_params *dwc,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Window partition (Sec. 3.2.2: the feature map is split into non-overlapping
  * windows).  The grid is extended at the bottom and right to multiples of the
  * window (padded_h x padded_w); windows are anchored at (0, 0) and numbered

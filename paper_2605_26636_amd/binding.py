@@ -19,12 +19,14 @@ JV_F32, JV_BF16 = 0, 1
 EXPORTS = [
     "jv_version", "jv_status_string", "jv_last_error",
     "jv_linear_attn_workspace_bytes", "jv_linear_attn_fwd",
+    "jv_linear_block_workspace_bytes", "jv_linear_block_fwd",
     "jv_window_geometry", "jv_window_maps_host", "jv_window_maps_device",
     "jv_window_attn_fwd", "jv_full_attn_fwd",
     "jv_layernorm_fwd", "jv_gemm_bias_act",
     "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_destroy",
 ]
 JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL = 0, 1, 2
+JV_DWC_NONE, JV_DWC_STATIC, JV_DWC_SQUEEZE_DYNAMIC = 0, 1, 2
 
 
 class JvStrides(ctypes.Structure):
@@ -37,6 +39,12 @@ class JvAttnDesc(ctypes.Structure):
                 ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int), ("o_dtype", ctypes.c_int),
                 ("q", JvStrides), ("k", JvStrides), ("v", JvStrides), ("o", JvStrides)]
+
+
+class JvDwcParams(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int), ("ksize", ctypes.c_int32), ("hidden", ctypes.c_int32),
+                ("static_kernel", ctypes.c_void_p), ("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p),
+                ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
 
 
 class JvEncoderConfig(ctypes.Structure):
@@ -79,6 +87,11 @@ def lib():
         vp = ctypes.c_void_p
         L.jv_linear_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
                                          ctypes.c_float, vp, ctypes.c_size_t, vp]
+        L.jv_linear_block_workspace_bytes.restype = ctypes.c_size_t
+        L.jv_linear_block_workspace_bytes.argtypes = [ctypes.POINTER(JvAttnDesc),
+                                                      ctypes.POINTER(JvDwcParams)]
+        L.jv_linear_block_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp, ctypes.c_float,
+                                          ctypes.POINTER(JvDwcParams), vp, ctypes.c_size_t, vp]
         L.jv_window_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp]
         L.jv_full_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
@@ -163,6 +176,42 @@ def jv_linear_attn_fwd(q, k, v, o, grid, eps=1e-6, workspace=None, stream=None):
     _check(lib().jv_linear_attn_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                     o.data_ptr(), eps, workspace.data_ptr(),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+    return workspace
+
+
+def make_dwc_params(static_kernel=None, squeeze=None, ksize=3):
+    """jv_dwc_params from device fp32 tensors: static_kernel [C, k, k], or squeeze =
+    (w1 [hidden, C], b1 [hidden], w2 [C*k*k, hidden], b2 [C*k*k]); neither = no convolution."""
+    if static_kernel is not None and squeeze is not None:
+        raise ValueError("give a static kernel or generator weights, not both")
+    for t in ([static_kernel] if static_kernel is not None else []) + list(squeeze or []):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("convolution parameters must be contiguous fp32 device tensors")
+    if static_kernel is not None:
+        return JvDwcParams(JV_DWC_STATIC, ksize, 0, static_kernel.data_ptr(), None, None, None, None)
+    if squeeze is not None:
+        w1, b1, w2, b2 = squeeze
+        return JvDwcParams(JV_DWC_SQUEEZE_DYNAMIC, ksize, w1.shape[0], None, w1.data_ptr(),
+                           b1.data_ptr(), w2.data_ptr(), b2.data_ptr())
+    return JvDwcParams(JV_DWC_NONE, ksize, 0, None, None, None, None, None)
+
+
+def jv_linear_block_workspace_bytes(desc, dwc):
+    return int(lib().jv_linear_block_workspace_bytes(ctypes.byref(desc), ctypes.byref(dwc)))
+
+
+def jv_linear_block_fwd(q, k, v, o, grid, eps=1e-6, static_kernel=None, squeeze=None, ksize=3,
+                        workspace=None, stream=None):
+    """o <- linear attention + depth-wise convolution of v (the paper's linear-attention block);
+    returns the workspace tensor used."""
+    desc = make_desc(q, k, v, o, grid)
+    dwc = make_dwc_params(static_kernel, squeeze, ksize)
+    if workspace is None:
+        need = jv_linear_block_workspace_bytes(desc, dwc)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib().jv_linear_block_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                     o.data_ptr(), eps, ctypes.byref(dwc), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
     return workspace
 
 

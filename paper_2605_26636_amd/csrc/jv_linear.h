@@ -1,4 +1,5 @@
-// Internal: launch plan of the two-pass linear attention, shared by the fp32 and bf16 paths.
+// Internal: launch plan of the two-pass linear attention and of the block's convolution branch,
+// shared by the fp32 and bf16 paths.
 #pragma once
 #include "jv_common.h"
 
@@ -16,7 +17,40 @@ struct LinearPlan {
 LinearPlan plan_linear(int B, int heads, int N);
 size_t linear_workspace_floats(const LinearPlan &p, int B, int heads);
 
+// The depth-wise convolution branch of the block (Eq. 4) as the launchers see it.  Workspace
+// regions (float offsets from the workspace base) follow the linear-attention states.
+struct DwcPlan {
+    int mode = JV_DWC_NONE;  // jv_dwc_mode
+    int ksize = 3, hidden = 0;
+    const float *static_kernel = nullptr, *w1 = nullptr, *b1 = nullptr, *w2 = nullptr, *b2 = nullptr;
+    size_t vsum_off = 0;    // [n_split][B*heads][64] partial token sums of V (dynamic mode)
+    size_t hidden_off = 0;  // [B][hidden] generator hidden layer (dynamic mode)
+    size_t kappa_off = 0;   // [B][C][k*k] generated filters (dynamic mode)
+    size_t total_floats = 0;
+};
+// Fills the offsets for a validated parameter block; dwc may be null (mode none).
+jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int heads, DwcPlan *out);
+
+// What the apply kernels need of the convolution: filters [.., C, k*k] with a batch stride
+// (0 for a static bank) on the H x W grid.
+struct DwcArg {
+    const float *kappa;
+    long long kappa_sb;
+    int H, W;
+};
+
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
-                      hipStream_t stream);
+                      const DwcPlan &dwc, hipStream_t stream);
+
+// Generator of the dynamic filters: partial token sums of V -> hidden layer -> filters.
+jv_status squeeze_generate(const DwcPlan &dwc, float *ws, int n_part, int B, int heads, int N,
+                           hipStream_t stream);
+
+// fp32 tensors: partial token sums of V, and o += DWC(v) as a pass of its own.
+jv_status vsum_f32_launch(const Problem &pr, const LinearPlan &plan, float *vsum, hipStream_t stream);
+jv_status dwc_add_f32_launch(const Problem &pr, const DwcArg &cv, int ksize, hipStream_t stream);
+
+jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params *dwc,
+                               void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace jv

@@ -131,46 +131,82 @@ size_t linear_workspace_bytes(int B, int heads, int N) {
     return linear_workspace_floats(plan_linear(B, heads, N), B, heads) * sizeof(float);
 }
 
-jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStream_t stream) {
-    LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
+// The block of Eq. 4.  Order of launches: state pass (which also sums V over the tokens when
+// the filters are generated from it), optional combine, filter generator, apply pass (bf16:
+// the convolution is fused into it; fp32: a pass of its own adds it).
+jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params *dwc,
+                               void *workspace, size_t workspace_bytes, hipStream_t stream) {
+    const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
+    DwcPlan cv;
+    jv_status st = plan_dwc(dwc, plan, pr.B, pr.heads, &cv);
+    if (st != JV_OK) return st;
+    if (workspace_bytes < cv.total_floats * sizeof(float))
+        return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                    cv.total_floats * sizeof(float));
     float *ws = (float *)workspace;
-    if (pr.bf16) return linear_bf16(pr, plan, eps, ws, stream);
+    if (pr.bf16) return linear_bf16(pr, plan, eps, ws, cv, stream);
     const int BH = pr.B * pr.heads;
-    jv_status st;
     hipLaunchKernelGGL(la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v, ws,
                        pr.heads, pr.N, plan.chunk);
     if ((st = launch_status("la_state_f32")) != JV_OK) return st;
     hipLaunchKernelGGL(la_apply_f32, dim3((pr.N + 255) / 256, BH), dim3(256), 0, stream, pr.q, pr.o,
                        ws, pr.heads, pr.N, plan.n_split, eps);
-    return launch_status("la_apply_f32");
+    if ((st = launch_status("la_apply_f32")) != JV_OK) return st;
+    if (cv.mode == JV_DWC_NONE) return JV_OK;
+    DwcArg arg = {cv.static_kernel, 0, pr.H, pr.W};
+    if (cv.mode == JV_DWC_SQUEEZE_DYNAMIC) {
+        if ((st = vsum_f32_launch(pr, plan, ws + cv.vsum_off, stream)) != JV_OK) return st;
+        if ((st = squeeze_generate(cv, ws, plan.n_split, pr.B, pr.heads, pr.N, stream)) != JV_OK) return st;
+        arg.kappa = ws + cv.kappa_off;
+        arg.kappa_sb = (long long)pr.heads * kHeadDim * cv.ksize * cv.ksize;
+    }
+    return dwc_add_f32_launch(pr, arg, cv.ksize, stream);
+}
+
+jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStream_t stream) {
+    return linear_block_forward(pr, eps, nullptr, workspace, linear_workspace_bytes(pr.B, pr.heads, pr.N), stream);
 }
 
 }  // namespace jv
 
+static jv_status check_linear_args(float eps, const void *workspace) {
+    if (!(eps >= 0.0f)) return jv::fail(JV_ERR_INVALID_ARG, "eps must be >= 0");
+    if (!workspace) return jv::fail(JV_ERR_INVALID_ARG, "workspace is null");
+    if ((uintptr_t)workspace & 255)
+        return jv::fail(JV_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    return JV_OK;
+}
+
 extern "C" {
 
 size_t jv_linear_attn_workspace_bytes(const jv_attn_desc *desc) {
+    return jv_linear_block_workspace_bytes(desc, nullptr);
+}
+
+size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_params *dwc) {
     jv::clear_error();
     if (jv::check_desc(desc) != JV_OK) return 0;
-    return jv::linear_workspace_bytes(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
+    jv::DwcPlan cv;
+    const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
+    if (jv::plan_dwc(dwc, plan, desc->batch, desc->heads, &cv) != JV_OK) return 0;
+    return cv.total_floats * sizeof(float);
 }
 
 jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void *k,
                              const void *v, void *o, float eps, void *workspace,
                              size_t workspace_bytes, void *hip_stream) {
+    return jv_linear_block_fwd(desc, q, k, v, o, eps, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+jv_status jv_linear_block_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                              const void *v, void *o, float eps, const jv_dwc_params *dwc,
+                              void *workspace, size_t workspace_bytes, void *hip_stream) {
     jv::clear_error();
     jv::Problem pr;
     jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
     if (st != JV_OK) return st;
-    if (!(eps >= 0.0f)) return jv::fail(JV_ERR_INVALID_ARG, "eps must be >= 0");
-    if (!workspace) return jv::fail(JV_ERR_INVALID_ARG, "workspace is null");
-    if ((uintptr_t)workspace & 255)
-        return jv::fail(JV_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
-    const size_t need = jv_linear_attn_workspace_bytes(desc);
-    if (workspace_bytes < need)
-        return jv::fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed",
-                        workspace_bytes, need);
-    return jv::linear_forward(pr, eps, workspace, (hipStream_t)hip_stream);
+    if ((st = check_linear_args(eps, workspace)) != JV_OK) return st;
+    return jv::linear_block_forward(pr, eps, dwc, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

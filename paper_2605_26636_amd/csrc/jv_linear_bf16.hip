@@ -15,11 +15,15 @@
 namespace jv {
 
 constexpr int kWaveLds = 64 * 68 * 4;  // per-wave LDS: K and V tiles (16 KB) or a padded state
-constexpr int kStateLds = 4 * kWaveLds + 8 * kHeadDim * 4;
+constexpr int kStateLds = 4 * kWaveLds + 2 * 8 * kHeadDim * 4;
 
 // grid (n_split, B*heads), 256 threads, kStateLds bytes of dynamic LDS.
+// VSUM: also write the chunk's token sum of V (the input of the dynamic-filter generator of
+// the block's convolution branch) to vsum[part][bh][64]; it falls out of the V operands.
+template <bool VSUM>
 __global__ void __launch_bounds__(256, 2)
-la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int N, int chunk) {
+la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restrict__ vsum,
+              int heads, int N, int chunk) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
     const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x;
@@ -38,7 +42,7 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    float zacc[2] = {0.f, 0.f};
+    float zacc[2] = {0.f, 0.f}, vacc[2] = {0.f, 0.f};
 
     u32x4 kreg[8], vreg[8];
     auto fetch = [&](int t0) {
@@ -81,6 +85,14 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = mfma32(a[mi], bv[ni], acc[mi][ni]);
             }
+            if (VSUM) {
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    u32x4 bu = as_u32x4(bv[ni]);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) vacc[ni] = add_bf16x2(bu[w], vacc[ni]);
+                }
+            }
         }
     }
 
@@ -100,7 +112,10 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int
                 *(f32x4 *)(mine + c2 * 68 + c1) = val;
             }
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) zbuf[(wave * 2 + g) * kHeadDim + 32 * mi + (lane & 31)] = zacc[mi];
+    for (int mi = 0; mi < 2; ++mi) {
+        zbuf[(wave * 2 + g) * kHeadDim + 32 * mi + (lane & 31)] = zacc[mi];
+        if (VSUM) zbuf[(8 + wave * 2 + g) * kHeadDim + 32 * mi + (lane & 31)] = vacc[mi];
+    }
     __syncthreads();
     float *out = ws + ((size_t)part * BH + bh) * kStateFloats;
     for (int e = tid; e < kHeadDim * kHeadDim; e += 256) {
@@ -115,6 +130,11 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int
 #pragma unroll
         for (int w = 0; w < 8; ++w) s += zbuf[w * kHeadDim + tid];
         out[kHeadDim * kHeadDim + tid] = s;
+    } else if (VSUM && tid < 2 * kHeadDim) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 8; w < 16; ++w) s += zbuf[w * kHeadDim + tid - kHeadDim];
+        vsum[((size_t)part * BH + bh) * kHeadDim + tid - kHeadDim] = s;
     }
 }
 
@@ -143,13 +163,20 @@ la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
 
 // grid (ceil(N / tokens_per_wg), B*heads), 256 threads.
 // `states` holds n_part partial states per (batch, head), part_stride floats apart.
-template <bool O_BF16>
+// KS = 0: linear attention alone.  KS = 3 or 5: the block's convolution branch is added before
+// the store: the normalised tile is staged in LDS as fp32, and the lane that stores 8 channels
+// of a token first adds sum_taps kappa[c][tap] * V[token + tap][c] for them (V rows of the
+// neighbouring tokens come from the caches: every V row is used by KS*KS tokens).
+template <bool O_BF16, int KS>
 __global__ void __launch_bounds__(256, 2)
 la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int n_part,
-              long long part_stride, int heads, int N, int tokens_per_wg, float eps) {
+              long long part_stride, int heads, int N, int tokens_per_wg, float eps, TensorArg vt,
+              DwcArg cv) {
     // St[c2][c1] fp32 with the 8-float group index rotated by the row, then z; afterwards the
-    // same bytes stage output tiles.  Then one 8 KB query tile per wave.
-    __shared__ __align__(16) unsigned char smem[kStateFloats * 4 + 4 * 8192];
+    // same bytes stage output tiles (4 KB of bf16 per wave, or 8 KB of fp32 with the
+    // convolution).  Then one 8 KB query tile per wave, then the filters as [tap][channel].
+    constexpr int kStageBytes = KS ? 4 * 8192 : kStateFloats * 4;
+    __shared__ __align__(16) unsigned char smem[kStageBytes + 4 * 8192 + KS * KS * kHeadDim * 4];
     float *St = (float *)smem;
     float *zs = St + kHeadDim * kHeadDim;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
@@ -171,6 +198,12 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
     };
     int t = n0 + wave * 64;
     if (t < n1) fetch(t);
+
+    float *kap = (float *)(smem + kStageBytes + 4 * 8192);
+    if (KS) {
+        const float *kbase = cv.kappa + b * cv.kappa_sb + (size_t)h * kHeadDim * KS * KS;
+        for (int e = tid; e < kHeadDim * KS * KS; e += 256) kap[(e % (KS * KS)) * kHeadDim + e / (KS * KS)] = kbase[e];
+    }
 
     // Sum the partial states: 16-byte loads, all of them issued before the first use.
     {
@@ -234,8 +267,9 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
         }
     __syncthreads();  // the state bytes are reused as output staging from here on
 
-    unsigned char *qtile = smem + kStateFloats * 4 + wave * 8192;
-    unsigned char *otile = smem + wave * 4096;
+    unsigned char *qtile = smem + kStageBytes + wave * 8192;
+    unsigned char *otile = smem + wave * (KS ? 8192 : 4096);
+    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh;
     for (; t < n1; t += 256) {
 #pragma unroll
         for (int r = 0; r < 8; ++r)
@@ -263,7 +297,63 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
             pair_values(accz[0] + accz[1], &den_lo, &den_hi);
             const float inv = __builtin_amdgcn_rcpf(den_lo + eps);
             const int n = t + row;
-            if (O_BF16) {
+            if (KS) {
+                // fp32 staging: 256-byte token rows, 16-byte chunk index rotated by the row
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        f32x4 val = {acc[mi][4 * q4] * inv, acc[mi][4 * q4 + 1] * inv,
+                                     acc[mi][4 * q4 + 2] * inv, acc[mi][4 * q4 + 3] * inv};
+                        *(f32x4 *)(otile + li * 256 + (((8 * mi + 2 * q4 + g) ^ (li & 15)) << 4)) = val;
+                    }
+                constexpr int kPad = KS / 2;
+                constexpr int kRowUnroll = 1;  // one tap row of loads in flight (register budget)
+#pragma unroll 1
+                for (int r = 0; r < 4; ++r) {
+                    const int orow = r * 8 + lrow, on = t + 32 * nt + orow;
+                    const f32x4 o0 = *(const f32x4 *)(otile + orow * 256 + (((2 * lchunk) ^ (orow & 15)) << 4));
+                    const f32x4 o1 = *(const f32x4 *)(otile + orow * 256 + (((2 * lchunk + 1) ^ (orow & 15)) << 4));
+                    float sum[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
+                    // Out-of-grid taps (and the slots past the end of the range) read a valid
+                    // row with weight zero, so all loads of a token can be in flight at once.
+                    const int tok = min(on, n1 - 1);
+                    const int gr = tok / cv.W, gc = tok - gr * cv.W;
+#pragma unroll kRowUnroll
+                    for (int di = -kPad; di <= kPad; ++di)
+#pragma unroll
+                        for (int dj = -kPad; dj <= kPad; ++dj) {
+                            const bool ok = (unsigned)(gr + di) < (unsigned)cv.H &&
+                                            (unsigned)(gc + dj) < (unsigned)cv.W;
+                            const int src = ok ? tok + di * cv.W + dj : tok;
+                            const u32x4 vv = *(const u32x4 *)(vp + (long long)src * vt.sn + lchunk * 8);
+                            const float *kr = kap + ((di + kPad) * KS + dj + kPad) * kHeadDim + 8 * lchunk;
+                            const f32x4 k0 = *(const f32x4 *)kr, k1 = *(const f32x4 *)(kr + 4);
+                            const float m = ok ? 1.0f : 0.0f;
+                            sum[0] = fmaf(k0[0] * m, bf16_lo(vv[0]), sum[0]);
+                            sum[1] = fmaf(k0[1] * m, bf16_hi(vv[0]), sum[1]);
+                            sum[2] = fmaf(k0[2] * m, bf16_lo(vv[1]), sum[2]);
+                            sum[3] = fmaf(k0[3] * m, bf16_hi(vv[1]), sum[3]);
+                            sum[4] = fmaf(k1[0] * m, bf16_lo(vv[2]), sum[4]);
+                            sum[5] = fmaf(k1[1] * m, bf16_hi(vv[2]), sum[5]);
+                            sum[6] = fmaf(k1[2] * m, bf16_lo(vv[3]), sum[6]);
+                            sum[7] = fmaf(k1[3] * m, bf16_hi(vv[3]), sum[7]);
+                        }
+                    if (on < n1) {
+                        if (O_BF16) {
+                            __bf16 *op = (__bf16 *)ot.ptr + b * ot.sb + h * ot.sh;
+                            u32x4 pk = {pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3]),
+                                        pack_bf16x2(sum[4], sum[5]), pack_bf16x2(sum[6], sum[7])};
+                            *(u32x4 *)(op + (long long)on * ot.sn + lchunk * 8) = pk;
+                        } else {
+                            float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)on * ot.sn + lchunk * 8;
+                            f32x4 s0 = {sum[0], sum[1], sum[2], sum[3]}, s1 = {sum[4], sum[5], sum[6], sum[7]};
+                            *(f32x4 *)op = s0;
+                            *(f32x4 *)(op + 4) = s1;
+                        }
+                    }
+                }
+            } else if (O_BF16) {
 #pragma unroll
                 for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -296,19 +386,35 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
     }
 }
 
+template <bool O_BF16, int KS>
+static void launch_apply(dim3 grid, hipStream_t stream, const Problem &pr, const float *states,
+                         int n_part, long long part_stride, int apply_tokens, float eps,
+                         const DwcArg &cv) {
+    hipLaunchKernelGGL((la_apply_bf16<O_BF16, KS>), grid, dim3(256), 0, stream, pr.q, pr.o, states,
+                       n_part, part_stride, pr.heads, pr.N, apply_tokens, eps, pr.v, cv);
+}
+
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
-                      hipStream_t stream) {
+                      const DwcPlan &dwc, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)la_state_bf16,
+        hipError_t e = hipFuncSetAttribute((const void *)la_state_bf16<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)la_state_bf16<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
         if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
         attr_set = true;
     }
     const int BH = pr.B * pr.heads;
+    const bool dynamic = dwc.mode == JV_DWC_SQUEEZE_DYNAMIC;
     jv_status st;
-    hipLaunchKernelGGL(la_state_bf16, dim3(plan.n_split, BH), dim3(256), kStateLds, stream, pr.k,
-                       pr.v, ws, pr.heads, pr.N, plan.chunk);
+    if (dynamic)
+        hipLaunchKernelGGL(la_state_bf16<true>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
+                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk);
+    else
+        hipLaunchKernelGGL(la_state_bf16<false>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk);
     if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
     const float *states = ws;
     int n_part = plan.n_split;
@@ -321,13 +427,23 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
         states = dst;
         n_part = 1;
     }
+    DwcArg cv = {dwc.static_kernel, 0, pr.H, pr.W};
+    if (dynamic) {
+        if ((st = squeeze_generate(dwc, ws, plan.n_split, pr.B, pr.heads, pr.N, stream)) != JV_OK) return st;
+        cv.kappa = ws + dwc.kappa_off;
+        cv.kappa_sb = (long long)pr.heads * kHeadDim * dwc.ksize * dwc.ksize;
+    }
     dim3 grid((pr.N + plan.apply_tokens - 1) / plan.apply_tokens, BH);
-    if (pr.o_bf16)
-        hipLaunchKernelGGL(la_apply_bf16<true>, grid, dim3(256), 0, stream, pr.q, pr.o, states,
-                           n_part, part_stride, pr.heads, pr.N, plan.apply_tokens, eps);
-    else
-        hipLaunchKernelGGL(la_apply_bf16<false>, grid, dim3(256), 0, stream, pr.q, pr.o, states,
-                           n_part, part_stride, pr.heads, pr.N, plan.apply_tokens, eps);
+    const int ks = dwc.mode == JV_DWC_NONE ? 0 : dwc.ksize;
+    if (pr.o_bf16) {
+        if (ks == 0) launch_apply<true, 0>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else if (ks == 3) launch_apply<true, 3>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else launch_apply<true, 5>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+    } else {
+        if (ks == 0) launch_apply<false, 0>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else if (ks == 3) launch_apply<false, 3>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else launch_apply<false, 5>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+    }
     return launch_status("la_apply_bf16");
 }
 

@@ -106,3 +106,19 @@ def block_weights(C, hidden, seed, bf16=True):
         "w_fc1": xavier((hidden, C), seed * 16 + 4), "b_fc1": np.zeros(hidden, np.float32),
         "w_fc2": xavier((C, hidden), seed * 16 + 5), "b_fc2": np.zeros(C, np.float32),
     }
+
+
+# ---------------------------------------------------------------------------
+# Convolution branch of the linear-attention block
+# ---------------------------------------------------------------------------
+def dwc_static_kernel(C, ksize, seed):
+    """Depth-wise filter bank [C, k, k], N(0, 1/k^2)."""
+    return normal((C, ksize, ksize), seed, 1.0 / ksize)
+
+
+def squeeze_weights(C, hidden, ksize, seed):
+    """Generator weights of the dynamic filters: w1 [hidden, C], b1 [hidden],
+    w2 [C*k*k, hidden], b2 [C*k*k]; scaled so that the generated filters are O(1/k)."""
+    return (normal((hidden, C), seed, 4.0 / np.sqrt(C)), normal((hidden,), seed + 1, 0.5),
+            normal((C * ksize * ksize, hidden), seed + 2, 1.0 / (ksize * np.sqrt(hidden))),
+            normal((C * ksize * ksize,), seed + 3, 0.5 / ksize))
