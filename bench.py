@@ -4,9 +4,11 @@
 One "step" = one linear-attention layer + one 16x16 window-attention layer + one full-attention
 layer on the ViT-L attention workload (bf16, batch 8, 64x64 grid = 4096 tokens, 16 heads x 64),
 all inputs resident in HBM.  value = tokens pushed through a mixer layer per second
-(3 layers x 32 768 tokens / step time).  Each mixer is also timed on its own with HIP events on
-the launch stream and priced against its roofline (HBM for linear and window attention, bf16
-MFMA for full attention); the dominant kernel of the step is full attention.
+(3 layers x 32 768 tokens / step time).  Each mixer (and the paper's linear-attention block with
+its squeeze-dynamic convolution branch) is also timed on its own with events on the launch
+stream and priced against its roofline (HBM for linear and window attention, bf16 MFMA for full
+attention); the dominant kernel of the step is full attention.  The hybrid ViT-L encoder
+forward (24 blocks, batch 4, 64x64 grid) is timed in the same run and reported under "encoder".
 
 Prints ONE JSON line.  Use --gpus 1 only: the library is a single-GPU path.
 """
@@ -23,6 +25,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def read_traffic():
+    """HBM bytes per launch measured with rocprofv3 counters (profiles/hbm_traffic.txt holds
+    'kernel-key: bytes' lines and the commands that produced them); {} when absent."""
+    out = {}
+    if os.path.exists(TRAFFIC_FILE):
+        for line in open(TRAFFIC_FILE):
+            line = line.split("#", 1)[0].strip()
+            if ":" in line:
+                key, val = line.split(":", 1)
+                try:
+                    out[key.strip()] = float(val)
+                except ValueError:
+                    pass
+    return out
 
 
 def main():
@@ -32,11 +51,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="mixer workload (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-encoder", action="store_true", help="skip the encoder leg")
     ap.add_argument("--buffers", type=int, default=6, help="rotating input/output sets")
     ap.add_argument("--encoder", action="store_true",
-                    help="time the hybrid ViT-L encoder forward (config 5) instead of the mixer step")
-    ap.add_argument("--only", choices=["linear", "window", "full"], default=None,
-                    help="run only this mixer's timing loop (for counter collection)")
+                    help="run only the hybrid ViT-L encoder forward (config 5)")
+    ap.add_argument("--only", choices=["linear", "window", "full", "block"], default=None,
+                    help="run only this mixer's launches (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference point for HBM counters)")
     args = ap.parse_args()
@@ -50,8 +70,25 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.lib()
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.encoder:
-        return bench_encoder(args)
+        enc = bench_encoder(args.steps, args.warmup)
+        print(json.dumps({
+            "metric": "hybrid ViT-L encoder forward, tokens/s per encoder",
+            "value": enc["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": enc["ms_per_encoder"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": enc["workload"]},
+            "roofline": {"bound": "mfma", "achieved": enc["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": enc["mfma_frac"], "traffic": None},
+            "encoder": enc, "cpu_baseline": None}))
+        return
     c = synth.CONFIGS[args.config]
     B, heads, H, W, d = c["B"], c["heads"], c["H"], c["W"], c["d"]
     N = H * W
@@ -67,12 +104,19 @@ def main():
     for i in range(args.buffers):
         qs, ks, vs = (t.clone() if i else t for t in base)
         sets.append((qs, ks, vs, torch.empty_like(qs)))
-    ws = torch.empty(max(256, binding.jv_linear_attn_workspace_bytes(
-        binding.make_desc(*sets[0], (H, W)))), dtype=torch.uint8, device="cuda")
+    C = heads * d
+    squeeze = tuple(torch.from_numpy(a).cuda() for a in synth.squeeze_weights(C, C // 16, 3, 2500))
+    dwc = binding.make_dwc_params(squeeze=squeeze, ksize=3)
+    ws = torch.empty(max(256, binding.jv_linear_block_workspace_bytes(
+        binding.make_desc(*sets[0], (H, W)), dwc)), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
 
     def linear(s):
         binding.jv_linear_attn_fwd(s[0], s[1], s[2], s[3], (H, W), 1e-6, ws, stream)
+
+    def block(s):
+        binding.jv_linear_block_fwd(s[0], s[1], s[2], s[3], (H, W), 1e-6, squeeze=squeeze, ksize=3,
+                                    workspace=ws, stream=stream)
 
     def win(s):
         binding.jv_window_attn_fwd(s[0], s[1], s[2], s[3], (H, W), window, 0.0, stream)
@@ -80,7 +124,7 @@ def main():
     def full(s):
         binding.jv_full_attn_fwd(s[0], s[1], s[2], s[3], (H, W), 0.0, stream)
 
-    mixers = {"linear": linear, "window": win, "full": full}
+    mixers = {"linear": linear, "window": win, "full": full, "block": block}
     if args.only:
         fn = mixers[args.only]
         for i in range(args.warmup + args.steps):
@@ -92,14 +136,6 @@ def main():
     def step(i):
         s = sets[i % len(sets)]
         linear(s); win(s); full(s)
-
-    if args.copy_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     for i in range(args.warmup):
         step(i)
@@ -127,30 +163,45 @@ def main():
                      "ms_median": float(np.median(t))}
 
     bytes_layer = 4 * tokens * heads * d * esz                 # read Q, K, V; write O
-    flops_full = 4.0 * N * N * d * B * heads                   # QK^T and PV
-    flops_window = 4.0 * N * (window[0] * window[1]) * d * B * heads
-    flops_linear = (4.0 * d * d + 2 * d) * tokens * heads
+    flops = {"full": 4.0 * N * N * d * B * heads,              # QK^T and PV
+             "window": 4.0 * N * (window[0] * window[1]) * d * B * heads,
+             "linear": (4.0 * d * d + 2 * d) * tokens * heads,
+             "block": (4.0 * d * d + 2 * d + 2 * 9) * tokens * heads}
+    traffic = read_traffic()
     for name in per:
         ms = per[name]["ms_avg"]
         per[name]["tokens_per_s"] = tokens / (ms * 1e-3)
         per[name]["hbm_GBs"] = bytes_layer / (ms * 1e-3) / 1e9
         per[name]["hbm_frac"] = per[name]["hbm_GBs"] / HBM_PEAK_GBS
-    for name, fl in (("full", flops_full), ("window", flops_window), ("linear", flops_linear)):
-        per[name]["TFLOPs"] = fl / (per[name]["ms_avg"] * 1e-3) / 1e12
+        per[name]["TFLOPs"] = flops[name] / (ms * 1e-3) / 1e12
         per[name]["mfma_frac"] = per[name]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+    per["block"]["note"] = "linear attention + squeeze-dynamic 3x3 convolution of V (Eq. 4)"
+
+    def hbm_roof(name, kernels):
+        return {"kernel": kernels, "bound": "hbm", "achieved": per[name]["hbm_GBs"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per[name]["hbm_frac"],
+                "traffic": traffic.get(name), "algorithmic_bytes": bytes_layer,
+                "mfma_frac": per[name]["mfma_frac"]}
 
     roofline = {"kernel": "attn_stream_bf16 (full attention)", "bound": "mfma",
                 "achieved": per["full"]["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"], "traffic": None}
+                "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"], "traffic": traffic.get("full"),
+                "algorithmic_flops": flops["full"], "avg_launch_ms": per["full"]["ms_avg"]}
     rooflines = {
-        "linear": {"bound": "hbm", "achieved": per["linear"]["hbm_GBs"], "peak": HBM_PEAK_GBS,
-                   "unit": "GB/s", "frac": per["linear"]["hbm_frac"]},
-        "window": {"bound": "hbm", "achieved": per["window"]["hbm_GBs"], "peak": HBM_PEAK_GBS,
-                   "unit": "GB/s", "frac": per["window"]["hbm_frac"],
-                   "mfma_frac": per["window"]["mfma_frac"]},
-        "full": {"bound": "mfma", "achieved": per["full"]["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                 "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"]},
+        "linear": hbm_roof("linear", "la_state_bf16 + la_apply_bf16"),
+        "block": hbm_roof("block", "la_state_bf16 + squeeze_* + la_apply_bf16 (convolution fused)"),
+        "window": hbm_roof("window", "attn_window_bf16"),
+        "full": dict(roofline),
     }
+
+    encoder = None
+    if not args.no_encoder and args.config == 2:
+        del sets, base
+        torch.cuda.empty_cache()
+        encoder = bench_encoder(10, 3)
+        rooflines["encoder"] = {"kernel": "gemm_bf16_kernel (+ mixers, LayerNorm)", "bound": "mfma",
+                                "achieved": encoder["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": encoder["mfma_frac"], "traffic": None}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -166,12 +217,13 @@ def main():
                                f"{'bf16' if c['bf16'] else 'fp32'}; step = linear + "
                                f"window{window[0]}x{window[1]} + full attention layer",
                    "tokens_per_layer": tokens},
-        "per_mixer": per, "roofline": roofline, "rooflines": rooflines, "cpu_baseline": cpu,
+        "per_mixer": per, "roofline": roofline, "rooflines": rooflines, "encoder": encoder,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 
 
-def bench_encoder(args):
+def bench_encoder(steps, warmup):
     """Config 5: 24 pre-LN blocks of width 1024 (16 heads, MLP 4096), batch 4 on a 64x64 grid;
     full attention at blocks 5, 11, 17, 23, window 16x16 at the other even blocks, linear
     attention at the rest.  Random-init (Xavier-normal, seeded) bf16 weights, fp32 residual."""
@@ -190,14 +242,15 @@ def bench_encoder(args):
     y = torch.empty_like(x)
     ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         enc.forward(x, y, (H, W), ws, stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         enc.forward(x, y, (H, W), ws, stream)
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    enc.close()
     T = B * N
     gemm_flops = 2.0 * T * C * (3 * C + C + 2 * hidden) * L
     n_full, n_win, n_lin = pattern.count(2), pattern.count(1), pattern.count(0)
@@ -205,17 +258,11 @@ def bench_encoder(args):
                              n_lin * (4.0 * 64 * 64 + 128) * N)
     flops = gemm_flops + mix_flops
     tf = flops / (ms * 1e-3) / 1e12
-    print(json.dumps({
-        "metric": "hybrid ViT-L encoder forward, tokens/s per encoder", "value": T / (ms * 1e-3),
-        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"config5: 24-block hybrid ViT-L encoder, B{B} {H}x{W} grid, width {C}, "
-                               f"{n_full} full / {n_win} window16x16 / {n_lin} linear blocks"},
-        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "flops_per_step": flops, "gemm_flops": gemm_flops},
-        "cpu_baseline": None}))
+    return {"workload": f"config5: 24-block hybrid ViT-L encoder, B{B} {H}x{W} grid, width {C}, "
+                        f"{n_full} full / {n_win} window16x16 / {n_lin} linear blocks",
+            "ms_per_encoder": ms, "ms_per_layer": ms / L, "tokens_per_s": T / (ms * 1e-3),
+            "steps": steps, "warmup": warmup, "flops_per_encoder": flops, "gemm_flops": gemm_flops,
+            "TFLOPs": tf, "mfma_frac": tf / MFMA_BF16_PEAK_TFLOPS}
 
 
 def cpu_baseline(q, k, v, H, W, window):

@@ -181,6 +181,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         a_off[j] = 2u * ((unsigned)ar * (unsigned)K + gchunk * 8);
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
+    const int n_k = K / kBK;
     auto issue_loads = [&](int kt) {
         unsigned char *abase = smem + (kt & (kGemmStages - 1)) * kGemmStage + wave * 64 * 64;
         unsigned char *wbase = abase + kGemmTileBytes;
@@ -204,44 +205,72 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
 
-    const int n_k = K / kBK;
-    for (int kt = 0; kt < kGemmStages - 1 && kt < n_k; ++kt) issue_loads(kt);
-    for (int kt = 0; kt < n_k; ++kt) {
-        // Stage kt has landed once at most the loads of the stages after it are pending; after
-        // the barrier every wavefront is also done with stage kt-1, whose buffer is refilled.
-        const int later = min(n_k - 1 - kt, kGemmStages - 2);
-        wait_loads_and_barrier(8 * later);
-        if (kt + kGemmStages - 1 < n_k) issue_loads(kt + kGemmStages - 1);
+    // Operand registers for the two k-steps (of 16) of a stage.  The LDS reads of a step are
+    // issued among the matrix instructions of the step before it, and the workgroup barrier
+    // sits in the middle of a stage: when a wavefront leaves it, the operands of the stage's
+    // second step are already in registers, so the matrix pipeline restarts at once, and the
+    // reads of the next stage's first step (which the barrier has just made visible) overlap
+    // with that second step.
+    bf16x8 aop[2][4], wop[2][4];
+    auto load_ops = [&](int kt, int ks) {
         const unsigned char *at = smem + (kt & (kGemmStages - 1)) * kGemmStage;
         const unsigned char *wt = at + kGemmTileBytes;
-        // Operand registers are double-buffered across the two k-steps of the stage: the LDS
-        // reads of the second step are issued among the matrix instructions of the first
-        // (one read per two matrix instructions; the scheduling groups below pin that order).
-        bf16x8 aop[2][4], wop[2][4];
-        auto load_ops = [&](int ks, int slot) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                aop[slot][i] = as_bf16x8(*(const u32x4 *)(at + gemm_tile_off(wm * 128 + i * 32 + li, 2 * ks + g)));
-                wop[slot][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_tile_off(wn * 128 + i * 32 + li, 2 * ks + g)));
-            }
-        };
-        load_ops(0, 0);
-        load_ops(1, 1);
+        for (int i = 0; i < 4; ++i) {
+            aop[ks][i] = as_bf16x8(*(const u32x4 *)(at + gemm_tile_off(wm * 128 + i * 32 + li, 2 * ks + g)));
+            wop[ks][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_tile_off(wn * 128 + i * 32 + li, 2 * ks + g)));
+        }
+    };
+    auto products = [&](int ks) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+        for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
+            for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[ks][nt], aop[ks][mt], acc[nt][mt]);
+    };
+    // One stage.  `issue`: start the loads of stage kt + 3 (its buffer held stage kt - 1, which
+    // every wavefront has finished once it is past this stage's barrier).  `pending`: how many of
+    // this wavefront's loads may still be outstanding at the barrier with stage kt + 1 complete
+    // (8 per later stage in flight).  `next`: there is a stage kt + 1.
+    auto stage = [&](int kt, bool issue, int pending, bool next) {
+        load_ops(kt, 1);
+        products(0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    acc[nt][mt] = mfma32(wop[ks][nt], aop[ks][mt], acc[nt][mt]);
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);  // LDS reads of step 0
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {                       // step 0: read, two products
+        for (int i = 0; i < 7; ++i) {  // one LDS read per two matrix instructions
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0); // step 1
-    }
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (next) wait_loads_and_barrier(pending);
+        if (issue) issue_loads(kt + kGemmStages - 1);
+        if (next) load_ops(kt + 1, 0);
+        products(1);
+        if (issue) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {  // one global load, one LDS read, one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        } else if (next) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+#pragma unroll
+            for (int i = 0; i < 7; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+    };
+    for (int kt = 0; kt < kGemmStages - 1 && kt < n_k; ++kt) issue_loads(kt);
+    wait_loads_and_barrier(8 * min(n_k - 1, kGemmStages - 2));  // stage 0 has landed
+    load_ops(0, 0);
+    int kt = 0;
+    for (; kt + kGemmStages - 1 < n_k; ++kt) stage(kt, true, 8, true);
+    for (; kt < n_k; ++kt) stage(kt, false, 8 * max(0, min(n_k - 2 - kt, 1)), kt + 1 < n_k);
 
     // Epilogue: accumulator register v of block (nt, mt) is output feature
     // n0 + 128 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
