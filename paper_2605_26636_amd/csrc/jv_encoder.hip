@@ -108,14 +108,20 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // GEMM  y = epilogue(a w^T + bias):  a [M, K], w [N, K], both bf16 with K contiguous, so both
 // matrix-instruction operands are 16-byte row pieces.  One workgroup (4 wavefronts, one per
 // SIMD, the whole register file each) owns a 256 x 256 tile of y; a wavefront owns 128 x 128 of
-// it (4 x 4 blocks of 32 x 32, 256 accumulator registers).  K is walked in steps of 32: the
-// 256 x 32 tiles of a and w go from global memory straight into LDS (no register staging)
-// through a ring of four stages, three steps ahead of the arithmetic: with 64 KB per step and
-// compute unit, the L2 round trip is longer than one step of arithmetic, so several steps
-// have to be in flight.  The wait before each step is therefore a counted one (the loads of
-// the two later stages may still be outstanding), written by hand next to the barrier.
-// Rows are 64 bytes in LDS; the 16-byte chunk index is rotated by the row pair so that the
-// row-per-lane operand reads spread over all banks.
+// it (4 x 4 blocks of 32 x 32, 256 accumulator registers).
+// K is walked in blocks of 64, i.e. whole 128-byte lines of every row: the 256 x 64 parts of a
+// and of w go from global memory straight into LDS (no register staging) through a ring of
+// five 32 KB slots filled in the order a0 w0 a1 w1 a2 ...  While block p is multiplied, the
+// parts of block p+1 and the a part of block p+2 are in flight or landed; the two slots of
+// block p are refilled (w of p+2, a of p+3) as soon as its last operands have been read.  The
+// wait before a block is therefore a counted one (the youngest part may still be
+// outstanding), written by hand next to the barrier.
+// A block is four steps of 16 in K; the LDS reads of a step are issued among the matrix
+// instructions of the step before it, and the workgroup barrier sits before the last step:
+// when a wavefront leaves it, the operands of that step are already in registers, so the
+// matrix pipeline restarts at once, and the reads of the next block's first step overlap it.
+// Rows are 128 bytes in LDS; the 16-byte chunk index is rotated by the row pair, which
+// spreads the sixteen rows that one pass of a row-per-lane read touches over all 64 banks.
 // The product is formed transposed (features x tokens): a lane then holds 4 consecutive output
 // features of one token, which makes the epilogue loads (bias, residual) and stores 8 or 16
 // bytes wide.
@@ -123,11 +129,10 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // range of tiles, feature-tile fastest: they share the a row-tile and keep w in that L2.
 // grid (8 * ceil(tiles / 8)), 256 threads, kGemmLds bytes of dynamic LDS.
 // ---------------------------------------------------------------------------------------
-constexpr int kBM = 256, kBN = 256, kBK = 32;
-constexpr int kGemmTileBytes = kBM * kBK * 2;          // one operand tile: 16 KB
-constexpr int kGemmStage = 2 * kGemmTileBytes;         // a tile then w tile: 32 KB
-constexpr int kGemmStages = 4;
-constexpr int kGemmLds = kGemmStages * kGemmStage;     // 128 KB
+constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kGemmPart = kBM * kBK * 2;               // one operand part: 32 KB
+constexpr int kGemmSlots = 5;
+constexpr int kGemmLds = kGemmSlots * kGemmPart;       // 160 KB
 
 typedef __attribute__((address_space(1))) const void global_cvoid;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -143,16 +148,20 @@ __device__ inline float gelu_erf(float x) {
     return 0.5f * x * (1.0f + erf_x);
 }
 
-// Byte offset of 16-byte chunk `chunk` (0..3) of row `row` in a [rows][32] bf16 LDS tile.
-__device__ inline unsigned gemm_tile_off(int row, int chunk) {
-    return (unsigned)(row * 64 + ((chunk ^ ((row >> 1) & 3)) << 4));
+// Byte offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 LDS part.
+__device__ inline unsigned gemm_part_off(int row, int chunk) {
+    return (unsigned)(row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
 }
 
 // Wait until at most `pending` of this wavefront's vector-memory loads are outstanding, then
 // the workgroup barrier.  "memory" keeps the compiler from moving LDS traffic across it.
 __device__ inline void wait_loads_and_barrier(int pending) {
-    if (pending >= 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // the count is an immediate: take the largest supported value not above `pending`
+    if (pending >= 24) asm volatile("s_waitcnt vmcnt(24) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (pending >= 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (pending >= 10) asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     else if (pending >= 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (pending >= 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
@@ -169,31 +178,34 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     const int m0 = (tile / tiles_n) * kBM, n0 = (tile % tiles_n) * kBN;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // Global -> LDS: a wavefront moves rows 64*wave .. +63 of both tiles, 16 rows (1 KB) per
-    // instruction; lane = 4 * (row in group) + LDS chunk slot, and it fetches the global chunk
-    // that belongs in that slot under the row rotation.  Eight loads per wavefront and stage.
-    const int lrow = lane >> 2, gchunk = (lane & 3) ^ ((lrow >> 1) & 3);
-    unsigned a_off[4], w_off[4];  // byte offsets of this lane's 16 bytes, k = 0
+    // Global -> LDS: a wavefront moves rows 64*wave .. +63 of a part, 8 rows (1 KB) per
+    // instruction; lane = 8 * (row in group) + LDS chunk slot, and it fetches the global chunk
+    // that belongs in that slot under the row rotation.  Eight loads per wavefront and part.
+    const int lrow = lane >> 3;
+    unsigned a_off[8], w_off[8];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = wave * 64 + j * 16 + lrow;
+    for (int j = 0; j < 8; ++j) {
+        const int r = wave * 64 + j * 8 + lrow;
+        const int gchunk = (lane & 7) ^ ((r >> 1) & 7);
         const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);  // edge tiles re-read the last row
         a_off[j] = 2u * ((unsigned)ar * (unsigned)K + gchunk * 8);
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
-    const int n_k = K / kBK;
-    auto issue_loads = [&](int kt) {
-        unsigned char *abase = smem + (kt & (kGemmStages - 1)) * kGemmStage + wave * 64 * 64;
-        unsigned char *wbase = abase + kGemmTileBytes;
-        const unsigned kbytes = 2u * kt * kBK;
+    const int n_b = K / kBK, n_parts = 2 * n_b;
+    // part = 2 * block + (0: a, 1: w); it lives in slot part % 5
+    auto issue_part = [&](int part, int slot) {
+        unsigned char *base = smem + slot * kGemmPart + wave * 64 * 128;
+        const unsigned kbytes = 2u * (unsigned)(part >> 1) * kBK;
+        if (part & 1) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            __builtin_amdgcn_global_load_lds(
-                (global_cvoid *)((const char *)A + (a_off[j] + kbytes)),
-                (lds_void *)(abase + j * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(
-                (global_cvoid *)((const char *)W + (w_off[j] + kbytes)),
-                (lds_void *)(wbase + j * 1024), 16, 0, 0);
+            for (int j = 0; j < 8; ++j)
+                __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)W + (w_off[j] + kbytes)),
+                                                 (lds_void *)(base + j * 1024), 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)A + (a_off[j] + kbytes)),
+                                                 (lds_void *)(base + j * 1024), 16, 0, 0);
         }
     };
 
@@ -205,72 +217,79 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
 
-    // Operand registers for the two k-steps (of 16) of a stage.  The LDS reads of a step are
-    // issued among the matrix instructions of the step before it, and the workgroup barrier
-    // sits in the middle of a stage: when a wavefront leaves it, the operands of the stage's
-    // second step are already in registers, so the matrix pipeline restarts at once, and the
-    // reads of the next stage's first step (which the barrier has just made visible) overlap
-    // with that second step.
+    // Operand registers, two sets used in turn by the steps.
     bf16x8 aop[2][4], wop[2][4];
-    auto load_ops = [&](int kt, int ks) {
-        const unsigned char *at = smem + (kt & (kGemmStages - 1)) * kGemmStage;
-        const unsigned char *wt = at + kGemmTileBytes;
+    auto load_ops = [&](int a_slot, int w_slot, int step, int set) {
+        const unsigned char *at = smem + a_slot * kGemmPart, *wt = smem + w_slot * kGemmPart;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            aop[ks][i] = as_bf16x8(*(const u32x4 *)(at + gemm_tile_off(wm * 128 + i * 32 + li, 2 * ks + g)));
-            wop[ks][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_tile_off(wn * 128 + i * 32 + li, 2 * ks + g)));
+            aop[set][i] = as_bf16x8(*(const u32x4 *)(at + gemm_part_off(wm * 128 + i * 32 + li, 2 * step + g)));
+            wop[set][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_part_off(wn * 128 + i * 32 + li, 2 * step + g)));
         }
     };
-    auto products = [&](int ks) {
+    auto products = [&](int set) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[ks][nt], aop[ks][mt], acc[nt][mt]);
+            for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[set][nt], aop[set][mt], acc[nt][mt]);
     };
-    // One stage.  `issue`: start the loads of stage kt + 3 (its buffer held stage kt - 1, which
-    // every wavefront has finished once it is past this stage's barrier).  `pending`: how many of
-    // this wavefront's loads may still be outstanding at the barrier with stage kt + 1 complete
-    // (8 per later stage in flight).  `next`: there is a stage kt + 1.
-    auto stage = [&](int kt, bool issue, int pending, bool next) {
-        load_ops(kt, 1);
-        products(0);
+    auto next_slot = [](int s, int by) { s += by; return s >= kGemmSlots ? s - kGemmSlots : s; };
+    // One step whose matrix instructions are interleaved with the 8 LDS reads of the next one.
+    auto step_with_reads = [&](int set) {
+        products(set);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
-        for (int i = 0; i < 7; ++i) {  // one LDS read per two matrix instructions
+        for (int i = 0; i < 8; ++i) {  // the reads early, so that they have landed by the end
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+    };
+    // One block of 64 in K.  a_slot/w_slot hold it; the set-0 operands of its first step are in
+    // registers.  `n_issue`: how many of the parts 2p+5, 2p+6 exist; they refill the block's
+    // two slots once those are free.  `pending`: loads that may be outstanding at the barrier
+    // with block p+1 complete.  `next`: there is a block p+1.
+    auto block = [&](int p, int a_slot, int w_slot, int n_issue, int pending, bool next) {
+        load_ops(a_slot, w_slot, 1, 1);
+        step_with_reads(0);
+        load_ops(a_slot, w_slot, 2, 0);
+        step_with_reads(1);
+        load_ops(a_slot, w_slot, 3, 1);
+        step_with_reads(0);
+        // every wavefront is done reading this block once it arrives here
         if (next) wait_loads_and_barrier(pending);
-        if (issue) issue_loads(kt + kGemmStages - 1);
-        if (next) load_ops(kt + 1, 0);
+        if (n_issue >= 1) issue_part(2 * p + 5, a_slot);
+        if (n_issue >= 2) issue_part(2 * p + 6, w_slot);
+        if (next) load_ops(next_slot(a_slot, 2), next_slot(w_slot, 2), 0, 0);
         products(1);
-        if (issue) {
+        if (n_issue >= 2) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x010, 16, 0);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {  // one global load, one LDS read, one matrix instruction
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-        } else if (next) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-#pragma unroll
-            for (int i = 0; i < 7; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
         }
     };
-    for (int kt = 0; kt < kGemmStages - 1 && kt < n_k; ++kt) issue_loads(kt);
-    wait_loads_and_barrier(8 * min(n_k - 1, kGemmStages - 2));  // stage 0 has landed
-    load_ops(0, 0);
-    int kt = 0;
-    for (; kt + kGemmStages - 1 < n_k; ++kt) stage(kt, true, 8, true);
-    for (; kt < n_k; ++kt) stage(kt, false, 8 * max(0, min(n_k - 2 - kt, 1)), kt + 1 < n_k);
+    for (int part = 0; part < kGemmSlots && part < n_parts; ++part) issue_part(part, part);
+    wait_loads_and_barrier(8 * min(n_parts - 2, kGemmSlots - 2));  // block 0 has landed
+    load_ops(0, 1, 0, 0);
+    int p = 0, a_slot = 0, w_slot = 1;
+    // Steady state: parts 2p+5 and 2p+6 exist; at the barrier only part 2p+4 may be pending.
+    for (; 2 * p + 6 < n_parts; ++p) {
+        block(p, a_slot, w_slot, 2, 8, true);
+        a_slot = next_slot(a_slot, 2);
+        w_slot = next_slot(w_slot, 2);
+    }
+    for (; p < n_b; ++p) {
+        // everything up to part 2p+4 has been issued; block p+1 is complete when at most that
+        // part is pending.  The last w part (2p+5) may still have to be issued here.
+        block(p, a_slot, w_slot, 2 * p + 5 < n_parts ? 1 : 0, 2 * p + 4 < n_parts ? 8 : 0, p + 1 < n_b);
+        a_slot = next_slot(a_slot, 2);
+        w_slot = next_slot(w_slot, 2);
+    }
 
     // Epilogue: accumulator register v of block (nt, mt) is output feature
     // n0 + 128 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
