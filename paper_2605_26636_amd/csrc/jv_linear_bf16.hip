@@ -161,7 +161,9 @@ la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
     ((f32x4 *)dst)[(size_t)bh * (kStateFloats / 4) + e4] = sum;
 }
 
-// grid (ceil(N / tokens_per_wg), B*heads), 256 threads.
+// grid (8 * ceil(n_chunks * B*heads / 8)), 256 threads.  Workgroups are dealt to the eight XCDs
+// in turn; the index is remapped so that the workgroups one XCD receives walk (batch, head)
+// pairs chunk by chunk: the token chunks of a pair then share that XCD's L2 copy of the state.
 // `states` holds n_part partial states per (batch, head), part_stride floats apart.
 // KS = 0: linear attention alone.  KS = 3 or 5: the block's convolution branch is added before
 // the store: the normalised tile is staged in LDS as fp32, and the lane that stores 8 channels
@@ -170,8 +172,8 @@ la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
 template <bool O_BF16, int KS>
 __global__ void __launch_bounds__(256, 2)
 la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int n_part,
-              long long part_stride, int heads, int N, int tokens_per_wg, float eps, TensorArg vt,
-              DwcArg cv) {
+              long long part_stride, int heads, int N, int tokens_per_wg, int n_chunks, int n_wg,
+              float eps, TensorArg vt, DwcArg cv) {
     // St[c2][c1] fp32 with the 8-float group index rotated by the row, then z; afterwards the
     // same bytes stage output tiles (4 KB of bf16 per wave, or 8 KB of fp32 with the
     // convolution).  Then one 8 KB query tile per wave, then the filters as [tap][channel].
@@ -180,9 +182,12 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
     float *St = (float *)smem;
     float *zs = St + kHeadDim * kHeadDim;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
-    const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
+    const int per_xcd = (n_wg + 7) / 8;
+    const int wg = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (wg >= n_wg) return;  // whole workgroup
+    const int bh = wg / n_chunks, b = bh / heads, h = bh % heads;
     const __bf16 *qp = (const __bf16 *)qt.ptr + b * qt.sb + h * qt.sh;
-    const int n0 = blockIdx.x * tokens_per_wg, n1 = min(N, n0 + tokens_per_wg);
+    const int n0 = (wg % n_chunks) * tokens_per_wg, n1 = min(N, n0 + tokens_per_wg);
     const int lrow = lane >> 3, lchunk = lane & 7;
 
     // Query tiles are fetched one step ahead; start the first fetch before the state prologue.
@@ -387,11 +392,12 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
 }
 
 template <bool O_BF16, int KS>
-static void launch_apply(dim3 grid, hipStream_t stream, const Problem &pr, const float *states,
-                         int n_part, long long part_stride, int apply_tokens, float eps,
-                         const DwcArg &cv) {
-    hipLaunchKernelGGL((la_apply_bf16<O_BF16, KS>), grid, dim3(256), 0, stream, pr.q, pr.o, states,
-                       n_part, part_stride, pr.heads, pr.N, apply_tokens, eps, pr.v, cv);
+static void launch_apply(hipStream_t stream, const Problem &pr, const float *states, int n_part,
+                         long long part_stride, int apply_tokens, float eps, const DwcArg &cv) {
+    const int n_chunks = (pr.N + apply_tokens - 1) / apply_tokens, n_wg = n_chunks * pr.B * pr.heads;
+    hipLaunchKernelGGL((la_apply_bf16<O_BF16, KS>), dim3(8 * ((n_wg + 7) / 8)), dim3(256), 0, stream,
+                       pr.q, pr.o, states, n_part, part_stride, pr.heads, pr.N, apply_tokens, n_chunks,
+                       n_wg, eps, pr.v, cv);
 }
 
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
@@ -433,16 +439,15 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
         cv.kappa = ws + dwc.kappa_off;
         cv.kappa_sb = (long long)pr.heads * kHeadDim * dwc.ksize * dwc.ksize;
     }
-    dim3 grid((pr.N + plan.apply_tokens - 1) / plan.apply_tokens, BH);
     const int ks = dwc.mode == JV_DWC_NONE ? 0 : dwc.ksize;
     if (pr.o_bf16) {
-        if (ks == 0) launch_apply<true, 0>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else if (ks == 3) launch_apply<true, 3>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else launch_apply<true, 5>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        if (ks == 0) launch_apply<true, 0>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else if (ks == 3) launch_apply<true, 3>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else launch_apply<true, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
     } else {
-        if (ks == 0) launch_apply<false, 0>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else if (ks == 3) launch_apply<false, 3>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else launch_apply<false, 5>(grid, stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        if (ks == 0) launch_apply<false, 0>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else if (ks == 3) launch_apply<false, 3>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        else launch_apply<false, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
     }
     return launch_status("la_apply_bf16");
 }
