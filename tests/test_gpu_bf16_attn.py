@@ -136,3 +136,15 @@ def test_padding_is_masked_not_merely_zero():
     v2 = synth.round_to_bf16(v + 4.0)
     o2 = _window(q, k, v2, H, W, (8, 8), torch.float32)
     check(err_bf16(to_host(o2), oracle.window_attn(q, k, v2, H, W, 8, 8)), BF16_TOL)
+
+@pytest.mark.parametrize("B,H,W", [(32, 32, 32), (2, 128, 128), (1, 256, 256)])
+def test_window_attention_token_sweep_sampled_rows(B, H, W):
+    """16 x 16 windows over the token-count sweep (1 024, 16 384 and 65 536 tokens per image at a
+    constant 32 768 or 65 536 tokens per batch), sampled rows against the oracle."""
+    heads, N = 16, H * W
+    q, k, v = synth.qkv(3, B, heads, N, 64, 0.125, True)
+    rows = synth.sample_rows(B, heads, N, 256, seed=7 + H)
+    o = _window(q, k, v, H, W, (16, 16))
+    ref = oracle.window_attn_rows(q, k, v, H, W, 16, 16, rows)
+    check_bf16_pair(_window(q, k, v, H, W, (16, 16), torch.float32), o, ref, rows)
+    assert torch.isfinite(o.float()).all()

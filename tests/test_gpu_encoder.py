@@ -121,3 +121,49 @@ def test_vit_l_blocks_teacher_forced():
         # the block's own contribution (output minus input) is what the kernels computed
         check(err_bf16(to_host(y) - x, ref - x), BF16_TOL)
         enc.close()
+
+
+def test_config5_first_six_blocks_full_size():
+    """The encoder workload at its real shape (64 x 64 grid, width 1024, 16 heads, MLP 4096),
+    image 0, through blocks 0..5 of the benchmark pattern (window, linear, window, linear,
+    window, full): every mixer and every GEMM shape at full size against the oracle."""
+    H = W = 64
+    heads, hidden, C = 16, 4096, 1024
+    pattern = synth.encoder_pattern(24)[:6]
+    assert pattern == [1, 0, 1, 0, 1, 2]
+    x = synth.normal((4, H * W, C), 5003)[:1]
+    blocks = [synth.block_weights(C, hidden, 5000 + l) for l in range(6)]
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16))
+    dx = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W))
+    ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16))
+    check(err_bf16(to_host(y), ref), BF16_TOL)
+    check(err_bf16(to_host(y) - x, ref - x), BF16_TOL)   # what the six blocks added
+    enc.close()
+
+
+def test_config5_full_depth_batch_properties():
+    """All 24 blocks on the whole batch of 4: the result is finite, and every image comes out
+    as it does when it is run alone (images never mix; only the split of the linear-attention
+    state reduction depends on the batch size, hence tolerances instead of equality)."""
+    H = W = 64
+    heads, hidden, C, L = 16, 4096, 1024, 24
+    pattern = synth.encoder_pattern(L)
+    assert (pattern.count(2), pattern.count(1), pattern.count(0)) == (4, 12, 8)
+    blocks = _device_blocks([synth.block_weights(C, hidden, 5000 + l) for l in range(L)])
+    enc = binding.Encoder(blocks, pattern, heads, hidden, window=(16, 16))
+    dx = torch.from_numpy(synth.normal((4, H * W, C), 5003)).cuda()
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W))
+    assert torch.isfinite(y).all()
+    for img in (0, 3):
+        y1 = torch.empty(1, H * W, C, device="cuda")
+        enc.forward(dx[img:img + 1].contiguous(), y1, (H, W))
+        rms = float(y1.pow(2).mean().sqrt())
+        diff = y1[0] - y[img]
+        err_max, err_rms = float(diff.abs().max()) / rms, float(diff.pow(2).mean().sqrt()) / rms
+        print(f"    image {img}: |batch - alone| / RMS: max {err_max:.2e}, rms {err_rms:.2e}")
+        # a different summation order moves a few bf16 roundings, which 24 blocks then carry along
+        assert err_rms <= 5e-3 and err_max <= 5e-2
+    enc.close()
