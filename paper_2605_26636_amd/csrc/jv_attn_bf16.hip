@@ -391,29 +391,55 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
 // ---------------------------------------------------------------------------------------
 // Window-resident kernel: windows of at most 64*WPW slots (WPW = wavefronts per window).
 // All keys and values of a window are brought into LDS once, then every wavefront runs its 64
-// query slots over the resident tiles with no further synchronisation.  WPW = 4: one
-// workgroup per window (e.g. 16x16 windows); WPW = 1: one wavefront per window, four windows
-// per workgroup (e.g. 8x8 windows).  Window attention moves 4 rows of 128 bytes per token and
-// does little arithmetic on them, so the point of this kernel is to have many bytes in flight:
-// 96 KB of loads per 256 query slots are issued up front.
-// grid (ceil(n_win * WPW / 4), B*heads), 256 threads, kWindowLds bytes of dynamic LDS.
+// query slots over the resident tiles.  WPW = 4: one workgroup per window (e.g. 16x16
+// windows); WPW = 1: one wavefront per window, four windows per workgroup (e.g. 8x8 windows).
+// Window attention moves 4 rows of 128 bytes per token and does little arithmetic on them, so
+// the point of this kernel is to have many bytes in flight and to start early: the loads of
+// the whole window (64 KB for 256 slots) are issued up front, from global memory straight
+// into LDS with no register staging, tile by tile; a wavefront starts on key tile j as soon
+// as tiles j and j+1 have landed (counted wait, then the barrier of the wavefronts that share
+// the window), so the arithmetic of the early tiles runs under the loads of the late ones.
+// grid (min(work items, 512)), 256 threads, kWindowLds bytes of dynamic LDS.
 // ---------------------------------------------------------------------------------------
 constexpr int kWindowLds = 4 * (2 * 64 * 128 + 64 * 4);
 
+typedef __attribute__((address_space(1))) const void attn_global_cvoid;
+typedef __attribute__((address_space(3))) void attn_lds_void;
+
+// Wait until at most `pending` of this wavefront's vector-memory loads are outstanding
+// (the count is an immediate; values are rounded down to a supported one).
+__device__ inline void wait_vm_loads(int pending) {
+    if (pending >= 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+    else if (pending >= 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (pending >= 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else if (pending >= 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+    else if (pending >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (pending >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else if (pending >= 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if (pending >= 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 template <bool O_BF16, int WPW>
-__global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
+__global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a, int n_items) {
     extern __shared__ __align__(16) unsigned char wsm[];
-    constexpr int R = 64 * WPW;  // LDS rows per window
-    constexpr int T = 64 * WPW;  // threads that load one window
+    constexpr int R = 64 * WPW;       // LDS rows per window
+    constexpr int kIpt = 4 / WPW;     // load instructions per tile, tensor and wavefront (8 rows each)
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int bh = blockIdx.y, b = bh / a.heads, h = bh % a.heads;
-    const int win = WPW == 4 ? blockIdx.x : blockIdx.x * 4 + wave;
+    // A workgroup walks over work items (a window, or four small windows, of one batch and
+    // head), a grid-sized step apart: long-lived workgroups do not pay the launch of a new one
+    // per window.
+    const int items_per_bh = (a.g.n_win * WPW + 3) / 4;
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int bh = item / items_per_bh, b = bh / a.heads, h = bh % a.heads;
+    const int item_x = item % items_per_bh;
+    const int win = WPW == 4 ? item_x : item_x * 4 + wave;
     const bool win_live = win < a.g.n_win;  // WPW == 1: the last workgroup may have idle waves
     const int wy = win_live ? win / a.g.wins_x : 0, wx = win_live ? win % a.g.wins_x : 0;
     unsigned char *ktile = wsm + (WPW == 4 ? 0 : wave * (2 * 64 * 128));
     unsigned char *vtile = ktile + R * 128;
     float *bias = (float *)(wsm + 4 * 2 * 64 * 128) + (WPW == 4 ? 0 : wave * 64);
-    const int t = WPW == 4 ? tid : lane;
+    const int ww = WPW == 4 ? wave : 0;  // this wavefront's share of the window's rows
     const int q0 = WPW == 4 ? wave * 64 : 0;
     const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
     const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
@@ -423,48 +449,50 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     bf16x8 qreg[2][4];
     if (wave_live) load_queries<2>(qreg, a, wy, wx, q0, qbase, lane);
 
+    // Loads, tile by tile: lane = 8 * (row in the group of 8) + 16-byte slot of the LDS row; it
+    // fetches the chunk of the token's K (V) row that belongs in that slot under the tile
+    // layouts.  Every wavefront issues the same number of loads whatever the padding (the
+    // waits below count them): a padding row fetches the window's first token, which is always
+    // real, and is kept out of the softmax by its -inf bias (its values meet zero weights).
     if (win_live) {
-        const int lchunk = t & 7;
-        const __bf16 *kptr = (const __bf16 *)a.k.ptr + kbase + lchunk * 8;
-        const __bf16 *vptr = (const __bf16 *)a.v.ptr + vbase + lchunk * 8;
+        const __bf16 *kptr = (const __bf16 *)a.k.ptr + kbase;
+        const __bf16 *vptr = (const __bf16 *)a.v.ptr + vbase;
+        const int lrow = lane >> 3, lslot = lane & 7;
+        const int tok_first = slot_token(a, wy, wx, 0);
+        for (int j = 0; j < n_tile; ++j) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            u32x4 kreg[4], vreg[4];
-            bool live[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = (4 * half + i) * (T / 8) + (t >> 3);
-                const int tok = row < 32 * n_tile ? slot_token(a, wy, wx, row) : -1;
-                u32x4 zero = {0u, 0u, 0u, 0u};
-                kreg[i] = zero;
-                vreg[i] = zero;
-                live[i] = tok >= 0;
-                if (tok >= 0) {
-                    kreg[i] = *(const u32x4 *)(kptr + (long long)tok * a.k.sn);
-                    vreg[i] = *(const u32x4 *)(vptr + (long long)tok * a.v.sn);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = (4 * half + i) * (T / 8) + (t >> 3);
-                if (row < 32 * n_tile) {
-                    *(u32x4 *)(ktile + tile_off_row(row, lchunk)) = kreg[i];
-                    *(u32x4 *)(vtile + tile_off_tr(row, lchunk)) = vreg[i];
-                    if (lchunk == 0) bias[row] = live[i] ? 0.f : -INFINITY;
-                }
+            for (int i = 0; i < kIpt; ++i) {
+                const int row0 = 32 * j + 8 * (i * WPW + ww), row = row0 + lrow;
+                const int tok = slot_token(a, wy, wx, row);
+                const int src = tok >= 0 ? tok : tok_first;
+                const int kchunk = lslot ^ (row & 7);
+                const int vchunk = lslot ^ (((row ^ (row >> 1)) & 1) << 2);
+                __builtin_amdgcn_global_load_lds(
+                    (attn_global_cvoid *)(kptr + (long long)src * a.k.sn + kchunk * 8),
+                    (attn_lds_void *)(ktile + row0 * 128), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(
+                    (attn_global_cvoid *)(vptr + (long long)src * a.v.sn + vchunk * 8),
+                    (attn_lds_void *)(vtile + row0 * 128), 16, 0, 0);
+                if (lslot == 0) bias[row] = tok >= 0 ? 0.f : -INFINITY;
             }
         }
     }
-    if (WPW == 4) __syncthreads();
-    else __builtin_amdgcn_wave_barrier();
+    // Tiles 0 .. upto have landed for every wavefront of the window.
+    auto tiles_ready = [&](int upto) {
+        wait_vm_loads(2 * kIpt * max(n_tile - 1 - upto, 0));
+        if (WPW == 4) __syncthreads();
+        else __builtin_amdgcn_wave_barrier();
+    };
 
     WaveState<2> w;
     wave_state_init<2>(w);
-    if (wave_live) {
-        const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
-        bf16x8 ka[4];
-        load_k_operands(ka, ktile, 0, lane);
-        for (int tile = 0; tile < n_tile; ++tile) {
+    const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
+    tiles_ready(0);
+    bf16x8 ka[4];
+    if (wave_live) load_k_operands(ka, ktile, 0, lane);
+    for (int tile = 0; tile < n_tile; ++tile) {
+        if (tile + 1 < n_tile) tiles_ready(tile + 1);  // all wavefronts of the workgroup take part
+        if (wave_live) {
             const bool masked = ragged || 32 * (tile + 1) > a.g.slots;
             attn_tile32<2>(w, qreg, ka, tile + 1 < n_tile ? ktile : nullptr, 32 * (tile + 1), vtile,
                            32 * tile, masked ? bias + 32 * tile : nullptr, a.c, lane);
@@ -474,6 +502,9 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     else __builtin_amdgcn_wave_barrier();
     if (wave_live)
         wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, ktile + (WPW == 4 ? wave * 4096 : 0), lane);
+    if (WPW == 4) __syncthreads();  // the staging bytes are the next item's tiles
+    else __builtin_amdgcn_wave_barrier();
+    }
 }
 
 static jv_status set_lds_limit(const void *fn, int bytes) {
@@ -490,8 +521,11 @@ static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
         if (st != JV_OK) return st;
         attr_set = true;
     }
-    dim3 grid((a.g.n_win * WPW + 3) / 4, BH);
-    hipLaunchKernelGGL((attn_window_bf16<O_BF16, WPW>), grid, dim3(256), kWindowLds, stream, a);
+    const long long n_items = (long long)((a.g.n_win * WPW + 3) / 4) * BH;
+    if (n_items >= (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "too many windows");
+    const int resident = 2 * 256;  // two workgroups per compute unit
+    dim3 grid((unsigned)(n_items < resident ? n_items : resident));
+    hipLaunchKernelGGL((attn_window_bf16<O_BF16, WPW>), grid, dim3(256), kWindowLds, stream, a, (int)n_items);
     return launch_status("attn_window_bf16");
 }
 
