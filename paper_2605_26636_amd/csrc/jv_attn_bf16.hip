@@ -399,7 +399,7 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
 // into LDS with no register staging, tile by tile; a wavefront starts on key tile j as soon
 // as tiles j and j+1 have landed (counted wait, then the barrier of the wavefronts that share
 // the window), so the arithmetic of the early tiles runs under the loads of the late ones.
-// grid (min(work items, 512)), 256 threads, kWindowLds bytes of dynamic LDS.
+// grid (ceil(n_win * WPW / 4), B*heads), 256 threads, kWindowLds bytes of dynamic LDS.
 // ---------------------------------------------------------------------------------------
 constexpr int kWindowLds = 4 * (2 * 64 * 128 + 64 * 4);
 
@@ -421,19 +421,13 @@ __device__ inline void wait_vm_loads(int pending) {
 }
 
 template <bool O_BF16, int WPW>
-__global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a, int n_items) {
+__global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char wsm[];
     constexpr int R = 64 * WPW;       // LDS rows per window
     constexpr int kIpt = 4 / WPW;     // load instructions per tile, tensor and wavefront (8 rows each)
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    // A workgroup walks over work items (a window, or four small windows, of one batch and
-    // head), a grid-sized step apart: long-lived workgroups do not pay the launch of a new one
-    // per window.
-    const int items_per_bh = (a.g.n_win * WPW + 3) / 4;
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const int bh = item / items_per_bh, b = bh / a.heads, h = bh % a.heads;
-    const int item_x = item % items_per_bh;
-    const int win = WPW == 4 ? item_x : item_x * 4 + wave;
+    const int bh = blockIdx.y, b = bh / a.heads, h = bh % a.heads;
+    const int win = WPW == 4 ? blockIdx.x : blockIdx.x * 4 + wave;
     const bool win_live = win < a.g.n_win;  // WPW == 1: the last workgroup may have idle waves
     const int wy = win_live ? win / a.g.wins_x : 0, wx = win_live ? win % a.g.wins_x : 0;
     unsigned char *ktile = wsm + (WPW == 4 ? 0 : wave * (2 * 64 * 128));
@@ -502,9 +496,6 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a, int n_ite
     else __builtin_amdgcn_wave_barrier();
     if (wave_live)
         wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, ktile + (WPW == 4 ? wave * 4096 : 0), lane);
-    if (WPW == 4) __syncthreads();  // the staging bytes are the next item's tiles
-    else __builtin_amdgcn_wave_barrier();
-    }
 }
 
 static jv_status set_lds_limit(const void *fn, int bytes) {
@@ -521,11 +512,8 @@ static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
         if (st != JV_OK) return st;
         attr_set = true;
     }
-    const long long n_items = (long long)((a.g.n_win * WPW + 3) / 4) * BH;
-    if (n_items >= (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "too many windows");
-    const int resident = 2 * 256;  // two workgroups per compute unit
-    dim3 grid((unsigned)(n_items < resident ? n_items : resident));
-    hipLaunchKernelGGL((attn_window_bf16<O_BF16, WPW>), grid, dim3(256), kWindowLds, stream, a, (int)n_items);
+    dim3 grid((a.g.n_win * WPW + 3) / 4, BH);
+    hipLaunchKernelGGL((attn_window_bf16<O_BF16, WPW>), grid, dim3(256), kWindowLds, stream, a);
     return launch_status("attn_window_bf16");
 }
 
