@@ -106,9 +106,10 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 
 // ---------------------------------------------------------------------------------------
 // GEMM  y = epilogue(a w^T + bias):  a [M, K], w [N, K], both bf16 with K contiguous, so both
-// matrix-instruction operands are 16-byte row pieces.  One workgroup (4 wavefronts, one per
-// SIMD, the whole register file each) owns a 256 x 256 tile of y; a wavefront owns 128 x 128 of
-// it (4 x 4 blocks of 32 x 32, 256 accumulator registers).
+// matrix-instruction operands are 16-byte row pieces.  One workgroup (8 wavefronts, two per
+// SIMD, half the register file each) owns a 256 x 256 tile of y; a wavefront owns 128 tokens x
+// 64 features of it (4 x 2 blocks of 32 x 32, 128 accumulator registers).  Two wavefronts per
+// SIMD: while one waits (barrier, operands), the other keeps the matrix pipeline busy.
 // K is walked in blocks of 64, i.e. whole 128-byte lines of every row: the 256 x 64 parts of a
 // and of w go from global memory straight into LDS (no register staging) through a ring of
 // five 32 KB slots filled in the order a0 w0 a1 w1 a2 ...  While block p is multiplied, the
@@ -127,7 +128,7 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // bytes wide.
 // Tiles are assigned so that the workgroups an XCD receives (every eighth) walk a contiguous
 // range of tiles, feature-tile fastest: they share the a row-tile and keep w in that L2.
-// grid (8 * ceil(tiles / 8)), 256 threads, kGemmLds bytes of dynamic LDS.
+// grid (8 * ceil(tiles / 8)), 512 threads, kGemmLds bytes of dynamic LDS.
 // ---------------------------------------------------------------------------------------
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kGemmPart = kBM * kBK * 2;               // one operand part: 32 KB
@@ -157,16 +158,14 @@ __device__ inline unsigned gemm_part_off(int row, int chunk) {
 // the workgroup barrier.  "memory" keeps the compiler from moving LDS traffic across it.
 __device__ inline void wait_loads_and_barrier(int pending) {
     // the count is an immediate: take the largest supported value not above `pending`
-    if (pending >= 24) asm volatile("s_waitcnt vmcnt(24) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if (pending >= 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if (pending >= 10) asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (pending >= 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     else if (pending >= 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if (pending >= 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (pending >= 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 template <int EPI, bool OUT_BF16>
-__global__ void __launch_bounds__(256, 1)
+__global__ void __launch_bounds__(512, 1)
 gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                  const float *__restrict__ bias, const float *residual, void *Y, int M, int N,
                  int K, int tiles_n, int n_tiles) {
@@ -176,16 +175,17 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile >= n_tiles) return;  // whole workgroup
     const int m0 = (tile / tiles_n) * kBM, n0 = (tile % tiles_n) * kBN;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 2, wn = wave & 3;  // 128-token half, 64-feature quarter
+    constexpr int kPartLoads = 4;             // load instructions per part and wavefront
 
-    // Global -> LDS: a wavefront moves rows 64*wave .. +63 of a part, 8 rows (1 KB) per
+    // Global -> LDS: a wavefront moves rows 32*wave .. +31 of a part, 8 rows (1 KB) per
     // instruction; lane = 8 * (row in group) + LDS chunk slot, and it fetches the global chunk
-    // that belongs in that slot under the row rotation.  Eight loads per wavefront and part.
+    // that belongs in that slot under the row rotation.  Four loads per wavefront and part.
     const int lrow = lane >> 3;
-    unsigned a_off[8], w_off[8];  // byte offsets of this lane's 16 bytes, k = 0
+    unsigned a_off[kPartLoads], w_off[kPartLoads];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int r = wave * 64 + j * 8 + lrow;
+    for (int j = 0; j < kPartLoads; ++j) {
+        const int r = wave * 32 + j * 8 + lrow;
         const int gchunk = (lane & 7) ^ ((r >> 1) & 7);
         const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);  // edge tiles re-read the last row
         a_off[j] = 2u * ((unsigned)ar * (unsigned)K + gchunk * 8);
@@ -194,56 +194,57 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     const int n_b = K / kBK, n_parts = 2 * n_b;
     // part = 2 * block + (0: a, 1: w); it lives in slot part % 5
     auto issue_part = [&](int part, int slot) {
-        unsigned char *base = smem + slot * kGemmPart + wave * 64 * 128;
+        unsigned char *base = smem + slot * kGemmPart + wave * 32 * 128;
         const unsigned kbytes = 2u * (unsigned)(part >> 1) * kBK;
         if (part & 1) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < kPartLoads; ++j)
                 __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)W + (w_off[j] + kbytes)),
                                                  (lds_void *)(base + j * 1024), 16, 0, 0);
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < kPartLoads; ++j)
                 __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)A + (a_off[j] + kbytes)),
                                                  (lds_void *)(base + j * 1024), 16, 0, 0);
         }
     };
 
-    f32x16 acc[4][4];  // [feature block][token block]
+    f32x16 acc[2][4];  // [feature block][token block]
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
 
     // Operand registers, two sets used in turn by the steps.
-    bf16x8 aop[2][4], wop[2][4];
+    bf16x8 aop[2][4], wop[2][2];
     auto load_ops = [&](int a_slot, int w_slot, int step, int set) {
         const unsigned char *at = smem + a_slot * kGemmPart, *wt = smem + w_slot * kGemmPart;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 4; ++i)
             aop[set][i] = as_bf16x8(*(const u32x4 *)(at + gemm_part_off(wm * 128 + i * 32 + li, 2 * step + g)));
-            wop[set][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_part_off(wn * 128 + i * 32 + li, 2 * step + g)));
-        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            wop[set][i] = as_bf16x8(*(const u32x4 *)(wt + gemm_part_off(wn * 64 + i * 32 + li, 2 * step + g)));
     };
     auto products = [&](int set) {
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[set][nt], aop[set][mt], acc[nt][mt]);
     };
     auto next_slot = [](int s, int by) { s += by; return s >= kGemmSlots ? s - kGemmSlots : s; };
-    // One step whose matrix instructions are interleaved with the 8 LDS reads of the next one.
+    // One step (8 matrix instructions) interleaved with the 6 LDS reads of the next one.
     auto step_with_reads = [&](int set) {
         products(set);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {  // the reads early, so that they have landed by the end
+        for (int i = 0; i < 6; ++i) {  // the reads early, so that they have landed by the end
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     };
     // One block of 64 in K.  a_slot/w_slot hold it; the set-0 operands of its first step are in
     // registers.  `n_issue`: how many of the parts 2p+5, 2p+6 exist; they refill the block's
@@ -264,43 +265,43 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         products(1);
         if (n_issue >= 2) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x010, 16, 0);
+            __builtin_amdgcn_sched_group_barrier(0x010, 2 * kPartLoads, 0);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < 6; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
     };
     for (int part = 0; part < kGemmSlots && part < n_parts; ++part) issue_part(part, part);
-    wait_loads_and_barrier(8 * min(n_parts - 2, kGemmSlots - 2));  // block 0 has landed
+    wait_loads_and_barrier(kPartLoads * min(n_parts - 2, kGemmSlots - 2));  // block 0 has landed
     load_ops(0, 1, 0, 0);
     int p = 0, a_slot = 0, w_slot = 1;
     // Steady state: parts 2p+5 and 2p+6 exist; at the barrier only part 2p+4 may be pending.
     for (; 2 * p + 6 < n_parts; ++p) {
-        block(p, a_slot, w_slot, 2, 8, true);
+        block(p, a_slot, w_slot, 2, kPartLoads, true);
         a_slot = next_slot(a_slot, 2);
         w_slot = next_slot(w_slot, 2);
     }
     for (; p < n_b; ++p) {
         // everything up to part 2p+4 has been issued; block p+1 is complete when at most that
         // part is pending.  The last w part (2p+5) may still have to be issued here.
-        block(p, a_slot, w_slot, 2 * p + 5 < n_parts ? 1 : 0, 2 * p + 4 < n_parts ? 8 : 0, p + 1 < n_b);
+        block(p, a_slot, w_slot, 2 * p + 5 < n_parts ? 1 : 0, 2 * p + 4 < n_parts ? kPartLoads : 0, p + 1 < n_b);
         a_slot = next_slot(a_slot, 2);
         w_slot = next_slot(w_slot, 2);
     }
 
     // Epilogue: accumulator register v of block (nt, mt) is output feature
-    // n0 + 128 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
+    // n0 + 64 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
     // Loads are batched ahead of their use (all bias pieces once, the residual pieces of a
     // token block together) so that their latencies overlap instead of adding up.
-    f32x4 bias_reg[4][4];
+    f32x4 bias_reg[2][4];
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
+            const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
             f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             bias_reg[nt][q4] = (bias && col < N) ? *(const f32x4 *)(bias + col) : zero;
         }
@@ -308,22 +309,22 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     for (int mt = 0; mt < 4; ++mt) {
         const int row = m0 + wm * 128 + mt * 32 + li;
         const bool row_ok = row < M;
-        f32x4 res_reg[4][4];
+        f32x4 res_reg[2][4];
         if (EPI == JV_EPI_RESIDUAL) {
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
+            for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
+                    const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
                     f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                     res_reg[nt][q4] = (row_ok && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
                 }
         }
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const int col = n0 + wn * 128 + nt * 32 + 8 * q4 + 4 * g;
+                const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
                 // N % 8 == 0: the four features of a piece are in or out together
                 f32x4 val = {acc[nt][mt][4 * q4], acc[nt][mt][4 * q4 + 1], acc[nt][mt][4 * q4 + 2],
                              acc[nt][mt][4 * q4 + 3]};
@@ -359,7 +360,7 @@ static jv_status launch_gemm(const void *a, const void *w, const float *bias, co
     const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (N + kBN - 1) / kBN;
     const int n_tiles = tiles_m * tiles_n;
     dim3 grid(8 * ((n_tiles + 7) / 8));
-    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16>), grid, dim3(256), kGemmLds, stream,
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16>), grid, dim3(512), kGemmLds, stream,
                        (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K,
                        tiles_n, n_tiles);
     return launch_status("gemm_bf16_kernel");
