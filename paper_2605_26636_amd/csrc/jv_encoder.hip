@@ -295,7 +295,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     // Epilogue: accumulator register v of block (nt, mt) is output feature
     // n0 + 64 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
     // Loads are batched ahead of their use (all bias pieces once, the residual pieces of a
-    // token block together) so that their latencies overlap instead of adding up.
+    // token block together, one block ahead) so that their latencies overlap.
     f32x4 bias_reg[2][4];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
@@ -305,21 +305,27 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             bias_reg[nt][q4] = (bias && col < N) ? *(const f32x4 *)(bias + col) : zero;
         }
+    // The residual rows of token block mt+1 are fetched before block mt is stored (different
+    // rows, so this is safe although the residual may be y itself): one round trip is exposed
+    // instead of four.
+    f32x4 res_reg[2][2][4];
+    auto load_residual = [&](int mt, int set) {
+        const int row = m0 + wm * 128 + mt * 32 + li;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
+                f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                res_reg[set][nt][q4] = (row < M && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
+            }
+    };
+    if (EPI == JV_EPI_RESIDUAL) load_residual(0, 0);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int row = m0 + wm * 128 + mt * 32 + li;
         const bool row_ok = row < M;
-        f32x4 res_reg[2][4];
-        if (EPI == JV_EPI_RESIDUAL) {
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
-                    f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                    res_reg[nt][q4] = (row_ok && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
-                }
-        }
+        if (EPI == JV_EPI_RESIDUAL && mt + 1 < 4) load_residual(mt + 1, (mt + 1) & 1);
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -333,7 +339,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
                     for (int e = 0; e < 4; ++e) val[e] = gelu_erf(val[e]);
                 }
-                if (EPI == JV_EPI_RESIDUAL) val += res_reg[nt][q4];
+                if (EPI == JV_EPI_RESIDUAL) val += res_reg[mt & 1][nt][q4];
                 if (row_ok && col < N) {
                     const size_t at_out = (size_t)row * N + col;
                     if (OUT_BF16) {
