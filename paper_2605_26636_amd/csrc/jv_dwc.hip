@@ -60,8 +60,16 @@ squeeze_hidden(const float *__restrict__ vsum, int n_part, const float *__restri
     extern __shared__ __align__(16) float gmean[];
     const int b = blockIdx.x, BH = gridDim.x * heads, C = heads * kHeadDim;
     for (int c = threadIdx.x; c < C; c += 256) {
+        const float *src = vsum + (size_t)b * heads * kHeadDim + c;
+        const size_t stride = (size_t)BH * kHeadDim;
         float s = 0.f;
-        for (int p = 0; p < n_part; ++p) s += vsum[((size_t)p * BH + (size_t)b * heads) * kHeadDim + c];
+        for (int p0 = 0; p0 < n_part; p0 += 8) {  // eight partials in flight at a time
+            float part[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) part[i] = p0 + i < n_part ? src[(size_t)(p0 + i) * stride] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += part[i];
+        }
         gmean[c] = s * inv_n;
     }
     __syncthreads();
@@ -70,7 +78,17 @@ squeeze_hidden(const float *__restrict__ vsum, int n_part, const float *__restri
     if (j >= hidden) return;
     const float *row = w1 + (size_t)j * C;
     float acc = 0.f;
-    for (int c = lane; c < C; c += 64) acc = fmaf(row[c], gmean[c], acc);
+    if ((C & 255) == 0) {  // 16-byte loads, lane-strided
+        for (int c = 4 * lane; c < C; c += 256) {
+            const f32x4 wv = *(const f32x4 *)(row + c), gv = *(const f32x4 *)(gmean + c);
+            acc = fmaf(wv[0], gv[0], acc);
+            acc = fmaf(wv[1], gv[1], acc);
+            acc = fmaf(wv[2], gv[2], acc);
+            acc = fmaf(wv[3], gv[3], acc);
+        }
+    } else {
+        for (int c = lane; c < C; c += 64) acc = fmaf(row[c], gmean[c], acc);
+    }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
     if (lane == 0) {

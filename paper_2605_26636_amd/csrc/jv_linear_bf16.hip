@@ -167,8 +167,8 @@ la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
 // `states` holds n_part partial states per (batch, head), part_stride floats apart.
 // KS = 0: linear attention alone.  KS = 3 or 5: the block's convolution branch is added before
 // the store: the normalised tile is staged in LDS as fp32, and the lane that stores 8 channels
-// of a token first adds sum_taps kappa[c][tap] * V[token + tap][c] for them (V rows of the
-// neighbouring tokens come from the caches: every V row is used by KS*KS tokens).
+// of 4 consecutive tokens first adds sum_taps kappa[c][tap] * V[token + tap][c] for them (V rows
+// of the neighbouring tokens come from the caches: every V row is used by KS*KS tokens).
 template <bool O_BF16, int KS>
 __global__ void __launch_bounds__(256, 2)
 la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int n_part,
@@ -312,47 +312,74 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
                                      acc[mi][4 * q4 + 2] * inv, acc[mi][4 * q4 + 3] * inv};
                         *(f32x4 *)(otile + li * 256 + (((8 * mi + 2 * q4 + g) ^ (li & 15)) << 4)) = val;
                     }
-                constexpr int kPad = KS / 2;
-                constexpr int kRowUnroll = 1;  // one tap row of loads in flight (register budget)
-#pragma unroll 1
-                for (int r = 0; r < 4; ++r) {
-                    const int orow = r * 8 + lrow, on = t + 32 * nt + orow;
-                    const f32x4 o0 = *(const f32x4 *)(otile + orow * 256 + (((2 * lchunk) ^ (orow & 15)) << 4));
-                    const f32x4 o1 = *(const f32x4 *)(otile + orow * 256 + (((2 * lchunk + 1) ^ (orow & 15)) << 4));
-                    float sum[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
-                    // Out-of-grid taps (and the slots past the end of the range) read a valid
-                    // row with weight zero, so all loads of a token can be in flight at once.
-                    const int tok = min(on, n1 - 1);
-                    const int gr = tok / cv.W, gc = tok - gr * cv.W;
-#pragma unroll kRowUnroll
-                    for (int di = -kPad; di <= kPad; ++di)
+                // A lane finishes 4 consecutive tokens x 8 channels: the taps of neighbouring
+                // tokens overlap, so one tap row needs 4 + KS - 1 loads instead of 4 * KS.
+                // Out-of-grid taps (and slots past the end of the range) read a valid row with
+                // weight zero, so the loads of a tap row are all in flight at once.
+                constexpr int kPad = KS / 2, kSpan = 4 + KS - 1;
+                const int tok0 = t + 32 * nt + 4 * lrow;            // first of this lane's tokens
+                const int last = n1 - 1;
+                float sum[4][8];
+                int gr[4], gc[4];
+                {
+                    const int base = min(tok0, last);
+                    int r0 = base / cv.W, c0 = base - r0 * cv.W;
 #pragma unroll
-                        for (int dj = -kPad; dj <= kPad; ++dj) {
-                            const bool ok = (unsigned)(gr + di) < (unsigned)cv.H &&
-                                            (unsigned)(gc + dj) < (unsigned)cv.W;
-                            const int src = ok ? tok + di * cv.W + dj : tok;
-                            const u32x4 vv = *(const u32x4 *)(vp + (long long)src * vt.sn + lchunk * 8);
-                            const float *kr = kap + ((di + kPad) * KS + dj + kPad) * kHeadDim + 8 * lchunk;
-                            const f32x4 k0 = *(const f32x4 *)kr, k1 = *(const f32x4 *)(kr + 4);
+                    for (int r = 0; r < 4; ++r) {
+                        const int orow = 4 * lrow + r;
+                        const f32x4 o0 = *(const f32x4 *)(otile + orow * 256 + (((2 * lchunk) ^ (orow & 15)) << 4));
+                        const f32x4 o1 = *(const f32x4 *)(otile + orow * 256 + (((2 * lchunk + 1) ^ (orow & 15)) << 4));
+                        sum[r][0] = o0[0]; sum[r][1] = o0[1]; sum[r][2] = o0[2]; sum[r][3] = o0[3];
+                        sum[r][4] = o1[0]; sum[r][5] = o1[1]; sum[r][6] = o1[2]; sum[r][7] = o1[3];
+                        gr[r] = r0;
+                        gc[r] = c0;
+                        if (++c0 == cv.W) { c0 = 0; ++r0; }
+                    }
+                }
+#pragma unroll 1
+                for (int di = -kPad; di <= kPad; ++di) {
+                    u32x4 vv[kSpan];
+#pragma unroll
+                    for (int j = 0; j < kSpan; ++j) {
+                        const int src = tok0 + j - kPad + di * cv.W;  // token of column j in this tap row
+                        const int safe = min(max(src, 0), N - 1);
+                        vv[j] = *(const u32x4 *)(vp + (long long)safe * vt.sn + lchunk * 8);
+                    }
+                    const float *krow = kap + (di + kPad) * KS * kHeadDim + 8 * lchunk;
+#pragma unroll
+                    for (int dj = -kPad; dj <= kPad; ++dj) {
+                        const f32x4 k0 = *(const f32x4 *)(krow + (dj + kPad) * kHeadDim);
+                        const f32x4 k1 = *(const f32x4 *)(krow + (dj + kPad) * kHeadDim + 4);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const bool ok = tok0 + r <= last && (unsigned)(gr[r] + di) < (unsigned)cv.H &&
+                                            (unsigned)(gc[r] + dj) < (unsigned)cv.W;
                             const float m = ok ? 1.0f : 0.0f;
-                            sum[0] = fmaf(k0[0] * m, bf16_lo(vv[0]), sum[0]);
-                            sum[1] = fmaf(k0[1] * m, bf16_hi(vv[0]), sum[1]);
-                            sum[2] = fmaf(k0[2] * m, bf16_lo(vv[1]), sum[2]);
-                            sum[3] = fmaf(k0[3] * m, bf16_hi(vv[1]), sum[3]);
-                            sum[4] = fmaf(k1[0] * m, bf16_lo(vv[2]), sum[4]);
-                            sum[5] = fmaf(k1[1] * m, bf16_hi(vv[2]), sum[5]);
-                            sum[6] = fmaf(k1[2] * m, bf16_lo(vv[3]), sum[6]);
-                            sum[7] = fmaf(k1[3] * m, bf16_hi(vv[3]), sum[7]);
+                            const u32x4 x = vv[r + dj + kPad];
+                            sum[r][0] = fmaf(k0[0] * m, bf16_lo(x[0]), sum[r][0]);
+                            sum[r][1] = fmaf(k0[1] * m, bf16_hi(x[0]), sum[r][1]);
+                            sum[r][2] = fmaf(k0[2] * m, bf16_lo(x[1]), sum[r][2]);
+                            sum[r][3] = fmaf(k0[3] * m, bf16_hi(x[1]), sum[r][3]);
+                            sum[r][4] = fmaf(k1[0] * m, bf16_lo(x[2]), sum[r][4]);
+                            sum[r][5] = fmaf(k1[1] * m, bf16_hi(x[2]), sum[r][5]);
+                            sum[r][6] = fmaf(k1[2] * m, bf16_lo(x[3]), sum[r][6]);
+                            sum[r][7] = fmaf(k1[3] * m, bf16_hi(x[3]), sum[r][7]);
                         }
-                    if (on < n1) {
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int on = tok0 + r;
+                    if (on <= last) {
                         if (O_BF16) {
                             __bf16 *op = (__bf16 *)ot.ptr + b * ot.sb + h * ot.sh;
-                            u32x4 pk = {pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3]),
-                                        pack_bf16x2(sum[4], sum[5]), pack_bf16x2(sum[6], sum[7])};
+                            u32x4 pk = {pack_bf16x2(sum[r][0], sum[r][1]), pack_bf16x2(sum[r][2], sum[r][3]),
+                                        pack_bf16x2(sum[r][4], sum[r][5]), pack_bf16x2(sum[r][6], sum[r][7])};
                             *(u32x4 *)(op + (long long)on * ot.sn + lchunk * 8) = pk;
                         } else {
                             float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)on * ot.sn + lchunk * 8;
-                            f32x4 s0 = {sum[0], sum[1], sum[2], sum[3]}, s1 = {sum[4], sum[5], sum[6], sum[7]};
+                            f32x4 s0 = {sum[r][0], sum[r][1], sum[r][2], sum[r][3]};
+                            f32x4 s1 = {sum[r][4], sum[r][5], sum[r][6], sum[r][7]};
                             *(f32x4 *)op = s0;
                             *(f32x4 *)(op + 4) = s1;
                         }
