@@ -22,6 +22,13 @@
  * gives the mean of V, V = 1 gives 1, softmax rows sum to 1, key-shift and
  * positive-scale invariances), exhaustive index-map enumeration.
  *
+ * Parity unpinned against the paper itself (the mathematics of every routine is pinned as
+ * above): jvo_squeeze_kernel -- the paper describes the generator of the dynamic filters only
+ * as a compact two-layer MLP with SiLU fed by the token average of V; where the activation
+ * sits, the biases and the hidden width are this file's reading -- and the encoder routines in
+ * the Python front end (pre-LN block, exact GELU, no final norm), which the paper leaves to the
+ * pretrained model it inherits from.
+ *
  * Return value: 0 on success, 1 on an invalid argument.
  */
 #include <math.h>
