@@ -344,12 +344,12 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
             }
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, bool all_live) {
         unsigned char *kt = smem + buf * kStageBytes, *vt = kt + kStage * 128;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = lrow + 32 * i;
-            if (!live[i]) {  // padding rows are zero in LDS and carry a -inf bias
+            if (!all_live && !live[i]) {  // padding rows are zero in LDS and carry a -inf bias
                 u32x4 zero = {0u, 0u, 0u, 0u};
                 kreg[i] = zero;
                 vreg[i] = zero;
@@ -374,12 +374,13 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
             attn_tile32<NT>(w, qreg, ka, nullptr, 0, vt, 32, masked ? &bias[buf][32] : nullptr, a.c,
                             lane);
         }
-        if (more) stash(buf ^ 1);
+        // (all_live is wave-uniform: a whole stage of real tokens needs no per-row select)
+        if (more) stash(buf ^ 1, FAST && (st + 2) * kStage <= tok_limit);
         __syncthreads();
     };
 
     fetch(0);
-    stash(0);
+    stash(0, false);
     __syncthreads();
     for (int st = 0; st < n_stage; st += 2) {
         run_stage(st, std::integral_constant<int, 0>());
@@ -459,7 +460,7 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
                 const int row0 = 32 * j + 8 * (i * WPW + ww), row = row0 + lrow;
                 const int tok = slot_token(a, wy, wx, row);
                 const int src = tok >= 0 ? tok : tok_first;
-                const int kchunk = lslot ^ (row & 7);
+                const int kchunk = lslot ^ tile_row_rotation(row);
                 const int vchunk = lslot ^ (((row ^ (row >> 1)) & 1) << 2);
                 __builtin_amdgcn_global_load_lds(
                     (attn_global_cvoid *)(kptr + (long long)src * a.k.sn + kchunk * 8),

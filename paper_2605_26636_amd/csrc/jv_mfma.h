@@ -88,9 +88,12 @@ __device__ inline void pair_values(float x, float *lo, float *hi) {
 __device__ inline unsigned tile_off_tr(int row, int chunk16) {
     return (unsigned)(row * 128 + ((chunk16 ^ (((row ^ (row >> 1)) & 1) << 2)) << 4));
 }
-// Same tile, for row-per-lane 16-byte reads: the chunk index is rotated by the row.
+// Same tile, for row-per-lane 16-byte reads: the chunk index is rotated by the row pair, so
+// that the 16 consecutive rows one pass of such a read touches (16 lanes x 16 bytes = all 64
+// banks) land on 16 different 16-byte bank groups.
+__device__ inline int tile_row_rotation(int row) { return (row >> 1) & 7; }
 __device__ inline unsigned tile_off_row(int row, int chunk16) {
-    return (unsigned)(row * 128 + ((chunk16 ^ (row & 7)) << 4));
+    return (unsigned)(row * 128 + ((chunk16 ^ tile_row_rotation(row)) << 4));
 }
 
 // Operand "lane = channel, k-slots = 8 tokens" read from a [token][channel] tile laid out
