@@ -499,6 +499,166 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
         wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, ktile + (WPW == 4 ? wave * 4096 : 0), lane);
 }
 
+// ---------------------------------------------------------------------------------------
+// Window-resident kernel for 256-slot windows on grids the window divides (e.g. 16x16 windows
+// on a 64x64 grid): one window per workgroup at a time, software-pipelined ACROSS windows so
+// that loads are in flight the whole time.  A persistent workgroup walks over its windows; the
+// two halves of the K/V tiles (key tiles 0-3 = half A, 4-7 = half B) are refilled for the next
+// window as soon as the current window is done with them:
+//     window start:   loads of half B (this window) are issued; half A is already in LDS
+//     tiles 0-3       (half A)
+//     middle:         wait for half B; barrier; issue half A of the NEXT window
+//     tiles 4-7       (half B)
+//     window end:     wait for the next window's half A; barrier; fetch the next window's
+//                     queries; normalise and store through staging bytes in half B; barrier
+// Both waits are "everything this wavefront has issued" (vmcnt 0): what is outstanding at
+// those points beyond the awaited loads are only stores and loads issued half a window
+// earlier.  Everything that depends on the lane but not on the window (which token of the
+// window a lane loads or stores, as a byte offset from the window's first token) is computed
+// once, so that a window switch costs a handful of scalar operations.
+// grid (min(windows * B*heads, 512)), 256 threads, 64 KB of dynamic LDS.
+// Requires: slots == 256, grid_h % win_h == 0, grid_w % win_w == 0, and byte offsets inside a
+// window below 2^31 (checked by the launcher).
+// ---------------------------------------------------------------------------------------
+constexpr int kWindow8Lds = 2 * 256 * 128;
+
+template <bool O_BF16>
+__global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_items) {
+    extern __shared__ __align__(16) unsigned char wsm[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+    unsigned char *ktile = wsm, *vtile = wsm + 256 * 128;
+    const int lrow = lane >> 3, lslot = lane & 7;
+    const int q0 = wave * 64;
+    const int esz_o = O_BF16 ? 2 : 4;
+
+    // token of window slot `row`, relative to the window's first token (256 slots: the window
+    // width is a power of two)
+    const int ww_shift = __builtin_ctz(a.g.ww);
+    auto rel_token = [&](int row) { return (row >> ww_shift) * a.g.W + (row & (a.g.ww - 1)); };
+    // K/V loads: byte offset of this lane's 16 bytes in key tile 0; 32 slots further on (the next
+    // tile) is a fixed number of tokens, and the chunk rotations repeat every 16 rows.
+    const int row_kv = 8 * wave + lrow;
+    const unsigned tile_tokens = a.g.ww >= 32 ? 32u : (unsigned)(32 >> ww_shift) * (unsigned)a.g.W;
+    const unsigned koff0 = 2u * ((unsigned)rel_token(row_kv) * (unsigned)a.k.sn + (lslot ^ tile_row_rotation(row_kv)) * 8);
+    const unsigned voff0 = 2u * ((unsigned)rel_token(row_kv) * (unsigned)a.v.sn + (lslot ^ (((row_kv ^ (row_kv >> 1)) & 1) << 2)) * 8);
+    const unsigned kstep = 2u * tile_tokens * (unsigned)a.k.sn, vstep = 2u * tile_tokens * (unsigned)a.v.sn;
+
+    struct Item {
+        const char *q, *k, *v;
+        char *o;
+    };
+    auto make_item = [&](int item) {
+        const int bh = item / a.g.n_win, win = item % a.g.n_win, b = bh / a.heads, h = bh % a.heads;
+        const long long origin = (long long)(win / a.g.wins_x) * a.g.wh * a.g.W + (win % a.g.wins_x) * a.g.ww;
+        // the bases are the same in every lane: say so, and the loads take them as scalar bases
+        auto uniform = [](const char *ptr) {
+            const unsigned long long u = (unsigned long long)ptr;
+            const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u);
+            const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+            return (const char *)(((unsigned long long)hi << 32) | lo);
+        };
+        Item it;
+        it.q = uniform((const char *)a.q.ptr + 2 * (b * a.q.sb + h * a.q.sh + origin * a.q.sn));
+        it.k = uniform((const char *)a.k.ptr + 2 * (b * a.k.sb + h * a.k.sh + origin * a.k.sn));
+        it.v = uniform((const char *)a.v.ptr + 2 * (b * a.v.sb + h * a.v.sh + origin * a.v.sn));
+        it.o = (char *)uniform((const char *)a.o.ptr + esz_o * (b * a.o.sb + h * a.o.sh + origin * a.o.sn));
+        return it;
+    };
+    auto issue_half = [&](const Item &it, int half) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int j = 4 * half + jj, row0 = 32 * j + 8 * wave;
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.k + (koff0 + j * kstep)),
+                                             (attn_lds_void *)(ktile + row0 * 128), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.v + (voff0 + j * vstep)),
+                                             (attn_lds_void *)(vtile + row0 * 128), 16, 0, 0);
+        }
+    };
+    bf16x8 qreg[2][4];
+    auto load_q = [&](const Item &it) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const unsigned qoff = 2u * ((unsigned)rel_token(q0 + 32 * nt + li) * (unsigned)a.q.sn + g * 8);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) qreg[nt][ks] = as_bf16x8(*(const u32x4 *)(it.q + (qoff + 32 * ks)));
+        }
+    };
+    auto drain_and_sync = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+
+    int item = blockIdx.x;
+    if (item >= n_items) return;  // whole workgroup
+    Item cur = make_item(item);
+    load_q(cur);
+    issue_half(cur, 0);
+    drain_and_sync();
+    for (;;) {
+        issue_half(cur, 1);
+        const int next = item + gridDim.x;
+        const bool has_next = next < n_items;
+        Item nxt = cur;
+        WaveState<2> w;
+        wave_state_init<2>(w);
+        bf16x8 ka[4];
+#pragma unroll 1
+        for (int tile = 0; tile < 8; ++tile) {
+            if (tile == 4) {
+                drain_and_sync();  // half B has landed; every wavefront is done with half A
+                if (has_next) {
+                    nxt = make_item(next);
+                    issue_half(nxt, 0);
+                }
+            }
+            if ((tile & 3) == 0) load_k_operands(ka, ktile, 32 * tile, lane);
+            attn_tile32<2>(w, qreg, ka, (tile & 3) != 3 ? ktile : nullptr, 32 * (tile + 1), vtile, 32 * tile,
+                           nullptr, a.c, lane);
+        }
+        drain_and_sync();  // the next window's half A has landed; half B is free
+        if (has_next) load_q(nxt);
+        unsigned char *stage = ktile + 128 * 128 + wave * 4096;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            float lo, hi;
+            pair_values(w.l[nt], &lo, &hi);
+            const float inv = __builtin_amdgcn_rcpf(lo + hi);
+            if (O_BF16) {
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x16 &x = w.acc[mi][nt];
+                        u32x2 pk = {pack_bf16x2(x[4 * q4] * inv, x[4 * q4 + 1] * inv),
+                                    pack_bf16x2(x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv)};
+                        *(u32x2 *)(stage + tile_off_row(li, 4 * mi + q4) + 8 * g) = pk;
+                    }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const u32x4 val = *(const u32x4 *)(stage + tile_off_row(r * 8 + lrow, lslot));
+                    const unsigned ooff = 2u * ((unsigned)rel_token(q0 + 32 * nt + r * 8 + lrow) * (unsigned)a.o.sn + lslot * 8);
+                    *(u32x4 *)(cur.o + ooff) = val;
+                }
+            } else {
+                const unsigned ooff = 4u * (unsigned)rel_token(q0 + 32 * nt + li) * (unsigned)a.o.sn;
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x16 &x = w.acc[mi][nt];
+                        f32x4 val = {x[4 * q4] * inv, x[4 * q4 + 1] * inv, x[4 * q4 + 2] * inv,
+                                     x[4 * q4 + 3] * inv};
+                        *(f32x4 *)(cur.o + (ooff + 4 * (32 * mi + 8 * q4 + 4 * g))) = val;
+                    }
+            }
+        }
+        __syncthreads();  // staging bytes are read out: half B may be refilled
+        if (!has_next) break;
+        cur = nxt;
+        item = next;
+    }
+}
+
 static jv_status set_lds_limit(const void *fn, int bytes) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
@@ -518,6 +678,22 @@ static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
     return launch_status("attn_window_bf16");
 }
 
+template <bool O_BF16>
+static jv_status launch_window8(const AttnArgs &a, int BH, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        jv_status st = set_lds_limit((const void *)attn_window8_bf16<O_BF16>, kWindow8Lds);
+        if (st != JV_OK) return st;
+        attr_set = true;
+    }
+    const long long n_items = (long long)a.g.n_win * BH;
+    if (n_items >= (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "too many windows");
+    const int resident = 2 * 256;  // two workgroups per compute unit
+    dim3 grid((unsigned)(n_items < resident ? n_items : resident));
+    hipLaunchKernelGGL((attn_window8_bf16<O_BF16>), grid, dim3(256), kWindow8Lds, stream, a, (int)n_items);
+    return launch_status("attn_window8_bf16");
+}
+
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStream_t stream) {
     AttnArgs a;
     a.q = pr.q; a.k = pr.k; a.v = pr.v; a.o = pr.o;
@@ -530,6 +706,14 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStre
     if (g.slots <= 64)
         return pr.o_bf16 ? launch_window<true, 1>(a, pr.B * pr.heads, stream)
                          : launch_window<false, 1>(a, pr.B * pr.heads, stream);
+    if (g.slots == 256 && g.n_win > 1 && g.H % g.wh == 0 && g.W % g.ww == 0) {
+        // byte offsets of a window's tokens from its first one in 32 bits?
+        long long max_sn = pr.q.sn;
+        for (long long sn : {pr.k.sn, pr.v.sn, pr.o.sn}) max_sn = sn > max_sn ? sn : max_sn;
+        if (((long long)(g.wh - 1) * g.W + g.ww) * max_sn * 4 + 256 < (1ll << 31))
+            return pr.o_bf16 ? launch_window8<true>(a, pr.B * pr.heads, stream)
+                             : launch_window8<false>(a, pr.B * pr.heads, stream);
+    }
     if (g.slots <= 256 && g.n_win > 1)
         return pr.o_bf16 ? launch_window<true, 4>(a, pr.B * pr.heads, stream)
                          : launch_window<false, 4>(a, pr.B * pr.heads, stream);

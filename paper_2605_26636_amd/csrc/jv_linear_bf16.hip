@@ -118,12 +118,13 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restr
     }
     __syncthreads();
     float *out = ws + ((size_t)part * BH + bh) * kStateFloats;
-    for (int e = tid; e < kHeadDim * kHeadDim; e += 256) {
-        const int at = (e >> 6) * 68 + (e & 63);
-        float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) s += ((const float *)(smem + w * kWaveLds))[at];
-        out[e] = s;
+    for (int i = 0; i < kHeadDim * kHeadDim / 4 / 256; ++i) {  // 16-byte pieces, 4 per thread
+        const int e4 = tid + 256 * i, at = (e4 >> 4) * 68 + (e4 & 15) * 4;
+        f32x4 s = *(const f32x4 *)((const float *)smem + at);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) s += *(const f32x4 *)((const float *)(smem + w * kWaveLds) + at);
+        *(f32x4 *)(out + 4 * e4) = s;
     }
     if (tid < kHeadDim) {
         float s = 0.f;
