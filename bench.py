@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--buffers", type=int, default=6, help="rotating input/output sets")
     ap.add_argument("--encoder", action="store_true",
                     help="run only the hybrid ViT-L encoder forward (config 5)")
+    ap.add_argument("--paper-ratio", action="store_true",
+                    help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
+                         "(the resolution of the paper's speed tables), as ratios")
     ap.add_argument("--only", choices=["linear", "window", "full", "block"], default=None,
                     help="run only this mixer's launches (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -77,6 +80,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.paper_ratio:
+        print(json.dumps(bench_paper_ratio(args.steps, args.warmup)))
+        return
     if args.encoder:
         enc = bench_encoder(args.steps, args.warmup)
         print(json.dumps({
@@ -263,6 +269,61 @@ def bench_encoder(steps, warmup):
             "ms_per_encoder": ms, "ms_per_layer": ms / L, "tokens_per_s": T / (ms * 1e-3),
             "steps": steps, "warmup": warmup, "flops_per_encoder": flops, "gemm_flops": gemm_flops,
             "TFLOPs": tf, "mfma_frac": tf / MFMA_BF16_PEAK_TFLOPS}
+
+
+def bench_paper_ratio(steps, warmup):
+    """The paper's speed comparison re-created with random weights: a 24-block ViT-L on a 64x128
+    token grid (1024x2048 px at patch 16, the resolution of its Tab. 1 and Tab. 3), batch 1,
+    all blocks full attention against hybrids that keep 0, 1 or 2 full-attention blocks (at
+    blocks 14 and 22, where the paper's search puts them for segmentation, Sec. 4.4); the first
+    block is linear attention, the others alternate window 16x16 and linear attention; linear
+    blocks carry the squeeze-dynamic 3x3 convolution branch (hidden width C/16)."""
+    import torch
+    from paper_2605_26636_amd import binding, synth
+    B, H, W, heads, hidden, L = 1, 64, 128, 16, 4096, 24
+    C, N = heads * 64, H * W
+    dev = []
+    for l in range(L):
+        wts = synth.block_weights(C, hidden, 5000 + l)
+        d = {k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_")
+                 else torch.from_numpy(v).cuda()) for k, v in wts.items()}
+        d["dwc"] = {"squeeze": tuple(torch.from_numpy(a).cuda()
+                                     for a in synth.squeeze_weights(C, C // 16, 3, 6000 + l)), "ksize": 3}
+        dev.append(d)
+
+    def hybrid(full_at):
+        out = []
+        for l in range(L):
+            if l in full_at:
+                out.append(synth.MIX_FULL)
+            else:
+                out.append(synth.MIX_LINEAR if l % 2 == 0 else synth.MIX_WINDOW)
+        return out
+
+    patterns = {"all_full": [synth.MIX_FULL] * L, "hybrid_0_full": hybrid(()),
+                "hybrid_1_full": hybrid((14,)), "hybrid_2_full": hybrid((14, 22))}
+    x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda()
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    ms = {}
+    for name, pattern in patterns.items():
+        enc = binding.Encoder(dev, pattern, heads, hidden, window=(16, 16))
+        ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")
+        for _ in range(warmup):
+            enc.forward(x, y, (H, W), ws, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            enc.forward(x, y, (H, W), ws, stream)
+        torch.cuda.synchronize()
+        ms[name] = (time.perf_counter() - t0) * 1e3 / steps
+        enc.close()
+    base = ms["all_full"]
+    return {"metric": "encoder latency ratio, all-full-attention ViT-L vs hybrid (64x128 grid, batch 1)",
+            "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16",
+            "data": "synthetic", "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
+            "paper_context_h100": {"DINOv3-L -> JetViT-L (2 full-attention blocks), whole model": "35.07 ms -> 18.77 ms (1.87x)",
+                                   "DINOv3-B -> JetViT-B 0/1/2 full-attention blocks": "12.86 ms -> 7.37 / 7.69 / 8.27 ms"}}
 
 
 def cpu_baseline(q, k, v, H, W, window):

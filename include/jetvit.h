@@ -236,6 +236,10 @@ typedef struct {
     const float *ln2_g, *ln2_b;
     const void *w_fc1; const float *b_fc1;
     const void *w_fc2; const float *b_fc2;
+    /* Linear-attention blocks only: the convolution branch of the paper's block (Eq. 4), as for
+     * jv_linear_block_fwd; host pointer, copied by jv_encoder_create; NULL = plain linear
+     * attention.  Ignored for window and full-attention blocks. */
+    const jv_dwc_params *dwc;
 } jv_block_weights;
 
 typedef struct jv_encoder jv_encoder;

@@ -262,7 +262,8 @@ MIX_LINEAR, MIX_WINDOW, MIX_FULL = 0, 1, 2
 def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
     """One pre-LN block:  x += W_O mix(split_heads(W_qkv LN(x))) + b_O;  x += MLP(LN(x)).
     x float64 [B, N, C]; wts: dict of float32 arrays (ln1_g, ln1_b, w_qkv [3C, C], b_qkv, w_o,
-    b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2).  Q, K, V reach the mixer routines as
+    b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2; optionally "dwc": dict with static_kernel or
+    squeeze = (w1, b1, w2, b2), and ksize, for a linear-attention block).  Q, K, V reach the mixer routines as
     float32 (their input type): a 2^-24 rounding, far below every tolerance used."""
     B, N, C = x.shape
     d = C // heads
@@ -271,7 +272,12 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
     q, k, v = (np.ascontiguousarray(qkv[:, :, i].transpose(0, 2, 1, 3)).astype(np.float32)
                for i in range(3))
     if mixer == MIX_LINEAR:
-        o = linear_attn_quadratic(q, k, v, la_eps)
+        dwc_cfg = wts.get("dwc")   # the block's convolution branch (Eq. 4), if it has one
+        if dwc_cfg:
+            o = linear_block(q, k, v, H, W, la_eps, static_kernel=dwc_cfg.get("static_kernel"),
+                             squeeze=dwc_cfg.get("squeeze"), ksize=dwc_cfg.get("ksize", 3))
+        else:
+            o = linear_attn_quadratic(q, k, v, la_eps)
     elif mixer == MIX_WINDOW:
         o = window_attn(q, k, v, H, W, window[0], window[1])
     else:

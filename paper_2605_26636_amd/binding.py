@@ -59,7 +59,7 @@ BLOCK_FIELDS = ["ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_
 
 
 class JvBlockWeights(ctypes.Structure):
-    _fields_ = [(name, ctypes.c_void_p) for name in BLOCK_FIELDS]
+    _fields_ = [(name, ctypes.c_void_p) for name in BLOCK_FIELDS] + [("dwc", ctypes.POINTER(JvDwcParams))]
 
 
 class JvError(RuntimeError):
@@ -297,9 +297,17 @@ class Encoder:
         cfg = JvEncoderConfig(n, self.width, heads, mlp_hidden, window[0], window[1], ln_eps, la_eps,
                               ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)))
         table = (JvBlockWeights * n)()
+        self._dwc = []   # parameter structs stay alive until the encoder has copied them
         for i, b in enumerate(blocks):
             for name in BLOCK_FIELDS:
                 setattr(table[i], name, b[name].data_ptr())
+            # optional convolution branch of a linear-attention block: b["dwc"] is a dict with
+            # "static_kernel" or "squeeze" (tuple of device tensors) and "ksize"
+            if b.get("dwc") is not None:
+                d = b["dwc"]
+                params = make_dwc_params(d.get("static_kernel"), d.get("squeeze"), d.get("ksize", 3))
+                self._dwc.append(params)
+                table[i].dwc = ctypes.pointer(params)
         self._handle = ctypes.c_void_p()
         _check(lib().jv_encoder_create(ctypes.byref(cfg), table, ctypes.byref(self._handle)))
 

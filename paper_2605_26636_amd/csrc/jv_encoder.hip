@@ -5,6 +5,7 @@
 #include <new>
 
 #include "jv_common.h"
+#include "jv_linear.h"
 #include "jv_mfma.h"
 
 namespace jv {
@@ -403,12 +404,35 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace jv
 
+struct jv_encoder;
+namespace jv {
+static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N);
+}
+
 // The encoder object: configuration and weight pointers, host memory only.
 struct jv_encoder {
     jv_encoder_config cfg;
     uint8_t *pattern;
     jv_block_weights *blocks;
+    jv_dwc_params *dwc;  // per block, a copy of the caller's parameters (mode none if absent)
 };
+
+namespace jv {
+// Largest linear-attention workspace any block needs (the blocks with a convolution branch
+// also keep their generated filters there).
+static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N) {
+    const LinearPlan lp = plan_linear(batch, enc->cfg.heads, N);
+    size_t need = linear_workspace_bytes(batch, enc->cfg.heads, N);
+    for (int l = 0; l < enc->cfg.n_blocks; ++l) {
+        DwcPlan plan;
+        if (plan_dwc(&enc->dwc[l], lp, batch, enc->cfg.heads, &plan) == JV_OK) {
+            const size_t bytes = plan.total_floats * sizeof(float);
+            need = bytes > need ? bytes : need;
+        }
+    }
+    return need;
+}
+}  // namespace jv
 
 extern "C" {
 
@@ -460,21 +484,31 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
         for (const void *p : ptrs)
             if (!p || ((uintptr_t)p & 15))
                 return jv::fail(JV_ERR_INVALID_ARG, "block %d: null or misaligned weight pointer", l);
+        if (c.pattern[l] == 0 && b.dwc) {  // validate the convolution parameters now
+            jv::DwcPlan plan;
+            jv_status st = jv::plan_dwc(b.dwc, jv::plan_linear(1, c.heads, 256), 1, c.heads, &plan);
+            if (st != JV_OK) return st;
+        }
     }
     jv_encoder *e = new (std::nothrow) jv_encoder;
     if (!e) return jv::fail(JV_ERR_INVALID_ARG, "out of host memory");
     e->cfg = c;
     e->pattern = new (std::nothrow) uint8_t[c.n_blocks];
     e->blocks = new (std::nothrow) jv_block_weights[c.n_blocks];
-    if (!e->pattern || !e->blocks) {
+    e->dwc = new (std::nothrow) jv_dwc_params[c.n_blocks];
+    if (!e->pattern || !e->blocks || !e->dwc) {
         delete[] e->pattern;
         delete[] e->blocks;
+        delete[] e->dwc;
         delete e;
         return jv::fail(JV_ERR_INVALID_ARG, "out of host memory");
     }
     for (int l = 0; l < c.n_blocks; ++l) {
         e->pattern[l] = c.pattern[l];
         e->blocks[l] = blocks[l];
+        jv_dwc_params none = {JV_DWC_NONE, 3, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
+        e->dwc[l] = (c.pattern[l] == 0 && blocks[l].dwc) ? *blocks[l].dwc : none;
+        e->blocks[l].dwc = &e->dwc[l];
     }
     e->cfg.pattern = e->pattern;
     *out = e;
@@ -485,6 +519,7 @@ void jv_encoder_destroy(jv_encoder *enc) {
     if (!enc) return;
     delete[] enc->pattern;
     delete[] enc->blocks;
+    delete[] enc->dwc;
     delete enc;
 }
 
@@ -497,7 +532,7 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
     const size_t T = (size_t)batch * grid_h * grid_w, C = enc->cfg.width;
     const size_t wide = 3 * C > (size_t)enc->cfg.mlp_hidden ? 3 * C : (size_t)enc->cfg.mlp_hidden;
     return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
-           jv::align256(jv::linear_workspace_bytes(batch, enc->cfg.heads, grid_h * grid_w));
+           jv::align256(jv::encoder_linear_workspace(enc, batch, grid_h * grid_w));
 }
 
 jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
@@ -523,6 +558,7 @@ jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, in
     __bf16 *narrow = (__bf16 *)ws;                                  // [T, C]
     __bf16 *widebuf = (__bf16 *)(ws + jv::align256(T * C * 2));     // [T, 3C] or [T, hidden]
     void *la_ws = ws + jv::align256(T * C * 2) + jv::align256(T * wide * 2);
+    const size_t la_ws_bytes = jv::align256(jv::encoder_linear_workspace(enc, batch, N));
 
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
     jv::Problem pr;
@@ -541,7 +577,9 @@ jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, in
         if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
         if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
         switch (enc->pattern[l]) {
-            case 0: st = jv::linear_forward(pr, c.la_eps, la_ws, stream); break;
+            case 0:
+                st = jv::linear_block_forward(pr, c.la_eps, &enc->dwc[l], la_ws, la_ws_bytes, stream);
+                break;
             case 1: st = jv::window_forward(pr, c.win_h, c.win_w, 0.f, stream); break;
             default: st = jv::full_forward(pr, 0.f, stream); break;
         }

@@ -74,6 +74,13 @@ def _device_blocks(blocks):
     for b in blocks:
         d = {}
         for k, v in b.items():
+            if k == "dwc":      # convolution branch of a linear-attention block: fp32 device tensors
+                d[k] = {"ksize": v.get("ksize", 3)}
+                if v.get("static_kernel") is not None:
+                    d[k]["static_kernel"] = torch.from_numpy(v["static_kernel"]).cuda()
+                if v.get("squeeze") is not None:
+                    d[k]["squeeze"] = tuple(torch.from_numpy(a).cuda() for a in v["squeeze"])
+                continue
             t = torch.from_numpy(v).cuda()
             d[k] = t.to(torch.bfloat16) if k.startswith("w_") else t
         out.append(d)
@@ -166,4 +173,28 @@ def test_config5_full_depth_batch_properties():
         print(f"    image {img}: |batch - alone| / RMS: max {err_max:.2e}, rms {err_rms:.2e}")
         # a different summation order moves a few bf16 roundings, which 24 blocks then carry along
         assert err_rms <= 5e-3 and err_max <= 5e-2
+    enc.close()
+
+
+def test_encoder_linear_blocks_with_convolution_branch():
+    """Linear-attention blocks carrying the paper's convolution branch (squeeze-dynamic and
+    static filters) inside the encoder, next to a window block, against the oracle."""
+    B, H, W, heads, hidden = 2, 12, 10, 2, 256
+    C = heads * 64
+    x = synth.normal((B, H * W, C), 900)
+    blocks = [synth.block_weights(C, hidden, 910 + i) for i in range(3)]
+    blocks[0]["dwc"] = {"squeeze": synth.squeeze_weights(C, 8, 3, 920), "ksize": 3}
+    blocks[2]["dwc"] = {"static_kernel": synth.dwc_static_kernel(C, 5, 921), "ksize": 5}
+    pattern = [0, 1, 0]
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(4, 5))
+    dx = torch.from_numpy(x).cuda()
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W))
+    ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 5))
+    check(err_bf16(to_host(y), ref), BF16_TOL)
+    # the branch really ran: without it the result differs
+    for b in blocks:
+        b.pop("dwc", None)
+    plain = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 5))
+    assert err_bf16(to_host(y), plain) > 10 * BF16_TOL
     enc.close()
