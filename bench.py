@@ -196,7 +196,7 @@ def main():
     rooflines = {
         "linear": hbm_roof("linear", "la_state_bf16 + la_apply_bf16"),
         "block": hbm_roof("block", "la_state_bf16 + squeeze_* + la_apply_bf16 (convolution fused)"),
-        "window": hbm_roof("window", "attn_window_bf16"),
+        "window": hbm_roof("window", "attn_window8_bf16"),
         "full": dict(roofline),
     }
 

@@ -286,7 +286,7 @@ __device__ inline void load_queries(bf16x8 (&qreg)[NT][4], const AttnArgs &a, in
 constexpr int kStage = 64;
 constexpr int kStageBytes = 2 * kStage * 128;  // K rows then V rows
 
-template <bool O_BF16, int NT, bool FAST>
+template <bool O_BF16, int NT>
 __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a) {
     __shared__ __align__(16) unsigned char smem[2 * kStageBytes];
     __shared__ __align__(16) float bias[2][kStage];
@@ -307,49 +307,28 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
     const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
     const int n_stage = (a.g.slots + kStage - 1) / kStage;
     const int lrow = tid >> 3, lchunk = tid & 7;
-    // This thread moves rows lrow and lrow + 32 of every stage.  FAST: the window spans whole
-    // grid rows (token = first token + slot) and every byte offset inside one (batch, head)
-    // slice fits in 32 bits, so a row's address is a uniform base plus a per-thread constant
-    // plus a per-stage uniform step.  Otherwise the slot goes through the window geometry.
+    // This thread moves rows lrow and lrow + 32 of every stage.
     const char *kbytes = (const char *)((const __bf16 *)a.k.ptr + kbase);
     const char *vbytes = (const char *)((const __bf16 *)a.v.ptr + vbase);
-    const int tok_first = wy * a.g.wh * a.g.W, n_tok = a.g.H * a.g.W;
-    const int tok_limit = min(a.g.slots, n_tok - tok_first);  // FAST: number of live slots
-    unsigned krow_off[2], vrow_off[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        krow_off[i] = 2u * ((unsigned)(tok_first + lrow + 32 * i) * (unsigned)a.k.sn + lchunk * 8);
-        vrow_off[i] = 2u * ((unsigned)(tok_first + lrow + 32 * i) * (unsigned)a.v.sn + lchunk * 8);
-    }
-    const unsigned kstep = 2u * kStage * (unsigned)a.k.sn, vstep = 2u * kStage * (unsigned)a.v.sn;
     u32x4 kreg[2], vreg[2];
     bool live[2];
     auto fetch = [&](int stage) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int slot = stage * kStage + lrow + 32 * i;
-            if (FAST) {
-                live[i] = slot < tok_limit;
-                if (live[i]) {
-                    kreg[i] = *(const u32x4 *)(kbytes + (krow_off[i] + stage * kstep));
-                    vreg[i] = *(const u32x4 *)(vbytes + (vrow_off[i] + stage * vstep));
-                }
-            } else {
-                const int tok = slot_token(a, wy, wx, slot);
-                live[i] = tok >= 0;
-                if (live[i]) {
-                    kreg[i] = *(const u32x4 *)(kbytes + 2 * ((long long)tok * a.k.sn + lchunk * 8));
-                    vreg[i] = *(const u32x4 *)(vbytes + 2 * ((long long)tok * a.v.sn + lchunk * 8));
-                }
+            const int tok = slot_token(a, wy, wx, stage * kStage + lrow + 32 * i);
+            live[i] = tok >= 0;
+            if (live[i]) {
+                kreg[i] = *(const u32x4 *)(kbytes + 2 * ((long long)tok * a.k.sn + lchunk * 8));
+                vreg[i] = *(const u32x4 *)(vbytes + 2 * ((long long)tok * a.v.sn + lchunk * 8));
             }
         }
     };
-    auto stash = [&](int buf, bool all_live) {
+    auto stash = [&](int buf) {
         unsigned char *kt = smem + buf * kStageBytes, *vt = kt + kStage * 128;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = lrow + 32 * i;
-            if (!all_live && !live[i]) {  // padding rows are zero in LDS and carry a -inf bias
+            if (!live[i]) {  // padding rows are zero in LDS and carry a -inf bias
                 u32x4 zero = {0u, 0u, 0u, 0u};
                 kreg[i] = zero;
                 vreg[i] = zero;
@@ -374,13 +353,12 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
             attn_tile32<NT>(w, qreg, ka, nullptr, 0, vt, 32, masked ? &bias[buf][32] : nullptr, a.c,
                             lane);
         }
-        // (all_live is wave-uniform: a whole stage of real tokens needs no per-row select)
-        if (more) stash(buf ^ 1, FAST && (st + 2) * kStage <= tok_limit);
+        if (more) stash(buf ^ 1);
         __syncthreads();
     };
 
     fetch(0);
-    stash(0, false);
+    stash(0);
     __syncthreads();
     for (int st = 0; st < n_stage; st += 2) {
         run_stage(st, std::integral_constant<int, 0>());
@@ -659,6 +637,208 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Streaming kernel for windows that span whole grid rows (full attention above all), with
+// byte offsets inside one (batch, head) slice below 2^31 (checked by the launcher).
+// Same tiling as attn_stream_bf16 (a workgroup holds 256 query slots, keys pass through LDS
+// in stages of 64), but built so that the inner loop is nothing but matrix instructions,
+// exponentials and LDS operand reads:
+//   * K/V stages go from global memory straight into a ring of three LDS stages (no register
+//     staging, no LDS stores, no per-row selects), two stages ahead of the arithmetic; a
+//     stage costs each wavefront four load instructions, one counted wait and one barrier;
+//   * every full stage runs the unmasked tile code, which is one basic block per tile apart
+//     from the (rarely taken) branch that raises the softmax reference; only the last,
+//     partial stage of a window masks keys, and it does so by key index, not through LDS.
+// grid (ceil(slots/256), n_win, B*heads), 256 threads.
+// ---------------------------------------------------------------------------------------
+constexpr int kRing = 3;
+
+// One tile of 32 keys of the ring kernel.  NEXT: the stage holds another tile after this one,
+// whose K operands are read into `ka` once the scores are issued.  MASKED: keys with index
+// (inside the stage) >= key_limit are padding.
+template <bool NEXT, bool MASKED>
+__device__ inline void ring_tile32(WaveState<2> &w, const bf16x8 (&qreg)[2][4], bf16x8 (&ka)[4],
+                                   const unsigned char *kstage, const unsigned char *vstage,
+                                   int krow0, int key_limit, float c, int lane) {
+    const int g = lane >> 5;
+    bf16x8 va[2][2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) va[kk][mi] = load_vt_operand(vstage, krow0 + 16 * kk, mi, lane);
+    f32x16 s[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) s[nt] = mfma32(ka[ks], qreg[nt][ks], s[nt]);
+    if (NEXT) load_k_operands(ka, kstage, krow0 + 32, lane);
+    if (MASKED) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const bool pad = krow0 + 8 * (v / 4) + 4 * g + (v % 4) >= key_limit;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) s[nt][v] = pad ? -INFINITY : s[nt][v];
+        }
+    }
+    // Lazy softmax reference, as in attn_tile32, with one test for both query blocks.
+    unsigned pk[2][8];
+    float sum0 = exp_block(s[0], pk[0], c, -w.m[0]);
+    float sum1 = exp_block(s[1], pk[1], c, -w.m[1]);
+    if (__builtin_amdgcn_ballot_w64(!(sum0 <= kLazySum) || !(sum1 <= kLazySum)) != 0) {  // NaN too
+        if (__builtin_amdgcn_ballot_w64(!(sum0 <= kLazySum)) != 0) {
+            raise_reference<2>(w, 0, s[0], c);
+            sum0 = exp_block(s[0], pk[0], c, -w.m[0]);
+        }
+        if (__builtin_amdgcn_ballot_w64(!(sum1 <= kLazySum)) != 0) {
+            raise_reference<2>(w, 1, s[1], c);
+            sum1 = exp_block(s[1], pk[1], c, -w.m[1]);
+        }
+    }
+    w.l[0] += sum0;
+    w.l[1] += sum1;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
+                w.acc[mi][nt] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][nt]);
+            }
+}
+
+template <bool O_BF16>
+__global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
+    __shared__ __align__(16) unsigned char smem[kRing * kStageBytes];
+    constexpr int WAVES = 4;
+    constexpr int kLoads = 8 / WAVES;  // load instructions per stage, tensor and wavefront (8 rows each)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
+    const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
+    const int q0 = blockIdx.x * (64 * WAVES) + wave * 64;
+    const long long qbase = b * a.q.sb + h * a.q.sh, obase = b * a.o.sb + h * a.o.sh;
+    const bool wave_live = q0 < a.g.slots;
+
+    bf16x8 qreg[2][4];
+    load_queries<2>(qreg, a, wy, wx, q0, qbase, lane);
+    WaveState<2> w;
+    wave_state_init<2>(w);
+
+    // Key slots of the window that hold tokens: slot s is token tok_first + s.
+    const int tok_first = wy * a.g.wh * a.g.W;
+    const int tok_limit = min(a.g.slots, a.g.H * a.g.W - tok_first);
+    const int n_full = tok_limit / kStage, n_stage = (tok_limit + kStage - 1) / kStage;
+
+    // Loads.  A wavefront moves rows 8 * (WAVES * i + wave) + lane / 8 (i < kLoads) of every
+    // stage, K and V: lane = 8 * (row in the group of 8) + 16-byte slot of the LDS row, and it
+    // fetches the chunk of the token's row that belongs in that slot under the tile layouts.
+    // The number of loads per stage is the same for every wavefront and stage (the waits count
+    // them); a row past the last token fetches the window's first token instead.  Stages are
+    // issued in order, so the byte offsets just advance by one stage per issue.
+    auto uniform = [](const char *ptr) {
+        const unsigned long long u = (unsigned long long)ptr;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+        return (const char *)(((unsigned long long)hi << 32) | lo);
+    };
+    const char *kbytes = uniform((const char *)((const __bf16 *)a.k.ptr + b * a.k.sb + h * a.k.sh + (long long)tok_first * a.k.sn));
+    const char *vbytes = uniform((const char *)((const __bf16 *)a.v.ptr + b * a.v.sb + h * a.v.sh + (long long)tok_first * a.v.sn));
+    const int lrow = lane >> 3, lslot = lane & 7;
+    unsigned kcur[kLoads], vcur[kLoads], kpad[kLoads], vpad[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int row = 8 * (WAVES * i + wave) + lrow;
+        kpad[i] = 2u * ((lslot ^ tile_row_rotation(row)) * 8);
+        vpad[i] = 2u * ((lslot ^ (((row ^ (row >> 1)) & 1) << 2)) * 8);
+        kcur[i] = 2u * (unsigned)row * (unsigned)a.k.sn + kpad[i];
+        vcur[i] = 2u * (unsigned)row * (unsigned)a.v.sn + vpad[i];
+    }
+    const unsigned kstep = 2u * kStage * (unsigned)a.k.sn, vstep = 2u * kStage * (unsigned)a.v.sn;
+    auto issue = [&](int stage) {
+        unsigned char *kt = smem + (stage % kRing) * kStageBytes, *vt = kt + kStage * 128;
+        const bool whole = (stage + 1) * kStage <= tok_limit;  // uniform
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            const int row0 = 8 * (WAVES * i + wave);
+            unsigned ko = kcur[i], vo = vcur[i];
+            if (!whole && stage * kStage + row0 + lrow >= tok_limit) {
+                ko = kpad[i];
+                vo = vpad[i];
+            }
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(kbytes + ko),
+                                             (attn_lds_void *)(kt + row0 * 128), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(vbytes + vo),
+                                             (attn_lds_void *)(vt + row0 * 128), 16, 0, 0);
+            kcur[i] += kstep;
+            vcur[i] += vstep;
+        }
+    };
+    // Stage `st` has landed for every wavefront, and every wavefront is done with stage st - 1,
+    // whose ring slot takes stage st + 2.
+    auto stage_ready = [&](int st) {
+        if (st + 1 < n_stage) {
+            static_assert(kLoads == 2, "the wait below leaves one stage (2 * kLoads loads) in flight");
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        __syncthreads();
+        if (st + 2 < n_stage) issue(st + 2);
+    };
+    // A full stage in ring slot `slot` (a compile-time constant, so that every LDS offset folds
+    // into the instruction).
+    auto full_stage = [&](int st, auto slot_tag) {
+        constexpr int slot = decltype(slot_tag)::value;
+        stage_ready(st);
+        if (wave_live) {
+            const unsigned char *kt = smem + slot * kStageBytes, *vt = kt + kStage * 128;
+            bf16x8 ka[4];
+            load_k_operands(ka, kt, 0, lane);
+            ring_tile32<true, false>(w, qreg, ka, kt, vt, 0, 0, a.c, lane);
+            ring_tile32<false, false>(w, qreg, ka, kt, vt, 32, 0, a.c, lane);
+        }
+    };
+
+    if (n_stage > 0) issue(0);
+    if (n_stage > 1) issue(1);
+    int st = 0;
+    for (; st + 2 < n_full; st += 3) {
+        full_stage(st, std::integral_constant<int, 0>());
+        full_stage(st + 1, std::integral_constant<int, 1>());
+        full_stage(st + 2, std::integral_constant<int, 2>());
+    }
+    if (st < n_full) {
+        full_stage(st, std::integral_constant<int, 0>());
+        ++st;
+        if (st < n_full) {
+            full_stage(st, std::integral_constant<int, 1>());
+            ++st;
+        }
+    }
+    if (st < n_stage) {  // the partial stage that ends the window
+        stage_ready(st);
+        if (wave_live) {
+            const unsigned char *kt = smem + (st % kRing) * kStageBytes, *vt = kt + kStage * 128;
+            const int key_limit = tok_limit - st * kStage;  // 1 .. 63
+            bf16x8 ka[4];
+            load_k_operands(ka, kt, 0, lane);
+            if (key_limit > 32) {
+                ring_tile32<true, true>(w, qreg, ka, kt, vt, 0, key_limit, a.c, lane);
+                ring_tile32<false, true>(w, qreg, ka, kt, vt, 32, key_limit, a.c, lane);
+            } else {
+                ring_tile32<false, true>(w, qreg, ka, kt, vt, 0, key_limit, a.c, lane);
+            }
+        }
+    }
+    __syncthreads();  // every wavefront is done with the ring: reuse it as staging
+    if (wave_live) wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
+}
+
 static jv_status set_lds_limit(const void *fn, int bytes) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
@@ -722,14 +902,15 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStre
     // 32-bit byte offsets inside one (batch, head) slice?
     const long long max_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
     const bool fast = a.contig && ((long long)pr.N + 2 * kStage) * max_sn * 2 + 256 < (1ll << 31);
-    if (pr.o_bf16 && fast)
-        hipLaunchKernelGGL((attn_stream_bf16<true, NT, true>), grid, dim3(256), 0, stream, a);
-    else if (pr.o_bf16)
-        hipLaunchKernelGGL((attn_stream_bf16<true, NT, false>), grid, dim3(256), 0, stream, a);
-    else if (fast)
-        hipLaunchKernelGGL((attn_stream_bf16<false, NT, true>), grid, dim3(256), 0, stream, a);
+    if (fast && NT == 2) {
+        if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_bf16<true>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((attn_ring_bf16<false>), grid, dim3(256), 0, stream, a);
+        return launch_status("attn_ring_bf16");
+    }
+    if (pr.o_bf16)
+        hipLaunchKernelGGL((attn_stream_bf16<true, NT>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((attn_stream_bf16<false, NT, false>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_stream_bf16<false, NT>), grid, dim3(256), 0, stream, a);
     return launch_status("attn_stream_bf16");
 }
 

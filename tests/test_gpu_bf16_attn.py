@@ -36,6 +36,8 @@ def _window(q, k, v, H, W, window, out_dtype=torch.bfloat16, scale=0.0):
     (1, 2, 5, 7, 1.0),      # N = 35: less than one tile
     (1, 1, 1, 1, 1.0),      # a single token
     (2, 2, 24, 40, 0.5),    # N = 960
+    (1, 2, 33, 33, 1.0),    # N = 1089 = 17 stages + 1 key: 512-slot workgroups, one-key tail
+    (1, 2, 40, 27, 0.5),    # N = 1080 = 16 stages + 56 keys: tail longer than one tile
 ])
 def test_full_attention_small_shapes(B, heads, H, W, vscale):
     q, k, v = synth.qkv(30, B, heads, H * W, 64, vscale, True)
@@ -51,6 +53,7 @@ def test_full_attention_small_shapes(B, heads, H, W, vscale):
     (1, 2, 20, 20, (32, 32), 1.0),    # window larger than the grid
     (1, 2, 18, 30, (6, 30), 1.0),     # windows spanning whole rows
     (1, 1, 40, 24, (24, 16), 0.5),    # 384-slot rectangular windows, ragged at the bottom
+    (1, 1, 50, 64, (20, 64), 1.0),    # 1280-slot windows of whole rows; the last one holds 640 tokens
 ])
 def test_window_attention_small_shapes(B, heads, H, W, window, vscale):
     q, k, v = synth.qkv(31, B, heads, H * W, 64, vscale, True)
