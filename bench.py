@@ -189,7 +189,7 @@ def main():
                 "traffic": traffic.get(name), "algorithmic_bytes": bytes_layer,
                 "mfma_frac": per[name]["mfma_frac"]}
 
-    roofline = {"kernel": "attn_stream_bf16 (full attention)", "bound": "mfma",
+    roofline = {"kernel": "attn_ring_bf16 (full attention)", "bound": "mfma",
                 "achieved": per["full"]["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"], "traffic": traffic.get("full"),
                 "algorithmic_flops": flops["full"], "avg_launch_ms": per["full"]["ms_avg"]}

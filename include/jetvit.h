@@ -221,6 +221,17 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * jv_encoder_forward: x and y are device fp32 [batch, grid_h*grid_w, width] (y may be x);
  * workspace is device memory of at least jv_encoder_workspace_bytes(...) bytes, 256-byte
  * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.
+ *
+ * jv_encoder_forward_taps: the same forward pass that also hands out the residual stream after
+ * chosen blocks, which is what a dense-prediction head attached to the encoder reads (the
+ * paper's depth and segmentation heads take features of four intermediate layers, Sec. 4.1
+ * and 4.2).  tap_blocks is a host array of n_taps block indices (0-based, strictly increasing,
+ * each < n_blocks); tap_out is a host array of n_taps device pointers, each fp32
+ * [batch, grid_h*grid_w, width], 16-byte aligned, distinct from each other and from x and y.
+ * tap_out[i] receives the stream after block tap_blocks[i].  The block's last GEMM writes
+ * there directly and the next block reads it from there, so a tap costs no extra pass over the
+ * stream (a tap on the last block is one device-to-device copy of y).  n_taps = 0 is
+ * jv_encoder_forward.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t n_blocks, width, heads, mlp_hidden;
@@ -251,6 +262,10 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
 jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
                              int32_t grid_h, int32_t grid_w, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
+jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+                                  int32_t grid_h, int32_t grid_w, int32_t n_taps,
+                                  const int32_t *tap_blocks, float *const *tap_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 void jv_encoder_destroy(jv_encoder *enc);
 
 #ifdef __cplusplus

@@ -289,9 +289,15 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
     return x + linear(hmid, wts["w_fc2"], wts["b_fc2"])
 
 
-def encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
-    """Hybrid encoder: blocks[l] run with mixer pattern[l]; returns the residual stream."""
+def encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
+                    taps=None):
+    """Hybrid encoder: blocks[l] run with mixer pattern[l]; returns the residual stream.  With
+    taps (an iterable of block indices) returns (stream, {l: stream after block l}): the
+    intermediate features a dense-prediction head reads (Sec. 4.1, 4.2)."""
     x = np.asarray(x, dtype=np.float64)
-    for wts, mixer in zip(blocks, pattern):
+    kept = {}
+    for l, (wts, mixer) in enumerate(zip(blocks, pattern)):
         x = encoder_block(x, wts, mixer, H, W, heads, window, ln_eps, la_eps)
-    return x
+        if taps is not None and l in taps:
+            kept[l] = x.copy()
+    return x if taps is None else (x, kept)

@@ -23,7 +23,7 @@ EXPORTS = [
     "jv_window_geometry", "jv_window_maps_host", "jv_window_maps_device",
     "jv_window_attn_fwd", "jv_full_attn_fwd",
     "jv_layernorm_fwd", "jv_gemm_bias_act",
-    "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_destroy",
+    "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_forward_taps", "jv_encoder_destroy",
 ]
 JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL = 0, 1, 2
 JV_DWC_NONE, JV_DWC_STATIC, JV_DWC_SQUEEZE_DYNAMIC = 0, 1, 2
@@ -110,6 +110,7 @@ def lib():
         L.jv_encoder_workspace_bytes.restype = ctypes.c_size_t
         L.jv_encoder_workspace_bytes.argtypes = [vp, i32, i32, i32]
         L.jv_encoder_forward.argtypes = [vp, vp, vp, i32, i32, i32, vp, ctypes.c_size_t, vp]
+        L.jv_encoder_forward_taps.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         L.jv_encoder_destroy.restype = None
         L.jv_encoder_destroy.argtypes = [vp]
         _lib = L
@@ -314,16 +315,30 @@ class Encoder:
     def workspace_bytes(self, batch, grid):
         return int(lib().jv_encoder_workspace_bytes(self._handle, batch, grid[0], grid[1]))
 
-    def forward(self, x, y, grid, workspace=None, stream=None):
-        """y <- encoder(x); x, y fp32 [batch, N, width] on the GPU; returns the workspace used."""
+    def forward(self, x, y, grid, workspace=None, stream=None, taps=None):
+        """y <- encoder(x); x, y fp32 [batch, N, width] on the GPU; returns the workspace used.
+        taps: optional dict {block index: fp32 tensor like y} that receives the residual stream
+        after those blocks (jv_encoder_forward_taps)."""
         batch = x.shape[0]
         if x.dtype != torch.float32 or y.dtype != torch.float32 or not x.is_contiguous() or not y.is_contiguous():
             raise ValueError("x and y must be contiguous fp32")
         if workspace is None:
             workspace = torch.empty(self.workspace_bytes(batch, grid), dtype=torch.uint8, device=x.device)
-        _check(lib().jv_encoder_forward(self._handle, x.data_ptr(), y.data_ptr(), batch, grid[0],
-                                        grid[1], workspace.data_ptr(), workspace.numel(),
-                                        _stream(stream)))
+        if not taps:
+            _check(lib().jv_encoder_forward(self._handle, x.data_ptr(), y.data_ptr(), batch, grid[0],
+                                            grid[1], workspace.data_ptr(), workspace.numel(),
+                                            _stream(stream)))
+            return workspace
+        order = sorted(taps)
+        for l in order:
+            t = taps[l]
+            if t.dtype != torch.float32 or not t.is_contiguous() or t.shape != y.shape:
+                raise ValueError("tap tensors must be contiguous fp32 of the shape of y")
+        blocks = (ctypes.c_int32 * len(order))(*order)
+        outs = (ctypes.c_void_p * len(order))(*[taps[l].data_ptr() for l in order])
+        _check(lib().jv_encoder_forward_taps(self._handle, x.data_ptr(), y.data_ptr(), batch, grid[0],
+                                             grid[1], len(order), blocks, outs, workspace.data_ptr(),
+                                             workspace.numel(), _stream(stream)))
         return workspace
 
     def close(self):

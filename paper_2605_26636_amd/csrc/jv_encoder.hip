@@ -538,8 +538,26 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
 jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
                              int32_t grid_h, int32_t grid_w, void *workspace,
                              size_t workspace_bytes, void *hip_stream) {
+    return jv_encoder_forward_taps(enc, x, y, batch, grid_h, grid_w, 0, nullptr, nullptr, workspace,
+                                   workspace_bytes, hip_stream);
+}
+
+jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+                                  int32_t grid_h, int32_t grid_w, int32_t n_taps,
+                                  const int32_t *tap_blocks, float *const *tap_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
     jv::clear_error();
     if (!enc || !x || !y || !workspace) return jv::fail(JV_ERR_INVALID_ARG, "null argument");
+    if (n_taps < 0 || (n_taps > 0 && (!tap_blocks || !tap_out)))
+        return jv::fail(JV_ERR_INVALID_ARG, "taps: negative count or null arrays");
+    for (int i = 0; i < n_taps; ++i) {
+        if (tap_blocks[i] < 0 || tap_blocks[i] >= enc->cfg.n_blocks || (i > 0 && tap_blocks[i] <= tap_blocks[i - 1]))
+            return jv::fail(JV_ERR_INVALID_ARG, "tap_blocks must be strictly increasing block indices");
+        if (!tap_out[i] || ((uintptr_t)tap_out[i] & 15) || tap_out[i] == x || tap_out[i] == y)
+            return jv::fail(JV_ERR_INVALID_ARG, "tap_out[%d] must be a 16-byte aligned buffer of its own", i);
+        for (int j = 0; j < i; ++j)
+            if (tap_out[j] == tap_out[i]) return jv::fail(JV_ERR_INVALID_ARG, "tap_out entries must be distinct");
+    }
     if (batch <= 0 || grid_h <= 0 || grid_w <= 0)
         return jv::fail(JV_ERR_INVALID_ARG, "batch and grid must be positive");
     if (((uintptr_t)x | (uintptr_t)y) & 15) return jv::fail(JV_ERR_INVALID_ARG, "x, y must be 16-byte aligned");
@@ -572,6 +590,7 @@ jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, in
 
     jv_status st;
     const float *resid = x;  // the first residual add reads the input and writes y
+    int next_tap = 0;
     for (int l = 0; l < c.n_blocks; ++l) {
         const jv_block_weights &b = enc->blocks[l];
         if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
@@ -585,10 +604,19 @@ jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, in
         }
         if (st != JV_OK) return st;
         if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
-        resid = y;
         if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
         if ((st = jv::gemm_forward(narrow, b.w_fc1, b.b_fc1, nullptr, widebuf, T, c.mlp_hidden, C, JV_EPI_GELU, true, stream)) != JV_OK) return st;
-        if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, y, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
+        // A tapped block leaves its result in the tap buffer and the next block picks the stream
+        // up from there; the last block's result has to be in y as well.
+        const bool tapped = next_tap < n_taps && tap_blocks[next_tap] == l;
+        float *out = tapped && l + 1 < c.n_blocks ? tap_out[next_tap] : y;
+        if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
+        if (tapped && out == y) {
+            hipError_t e = hipMemcpyAsync(tap_out[next_tap], y, (size_t)T * C * sizeof(float), hipMemcpyDeviceToDevice, stream);
+            if (e != hipSuccess) return jv::fail(JV_ERR_HIP, "hipMemcpyAsync: %s", hipGetErrorString(e));
+        }
+        if (tapped) ++next_tap;
+        resid = out;
     }
     return JV_OK;
 }

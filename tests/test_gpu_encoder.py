@@ -198,3 +198,38 @@ def test_encoder_linear_blocks_with_convolution_branch():
     plain = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 5))
     assert err_bf16(to_host(y), plain) > 10 * BF16_TOL
     enc.close()
+
+
+def test_encoder_taps_intermediate_streams():
+    """jv_encoder_forward_taps: the residual stream after chosen blocks (what a dense-prediction
+    head reads), against the oracle; the final output is bit-identical to the untapped run; a tap
+    on the last block equals y; invalid tap lists are rejected before any launch."""
+    B, H, W, heads, hidden = 2, 8, 6, 2, 256
+    C = heads * 64
+    x = synth.normal((B, H * W, C), 950)
+    blocks = [synth.block_weights(C, hidden, 960 + i) for i in range(5)]
+    pattern = [0, 1, 2, 1, 0]
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(4, 3))
+    dx = torch.from_numpy(x).cuda()
+    y_plain = torch.empty_like(dx)
+    enc.forward(dx, y_plain, (H, W))
+    ref, kept = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 3), taps={0, 2, 4})
+    taps = {l: torch.full_like(dx, float("nan")) for l in (0, 2, 4)}
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W), taps=taps)
+    assert torch.equal(y, y_plain)
+    assert torch.equal(taps[4], y)
+    for l in (0, 2, 4):
+        check(err_bf16(to_host(taps[l]), kept[l]), BF16_TOL)
+    check(err_bf16(to_host(y), ref), BF16_TOL)
+    # in place (y is x) with taps
+    y2 = dx.clone()
+    t2 = {1: torch.empty_like(dx)}
+    enc.forward(y2, y2, (H, W), taps=t2)
+    assert torch.equal(y2, y_plain)
+    # rejected: block index out of range, tap buffer aliasing y
+    with pytest.raises(binding.JvError):
+        enc.forward(dx, y, (H, W), taps={5: torch.empty_like(dx)})
+    with pytest.raises(binding.JvError):
+        enc.forward(dx, y, (H, W), taps={1: y})
+    enc.close()
