@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--paper-ratio", action="store_true",
                     help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
                          "(the resolution of the paper's speed tables), as ratios")
+    ap.add_argument("--la-ablation", action="store_true",
+                    help="time the linear-attention block variants of the paper's Tab. 1 in a pure "
+                         "linear-attention ViT-L and print their ratios")
     ap.add_argument("--only", choices=["linear", "window", "full", "block"], default=None,
                     help="run only this mixer's launches (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -80,6 +83,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.la_ablation:
+        print(json.dumps(bench_la_ablation(args.steps, args.warmup)))
+        return
     if args.paper_ratio:
         print(json.dumps(bench_paper_ratio(args.steps, args.warmup)))
         return
@@ -324,6 +330,55 @@ def bench_paper_ratio(steps, warmup):
             "data": "synthetic", "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
             "paper_context_h100": {"DINOv3-L -> JetViT-L (2 full-attention blocks), whole model": "35.07 ms -> 18.77 ms (1.87x)",
                                    "DINOv3-B -> JetViT-B 0/1/2 full-attention blocks": "12.86 ms -> 7.37 / 7.69 / 8.27 ms"}}
+
+
+def bench_la_ablation(steps, warmup):
+    """The paper's linear-attention block ablation (Tab. 1) re-created for speed only, with random
+    weights: a pure linear-attention ViT-L (24 blocks) on a 64x128 token grid, batch 1, with the
+    block variants the table lists: ReLU linear attention; + static 3x3 convolution on V;
+    + the focused feature map (p = 3) on top of that; + squeeze-dynamic convolution instead (the
+    paper's block).  The token-wise dynamic convolution of the table is not built."""
+    import torch
+    from paper_2605_26636_amd import binding, synth
+    B, H, W, heads, hidden, L = 1, 64, 128, 16, 4096, 24
+    C, N = heads * 64, H * W
+    base_blocks = []
+    for l in range(L):
+        wts = synth.block_weights(C, hidden, 5000 + l)
+        base_blocks.append({k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_")
+                                else torch.from_numpy(v).cuda()) for k, v in wts.items()})
+    static = [{"static_kernel": torch.from_numpy(synth.dwc_static_kernel(C, 3, 6100 + l)).cuda(), "ksize": 3}
+              for l in range(L)]
+    squeeze = [{"squeeze": tuple(torch.from_numpy(a).cuda() for a in synth.squeeze_weights(C, C // 16, 3, 6000 + l)),
+                "ksize": 3} for l in range(L)]
+
+    def with_dwc(dwc):
+        return [dict(b, dwc=dwc[l]) if dwc else dict(b) for l, b in enumerate(base_blocks)]
+
+    variants = {"relu": (with_dwc(None), 1), "relu+static_dwc": (with_dwc(static), 1),
+                "focused_p3+static_dwc": (with_dwc(static), 3), "relu+squeeze_dwc": (with_dwc(squeeze), 1)}
+    x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda()
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    ms = {}
+    for name, (blocks, focus_p) in variants.items():
+        enc = binding.Encoder(blocks, [synth.MIX_LINEAR] * L, heads, hidden, la_focus_p=focus_p)
+        ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")
+        for _ in range(warmup):
+            enc.forward(x, y, (H, W), ws, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            enc.forward(x, y, (H, W), ws, stream)
+        torch.cuda.synchronize()
+        ms[name] = (time.perf_counter() - t0) * 1e3 / steps
+        enc.close()
+    base = ms["relu"]
+    return {"metric": "pure linear-attention ViT-L latency by block variant (64x128 grid, batch 1)",
+            "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16",
+            "data": "synthetic", "ms": ms, "relative_to_relu": {k: v / base for k, v in ms.items()},
+            "paper_context_h100": {"latency ms (ReLU, +DWC, +DWC+focusing, token-wise dynamic, squeeze-dynamic)":
+                                   "5.33, 5.72, 6.00, 8.94, 5.88 (1.00 : 1.07 : 1.13 : 1.68 : 1.10)"}}
 
 
 def cpu_baseline(q, k, v, H, W, window):

@@ -130,6 +130,21 @@ jv_status jv_linear_block_fwd(const jv_attn_desc *desc, const void *q, const voi
                               const void *v, void *o, float eps, const jv_dwc_params *dwc,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same block with the focused feature map in place of ReLU (Eq. 3: the kernel function
+ * the paper tries on top of the convolution branch and rejects for its cost, Table 1 row
+ * "+ DWC on V + Focusing Factor"; provided to measure that variant):
+ *     phi_p(x) = |r| / |r^p| * r^p,   r = max(x, 0),
+ * powers element-wise, Euclidean norms over the 64 channels of the token's head, phi_p(x) = 0
+ * where r = 0.  (The printed denominator is read as the norm of the powered vector, which
+ * makes phi_p norm-preserving.)  focus_p is an integer power, 1 <= focus_p <= 16;
+ * focus_p = 1 is jv_linear_block_fwd.  Applied to q and k in fp32 from the stored values; for
+ * bf16 tensors the mapped rows are rounded to bf16 again before the matrix products.
+ * Everything else (arguments, workspace size, errors) as for jv_linear_block_fwd. */
+jv_status jv_linear_block_focused_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                                      const void *v, void *o, float eps, int32_t focus_p,
+                                      const jv_dwc_params *dwc, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream);
+
 /* ---------------------------------------------------------------------------
  * Window partition (Sec. 3.2.2: the feature map is split into non-overlapping
  * windows).  The grid is extended at the bottom and right to multiples of the
@@ -238,6 +253,9 @@ typedef struct {
     int32_t win_h, win_w;  /* window of the window-attention blocks */
     float ln_eps, la_eps;  /* LayerNorm epsilon; linear-attention denominator epsilon */
     const uint8_t *pattern; /* host, n_blocks entries: 0 linear, 1 window, 2 full */
+    int32_t la_focus_p;     /* feature map of the linear-attention blocks: 0 or 1 = ReLU (the
+                               paper's block), 2 .. 16 = focused map of that power (the ablation
+                               variant, see jv_linear_block_focused_fwd) */
 } jv_encoder_config;
 
 typedef struct {

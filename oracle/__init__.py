@@ -245,10 +245,33 @@ def squeeze_kernel(v, w1, b1, w2, b2, k):
     return kappa
 
 
-def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksize=3):
+def focused_map(x, p):
+    """Focused feature map, Eq. 3: phi_p(x) = |r| / |r^p| * r^p with r = max(x, 0), the power
+    element-wise and the Euclidean norms over the last axis (the channels of one token's head).
+    The printed denominator is read as the norm of the powered vector, which makes the map
+    norm-preserving; rows with r = 0 map to 0.  float64."""
+    r = np.maximum(np.asarray(x, dtype=np.float64), 0.0)
+    y = r ** p
+    nr = np.sqrt((r * r).sum(axis=-1, keepdims=True))
+    ny = np.sqrt((y * y).sum(axis=-1, keepdims=True))
+    return np.where(ny > 0, y * (nr / np.where(ny > 0, ny, 1.0)), 0.0)
+
+
+def focused_linear_attn(q, k, v, p, eps=1e-6):
+    """Linear attention in its quadratic form (Eq. 2, key-sum normaliser) with the focused map
+    of Eq. 3 on queries and keys:  a_ij = phi_p(q_i) . phi_p(k_j);  o_i = sum_j a_ij v_j /
+    (sum_j a_ij + eps).  [B, h, N, d] arrays, float64 arithmetic."""
+    fq, fk = focused_map(q, p), focused_map(k, p)
+    a = np.einsum("bhic,bhjc->bhij", fq, fk)
+    num = np.einsum("bhij,bhjc->bhic", a, np.asarray(v, dtype=np.float64))
+    return num / (a.sum(axis=-1, keepdims=True) + eps)
+
+
+def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksize=3, focus_p=1):
     """The paper's linear-attention block output, Eq. 4: normalised ReLU linear attention plus
-    DWC(V).  static_kernel: [C, k, k]; squeeze: (w1, b1, w2, b2) for the dynamic kernel."""
-    o = linear_attn_quadratic(q, k, v, eps)
+    DWC(V).  static_kernel: [C, k, k]; squeeze: (w1, b1, w2, b2) for the dynamic kernel;
+    focus_p > 1: the focused map of Eq. 3 instead of ReLU (the variant Table 1 lists)."""
+    o = linear_attn_quadratic(q, k, v, eps) if focus_p == 1 else focused_linear_attn(q, k, v, focus_p, eps)
     if static_kernel is not None:
         o = o + dwc(v, np.asarray(static_kernel, dtype=np.float64)[None], H, W)
     if squeeze is not None:
@@ -259,7 +282,7 @@ def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksiz
 MIX_LINEAR, MIX_WINDOW, MIX_FULL = 0, 1, 2
 
 
-def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
+def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6, la_focus_p=1):
     """One pre-LN block:  x += W_O mix(split_heads(W_qkv LN(x))) + b_O;  x += MLP(LN(x)).
     x float64 [B, N, C]; wts: dict of float32 arrays (ln1_g, ln1_b, w_qkv [3C, C], b_qkv, w_o,
     b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2; optionally "dwc": dict with static_kernel or
@@ -272,10 +295,11 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
     q, k, v = (np.ascontiguousarray(qkv[:, :, i].transpose(0, 2, 1, 3)).astype(np.float32)
                for i in range(3))
     if mixer == MIX_LINEAR:
-        dwc_cfg = wts.get("dwc")   # the block's convolution branch (Eq. 4), if it has one
-        if dwc_cfg:
+        dwc_cfg = wts.get("dwc") or {}   # the block's convolution branch (Eq. 4), if it has one
+        if dwc_cfg or la_focus_p > 1:
             o = linear_block(q, k, v, H, W, la_eps, static_kernel=dwc_cfg.get("static_kernel"),
-                             squeeze=dwc_cfg.get("squeeze"), ksize=dwc_cfg.get("ksize", 3))
+                             squeeze=dwc_cfg.get("squeeze"), ksize=dwc_cfg.get("ksize", 3),
+                             focus_p=la_focus_p)
         else:
             o = linear_attn_quadratic(q, k, v, la_eps)
     elif mixer == MIX_WINDOW:
@@ -290,14 +314,14 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
 
 
 def encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
-                    taps=None):
+                    taps=None, la_focus_p=1):
     """Hybrid encoder: blocks[l] run with mixer pattern[l]; returns the residual stream.  With
     taps (an iterable of block indices) returns (stream, {l: stream after block l}): the
     intermediate features a dense-prediction head reads (Sec. 4.1, 4.2)."""
     x = np.asarray(x, dtype=np.float64)
     kept = {}
     for l, (wts, mixer) in enumerate(zip(blocks, pattern)):
-        x = encoder_block(x, wts, mixer, H, W, heads, window, ln_eps, la_eps)
+        x = encoder_block(x, wts, mixer, H, W, heads, window, ln_eps, la_eps, la_focus_p)
         if taps is not None and l in taps:
             kept[l] = x.copy()
     return x if taps is None else (x, kept)

@@ -19,7 +19,7 @@ JV_F32, JV_BF16 = 0, 1
 EXPORTS = [
     "jv_version", "jv_status_string", "jv_last_error",
     "jv_linear_attn_workspace_bytes", "jv_linear_attn_fwd",
-    "jv_linear_block_workspace_bytes", "jv_linear_block_fwd",
+    "jv_linear_block_workspace_bytes", "jv_linear_block_fwd", "jv_linear_block_focused_fwd",
     "jv_window_geometry", "jv_window_maps_host", "jv_window_maps_device",
     "jv_window_attn_fwd", "jv_full_attn_fwd",
     "jv_layernorm_fwd", "jv_gemm_bias_act",
@@ -51,7 +51,7 @@ class JvEncoderConfig(ctypes.Structure):
     _fields_ = [("n_blocks", ctypes.c_int32), ("width", ctypes.c_int32), ("heads", ctypes.c_int32),
                 ("mlp_hidden", ctypes.c_int32), ("win_h", ctypes.c_int32), ("win_w", ctypes.c_int32),
                 ("ln_eps", ctypes.c_float), ("la_eps", ctypes.c_float),
-                ("pattern", ctypes.POINTER(ctypes.c_uint8))]
+                ("pattern", ctypes.POINTER(ctypes.c_uint8)), ("la_focus_p", ctypes.c_int32)]
 
 
 BLOCK_FIELDS = ["ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_fc1", "b_fc1",
@@ -92,6 +92,8 @@ def lib():
                                                       ctypes.POINTER(JvDwcParams)]
         L.jv_linear_block_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp, ctypes.c_float,
                                           ctypes.POINTER(JvDwcParams), vp, ctypes.c_size_t, vp]
+        L.jv_linear_block_focused_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp, ctypes.c_float,
+                                                  ctypes.c_int32, ctypes.POINTER(JvDwcParams), vp, ctypes.c_size_t, vp]
         L.jv_window_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp]
         L.jv_full_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
@@ -216,6 +218,22 @@ def jv_linear_block_fwd(q, k, v, o, grid, eps=1e-6, static_kernel=None, squeeze=
     return workspace
 
 
+def jv_linear_block_focused_fwd(q, k, v, o, grid, focus_p, eps=1e-6, static_kernel=None, squeeze=None,
+                                ksize=3, workspace=None, stream=None):
+    """The linear-attention block with the focused feature map of power focus_p in place of
+    ReLU; returns the workspace tensor used."""
+    desc = make_desc(q, k, v, o, grid)
+    dwc = make_dwc_params(static_kernel, squeeze, ksize)
+    if workspace is None:
+        need = jv_linear_block_workspace_bytes(desc, dwc)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib().jv_linear_block_focused_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                             o.data_ptr(), eps, focus_p, ctypes.byref(dwc),
+                                             workspace.data_ptr(),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)))
+    return workspace
+
+
 def jv_window_attn_fwd(q, k, v, o, grid, window, scale=0.0, stream=None):
     desc = make_desc(q, k, v, o, grid)
     _check(lib().jv_window_attn_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
@@ -290,13 +308,14 @@ class Encoder:
     """Handle of a jv_encoder.  `blocks` is a list of dicts of device tensors (BLOCK_FIELDS:
     weights bf16, biases and LayerNorm parameters fp32); the tensors are kept alive here."""
 
-    def __init__(self, blocks, pattern, heads, mlp_hidden, window=(16, 16), ln_eps=1e-6, la_eps=1e-6):
+    def __init__(self, blocks, pattern, heads, mlp_hidden, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
+                 la_focus_p=1):
         self.blocks = blocks
         self.width = blocks[0]["w_o"].shape[0]
         n = len(blocks)
         self._pattern = (ctypes.c_uint8 * n)(*pattern)
         cfg = JvEncoderConfig(n, self.width, heads, mlp_hidden, window[0], window[1], ln_eps, la_eps,
-                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)))
+                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)), la_focus_p)
         table = (JvBlockWeights * n)()
         self._dwc = []   # parameter structs stay alive until the encoder has copied them
         for i, b in enumerate(blocks):

@@ -476,6 +476,7 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
         return jv::fail(JV_ERR_UNSUPPORTED, "mlp_hidden must be a positive multiple of 64");
     if (c.win_h <= 0 || c.win_w <= 0) return jv::fail(JV_ERR_INVALID_ARG, "window must be positive");
     if (!(c.ln_eps >= 0.f) || !(c.la_eps >= 0.f)) return jv::fail(JV_ERR_INVALID_ARG, "bad epsilon");
+    if (c.la_focus_p < 0 || c.la_focus_p > 16) return jv::fail(JV_ERR_INVALID_ARG, "la_focus_p must be 0 .. 16");
     for (int l = 0; l < c.n_blocks; ++l) {
         if (c.pattern[l] > 2) return jv::fail(JV_ERR_INVALID_ARG, "pattern[%d] is not 0, 1 or 2", l);
         const jv_block_weights &b = blocks[l];
@@ -597,7 +598,8 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *
         if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
         switch (enc->pattern[l]) {
             case 0:
-                st = jv::linear_block_forward(pr, c.la_eps, &enc->dwc[l], la_ws, la_ws_bytes, stream);
+                st = jv::linear_block_forward(pr, c.la_eps, &enc->dwc[l], la_ws, la_ws_bytes, stream,
+                                              c.la_focus_p > 1 ? c.la_focus_p : 1);
                 break;
             case 1: st = jv::window_forward(pr, c.win_h, c.win_w, 0.f, stream); break;
             default: st = jv::full_forward(pr, 0.f, stream); break;

@@ -39,8 +39,9 @@ struct DwcArg {
     int H, W;
 };
 
+// focus_p: 1 = ReLU feature map; >= 2 = focused map of Eq. 3 with that integer power.
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
-                      const DwcPlan &dwc, hipStream_t stream);
+                      const DwcPlan &dwc, int focus_p, hipStream_t stream);
 
 // Generator of the dynamic filters: partial token sums of V -> hidden layer -> filters.
 jv_status squeeze_generate(const DwcPlan &dwc, float *ws, int n_part, int B, int heads, int N,
@@ -51,6 +52,7 @@ jv_status vsum_f32_launch(const Problem &pr, const LinearPlan &plan, float *vsum
 jv_status dwc_add_f32_launch(const Problem &pr, const DwcArg &cv, int ksize, hipStream_t stream);
 
 jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params *dwc,
-                               void *workspace, size_t workspace_bytes, hipStream_t stream);
+                               void *workspace, size_t workspace_bytes, hipStream_t stream,
+                               int focus_p = 1);
 
 }  // namespace jv

@@ -1,4 +1,5 @@
-// ReLU linear attention (Eq. 2 of the paper with phi = ReLU, key-sum normaliser):
+// Linear attention (Eq. 2 of the paper, key-sum normaliser; phi = ReLU unless the focused map
+// of Eq. 3 is asked for):
 //   pass 1  la_state_*  : S_p = sum_j relu(k_j)^T v_j, z_p = sum_j relu(k_j) over one token chunk
 //   pass 2  la_apply_*  : S = sum_p S_p, z = sum_p z_p;  o_i = relu(q_i) S / (relu(q_i).z + eps)
 //
@@ -35,9 +36,34 @@ size_t linear_workspace_floats(const LinearPlan &p, int B, int heads) {
 // fp32 path: plain FMA arithmetic, used for fp32 tensors.
 // ---------------------------------------------------------------------------------------
 
+// Focused feature map (Eq. 3; see focus_bf16x8 in the bf16 path) applied in place to `rows`
+// token rows of 64 already-rectified channels in shared memory; one thread per row.
+__device__ inline void focus_rows_f32(float (*rows)[kHeadDim], int n_rows, int p, int t) {
+    if (t < n_rows) {
+        float *r = rows[t];
+        float top = 0.f;
+        for (int c = 0; c < kHeadDim; ++c) top = fmaxf(top, r[c]);
+        if (top > 0.f) {
+            const float inv_top = 1.0f / top;
+            float ss = 0.f, sy = 0.f;
+            for (int c = 0; c < kHeadDim; ++c) {
+                const float x = r[c] * inv_top;
+                float y = x;
+                for (int i = 1; i < p; ++i) y *= x;
+                ss = fmaf(x, x, ss);
+                sy = fmaf(y, y, sy);
+                r[c] = y;
+            }
+            const float scale = top * sqrtf(ss / sy);
+            for (int c = 0; c < kHeadDim; ++c) r[c] *= scale;
+        }
+    }
+}
+
 // grid (n_split, B*heads), 256 threads.  Thread t owns S[16*(t/64) .. +15][t%64].
 __global__ void __launch_bounds__(256)
-la_state_f32(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int N, int chunk) {
+la_state_f32(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int N, int chunk,
+             int focus_p) {
     __shared__ float Ks[32][kHeadDim];
     __shared__ float Vs[32][kHeadDim];
     const int bh = blockIdx.y, b = bh / heads, h = bh % heads, p = blockIdx.x;
@@ -66,6 +92,10 @@ la_state_f32(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int 
             *(float4 *)&Vs[j][c4] = vv;
         }
         __syncthreads();
+        if (focus_p > 1) {  // uniform
+            focus_rows_f32(Ks, 32, focus_p, t);
+            __syncthreads();
+        }
         for (int j = 0; j < 32; ++j) {
             float vj = Vs[j][c2];
 #pragma unroll
@@ -83,7 +113,7 @@ la_state_f32(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int 
 // grid (ceil(N/256), B*heads), 256 threads.
 __global__ void __launch_bounds__(256)
 la_apply_f32(TensorArg qt, TensorArg ot, const float *__restrict__ ws, int heads, int N,
-             int n_split, float eps) {
+             int n_split, float eps, int focus_p) {
     __shared__ float S[kHeadDim][kHeadDim + 1];  // S[c1][c2]
     __shared__ float z[kHeadDim];
     __shared__ float Qs[64][kHeadDim];
@@ -112,6 +142,10 @@ la_apply_f32(TensorArg qt, TensorArg ot, const float *__restrict__ ws, int heads
             Qs[j][c4 + 3] = fmaxf(qq.w, 0.f);
         }
         __syncthreads();
+        if (focus_p > 1) {  // uniform
+            focus_rows_f32(Qs, 64, focus_p, t);
+            __syncthreads();
+        }
         for (int jj = 0; jj < 16; ++jj) {
             int j = tg * 16 + jj, n = base + j;
             if (n >= n1) break;
@@ -135,7 +169,9 @@ size_t linear_workspace_bytes(int B, int heads, int N) {
 // the filters are generated from it), optional combine, filter generator, apply pass (bf16:
 // the convolution is fused into it; fp32: a pass of its own adds it).
 jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params *dwc,
-                               void *workspace, size_t workspace_bytes, hipStream_t stream) {
+                               void *workspace, size_t workspace_bytes, hipStream_t stream,
+                               int focus_p) {
+    if (focus_p < 1 || focus_p > 16) return fail(JV_ERR_INVALID_ARG, "focusing power must be 1 .. 16");
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;
     jv_status st = plan_dwc(dwc, plan, pr.B, pr.heads, &cv);
@@ -144,13 +180,13 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
         return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes,
                     cv.total_floats * sizeof(float));
     float *ws = (float *)workspace;
-    if (pr.bf16) return linear_bf16(pr, plan, eps, ws, cv, stream);
+    if (pr.bf16) return linear_bf16(pr, plan, eps, ws, cv, focus_p, stream);
     const int BH = pr.B * pr.heads;
     hipLaunchKernelGGL(la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v, ws,
-                       pr.heads, pr.N, plan.chunk);
+                       pr.heads, pr.N, plan.chunk, focus_p);
     if ((st = launch_status("la_state_f32")) != JV_OK) return st;
     hipLaunchKernelGGL(la_apply_f32, dim3((pr.N + 255) / 256, BH), dim3(256), 0, stream, pr.q, pr.o,
-                       ws, pr.heads, pr.N, plan.n_split, eps);
+                       ws, pr.heads, pr.N, plan.n_split, eps, focus_p);
     if ((st = launch_status("la_apply_f32")) != JV_OK) return st;
     if (cv.mode == JV_DWC_NONE) return JV_OK;
     DwcArg arg = {cv.static_kernel, 0, pr.H, pr.W};
@@ -207,6 +243,18 @@ jv_status jv_linear_block_fwd(const jv_attn_desc *desc, const void *q, const voi
     if (st != JV_OK) return st;
     if ((st = check_linear_args(eps, workspace)) != JV_OK) return st;
     return jv::linear_block_forward(pr, eps, dwc, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+jv_status jv_linear_block_focused_fwd(const jv_attn_desc *desc, const void *q, const void *k,
+                                      const void *v, void *o, float eps, int32_t focus_p,
+                                      const jv_dwc_params *dwc, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream) {
+    jv::clear_error();
+    jv::Problem pr;
+    jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
+    if (st != JV_OK) return st;
+    if ((st = check_linear_args(eps, workspace)) != JV_OK) return st;
+    return jv::linear_block_forward(pr, eps, dwc, workspace, workspace_bytes, (hipStream_t)hip_stream, focus_p);
 }
 
 }  // extern "C"

@@ -1,5 +1,5 @@
-// ReLU linear attention (Eq. 2 of the paper, phi = ReLU, key-sum normaliser) for bf16 tensors
-// on the matrix cores, fp32 accumulation.
+// Linear attention (Eq. 2 of the paper, key-sum normaliser; phi = ReLU, or the focused map of
+// Eq. 3 for the ablation variant) for bf16 tensors on the matrix cores, fp32 accumulation.
 //
 //   la_state_bf16   streams K and V once: every wavefront owns a 64 x 64 fp32 state in
 //                   accumulators and adds relu(K_tile)^T V_tile per 64-token tile; the token
@@ -9,10 +9,70 @@
 //   la_apply_bf16   sums the (few) partials, splits S and z into bf16 high and low parts held
 //                   in registers, and streams Q -> O:  O^T = S^T relu(Q)^T on the matrix
 //                   cores, the denominator relu(q).z as one more row block, fp32 divide.
+#include <type_traits>
+
 #include "jv_linear.h"
 #include "jv_mfma.h"
 
 namespace jv {
+
+// Focused feature map (Eq. 3 of the paper, one of the block variants its Table 1 measures):
+//   phi_p(x) = |r| / |r^p| * r^p,   r = relu(x), powers element-wise, norms over the 64 channels
+// of the token's head; p is an integer >= 2 here (p = 1 is ReLU itself).  A token row is spread
+// over the 8 consecutive lanes lane/8*8 .. +7, 8 channels each.  The row is divided by its
+// largest entry before the power so that nothing overflows; fp32 arithmetic, result rounded to
+// bf16 (the operand type of the matrix instructions).
+__device__ inline float row8_combine(float x, bool take_max) {
+    // lanes ^1 and ^2 through quad permutes, then the other quad of the 8-lane group through
+    // the half-row mirror
+    auto with = [&](float a, float b) { return take_max ? fmaxf(a, b) : a + b; };
+    auto dpp = [](float v, auto ctrl_tag) {
+        constexpr int ctrl = decltype(ctrl_tag)::value;
+        return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
+    };
+    x = with(x, dpp(x, std::integral_constant<int, 0xB1>()));   // quad_perm [1, 0, 3, 2]
+    x = with(x, dpp(x, std::integral_constant<int, 0x4E>()));   // quad_perm [2, 3, 0, 1]
+    x = with(x, dpp(x, std::integral_constant<int, 0x141>()));  // row_half_mirror
+    return x;
+}
+
+__device__ inline u32x4 focus_bf16x8(u32x4 x, int p) {
+    float r[8] = {bf16_lo(x[0]), bf16_hi(x[0]), bf16_lo(x[1]), bf16_hi(x[1]),
+                  bf16_lo(x[2]), bf16_hi(x[2]), bf16_lo(x[3]), bf16_hi(x[3])};
+    float top = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        r[e] = fmaxf(r[e], 0.f);
+        top = fmaxf(top, r[e]);
+    }
+    top = row8_combine(top, true);
+    const float inv_top = top > 0.f ? __builtin_amdgcn_rcpf(top) : 0.f;
+    float y[8], ss = 0.f, sy = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        r[e] *= inv_top;
+        y[e] = r[e];
+    }
+    for (int i = 1; i < p; ++i) {  // uniform trip count
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[e] *= r[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        ss = fmaf(r[e], r[e], ss);
+        sy = fmaf(y[e], y[e], sy);
+    }
+    ss = row8_combine(ss, false);
+    sy = row8_combine(sy, false);
+    // |r| = top * sqrt(ss); sy >= 1 whenever top > 0 (the largest entry contributes 1)
+    const float scale = top > 0.f ? top * __builtin_amdgcn_sqrtf(ss) * __builtin_amdgcn_rsqf(sy) : 0.f;
+    u32x4 out = {pack_bf16x2(y[0] * scale, y[1] * scale), pack_bf16x2(y[2] * scale, y[3] * scale),
+                 pack_bf16x2(y[4] * scale, y[5] * scale), pack_bf16x2(y[6] * scale, y[7] * scale)};
+    return out;
+}
+__device__ inline u32x4 feature_map_bf16x8(u32x4 x, int focus_p) {
+    return focus_p > 1 ? focus_bf16x8(x, focus_p) : relu_bf16x8(x);  // uniform
+}
 
 constexpr int kWaveLds = 64 * 68 * 4;  // per-wave LDS: K and V tiles (16 KB) or a padded state
 constexpr int kStateLds = 4 * kWaveLds + 2 * 8 * kHeadDim * 4;
@@ -23,7 +83,7 @@ constexpr int kStateLds = 4 * kWaveLds + 2 * 8 * kHeadDim * 4;
 template <bool VSUM>
 __global__ void __launch_bounds__(256, 2)
 la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restrict__ vsum,
-              int heads, int N, int chunk) {
+              int heads, int N, int chunk, int focus_p) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
     const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x;
@@ -65,7 +125,7 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restr
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const unsigned off = tile_off_tr(r * 8 + lrow, lchunk);
-            *(u32x4 *)(ktile + off) = relu_bf16x8(kreg[r]);
+            *(u32x4 *)(ktile + off) = feature_map_bf16x8(kreg[r], focus_p);
             *(u32x4 *)(vtile + off) = vreg[r];
         }
         if (t + 256 < n1) fetch(t + 256);
@@ -174,7 +234,7 @@ template <bool O_BF16, int KS>
 __global__ void __launch_bounds__(256, 2)
 la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int n_part,
               long long part_stride, int heads, int N, int tokens_per_wg, int n_chunks, int n_wg,
-              float eps, TensorArg vt, DwcArg cv) {
+              float eps, TensorArg vt, DwcArg cv, int focus_p) {
     // St[c2][c1] fp32 with the 8-float group index rotated by the row, then z; afterwards the
     // same bytes stage output tiles (4 KB of bf16 per wave, or 8 KB of fp32 with the
     // convolution).  Then one 8 KB query tile per wave, then the filters as [tap][channel].
@@ -279,7 +339,7 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
     for (; t < n1; t += 256) {
 #pragma unroll
         for (int r = 0; r < 8; ++r)
-            *(u32x4 *)(qtile + tile_off_row(r * 8 + lrow, lchunk)) = relu_bf16x8(qreg[r]);
+            *(u32x4 *)(qtile + tile_off_row(r * 8 + lrow, lchunk)) = feature_map_bf16x8(qreg[r], focus_p);
         if (t + 256 < n1) fetch(t + 256);
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
@@ -421,15 +481,16 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
 
 template <bool O_BF16, int KS>
 static void launch_apply(hipStream_t stream, const Problem &pr, const float *states, int n_part,
-                         long long part_stride, int apply_tokens, float eps, const DwcArg &cv) {
+                         long long part_stride, int apply_tokens, float eps, const DwcArg &cv,
+                         int focus_p) {
     const int n_chunks = (pr.N + apply_tokens - 1) / apply_tokens, n_wg = n_chunks * pr.B * pr.heads;
     hipLaunchKernelGGL((la_apply_bf16<O_BF16, KS>), dim3(8 * ((n_wg + 7) / 8)), dim3(256), 0, stream,
                        pr.q, pr.o, states, n_part, part_stride, pr.heads, pr.N, apply_tokens, n_chunks,
-                       n_wg, eps, pr.v, cv);
+                       n_wg, eps, pr.v, cv, focus_p);
 }
 
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
-                      const DwcPlan &dwc, hipStream_t stream) {
+                      const DwcPlan &dwc, int focus_p, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)la_state_bf16<false>,
@@ -445,10 +506,10 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
     jv_status st;
     if (dynamic)
         hipLaunchKernelGGL(la_state_bf16<true>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk);
+                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p);
     else
         hipLaunchKernelGGL(la_state_bf16<false>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk);
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
     if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
     const float *states = ws;
     int n_part = plan.n_split;
@@ -469,13 +530,13 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
     }
     const int ks = dwc.mode == JV_DWC_NONE ? 0 : dwc.ksize;
     if (pr.o_bf16) {
-        if (ks == 0) launch_apply<true, 0>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else if (ks == 3) launch_apply<true, 3>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else launch_apply<true, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        if (ks == 0) launch_apply<true, 0>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
+        else if (ks == 3) launch_apply<true, 3>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
+        else launch_apply<true, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
     } else {
-        if (ks == 0) launch_apply<false, 0>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else if (ks == 3) launch_apply<false, 3>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
-        else launch_apply<false, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv);
+        if (ks == 0) launch_apply<false, 0>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
+        else if (ks == 3) launch_apply<false, 3>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
+        else launch_apply<false, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
     }
     return launch_status("la_apply_bf16");
 }

@@ -233,3 +233,23 @@ def test_encoder_taps_intermediate_streams():
     with pytest.raises(binding.JvError):
         enc.forward(dx, y, (H, W), taps={1: y})
     enc.close()
+
+
+def test_encoder_focused_feature_map_variant():
+    """la_focus_p: linear-attention blocks with the focused map (and a static convolution
+    branch), the variant of the paper's block ablation, against the oracle."""
+    B, H, W, heads, hidden = 2, 9, 7, 2, 256
+    C = heads * 64
+    x = synth.normal((B, H * W, C), 970)
+    blocks = [synth.block_weights(C, hidden, 980 + i) for i in range(2)]
+    blocks[1]["dwc"] = {"static_kernel": synth.dwc_static_kernel(C, 3, 990), "ksize": 3}
+    pattern = [0, 0]
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, la_focus_p=3)
+    dx = torch.from_numpy(x).cuda()
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W))
+    ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, la_focus_p=3)
+    check(err_bf16(to_host(y), ref), BF16_TOL)
+    relu = oracle.encoder_forward(x, blocks, pattern, H, W, heads)
+    assert err_bf16(to_host(y), relu) > 5 * BF16_TOL   # the map really differs from ReLU
+    enc.close()

@@ -110,3 +110,65 @@ def test_block_rejects_bad_parameters():
         binding.jv_linear_block_fwd(q, q.clone(), q.clone(), o, (4, 4),
                                     static_kernel=torch.zeros(64, 4, 4, device="cuda"), ksize=4)
     assert e.value.status == binding.JV_ERR_UNSUPPORTED
+
+
+# ---- the block with the focused feature map (Eq. 3) in place of ReLU ----------------------------
+
+def _focused(q, k, v, H, W, p, bf16, out_dtype, **kw):
+    dq, dk, dv = (to_device(x, bf16) for x in (q, k, v))
+    o = torch.full(dq.shape, float("nan"), dtype=out_dtype, device="cuda")
+    binding.jv_linear_block_focused_fwd(dq, dk, dv, o, (H, W), p, 1e-6, **kw)
+    torch.cuda.synchronize()
+    return o
+
+
+@pytest.mark.parametrize("p", [2, 3])
+@pytest.mark.parametrize("B,heads,H,W", [(1, 6, 16, 16), (2, 2, 5, 7), (1, 1, 1, 1), (1, 2, 3, 40)])
+def test_focused_fp32(B, heads, H, W, p):
+    C = heads * 64
+    q, k, v = synth.qkv(40, B, heads, H * W, 64, 1.0, False)
+    ref = oracle.focused_linear_attn(q, k, v, p)
+    check(err_fp32(to_host(_focused(q, k, v, H, W, p, False, torch.float32)), ref), FP32_TOL)
+    kern = synth.dwc_static_kernel(C, 3, 4100)
+    ref = oracle.linear_block(q, k, v, H, W, 1e-6, static_kernel=kern, focus_p=p)
+    got = _focused(q, k, v, H, W, p, False, torch.float32, static_kernel=_dev(kern)[0])
+    check(err_fp32(to_host(got), ref), FP32_TOL)
+
+
+@pytest.mark.parametrize("p", [2, 3, 5])
+@pytest.mark.parametrize("B,heads,H,W", [
+    (2, 3, 37, 37),   # ragged tiles
+    (1, 2, 5, 7),     # less than one tile
+    (1, 1, 1, 1),
+    (1, 2, 20, 130),  # several chunks
+])
+def test_focused_bf16(B, heads, H, W, p):
+    C = heads * 64
+    q, k, v = synth.qkv(41, B, heads, H * W, 64, 0.5, True)
+    ref = oracle.focused_linear_attn(q, k, v, p)
+    check_bf16_pair(_focused(q, k, v, H, W, p, True, torch.float32),
+                    _focused(q, k, v, H, W, p, True, torch.bfloat16), ref)
+    sq = synth.squeeze_weights(C, 16, 3, 4200)
+    ref = oracle.linear_block(q, k, v, H, W, 1e-6, squeeze=sq, focus_p=p)
+    check_bf16_pair(_focused(q, k, v, H, W, p, True, torch.float32, squeeze=_dev(*sq)),
+                    _focused(q, k, v, H, W, p, True, torch.bfloat16, squeeze=_dev(*sq)), ref)
+
+
+def test_focused_special_cases():
+    """p = 1 is the ReLU block bit for bit; rows without a positive entry give zero weights;
+    huge magnitudes do not overflow (the rows are normalised before the power)."""
+    B, heads, H, W = 1, 2, 12, 9
+    q, k, v = synth.qkv(42, B, heads, H * W, 64, 0.5, True)
+    dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+    a, b = torch.empty_like(dq, dtype=torch.float32), torch.empty_like(dq, dtype=torch.float32)
+    binding.jv_linear_attn_fwd(dq, dk, dv, a, (H, W))
+    binding.jv_linear_block_focused_fwd(dq, dk, dv, b, (H, W), 1)
+    assert torch.equal(a, b)
+    qn = -np.abs(q)
+    o = _focused(qn, k, v, H, W, 3, True, torch.float32)
+    assert torch.count_nonzero(o) == 0
+    big = synth.round_to_bf16(q * 1e12)
+    ref = oracle.focused_linear_attn(big, k, v, 3)
+    check(err_bf16(to_host(_focused(big, k, v, H, W, 3, True, torch.float32)), ref), BF16_TOL)
+    with pytest.raises(binding.JvError):
+        binding.jv_linear_block_focused_fwd(dq, dk, dv, b, (H, W), 0)

@@ -94,3 +94,57 @@ def test_eps_enters_the_denominator_additively():
     o1 = oracle.linear_attn_quadratic(q, k, v, eps=0.5)
     den = (np.maximum(q, 0).astype(np.float64) @ np.maximum(k, 0).astype(np.float64).sum(2)[..., None])
     assert np.abs(o1 * (den + 0.5) - o0 * den).max() < 1e-13
+
+
+# ---- focused feature map (Eq. 3) and the linear attention that uses it -------------------------
+
+def test_focused_map_hand_case(golden):
+    g = golden("focused_map_hand_case.txt")
+    got = oracle.focused_map(np.array(g["x"]), int(g["p"][0]))
+    assert np.abs(got - np.array(g["phi"])).max() < 1e-14
+    got = oracle.focused_map(np.array(g["x3"]), int(g["p3"][0]))
+    assert np.abs(got - np.array(g["phi3"])).max() < 1e-14
+
+
+def test_focused_map_properties():
+    x = synth.normal((5, 7, 16), 300).astype(np.float64)
+    r = np.maximum(x, 0)
+    for p in (2, 3, 5):
+        f = oracle.focused_map(x, p)
+        # norm-preserving, sign pattern of relu, degree-1 homogeneous
+        assert np.abs(np.linalg.norm(f, axis=-1) - np.linalg.norm(r, axis=-1)).max() < 1e-12
+        assert np.array_equal(f > 0, r > 0)
+        assert np.abs(oracle.focused_map(3.5 * x, p) - 3.5 * f).max() < 1e-12
+        # sharpening: ratios of entries are raised to the power p
+        i, j = 3, 11
+        ok = (r[..., i] > 0) & (r[..., j] > 0)
+        assert ok.any()
+        assert np.allclose(f[..., i][ok] / f[..., j][ok], (r[..., i][ok] / r[..., j][ok]) ** p, rtol=1e-12)
+    assert np.array_equal(oracle.focused_map(x, 1), r)                      # p = 1 is ReLU
+    assert np.array_equal(oracle.focused_map(-np.abs(x), 3), np.zeros_like(x))  # nothing positive
+
+
+def test_focused_linear_attention_reduces_and_is_scale_free():
+    q, k, v = _qkv(310)
+    # p = 1: the ReLU linear attention of the C oracle (independent code)
+    assert np.abs(oracle.focused_linear_attn(q, k, v, 1) - oracle.linear_attn_quadratic(q, k, v)).max() < 1e-12
+    # the map is homogeneous, so positive rescaling of q or k still changes nothing
+    a = oracle.focused_linear_attn(q, k, v, 3, eps=1e-30)
+    b = oracle.focused_linear_attn(2.5 * q.astype(np.float64), 0.25 * k.astype(np.float64), v, 3, eps=1e-30)
+    assert np.abs(a - b).max() < 1e-12
+    # brute force over tokens for one head
+    fq, fk = oracle.focused_map(q[0, 0], 3), oracle.focused_map(k[0, 0], 3)
+    for i in (0, 7, 44):
+        w = np.array([fq[i] @ fk[j] for j in range(k.shape[2])])
+        want = (w[:, None] * v[0, 0].astype(np.float64)).sum(0) / (w.sum() + 1e-30)
+        assert np.abs(a[0, 0, i] - want).max() < 1e-12
+    # sharper than ReLU: the weights concentrate (larger maximum share) for p = 3
+    w1 = np.einsum("ic,jc->ij", oracle.focused_map(q[0, 0], 1), oracle.focused_map(k[0, 0], 1))
+    w3 = np.einsum("ic,jc->ij", fq, fk)
+    share = lambda w: (w.max(1) / w.sum(1)).mean()
+    assert share(w3) > share(w1)
+    # and the block adds the convolution branch on top of it
+    kern = synth.dwc_static_kernel(3 * 16, 3, 320)
+    H, W = 9, 5
+    blk = oracle.linear_block(q, k, v, H, W, static_kernel=kern, focus_p=3)
+    assert np.abs(blk - (oracle.focused_linear_attn(q, k, v, 3) + oracle.dwc(v, kern[None], H, W))).max() < 1e-12
