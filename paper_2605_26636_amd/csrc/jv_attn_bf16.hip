@@ -553,10 +553,13 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
         }
     };
     bf16x8 qreg[2][4];
-    auto load_q = [&](const Item &it) {
+    // `fresh` is zero, but opaque to the compiler: the offsets are then recomputed per window (a
+    // few integer operations) instead of being kept, loop-invariant, in registers that the
+    // loop does not have to spare (they were spilled to scratch memory and reloaded per window).
+    auto load_q = [&](const Item &it, int fresh) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            const unsigned qoff = 2u * ((unsigned)rel_token(q0 + 32 * nt + li) * (unsigned)a.q.sn + g * 8);
+            const unsigned qoff = 2u * ((unsigned)rel_token(q0 + 32 * nt + li + fresh) * (unsigned)a.q.sn + g * 8);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) qreg[nt][ks] = as_bf16x8(*(const u32x4 *)(it.q + (qoff + 32 * ks)));
         }
@@ -569,7 +572,7 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
     int item = blockIdx.x;
     if (item >= n_items) return;  // whole workgroup
     Item cur = make_item(item);
-    load_q(cur);
+    load_q(cur, 0);
     issue_half(cur, 0);
     drain_and_sync();
     for (;;) {
@@ -594,7 +597,9 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
                            nullptr, a.c, lane);
         }
         drain_and_sync();  // the next window's half A has landed; half B is free
-        if (has_next) load_q(nxt);
+        int fresh = 0;
+        asm volatile("" : "+v"(fresh));
+        if (has_next) load_q(nxt, fresh);
         unsigned char *stage = ktile + 128 * 128 + wave * 4096;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
@@ -614,11 +619,11 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const u32x4 val = *(const u32x4 *)(stage + tile_off_row(r * 8 + lrow, lslot));
-                    const unsigned ooff = 2u * ((unsigned)rel_token(q0 + 32 * nt + r * 8 + lrow) * (unsigned)a.o.sn + lslot * 8);
+                    const unsigned ooff = 2u * ((unsigned)rel_token(q0 + 32 * nt + r * 8 + lrow + fresh) * (unsigned)a.o.sn + lslot * 8);
                     *(u32x4 *)(cur.o + ooff) = val;
                 }
             } else {
-                const unsigned ooff = 4u * (unsigned)rel_token(q0 + 32 * nt + li) * (unsigned)a.o.sn;
+                const unsigned ooff = 4u * (unsigned)rel_token(q0 + 32 * nt + li + fresh) * (unsigned)a.o.sn;
 #pragma unroll
                 for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
