@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--paper-ratio", action="store_true",
                     help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
                          "(the resolution of the paper's speed tables), as ratios")
+    ap.add_argument("--model", choices=["L", "B"], default="L", help="ViT size for --paper-ratio")
     ap.add_argument("--la-ablation", action="store_true",
                     help="time the linear-attention block variants of the paper's Tab. 1 in a pure "
                          "linear-attention ViT-L and print their ratios")
@@ -87,7 +88,7 @@ def main():
         print(json.dumps(bench_la_ablation(args.steps, args.warmup)))
         return
     if args.paper_ratio:
-        print(json.dumps(bench_paper_ratio(args.steps, args.warmup)))
+        print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model)))
         return
     if args.encoder:
         enc = bench_encoder(args.steps, args.warmup)
@@ -277,16 +278,19 @@ def bench_encoder(steps, warmup):
             "TFLOPs": tf, "mfma_frac": tf / MFMA_BF16_PEAK_TFLOPS}
 
 
-def bench_paper_ratio(steps, warmup):
+def bench_paper_ratio(steps, warmup, model="L"):
     """The paper's speed comparison re-created with random weights: a 24-block ViT-L on a 64x128
     token grid (1024x2048 px at patch 16, the resolution of its Tab. 1 and Tab. 3), batch 1,
     all blocks full attention against hybrids that keep 0, 1 or 2 full-attention blocks (at
     blocks 14 and 22, where the paper's search puts them for segmentation, Sec. 4.4); the first
     block is linear attention, the others alternate window 16x16 and linear attention; linear
-    blocks carry the squeeze-dynamic 3x3 convolution branch (hidden width C/16)."""
+    blocks carry the squeeze-dynamic 3x3 convolution branch (hidden width C/16).  model "B": the
+    same with ViT-B (12 blocks, width 768, 12 heads), full attention kept at blocks 7 and 11 (the
+    paper does not print its ViT-B positions: the ViT-L ones scaled to 12 blocks)."""
     import torch
     from paper_2605_26636_amd import binding, synth
-    B, H, W, heads, hidden, L = 1, 64, 128, 16, 4096, 24
+    B, H, W = 1, 64, 128
+    heads, hidden, L, full_at_two = (16, 4096, 24, (14, 22)) if model == "L" else (12, 3072, 12, (7, 11))
     C, N = heads * 64, H * W
     dev = []
     for l in range(L):
@@ -307,7 +311,7 @@ def bench_paper_ratio(steps, warmup):
         return out
 
     patterns = {"all_full": [synth.MIX_FULL] * L, "hybrid_0_full": hybrid(()),
-                "hybrid_1_full": hybrid((14,)), "hybrid_2_full": hybrid((14, 22))}
+                "hybrid_1_full": hybrid(full_at_two[:1]), "hybrid_2_full": hybrid(full_at_two)}
     x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda()
     y = torch.empty_like(x)
     stream = torch.cuda.current_stream()
@@ -325,7 +329,7 @@ def bench_paper_ratio(steps, warmup):
         ms[name] = (time.perf_counter() - t0) * 1e3 / steps
         enc.close()
     base = ms["all_full"]
-    return {"metric": "encoder latency ratio, all-full-attention ViT-L vs hybrid (64x128 grid, batch 1)",
+    return {"metric": "encoder latency ratio, all-full-attention ViT-%s vs hybrid (64x128 grid, batch 1)" % model,
             "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16",
             "data": "synthetic", "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
             "paper_context_h100": {"DINOv3-L -> JetViT-L (2 full-attention blocks), whole model": "35.07 ms -> 18.77 ms (1.87x)",

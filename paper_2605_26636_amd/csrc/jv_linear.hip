@@ -42,10 +42,12 @@ __device__ inline void focus_rows_f32(float (*rows)[kHeadDim], int n_rows, int p
     if (t < n_rows) {
         float *r = rows[t];
         float top = 0.f;
+#pragma unroll 4
         for (int c = 0; c < kHeadDim; ++c) top = fmaxf(top, r[c]);
         if (top > 0.f) {
             const float inv_top = 1.0f / top;
             float ss = 0.f, sy = 0.f;
+#pragma unroll 2
             for (int c = 0; c < kHeadDim; ++c) {
                 const float x = r[c] * inv_top;
                 float y = x;
@@ -55,6 +57,7 @@ __device__ inline void focus_rows_f32(float (*rows)[kHeadDim], int n_rows, int p
                 r[c] = y;
             }
             const float scale = top * sqrtf(ss / sy);
+#pragma unroll 4
             for (int c = 0; c < kHeadDim; ++c) r[c] *= scale;
         }
     }
@@ -96,6 +99,7 @@ la_state_f32(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int 
             focus_rows_f32(Ks, 32, focus_p, t);
             __syncthreads();
         }
+#pragma unroll 4
         for (int j = 0; j < 32; ++j) {
             float vj = Vs[j][c2];
 #pragma unroll
