@@ -844,20 +844,11 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
     if (wave_live) wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
 }
 
-static jv_status set_lds_limit(const void *fn, int bytes) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-    return JV_OK;
-}
-
 template <bool O_BF16, int WPW>
 static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        jv_status st = set_lds_limit((const void *)attn_window_bf16<O_BF16, WPW>, kWindowLds);
-        if (st != JV_OK) return st;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)attn_window_bf16<O_BF16, WPW>, kWindowLds);
+    if (st != JV_OK) return st;
     dim3 grid((a.g.n_win * WPW + 3) / 4, BH);
     hipLaunchKernelGGL((attn_window_bf16<O_BF16, WPW>), grid, dim3(256), kWindowLds, stream, a);
     return launch_status("attn_window_bf16");
@@ -865,12 +856,9 @@ static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
 
 template <bool O_BF16>
 static jv_status launch_window8(const AttnArgs &a, int BH, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        jv_status st = set_lds_limit((const void *)attn_window8_bf16<O_BF16>, kWindow8Lds);
-        if (st != JV_OK) return st;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)attn_window8_bf16<O_BF16>, kWindow8Lds);
+    if (st != JV_OK) return st;
     const long long n_items = (long long)a.g.n_win * BH;
     if (n_items >= (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "too many windows");
     const int resident = 2 * 256;  // two workgroups per compute unit

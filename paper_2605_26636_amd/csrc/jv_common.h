@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "jetvit.h"
 
 namespace jv {
@@ -38,6 +40,24 @@ jv_status check_desc(const jv_attn_desc *desc);
 inline jv_status launch_status(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(JV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return JV_OK;
+}
+
+// Kernels that use more than 64 KB of dynamic LDS need their limit raised, once per device (the
+// attribute belongs to the device's copy of the kernel).  One LdsLimit object per kernel, with
+// static storage: it remembers the devices (by ordinal, the first 64) that have been set.
+struct LdsLimit {
+    std::atomic<unsigned long long> devices_done{0};
+};
+inline jv_status ensure_lds_limit(LdsLimit &state, const void *kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(JV_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    const unsigned long long bit = dev >= 0 && dev < 64 ? 1ull << dev : 0ull;
+    if (bit && (state.devices_done.load(std::memory_order_acquire) & bit)) return JV_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    if (bit) state.devices_done.fetch_or(bit, std::memory_order_release);
     return JV_OK;
 }
 

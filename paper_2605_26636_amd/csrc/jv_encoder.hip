@@ -357,13 +357,9 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 template <int EPI, bool OUT_BF16>
 static jv_status launch_gemm(const void *a, const void *w, const float *bias, const float *residual,
                              void *y, long long M, int N, int K, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<EPI, OUT_BF16>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)gemm_bf16_kernel<EPI, OUT_BF16>, kGemmLds);
+    if (st != JV_OK) return st;
     const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (N + kBN - 1) / kBN;
     const int n_tiles = tiles_m * tiles_n;
     dim3 grid(8 * ((n_tiles + 7) / 8));

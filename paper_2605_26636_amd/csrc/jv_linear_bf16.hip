@@ -491,19 +491,12 @@ static void launch_apply(hipStream_t stream, const Problem &pr, const float *sta
 
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
                       const DwcPlan &dwc, int focus_p, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)la_state_bf16<false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)la_state_bf16<true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
-        if (e != hipSuccess) return fail(JV_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
+    static LdsLimit lds_limit[2];
+    jv_status st = ensure_lds_limit(lds_limit[0], (const void *)la_state_bf16<false>, kStateLds);
+    if (st == JV_OK) st = ensure_lds_limit(lds_limit[1], (const void *)la_state_bf16<true>, kStateLds);
+    if (st != JV_OK) return st;
     const int BH = pr.B * pr.heads;
     const bool dynamic = dwc.mode == JV_DWC_SQUEEZE_DYNAMIC;
-    jv_status st;
     if (dynamic)
         hipLaunchKernelGGL(la_state_bf16<true>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
                            pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p);
