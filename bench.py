@@ -59,6 +59,8 @@ def main():
                     help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
                          "(the resolution of the paper's speed tables), as ratios")
     ap.add_argument("--model", choices=["L", "B"], default="L", help="ViT size for --paper-ratio")
+    ap.add_argument("--graph", action="store_true",
+                    help="--paper-ratio: replay each forward pass as one captured HIP graph")
     ap.add_argument("--la-ablation", action="store_true",
                     help="time the linear-attention block variants of the paper's Tab. 1 in a pure "
                          "linear-attention ViT-L and print their ratios")
@@ -88,7 +90,7 @@ def main():
         print(json.dumps(bench_la_ablation(args.steps, args.warmup)))
         return
     if args.paper_ratio:
-        print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model)))
+        print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model, args.graph)))
         return
     if args.encoder:
         enc = bench_encoder(args.steps, args.warmup)
@@ -278,7 +280,7 @@ def bench_encoder(steps, warmup):
             "TFLOPs": tf, "mfma_frac": tf / MFMA_BF16_PEAK_TFLOPS}
 
 
-def bench_paper_ratio(steps, warmup, model="L"):
+def bench_paper_ratio(steps, warmup, model="L", graph=False):
     """The paper's speed comparison re-created with random weights: a 24-block ViT-L on a 64x128
     token grid (1024x2048 px at patch 16, the resolution of its Tab. 1 and Tab. 3), batch 1,
     all blocks full attention against hybrids that keep 0, 1 or 2 full-attention blocks (at
@@ -322,16 +324,28 @@ def bench_paper_ratio(steps, warmup, model="L"):
         for _ in range(warmup):
             enc.forward(x, y, (H, W), ws, stream)
         torch.cuda.synchronize()
+        run = lambda: enc.forward(x, y, (H, W), ws, stream)
+        if graph:  # the whole forward as one HIP graph: no per-kernel launch cost on the host
+            g = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    enc.forward(x, y, (H, W), ws, side)
+            stream.wait_stream(side)
+            run = g.replay
+            run()
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            enc.forward(x, y, (H, W), ws, stream)
+            run()
         torch.cuda.synchronize()
         ms[name] = (time.perf_counter() - t0) * 1e3 / steps
         enc.close()
     base = ms["all_full"]
     return {"metric": "encoder latency ratio, all-full-attention ViT-%s vs hybrid (64x128 grid, batch 1)" % model,
             "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16",
-            "data": "synthetic", "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
+            "data": "synthetic", "hip_graph": bool(graph), "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
             "paper_context_h100": {"DINOv3-L -> JetViT-L (2 full-attention blocks), whole model": "35.07 ms -> 18.77 ms (1.87x)",
                                    "DINOv3-B -> JetViT-B 0/1/2 full-attention blocks": "12.86 ms -> 7.37 / 7.69 / 8.27 ms"}}
 

@@ -253,3 +253,43 @@ def test_encoder_focused_feature_map_variant():
     relu = oracle.encoder_forward(x, blocks, pattern, H, W, heads)
     assert err_bf16(to_host(y), relu) > 5 * BF16_TOL   # the map really differs from ReLU
     enc.close()
+
+
+def test_encoder_forward_under_graph_capture():
+    """The forward pass allocates nothing and never synchronises, so it can be captured in a HIP
+    graph (after one eager call, which raises the kernels' LDS limits): every replay, with new
+    input copied into the captured buffers and eager work in between, equals the eager result."""
+    B, H, W, heads, hidden = 1, 16, 16, 2, 256
+    C = heads * 64
+    blocks = [synth.block_weights(C, hidden, 1010 + i) for i in range(3)]
+    blocks[0]["dwc"] = {"squeeze": synth.squeeze_weights(C, 8, 3, 1020), "ksize": 3}
+    pattern = [0, 1, 2]
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16))
+    xs = [torch.from_numpy(synth.normal((B, H * W, C), 1030 + i)).cuda() for i in range(3)]
+    eager = []
+    ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")
+    for x in xs:
+        y = torch.empty_like(x)
+        enc.forward(x, y, (H, W), ws)
+        eager.append(y)
+    torch.cuda.synchronize()
+    x_cap, y_cap, tap_cap = torch.empty_like(xs[0]), torch.empty_like(xs[0]), torch.empty_like(xs[0])
+    x_cap.copy_(xs[0])
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enc.forward(x_cap, y_cap, (H, W), ws, stream=side, taps={1: tap_cap})
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(2):
+        for x, want in zip(xs, eager):
+            x_cap.copy_(x)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_cap, want)
+            scratch = torch.empty_like(x)
+            enc.forward(x, scratch, (H, W), ws)        # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(scratch, want)
+    enc.close()
