@@ -35,8 +35,11 @@
  *    attempted and the HIP runtime refused it).  No call aborts, throws or
  *    prints.  jv_last_error() returns a thread-local description of the last
  *    failure on the calling thread.
- *  - Thread safety: no mutable global state; concurrent calls are safe as long
- *    as their output and workspace buffers do not overlap.
+ *  - Thread safety: concurrent calls are safe as long as their output and
+ *    workspace buffers do not overlap.  The only process-wide state is, per kernel
+ *    that needs more than 64 KB of LDS, an atomic record of the devices on which
+ *    that limit has been raised (done on the first call on each device, with that
+ *    device current: make the first call on a device outside stream capture).
  */
 #ifndef JETVIT_H
 #define JETVIT_H
