@@ -18,7 +18,8 @@
  *    the stream it is given (hip_stream is a hipStream_t; NULL is the default
  *    stream).  Scratch memory comes in through `workspace`.
  *  - Tensors Q, K, V, O are logically [batch, heads, N, head_dim] with
- *    N = grid_h * grid_w tokens in row-major raster order (token n = r*grid_w+c).
+ *    N = n_prefix + grid_h * grid_w tokens: the prefix tokens, then the grid in row-major
+ *    raster order (grid cell (r, c) is token n_prefix + r*grid_w + c).
  *    The head_dim axis is contiguous; the other three axes have the element
  *    strides given in jv_strides, so a fused QKV projection output laid out
  *    [batch, N, 3, heads, head_dim] can be consumed without a transpose.
@@ -68,12 +69,26 @@ typedef struct {
 
 typedef struct {
     int32_t batch, heads;
-    int32_t grid_h, grid_w; /* token grid; N = grid_h * grid_w */
+    int32_t grid_h, grid_w; /* token grid */
     int32_t head_dim;       /* 64 */
     jv_dtype dtype;         /* element type of Q, K, V */
     jv_dtype o_dtype;       /* element type of O: equal to dtype, or JV_F32 with JV_BF16 inputs */
     jv_strides q, k, v, o;
+    int32_t n_prefix;       /* tokens in front of the grid (class / register tokens), 0 .. 64;
+                               N = n_prefix + grid_h * grid_w.  See "Prefix tokens" below. */
 } jv_attn_desc;
+
+/* Prefix tokens.  Backbones such as the paper's teachers carry a few tokens that belong to no
+ * grid position (a class token, register tokens) in front of the patch tokens.  The paper does
+ * not say how its mixers treat them; this library's rule, for a sequence of n_prefix such
+ * tokens followed by the grid tokens in raster order:
+ *  - full attention and linear attention take all N tokens as ordinary tokens;
+ *  - window attention: a grid token attends to the grid tokens of its window (prefix tokens
+ *    are in no window); a prefix token attends to all N tokens;
+ *  - the depth-wise convolution of the linear-attention block runs over the grid only (zero
+ *    padding at its border as before): prefix tokens receive no convolution term and feed
+ *    none; the token average that generates the dynamic filters runs over all N tokens.
+ * Token n of the tensors is prefix token n for n < n_prefix, else grid cell n - n_prefix. */
 
 const char *jv_version(void);
 const char *jv_status_string(jv_status status);
@@ -236,7 +251,7 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * w_fc2 bf16 [width, mlp_hidden], b_fc2 fp32.  width = heads * 64, width and mlp_hidden
  * multiples of 64.
  *
- * jv_encoder_forward: x and y are device fp32 [batch, grid_h*grid_w, width] (y may be x);
+ * jv_encoder_forward: x and y are device fp32 [batch, n_prefix + grid_h*grid_w, width] (y may be x);
  * workspace is device memory of at least jv_encoder_workspace_bytes(...) bytes, 256-byte
  * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.
  *
@@ -259,6 +274,9 @@ typedef struct {
     int32_t la_focus_p;     /* feature map of the linear-attention blocks: 0 or 1 = ReLU (the
                                paper's block), 2 .. 16 = focused map of that power (the ablation
                                variant, see jv_linear_block_focused_fwd) */
+    int32_t n_prefix;       /* prefix tokens in front of the grid tokens of every image, 0 .. 64
+                               (see "Prefix tokens" at jv_attn_desc); x and y are then
+                               [batch, n_prefix + grid_h*grid_w, width] */
 } jv_encoder_config;
 
 typedef struct {

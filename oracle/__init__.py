@@ -142,6 +142,24 @@ def window_attn_rows(q, k, v, H, W, wh, ww, rows, scale=None):
     return o
 
 
+def prefix_window_allow(P, H, W, wh, ww):
+    """0/1 matrix allow[i, j] of window attention on a sequence of P prefix tokens followed by the
+    H x W grid (the library's stated rule; the paper gives none): a grid token sees the grid
+    tokens of its own window and no prefix token; a prefix token sees every token."""
+    _, _, wt = window_maps(H, W, wh, ww)
+    N = P + H * W
+    allow = np.zeros((N, N), dtype=np.uint8)
+    allow[:P, :] = 1
+    allow[P:, P:] = (wt[:, None] == wt[None, :]).astype(np.uint8)
+    return allow
+
+
+def window_attn_prefix(q, k, v, P, H, W, wh, ww, scale=None):
+    """Window attention with P prefix tokens in front of the grid: masked full attention under
+    prefix_window_allow."""
+    return masked_attn(q, k, v, prefix_window_allow(P, H, W, wh, ww), scale)
+
+
 def linear_attn_quadratic(q, k, v, eps=1e-6):
     """ReLU linear attention in its explicit N x N form (the reference form)."""
     q, qp = _f32(q); k, kp = _f32(k); v, vp = _f32(v)
@@ -270,19 +288,27 @@ def focused_linear_attn(q, k, v, p, eps=1e-6):
 def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksize=3, focus_p=1):
     """The paper's linear-attention block output, Eq. 4: normalised ReLU linear attention plus
     DWC(V).  static_kernel: [C, k, k]; squeeze: (w1, b1, w2, b2) for the dynamic kernel;
-    focus_p > 1: the focused map of Eq. 3 instead of ReLU (the variant Table 1 lists)."""
+    focus_p > 1: the focused map of Eq. 3 instead of ReLU (the variant Table 1 lists).
+    Tokens beyond H * W are prefix tokens in front of the grid (the library's stated rule): they
+    are ordinary tokens of the linear attention and of the token average that generates the
+    dynamic filters, but the convolution runs over the grid tokens only."""
+    P = q.shape[2] - H * W
+    if P < 0:
+        raise ValueError("fewer tokens than grid cells")
     o = linear_attn_quadratic(q, k, v, eps) if focus_p == 1 else focused_linear_attn(q, k, v, focus_p, eps)
+    vg = np.ascontiguousarray(np.asarray(v)[:, :, P:])
     if static_kernel is not None:
-        o = o + dwc(v, np.asarray(static_kernel, dtype=np.float64)[None], H, W)
+        o[:, :, P:] += dwc(vg, np.asarray(static_kernel, dtype=np.float64)[None], H, W)
     if squeeze is not None:
-        o = o + dwc(v, squeeze_kernel(v, *squeeze, ksize), H, W)
+        o[:, :, P:] += dwc(vg, squeeze_kernel(v, *squeeze, ksize), H, W)
     return o
 
 
 MIX_LINEAR, MIX_WINDOW, MIX_FULL = 0, 1, 2
 
 
-def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6, la_focus_p=1):
+def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6, la_focus_p=1,
+                  n_prefix=0):
     """One pre-LN block:  x += W_O mix(split_heads(W_qkv LN(x))) + b_O;  x += MLP(LN(x)).
     x float64 [B, N, C]; wts: dict of float32 arrays (ln1_g, ln1_b, w_qkv [3C, C], b_qkv, w_o,
     b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2; optionally "dwc": dict with static_kernel or
@@ -296,14 +322,15 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
                for i in range(3))
     if mixer == MIX_LINEAR:
         dwc_cfg = wts.get("dwc") or {}   # the block's convolution branch (Eq. 4), if it has one
-        if dwc_cfg or la_focus_p > 1:
+        if dwc_cfg or la_focus_p > 1 or n_prefix > 0:
             o = linear_block(q, k, v, H, W, la_eps, static_kernel=dwc_cfg.get("static_kernel"),
                              squeeze=dwc_cfg.get("squeeze"), ksize=dwc_cfg.get("ksize", 3),
                              focus_p=la_focus_p)
         else:
             o = linear_attn_quadratic(q, k, v, la_eps)
     elif mixer == MIX_WINDOW:
-        o = window_attn(q, k, v, H, W, window[0], window[1])
+        o = (window_attn(q, k, v, H, W, window[0], window[1]) if n_prefix == 0
+             else window_attn_prefix(q, k, v, n_prefix, H, W, window[0], window[1]))
     else:
         o = full_attn(q, k, v)
     o = o.transpose(0, 2, 1, 3).reshape(B, N, C)
@@ -314,14 +341,14 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
 
 
 def encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
-                    taps=None, la_focus_p=1):
+                    taps=None, la_focus_p=1, n_prefix=0):
     """Hybrid encoder: blocks[l] run with mixer pattern[l]; returns the residual stream.  With
     taps (an iterable of block indices) returns (stream, {l: stream after block l}): the
     intermediate features a dense-prediction head reads (Sec. 4.1, 4.2)."""
     x = np.asarray(x, dtype=np.float64)
     kept = {}
     for l, (wts, mixer) in enumerate(zip(blocks, pattern)):
-        x = encoder_block(x, wts, mixer, H, W, heads, window, ln_eps, la_eps, la_focus_p)
+        x = encoder_block(x, wts, mixer, H, W, heads, window, ln_eps, la_eps, la_focus_p, n_prefix)
         if taps is not None and l in taps:
             kept[l] = x.copy()
     return x if taps is None else (x, kept)

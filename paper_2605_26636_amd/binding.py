@@ -38,7 +38,8 @@ class JvAttnDesc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32),
                 ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int), ("o_dtype", ctypes.c_int),
-                ("q", JvStrides), ("k", JvStrides), ("v", JvStrides), ("o", JvStrides)]
+                ("q", JvStrides), ("k", JvStrides), ("v", JvStrides), ("o", JvStrides),
+                ("n_prefix", ctypes.c_int32)]
 
 
 class JvDwcParams(ctypes.Structure):
@@ -51,7 +52,8 @@ class JvEncoderConfig(ctypes.Structure):
     _fields_ = [("n_blocks", ctypes.c_int32), ("width", ctypes.c_int32), ("heads", ctypes.c_int32),
                 ("mlp_hidden", ctypes.c_int32), ("win_h", ctypes.c_int32), ("win_w", ctypes.c_int32),
                 ("ln_eps", ctypes.c_float), ("la_eps", ctypes.c_float),
-                ("pattern", ctypes.POINTER(ctypes.c_uint8)), ("la_focus_p", ctypes.c_int32)]
+                ("pattern", ctypes.POINTER(ctypes.c_uint8)), ("la_focus_p", ctypes.c_int32),
+                ("n_prefix", ctypes.c_int32)]
 
 
 BLOCK_FIELDS = ["ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_fc1", "b_fc1",
@@ -140,11 +142,12 @@ def _strides(t):
 
 
 def make_desc(q, k, v, o, grid):
-    """Descriptor for [B, heads, N, d] tensor views q, k, v, o on an H x W grid."""
+    """Descriptor for [B, heads, N, d] tensor views q, k, v, o on an H x W grid; tokens beyond
+    H * W are prefix tokens in front of the grid (N = n_prefix + H * W)."""
     B, heads, N, d = q.shape
     H, W = grid
-    if H * W != N:
-        raise ValueError("grid does not match the token count")
+    if N < H * W:
+        raise ValueError("fewer tokens than grid cells")
     for t in (k, v, o):
         if tuple(t.shape) != (B, heads, N, d):
             raise ValueError("q, k, v, o must share one shape")
@@ -154,7 +157,7 @@ def make_desc(q, k, v, o, grid):
         if not t.is_cuda:
             raise ValueError("tensors must live on the GPU")
     return JvAttnDesc(B, heads, H, W, d, _dtype_code(q), _dtype_code(o),
-                      _strides(q), _strides(k), _strides(v), _strides(o))
+                      _strides(q), _strides(k), _strides(v), _strides(o), N - H * W)
 
 
 def _stream(stream):
@@ -309,13 +312,13 @@ class Encoder:
     weights bf16, biases and LayerNorm parameters fp32); the tensors are kept alive here."""
 
     def __init__(self, blocks, pattern, heads, mlp_hidden, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
-                 la_focus_p=1):
+                 la_focus_p=1, n_prefix=0):
         self.blocks = blocks
         self.width = blocks[0]["w_o"].shape[0]
         n = len(blocks)
         self._pattern = (ctypes.c_uint8 * n)(*pattern)
         cfg = JvEncoderConfig(n, self.width, heads, mlp_hidden, window[0], window[1], ln_eps, la_eps,
-                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)), la_focus_p)
+                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)), la_focus_p, n_prefix)
         table = (JvBlockWeights * n)()
         self._dwc = []   # parameter structs stay alive until the encoder has copied them
         for i, b in enumerate(blocks):

@@ -37,6 +37,8 @@ jv_status check_desc(const jv_attn_desc *d) {
         return fail(JV_ERR_INVALID_ARG, "batch, heads, grid_h, grid_w must be positive");
     if ((int64_t)d->grid_h * d->grid_w > (1 << 24))
         return fail(JV_ERR_UNSUPPORTED, "more than 2^24 tokens per image");
+    if (d->n_prefix < 0 || d->n_prefix > 64)
+        return fail(JV_ERR_INVALID_ARG, "n_prefix must be 0 .. 64");
     if ((int64_t)d->batch * d->heads > 65535)
         return fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
     if (d->head_dim <= 0) return fail(JV_ERR_INVALID_ARG, "head_dim must be positive");
@@ -67,7 +69,8 @@ jv_status make_problem(const jv_attn_desc *d, const void *q, const void *k, cons
     p->heads = d->heads;
     p->H = d->grid_h;
     p->W = d->grid_w;
-    p->N = d->grid_h * d->grid_w;
+    p->P = d->n_prefix;
+    p->N = d->n_prefix + d->grid_h * d->grid_w;
     p->bf16 = d->dtype == JV_BF16;
     p->o_bf16 = d->o_dtype == JV_BF16;
     p->q = {q, d->q.stride_b, d->q.stride_h, d->q.stride_n};

@@ -31,17 +31,18 @@ __device__ inline float wave_sum(float x) {
 // fp32 path.  One wavefront per query slot; a workgroup holds four consecutive slots of one
 // window.  Key tiles of 64 slots: lane j scores key j (dot product over 64 channels), the
 // tile joins the running softmax, then lane c accumulates channel c of the output.
-// grid (ceil(slots/4), n_win, B*heads), 256 threads.
+// Only the first q_slots query slots of every window are computed.
+// grid (ceil(q_slots/4), n_win, B*heads), 256 threads.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 attn_f32(TensorArg qt, TensorArg kt, TensorArg vt, TensorArg ot, WindowGeom g, int heads,
-         float scale) {
+         float scale, int q_slots) {
     __shared__ float qs[4][kHeadDim];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int bh = blockIdx.z, b = bh / heads, h = bh % heads;
     const int win = blockIdx.y, wy = win / g.wins_x, wx = win % g.wins_x;
     const int qslot = blockIdx.x * 4 + wave;
-    const int qtok = slot_token(g, wy, wx, qslot);
+    const int qtok = qslot < q_slots ? slot_token(g, wy, wx, qslot) : -1;
     if (qtok < 0) return;  // wave-uniform: padded query slots produce nothing
     const float *qp = (const float *)qt.ptr + b * qt.sb + h * qt.sh + (long long)qtok * qt.sn;
     const float *kp = (const float *)kt.ptr + b * kt.sb + h * kt.sh;
@@ -83,31 +84,59 @@ attn_f32(TensorArg qt, TensorArg kt, TensorArg vt, TensorArg ot, WindowGeom g, i
     op[lane] = acc / l;
 }
 
-jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStream_t stream);
+// q_slots: number of leading query slots of each window to compute (all keys always take part).
+jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_slots, hipStream_t stream);
 
-static jv_status attn_dispatch(const Problem &pr, const WindowGeom &g, float scale,
+static jv_status attn_dispatch(const Problem &pr, const WindowGeom &g, float scale, int q_slots,
                                hipStream_t stream) {
-    if (pr.bf16) return attn_bf16(pr, g, scale, stream);
-    const long long qblocks = (g.slots + 3) / 4;
+    if (pr.bf16) return attn_bf16(pr, g, scale, q_slots, stream);
+    const long long qblocks = (q_slots + 3) / 4;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
     hipLaunchKernelGGL(attn_f32, dim3((unsigned)qblocks, g.n_win, pr.B * pr.heads), dim3(256), 0,
-                       stream, pr.q, pr.k, pr.v, pr.o, g, pr.heads, scale);
+                       stream, pr.q, pr.k, pr.v, pr.o, g, pr.heads, scale, q_slots);
     return launch_status("attn_f32");
+}
+
+// All tokens of the sequence as one window of 1 x N slots (token = slot).
+static WindowGeom sequence_geom(int N) {
+    WindowGeom g;
+    g.H = 1; g.W = N; g.wh = 1; g.ww = N;
+    g.Hp = 1; g.Wp = N; g.wins_x = 1; g.wins_y = 1; g.n_win = 1; g.slots = N;
+    return g;
+}
+
+// The same tensors from token `first` on.
+static TensorArg from_token(const TensorArg &t, int first, bool bf16) {
+    TensorArg r = t;
+    r.ptr = (const char *)t.ptr + (long long)first * t.sn * (bf16 ? 2 : 4);
+    return r;
 }
 
 jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStream_t stream) {
     WindowGeom g;
     jv_status st = make_window_geom(pr.H, pr.W, wh, ww, &g);
     if (st != JV_OK) return st;
-    return attn_dispatch(pr, g, resolve_scale(scale), stream);
+    if (pr.P == 0) return attn_dispatch(pr, g, resolve_scale(scale), g.slots, stream);
+    // Prefix tokens: the grid tokens run window attention among themselves; the prefix
+    // tokens (the first P query slots of the whole sequence) attend to every token.
+    Problem grid = pr;
+    grid.P = 0;
+    grid.N = pr.H * pr.W;
+    grid.q = from_token(pr.q, pr.P, pr.bf16);
+    grid.k = from_token(pr.k, pr.P, pr.bf16);
+    grid.v = from_token(pr.v, pr.P, pr.bf16);
+    grid.o = from_token(pr.o, pr.P, pr.o_bf16);
+    if ((st = attn_dispatch(grid, g, resolve_scale(scale), g.slots, stream)) != JV_OK) return st;
+    return attn_dispatch(pr, sequence_geom(pr.N), resolve_scale(scale), pr.P, stream);
 }
 
 jv_status full_forward(const Problem &pr, float scale, hipStream_t stream) {
+    if (pr.P > 0) return attn_dispatch(pr, sequence_geom(pr.N), resolve_scale(scale), pr.N, stream);
     // One window that spans the grid; the token order inside it is the raster order.
     WindowGeom g;
     g.H = pr.H; g.W = pr.W; g.wh = pr.H; g.ww = pr.W;
     g.Hp = pr.H; g.Wp = pr.W; g.wins_x = 1; g.wins_y = 1; g.n_win = 1; g.slots = pr.N;
-    return attn_dispatch(pr, g, resolve_scale(scale), stream);
+    return attn_dispatch(pr, g, resolve_scale(scale), g.slots, stream);
 }
 
 }  // namespace jv

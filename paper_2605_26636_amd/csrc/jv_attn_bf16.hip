@@ -32,6 +32,7 @@ struct AttnArgs {
     WindowGeom g;
     int heads;
     int contig;  // windows span whole grid rows: token = first token of the window + slot
+    int q_slots; // leading query slots of each window to compute (all keys always take part)
     float c;     // logit scale times log2(e)
 };
 
@@ -296,7 +297,7 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
     const int q0 = blockIdx.x * (128 * NT) + wave * (32 * NT);
     const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
     const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
-    const bool wave_live = q0 < a.g.slots;
+    const bool wave_live = q0 < a.q_slots;
 
     bf16x8 qreg[NT][4];
     load_queries<NT>(qreg, a, wy, wx, q0, qbase, lane);
@@ -364,7 +365,11 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
         run_stage(st, std::integral_constant<int, 0>());
         if (st + 1 < n_stage) run_stage(st + 1, std::integral_constant<int, 1>());
     }
-    if (wave_live) wave_store<O_BF16, NT>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
+    if (wave_live) {
+        AttnArgs st = a;
+        st.g.slots = a.q_slots;  // query slots past the limit are not stored
+        wave_store<O_BF16, NT>(w, st, wy, wx, q0, obase, smem + wave * 4096, lane);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -727,7 +732,7 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
     const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
     const int q0 = blockIdx.x * (64 * WAVES) + wave * 64;
     const long long qbase = b * a.q.sb + h * a.q.sh, obase = b * a.o.sb + h * a.o.sh;
-    const bool wave_live = q0 < a.g.slots;
+    const bool wave_live = q0 < a.q_slots;
 
     bf16x8 qreg[2][4];
     load_queries<2>(qreg, a, wy, wx, q0, qbase, lane);
@@ -841,7 +846,11 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
         }
     }
     __syncthreads();  // every wavefront is done with the ring: reuse it as staging
-    if (wave_live) wave_store<O_BF16, 2>(w, a, wy, wx, q0, obase, smem + wave * 4096, lane);
+    if (wave_live) {
+        AttnArgs st = a;
+        st.g.slots = a.q_slots;  // query slots past the limit are not stored
+        wave_store<O_BF16, 2>(w, st, wy, wx, q0, obase, smem + wave * 4096, lane);
+    }
 }
 
 template <bool O_BF16, int WPW>
@@ -867,19 +876,21 @@ static jv_status launch_window8(const AttnArgs &a, int BH, hipStream_t stream) {
     return launch_status("attn_window8_bf16");
 }
 
-jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStream_t stream) {
+jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_slots, hipStream_t stream) {
     AttnArgs a;
     a.q = pr.q; a.k = pr.k; a.v = pr.v; a.o = pr.o;
     a.g = g;
     a.heads = pr.heads;
     a.contig = g.ww == g.W ? 1 : 0;
+    a.q_slots = q_slots < g.slots ? q_slots : g.slots;
     a.c = scale * kLog2e;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
+    const bool all_queries = a.q_slots == g.slots;  // the window-resident kernels compute every slot
     // Windows that fit in LDS whole take the window-resident kernel.
-    if (g.slots <= 64)
+    if (all_queries && g.slots <= 64)
         return pr.o_bf16 ? launch_window<true, 1>(a, pr.B * pr.heads, stream)
                          : launch_window<false, 1>(a, pr.B * pr.heads, stream);
-    if (g.slots == 256 && g.n_win > 1 && g.H % g.wh == 0 && g.W % g.ww == 0) {
+    if (all_queries && g.slots == 256 && g.n_win > 1 && g.H % g.wh == 0 && g.W % g.ww == 0) {
         // byte offsets of a window's tokens from its first one in 32 bits?
         long long max_sn = pr.q.sn;
         for (long long sn : {pr.k.sn, pr.v.sn, pr.o.sn}) max_sn = sn > max_sn ? sn : max_sn;
@@ -887,11 +898,11 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, hipStre
             return pr.o_bf16 ? launch_window8<true>(a, pr.B * pr.heads, stream)
                              : launch_window8<false>(a, pr.B * pr.heads, stream);
     }
-    if (g.slots <= 256 && g.n_win > 1)
+    if (all_queries && g.slots <= 256 && g.n_win > 1)
         return pr.o_bf16 ? launch_window<true, 4>(a, pr.B * pr.heads, stream)
                          : launch_window<false, 4>(a, pr.B * pr.heads, stream);
     constexpr int NT = JV_ATTN_NT;
-    dim3 grid((g.slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
+    dim3 grid((a.q_slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
     // 32-bit byte offsets inside one (batch, head) slice?
     const long long max_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
     const bool fast = a.contig && ((long long)pr.N + 2 * kStage) * max_sn * 2 + 256 < (1ll << 31);

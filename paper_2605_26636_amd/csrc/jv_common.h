@@ -25,7 +25,8 @@ struct TensorArg {
 
 // Everything a mixer kernel needs to know about the problem.
 struct Problem {
-    int B, heads, H, W, N;
+    int B, heads, H, W, N;  // N = P + H * W tokens
+    int P;                  // prefix tokens in front of the grid
     bool bf16;      // element type of Q, K, V
     bool o_bf16;    // element type of O
     TensorArg q, k, v, o;

@@ -171,13 +171,14 @@ dwc_add_f32(TensorArg vt, TensorArg ot, DwcArg cv, int ksize, int heads, int N) 
     for (int i = 0; i < 4; ++i) {
         const int n = blockIdx.x * 64 + i * 16 + tr;
         if (n >= N) break;
-        const int r = n / cv.W, c = n - r * cv.W;
+        if (n < cv.P) continue;  // prefix tokens get no convolution term
+        const int r = (n - cv.P) / cv.W, c = (n - cv.P) - r * cv.W;
         f32x4 acc = *(const f32x4 *)(op + (long long)n * ot.sn + c4);
         for (int di = -pad; di <= pad; ++di)
             for (int dj = -pad; dj <= pad; ++dj) {
                 const int r2 = r + di, c2 = c + dj;
                 if (r2 < 0 || r2 >= cv.H || c2 < 0 || c2 >= cv.W) continue;
-                const f32x4 vv = *(const f32x4 *)(vp + (long long)(r2 * cv.W + c2) * vt.sn + c4);
+                const f32x4 vv = *(const f32x4 *)(vp + (long long)(cv.P + r2 * cv.W + c2) * vt.sn + c4);
                 const f32x4 kv = *(const f32x4 *)&kap[(di + pad) * ksize + dj + pad][c4];
                 acc[0] = fmaf(kv[0], vv[0], acc[0]);
                 acc[1] = fmaf(kv[1], vv[1], acc[1]);

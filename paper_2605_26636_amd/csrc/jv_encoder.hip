@@ -473,6 +473,7 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
     if (c.win_h <= 0 || c.win_w <= 0) return jv::fail(JV_ERR_INVALID_ARG, "window must be positive");
     if (!(c.ln_eps >= 0.f) || !(c.la_eps >= 0.f)) return jv::fail(JV_ERR_INVALID_ARG, "bad epsilon");
     if (c.la_focus_p < 0 || c.la_focus_p > 16) return jv::fail(JV_ERR_INVALID_ARG, "la_focus_p must be 0 .. 16");
+    if (c.n_prefix < 0 || c.n_prefix > 64) return jv::fail(JV_ERR_INVALID_ARG, "n_prefix must be 0 .. 64");
     for (int l = 0; l < c.n_blocks; ++l) {
         if (c.pattern[l] > 2) return jv::fail(JV_ERR_INVALID_ARG, "pattern[%d] is not 0, 1 or 2", l);
         const jv_block_weights &b = blocks[l];
@@ -526,10 +527,10 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
                                   int32_t grid_w) {
     jv::clear_error();
     if (!enc || batch <= 0 || grid_h <= 0 || grid_w <= 0) return 0;
-    const size_t T = (size_t)batch * grid_h * grid_w, C = enc->cfg.width;
+    const size_t T = (size_t)batch * (enc->cfg.n_prefix + (size_t)grid_h * grid_w), C = enc->cfg.width;
     const size_t wide = 3 * C > (size_t)enc->cfg.mlp_hidden ? 3 * C : (size_t)enc->cfg.mlp_hidden;
     return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
-           jv::align256(jv::encoder_linear_workspace(enc, batch, grid_h * grid_w));
+           jv::align256(jv::encoder_linear_workspace(enc, batch, enc->cfg.n_prefix + grid_h * grid_w));
 }
 
 jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
@@ -564,7 +565,7 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *
         return jv::fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed",
                         workspace_bytes, need);
     const jv_encoder_config &c = enc->cfg;
-    const int N = grid_h * grid_w, C = c.width;
+    const int N = c.n_prefix + grid_h * grid_w, C = c.width;
     const long long T = (long long)batch * N;
     if ((long long)batch * c.heads > 65535) return jv::fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -577,7 +578,7 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *
 
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
     jv::Problem pr;
-    pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = N;
+    pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = N; pr.P = c.n_prefix;
     pr.bf16 = true; pr.o_bf16 = true;
     const long long sb = (long long)N * 3 * C, sn = 3LL * C;
     pr.q = {widebuf, sb, jv::kHeadDim, sn};

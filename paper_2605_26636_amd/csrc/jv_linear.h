@@ -32,11 +32,12 @@ struct DwcPlan {
 jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int heads, DwcPlan *out);
 
 // What the apply kernels need of the convolution: filters [.., C, k*k] with a batch stride
-// (0 for a static bank) on the H x W grid.
+// (0 for a static bank) on the H x W grid that follows P prefix tokens.
 struct DwcArg {
     const float *kappa;
     long long kappa_sb;
     int H, W;
+    int P;  // prefix tokens in front of the grid: token n is grid cell n - P; they take no part
 };
 
 // focus_p: 1 = ReLU feature map; >= 2 = focused map of Eq. 3 with that integer power.

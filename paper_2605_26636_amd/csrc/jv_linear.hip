@@ -193,7 +193,7 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
                        ws, pr.heads, pr.N, plan.n_split, eps, focus_p);
     if ((st = launch_status("la_apply_f32")) != JV_OK) return st;
     if (cv.mode == JV_DWC_NONE) return JV_OK;
-    DwcArg arg = {cv.static_kernel, 0, pr.H, pr.W};
+    DwcArg arg = {cv.static_kernel, 0, pr.H, pr.W, pr.P};
     if (cv.mode == JV_DWC_SQUEEZE_DYNAMIC) {
         if ((st = vsum_f32_launch(pr, plan, ws + cv.vsum_off, stream)) != JV_OK) return st;
         if ((st = squeeze_generate(cv, ws, plan.n_split, pr.B, pr.heads, pr.N, stream)) != JV_OK) return st;
@@ -227,7 +227,7 @@ size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_pa
     jv::clear_error();
     if (jv::check_desc(desc) != JV_OK) return 0;
     jv::DwcPlan cv;
-    const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->grid_h * desc->grid_w);
+    const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->n_prefix + desc->grid_h * desc->grid_w);
     if (jv::plan_dwc(dwc, plan, desc->batch, desc->heads, &cv) != JV_OK) return 0;
     return cv.total_floats * sizeof(float);
 }

@@ -382,8 +382,10 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
                 const int last = n1 - 1;
                 float sum[4][8];
                 int gr[4], gc[4];
+                bool on_grid[4];  // prefix tokens (grid index below zero) get no convolution term
                 {
-                    const int base = min(tok0, last);
+                    const int g0 = min(tok0, last) - cv.P;  // grid index of the lane's first token
+                    const int base = max(g0, 0);
                     int r0 = base / cv.W, c0 = base - r0 * cv.W;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -394,7 +396,8 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
                         sum[r][4] = o1[0]; sum[r][5] = o1[1]; sum[r][6] = o1[2]; sum[r][7] = o1[3];
                         gr[r] = r0;
                         gc[r] = c0;
-                        if (++c0 == cv.W) { c0 = 0; ++r0; }
+                        on_grid[r] = g0 + r >= 0;
+                        if (on_grid[r] && ++c0 == cv.W) { c0 = 0; ++r0; }
                     }
                 }
 #pragma unroll 1
@@ -413,7 +416,7 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
                         const f32x4 k1 = *(const f32x4 *)(krow + (dj + kPad) * kHeadDim + 4);
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            const bool ok = tok0 + r <= last && (unsigned)(gr[r] + di) < (unsigned)cv.H &&
+                            const bool ok = tok0 + r <= last && on_grid[r] && (unsigned)(gr[r] + di) < (unsigned)cv.H &&
                                             (unsigned)(gc[r] + dj) < (unsigned)cv.W;
                             const float m = ok ? 1.0f : 0.0f;
                             const u32x4 x = vv[r + dj + kPad];
@@ -515,7 +518,7 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
         states = dst;
         n_part = 1;
     }
-    DwcArg cv = {dwc.static_kernel, 0, pr.H, pr.W};
+    DwcArg cv = {dwc.static_kernel, 0, pr.H, pr.W, pr.P};
     if (dynamic) {
         if ((st = squeeze_generate(dwc, ws, plan.n_split, pr.B, pr.heads, pr.N, stream)) != JV_OK) return st;
         cv.kappa = ws + dwc.kappa_off;

@@ -120,3 +120,30 @@ def test_encoder_patterns():
     assert pattern.count(oracle.MIX_FULL) == 4 and pattern.count(oracle.MIX_WINDOW) == 12
     assert pattern.count(oracle.MIX_LINEAR) == 8
     assert [i for i, p in enumerate(pattern) if p == oracle.MIX_FULL] == [5, 11, 17, 23]
+
+
+def test_linear_block_with_prefix_tokens():
+    """Prefix tokens are ordinary tokens of the linear attention and of the filter generator's
+    token average; the convolution runs over the grid tokens only."""
+    P, H, W, heads, d = 2, 4, 5, 2, 16
+    N, C = P + H * W, heads * d
+    q, k, v = (synth.normal((1, heads, N, d), 500 + i) for i in range(3))
+    kern = synth.dwc_static_kernel(C, 3, 510)
+    o = oracle.linear_block(q, k, v, H, W, static_kernel=kern)
+    la = oracle.linear_attn_quadratic(q, k, v)
+    assert np.abs(o[:, :, :P] - la[:, :, :P]).max() < 1e-15          # prefix rows: no convolution term
+    conv = oracle.dwc(np.ascontiguousarray(v[:, :, P:]), kern[None], H, W)
+    assert np.abs(o[:, :, P:] - (la[:, :, P:] + conv)).max() < 1e-12
+    # changing a prefix value row changes the convolution term of no grid token ...
+    v2 = v.copy(); v2[:, :, 0] += 1.0
+    conv_part = lambda vv: oracle.linear_block(q, k, vv, H, W, static_kernel=kern) - oracle.linear_attn_quadratic(q, k, vv)
+    assert np.abs(conv_part(v2) - conv_part(v)).max() < 1e-12
+    # ... but it moves the token average the dynamic filters are generated from
+    sq = synth.squeeze_weights(C, 4, 3, 520)
+    ka, kb = oracle.squeeze_kernel(v, *sq, 3), oracle.squeeze_kernel(v2, *sq, 3)
+    assert np.abs(ka - kb).max() > 1e-6
+    g = v.astype(np.float64).transpose(0, 2, 1, 3).reshape(1, N, C).mean(1)     # mean over all N tokens
+    u = sq[0].astype(np.float64) @ g[0] + sq[1]
+    u = u / (1.0 + np.exp(-u))
+    want = (sq[2].astype(np.float64) @ u + sq[3]).reshape(C, 3, 3)
+    assert np.abs(ka[0] - want).max() < 1e-12

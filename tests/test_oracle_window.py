@@ -110,3 +110,29 @@ def test_against_reshape_partition_and_library_attention():
         rows = synth.sample_rows(1, 2, H * W, 7, seed=H)
         got_rows = oracle.window_attn_rows(q, k, v, H, W, wh, ww, rows)
         assert np.array_equal(got_rows, np.stack([got[b, hh, i] for b, hh, i in rows]))
+
+
+# ---- prefix tokens in front of the grid (the library's stated rule) ----------------------------
+
+def test_prefix_rule_of_window_attention():
+    P, H, W, wh, ww = 3, 5, 6, 2, 4
+    N = P + H * W
+    allow = oracle.prefix_window_allow(P, H, W, wh, ww)
+    assert allow.shape == (N, N)
+    assert allow[:P].all()                      # prefix queries see everything
+    assert not allow[P:, :P].any()              # grid queries see no prefix key
+    _, _, wt = oracle.window_maps(H, W, wh, ww)
+    sizes = np.bincount(wt)
+    assert np.array_equal(allow[P:, P:].sum(1), sizes[wt])   # and exactly their window
+    assert np.array_equal(allow[P:, P:], allow[P:, P:].T)
+    q, k, v = (synth.normal((2, 2, N, 16), 400 + i) for i in range(3))
+    o = oracle.window_attn_prefix(q, k, v, P, H, W, wh, ww)
+    # grid rows: window attention of the grid tokens alone (the C routine, independent of the mask path)
+    grid = oracle.window_attn(*(np.ascontiguousarray(t[:, :, P:]) for t in (q, k, v)), H, W, wh, ww)
+    assert np.abs(o[:, :, P:] - grid).max() < 1e-12
+    # prefix rows: full attention over the whole sequence
+    full = oracle.full_attn(q, k, v)
+    assert np.abs(o[:, :, :P] - full[:, :, :P]).max() < 1e-12
+    # no prefix: the mask rule is plain window attention
+    o0 = oracle.window_attn_prefix(q[:, :, P:], k[:, :, P:], v[:, :, P:], 0, H, W, wh, ww)
+    assert np.abs(o0 - grid).max() < 1e-12
