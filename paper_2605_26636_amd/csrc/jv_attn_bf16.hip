@@ -853,6 +853,139 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// A few queries against a whole sequence: the prefix tokens (at most 64, the first query slots
+// of a one-window geometry whose slot s is token s) attend to all N tokens.  With so few
+// queries the parallelism has to come from the keys: one workgroup of eight wavefronts per
+// (batch, head); every wavefront holds all the queries, takes every eighth stage of 64 keys
+// into a tile of its own (loads straight into LDS, no barriers in the loop) and keeps its own
+// running softmax; at the end the eight partial results are merged through LDS,
+//     O = sum_w acc_w 2^(m_w - M) / sum_w l_w 2^(m_w - M),   M = max_w m_w.
+// grid (B*heads), 512 threads, kPrefixLds bytes of dynamic LDS.  Requirements as attn_ring_bf16.
+// ---------------------------------------------------------------------------------------
+constexpr int kPrefixWaves = 8;
+constexpr int kPrefixLds = kPrefixWaves * kStageBytes + 2 * kPrefixWaves * 64 * 4;
+
+template <bool O_BF16>
+__global__ void __launch_bounds__(512, 1) attn_prefix_bf16(AttnArgs a) {
+    extern __shared__ __align__(16) unsigned char psm[];
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, li = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bh = blockIdx.x, b = bh / a.heads, h = bh % a.heads;
+    const long long qbase = b * a.q.sb + h * a.q.sh;
+    const int N = a.g.slots;
+
+    bf16x8 qreg[2][4];
+    load_queries<2>(qreg, a, 0, 0, 0, qbase, lane);
+    WaveState<2> w;
+    wave_state_init<2>(w);
+
+    auto uniform = [](const char *ptr) {
+        const unsigned long long u = (unsigned long long)ptr;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+        return (const char *)(((unsigned long long)hi << 32) | lo);
+    };
+    const char *kbytes = uniform((const char *)((const __bf16 *)a.k.ptr + b * a.k.sb + h * a.k.sh));
+    const char *vbytes = uniform((const char *)((const __bf16 *)a.v.ptr + b * a.v.sb + h * a.v.sh));
+    unsigned char *kt = psm + wave * kStageBytes, *vt = kt + kStage * 128;
+    const int lrow = lane >> 3, lslot = lane & 7;
+    const int n_stage = (N + kStage - 1) / kStage;
+    for (int st = wave; st < n_stage; st += kPrefixWaves) {
+        // (the LDS reads of the previous stage have been waited for before the matrix
+        // instructions that used them, so the tile may be overwritten)
+#pragma unroll 1
+        for (int i = 0; i < 8; ++i) {
+            const int row = 8 * i + lrow;
+            const int tok = st * kStage + row < N ? st * kStage + row : 0;  // past the end: any valid row
+            const unsigned ko = 2u * ((unsigned)tok * (unsigned)a.k.sn + (lslot ^ tile_row_rotation(row)) * 8);
+            const unsigned vo = 2u * ((unsigned)tok * (unsigned)a.v.sn + (lslot ^ (((row ^ (row >> 1)) & 1) << 2)) * 8);
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(kbytes + ko),
+                                             (attn_lds_void *)(kt + 8 * i * 128), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(vbytes + vo),
+                                             (attn_lds_void *)(vt + 8 * i * 128), 16, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int key_limit = N - st * kStage;
+        // The operand addresses depend on the lane only; `ln` is the lane, but opaque to the
+        // compiler, which would otherwise keep every address of every tile variant in a
+        // register of its own across the loop (and spill them).
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        bf16x8 ka[4];
+        load_k_operands(ka, kt, 0, ln);
+        // (one masked tile code for whole and partial stages: this kernel waits for its loads,
+        // not for its arithmetic)
+        ring_tile32<true, true>(w, qreg, ka, kt, vt, 0, key_limit, a.c, ln);
+        if (key_limit > 32) ring_tile32<false, true>(w, qreg, ka, kt, vt, 32, key_limit, a.c, ln);
+    }
+
+    // Partial results into LDS: the accumulators as [query][channel] fp32 in the wavefront's own
+    // tile bytes (16-byte pieces rotated by the query to spread the banks), references and sums
+    // behind the tiles.
+    float *mine = (float *)(psm + wave * kStageBytes);
+    float *mbuf = (float *)(psm + kPrefixWaves * kStageBytes), *lbuf = mbuf + kPrefixWaves * 64;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int qcol = 32 * nt + li;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x16 &x = w.acc[mi][nt];
+                f32x4 val = {x[4 * q4], x[4 * q4 + 1], x[4 * q4 + 2], x[4 * q4 + 3]};
+                *(f32x4 *)(mine + qcol * 64 + (((8 * mi + 2 * q4 + g) ^ (qcol & 15)) << 2)) = val;
+            }
+        float lo, hi;
+        pair_values(w.l[nt], &lo, &hi);
+        if (g == 0) {
+            mbuf[wave * 64 + qcol] = w.m[nt];
+            lbuf[wave * 64 + qcol] = lo + hi;
+        }
+    }
+    __syncthreads();
+    // Merge: thread = (query, 8 channels).
+    const int qcol = tid >> 3, piece = tid & 7;
+    if (qcol < a.q_slots && qcol < N) {
+        float top = kMinusHuge;
+#pragma unroll
+        for (int wv = 0; wv < kPrefixWaves; ++wv) top = fmaxf(top, mbuf[wv * 64 + qcol]);
+        float den = 0.f;
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+        for (int wv = 0; wv < kPrefixWaves; ++wv) {
+            const float scale = __builtin_amdgcn_exp2f(mbuf[wv * 64 + qcol] - top);
+            den = fmaf(lbuf[wv * 64 + qcol], scale, den);
+            const float *row = (const float *)(psm + wv * kStageBytes) + qcol * 64;
+            const f32x4 x0 = *(const f32x4 *)(row + (((2 * piece) ^ (qcol & 15)) << 2));
+            const f32x4 x1 = *(const f32x4 *)(row + (((2 * piece + 1) ^ (qcol & 15)) << 2));
+            s0 += x0 * scale;
+            s1 += x1 * scale;
+        }
+        const float inv = 1.0f / den;
+        s0 *= inv;
+        s1 *= inv;
+        const long long at = b * a.o.sb + h * a.o.sh + (long long)qcol * a.o.sn + 8 * piece;
+        if (O_BF16) {
+            u32x4 pk = {pack_bf16x2(s0[0], s0[1]), pack_bf16x2(s0[2], s0[3]), pack_bf16x2(s1[0], s1[1]),
+                        pack_bf16x2(s1[2], s1[3])};
+            *(u32x4 *)((__bf16 *)a.o.ptr + at) = pk;
+        } else {
+            *(f32x4 *)((float *)a.o.ptr + at) = s0;
+            *(f32x4 *)((float *)a.o.ptr + at + 4) = s1;
+        }
+    }
+}
+
+template <bool O_BF16>
+static jv_status launch_prefix(const AttnArgs &a, int BH, hipStream_t stream) {
+    static LdsLimit lds_limit;
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)attn_prefix_bf16<O_BF16>, kPrefixLds);
+    if (st != JV_OK) return st;
+    hipLaunchKernelGGL((attn_prefix_bf16<O_BF16>), dim3(BH), dim3(512), kPrefixLds, stream, a);
+    return launch_status("attn_prefix_bf16");
+}
+
 template <bool O_BF16, int WPW>
 static jv_status launch_window(const AttnArgs &a, int BH, hipStream_t stream) {
     static LdsLimit lds_limit;
@@ -906,6 +1039,10 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     // 32-bit byte offsets inside one (batch, head) slice?
     const long long max_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
     const bool fast = a.contig && ((long long)pr.N + 2 * kStage) * max_sn * 2 + 256 < (1ll << 31);
+    // a handful of queries against the whole sequence (prefix tokens): split the keys instead
+    if (fast && !all_queries && a.q_slots <= 64 && g.n_win == 1)
+        return pr.o_bf16 ? launch_prefix<true>(a, pr.B * pr.heads, stream)
+                         : launch_prefix<false>(a, pr.B * pr.heads, stream);
     if (fast && NT == 2) {
         if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_bf16<true>), grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((attn_ring_bf16<false>), grid, dim3(256), 0, stream, a);

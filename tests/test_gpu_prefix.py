@@ -73,7 +73,9 @@ def test_fp32_mixers_with_prefix(P, B, heads, H, W, window):
 
 def test_prefix_rows_do_not_disturb_grid_rows_of_window_attention():
     """Grid rows with prefix tokens present are bit-identical to window attention on the grid
-    tokens alone (the same kernels on the same rows); the prefix rows equal full attention's."""
+    tokens alone (the same kernels on the same rows); the prefix rows are full attention's (a
+    kernel of their own that splits the keys, so equal to the oracle within the tolerance, not
+    bit for bit to the full-attention kernel)."""
     P, B, heads, H, W, window = 5, 1, 2, 32, 32, (16, 16)
     N = P + H * W
     q, k, v = synth.qkv(62, B, heads, N, 64, 0.5, True)
@@ -81,8 +83,9 @@ def test_prefix_rows_do_not_disturb_grid_rows_of_window_attention():
     grid = _run(binding.jv_window_attn_fwd, *(np.ascontiguousarray(t[:, :, P:]) for t in (q, k, v)),
                 True, torch.bfloat16, (H, W), window)
     assert torch.equal(o[:, :, P:], grid)
-    full = _run(binding.jv_full_attn_fwd, q, k, v, True, torch.bfloat16, (H, W))
-    assert torch.equal(o[:, :, :P], full[:, :, :P])
+    o32 = _run(binding.jv_window_attn_fwd, q, k, v, True, torch.float32, (H, W), window)
+    ref = oracle.full_attn(q, k, v)[:, :, :P]
+    check(err_bf16(to_host(o32[:, :, :P]), ref), BF16_TOL)
 
 
 def test_encoder_with_prefix_tokens():
