@@ -34,6 +34,8 @@ def test_layernorm(rows, cols):
     (1, 8, 64),          # smallest
     (1024, 768, 1024),   # several tiles per XCD slot
     (515, 1024, 4096),   # long K
+    (4600, 4360, 128),   # 324 ragged tiles: workgroups run two tiles as one stream of K blocks
+    (6400, 6200, 64),    # 625 tiles of a single K block each: three tiles per workgroup in flight
 ])
 def test_gemm_epilogues(M, N, K):
     a = synth.round_to_bf16(synth.normal((M, K), 600 + M))
