@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--paper-ratio", action="store_true",
                     help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
                          "(the resolution of the paper's speed tables), as ratios")
-    ap.add_argument("--model", choices=["L", "B"], default="L", help="ViT size for --paper-ratio")
+    ap.add_argument("--model", choices=["L", "B", "H"], default="L", help="ViT size for --paper-ratio")
     ap.add_argument("--graph", action="store_true",
                     help="--paper-ratio: replay each forward pass as one captured HIP graph")
     ap.add_argument("--la-ablation", action="store_true",
@@ -287,12 +287,14 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
     blocks 14 and 22, where the paper's search puts them for segmentation, Sec. 4.4); the first
     block is linear attention, the others alternate window 16x16 and linear attention; linear
     blocks carry the squeeze-dynamic 3x3 convolution branch (hidden width C/16).  model "B": the
-    same with ViT-B (12 blocks, width 768, 12 heads), full attention kept at blocks 7 and 11 (the
-    paper does not print its ViT-B positions: the ViT-L ones scaled to 12 blocks)."""
+    same with ViT-B (12 blocks, width 768, 12 heads), full attention kept at blocks 7 and 11, or
+    "H" (32 blocks, width 1280, 20 heads, MLP 5120), blocks 19 and 29 (the paper prints positions
+    for ViT-L only: scaled to the other depths)."""
     import torch
     from paper_2605_26636_amd import binding, synth
     B, H, W = 1, 64, 128
-    heads, hidden, L, full_at_two = (16, 4096, 24, (14, 22)) if model == "L" else (12, 3072, 12, (7, 11))
+    heads, hidden, L, full_at_two = {"L": (16, 4096, 24, (14, 22)), "B": (12, 3072, 12, (7, 11)),
+                                     "H": (20, 5120, 32, (19, 29))}[model]
     C, N = heads * 64, H * W
     dev = []
     for l in range(L):
