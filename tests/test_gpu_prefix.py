@@ -119,3 +119,33 @@ def test_prefix_count_is_validated():
     o = torch.empty_like(q)
     with pytest.raises(binding.JvError):
         binding.jv_full_attn_fwd(q, q.clone(), q.clone(), o, (4, 4))   # 65 prefix tokens
+
+
+def test_config2_size_with_prefix_sampled_rows():
+    """The benchmark layer (batch 8, 64x64 grid, 16 heads) with a class token and four register
+    tokens in front, at full size, on sampled rows: the prefix rows and the first and last grid
+    rows are always in the sample."""
+    P, B, heads, H, W, window = 5, 8, 16, 64, 64, (16, 16)
+    N = P + H * W
+    q, k, v = synth.qkv(63, B, heads, N, 64, 0.125, True)
+    rows = synth.sample_rows(B, heads, N, 384, seed=9)
+    rows[1:6, 2] = np.arange(P)              # every prefix row of some (batch, head)
+    rows[6, 2] = P                           # first grid token
+    is_prefix = rows[:, 2] < P
+    grid_rows = rows[~is_prefix].copy()
+    grid_rows[:, 2] -= P
+    qg, kg, vg = (np.ascontiguousarray(t[:, :, P:]) for t in (q, k, v))
+    # full attention: all N tokens
+    ref = oracle.full_attn_rows(q, k, v, rows)
+    check_bf16_pair(_run(binding.jv_full_attn_fwd, q, k, v, True, torch.float32, (H, W)),
+                    _run(binding.jv_full_attn_fwd, q, k, v, True, torch.bfloat16, (H, W)), ref, rows)
+    # window attention: grid rows see their window of the grid, prefix rows everything
+    ref = np.empty((rows.shape[0], 64))
+    ref[is_prefix] = oracle.full_attn_rows(q, k, v, rows[is_prefix])
+    ref[~is_prefix] = oracle.window_attn_rows(qg, kg, vg, H, W, *window, grid_rows)
+    check_bf16_pair(_run(binding.jv_window_attn_fwd, q, k, v, True, torch.float32, (H, W), window),
+                    _run(binding.jv_window_attn_fwd, q, k, v, True, torch.bfloat16, (H, W), window), ref, rows)
+    # linear attention: all N tokens
+    ref = oracle.linear_attn_rows(q, k, v, rows)
+    check_bf16_pair(_run(binding.jv_linear_attn_fwd, q, k, v, True, torch.float32, (H, W)),
+                    _run(binding.jv_linear_attn_fwd, q, k, v, True, torch.bfloat16, (H, W)), ref, rows)
