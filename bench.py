@@ -357,7 +357,8 @@ def bench_la_ablation(steps, warmup):
     weights: a pure linear-attention ViT-L (24 blocks) on a 64x128 token grid, batch 1, with the
     block variants the table lists: ReLU linear attention; + static 3x3 convolution on V;
     + the focused feature map (p = 3) on top of that; + squeeze-dynamic convolution instead (the
-    paper's block).  The token-wise dynamic convolution of the table is not built."""
+    paper's block); + token-wise dynamic convolution (the same generator run on every token, the
+    variant the paper rejects for its cost)."""
     import torch
     from paper_2605_26636_amd import binding, synth
     B, H, W, heads, hidden, L = 1, 64, 128, 16, 4096, 24
@@ -376,7 +377,8 @@ def bench_la_ablation(steps, warmup):
         return [dict(b, dwc=dwc[l]) if dwc else dict(b) for l, b in enumerate(base_blocks)]
 
     variants = {"relu": (with_dwc(None), 1), "relu+static_dwc": (with_dwc(static), 1),
-                "focused_p3+static_dwc": (with_dwc(static), 3), "relu+squeeze_dwc": (with_dwc(squeeze), 1)}
+                "focused_p3+static_dwc": (with_dwc(static), 3), "relu+squeeze_dwc": (with_dwc(squeeze), 1),
+                "relu+token_dwc": (with_dwc([{"token": d["squeeze"], "ksize": 3} for d in squeeze]), 1)}
     x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda()
     y = torch.empty_like(x)
     stream = torch.cuda.current_stream()

@@ -129,18 +129,36 @@ jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void
  *           g = mean_n V[b, :, n];  u = silu(w1 g + b1);  kernel[b] = reshape(w2 u + b2, [C, k, k])
  *       w1 fp32 [hidden, C], b1 fp32 [hidden], w2 fp32 [C*k*k, hidden], b2 fp32 [C*k*k], device.
  *       The token sum of V is taken in the same pass that reduces K and V into the state.
+ *   JV_DWC_TOKEN_DYNAMIC    the variant the paper tried first and rejected for its cost (Sec. 3.2.1;
+ *       Tab. 1, "Token-wise Dynamic DWC"): the same generator applied to every grid token's own
+ *       V row, so that each token carries a filter bank of its own, which weights that token's
+ *       ksize x ksize neighbourhood:
+ *           u_n = silu(w1 V[b, :, n] + b1);  kernel[b, n] = reshape(w2 u_n + b2, [C, k, k]);
+ *           DWC(V)[b, c, n] = sum_taps kernel[b, n][c, tap] * V[b, c, n + tap]
+ *       Weights as for the squeeze-dynamic mode.  bf16 tensors only, hidden a multiple of 64
+ *       (JV_ERR_UNSUPPORTED otherwise).  The generator runs as two matrix products in bf16 with
+ *       fp32 accumulation (weights, hidden layer and filters are rounded to bf16) over V as the
+ *       matrix [batch * tokens, C] -- read in place when V's strides already describe one (head
+ *       stride 64, batch stride = tokens * token stride), from a packed copy otherwise; the
+ *       workspace holds the filters of all tokens (batch * tokens * C * k * k bf16), the cost
+ *       the paper rejects the variant for.  Prefix tokens get no convolution term.
  * ksize is 3 or 5; C <= 8192 and hidden <= 1024 (JV_ERR_UNSUPPORTED otherwise).  Pointers the
  * mode does not use are ignored.  workspace as for jv_linear_attn_fwd, sized by
  * jv_linear_block_workspace_bytes (0 for an invalid descriptor or parameter block).
  * ------------------------------------------------------------------------- */
-typedef enum { JV_DWC_NONE = 0, JV_DWC_STATIC = 1, JV_DWC_SQUEEZE_DYNAMIC = 2 } jv_dwc_mode;
+typedef enum {
+    JV_DWC_NONE = 0,
+    JV_DWC_STATIC = 1,
+    JV_DWC_SQUEEZE_DYNAMIC = 2,
+    JV_DWC_TOKEN_DYNAMIC = 3
+} jv_dwc_mode;
 
 typedef struct {
     jv_dwc_mode mode;
     int32_t ksize;              /* 3 or 5 */
-    int32_t hidden;             /* hidden width of the generator (squeeze-dynamic only) */
+    int32_t hidden;             /* hidden width of the generator (dynamic modes) */
     const float *static_kernel; /* device, [C, ksize, ksize] (static only) */
-    const float *w1, *b1, *w2, *b2; /* device (squeeze-dynamic only) */
+    const float *w1, *b1, *w2, *b2; /* device (dynamic modes) */
 } jv_dwc_params;
 
 size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_params *dwc);
@@ -221,10 +239,11 @@ jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *
  *   JV_EPI_NONE      y = acc + bias
  *   JV_EPI_GELU      y = gelu(acc + bias), the exact (erf) GELU, erf to 3e-5 absolute
  *   JV_EPI_RESIDUAL  y = acc + bias + residual, residual fp32 [M, N] (may be y itself)
+ *   JV_EPI_SILU      y = silu(acc + bias), silu(x) = x / (1 + exp(-x))
  * y is [M, N] of y_dtype (JV_BF16 or JV_F32).  K % 64 == 0 and N % 8 == 0 are required
  * (JV_ERR_UNSUPPORTED otherwise); M is arbitrary.  All pointers device, 16-byte aligned.
  * ------------------------------------------------------------------------- */
-typedef enum { JV_EPI_NONE = 0, JV_EPI_GELU = 1, JV_EPI_RESIDUAL = 2 } jv_epilogue;
+typedef enum { JV_EPI_NONE = 0, JV_EPI_GELU = 1, JV_EPI_RESIDUAL = 2, JV_EPI_SILU = 3 } jv_epilogue;
 
 jv_status jv_layernorm_fwd(const void *x, const float *gamma, const float *beta, void *y,
                            int64_t rows, int32_t cols, float eps, jv_dtype x_dtype,

@@ -263,6 +263,45 @@ def squeeze_kernel(v, w1, b1, w2, b2, k):
     return kappa
 
 
+def tokenwise_kernels(v, w1, b1, w2, b2, k):
+    """Filters of every token, [B, N, C, k, k]: the Linear-SiLU-Linear generator of the dynamic
+    convolution applied to each token's own V row (channel = head * d + c) instead of the token
+    average -- the per-token kernel generation the paper tried first (Sec. 3.2.1; Tab. 1,
+    "Token-wise Dynamic DWC").  float64."""
+    v = np.asarray(v, dtype=np.float64)
+    B, h, N, d = v.shape
+    w1 = np.asarray(w1, dtype=np.float64); b1 = np.asarray(b1, dtype=np.float64)
+    w2 = np.asarray(w2, dtype=np.float64); b2 = np.asarray(b2, dtype=np.float64)
+    C = h * d
+    if w1.shape[1] != C or w2.shape != (C * k * k, w1.shape[0]):
+        raise ValueError("shape mismatch")
+    rows = v.transpose(0, 2, 1, 3).reshape(B, N, C)
+    pre = rows @ w1.T + b1
+    u = pre / (1.0 + np.exp(-pre))
+    return (u @ w2.T + b2).reshape(B, N, C, k, k)
+
+
+def dwc_tokenwise(v, kappa, H, W):
+    """out[b, h, n, c] = sum_{di, dj} kappa[b, n, h*d + c, di, dj] * V[b, h, (r + di - k/2,
+    s + dj - k/2), c] for grid token n = (r, s), zero outside the grid: a depth-wise
+    cross-correlation in which the output token brings its own filters.  V [B, h, H*W, d],
+    kappa [B, H*W, C, k, k]; float64."""
+    v = np.asarray(v, dtype=np.float64)
+    B, h, N, d = v.shape
+    k = kappa.shape[-1]
+    if N != H * W or kappa.shape != (B, N, h * d, k, k):
+        raise ValueError("shape mismatch")
+    pad = k // 2
+    grid = np.zeros((B, h, H + 2 * pad, W + 2 * pad, d))
+    grid[:, :, pad:pad + H, pad:pad + W] = v.reshape(B, h, H, W, d)
+    kap = kappa.reshape(B, H, W, h, d, k, k).transpose(0, 3, 1, 2, 4, 5, 6)  # [B, h, H, W, d, k, k]
+    out = np.zeros((B, h, H, W, d))
+    for di in range(k):
+        for dj in range(k):
+            out += kap[..., di, dj] * grid[:, :, di:di + H, dj:dj + W]
+    return out.reshape(B, h, N, d)
+
+
 def focused_map(x, p):
     """Focused feature map, Eq. 3: phi_p(x) = |r| / |r^p| * r^p with r = max(x, 0), the power
     element-wise and the Euclidean norms over the last axis (the channels of one token's head).
@@ -285,9 +324,11 @@ def focused_linear_attn(q, k, v, p, eps=1e-6):
     return num / (a.sum(axis=-1, keepdims=True) + eps)
 
 
-def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksize=3, focus_p=1):
+def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksize=3, focus_p=1,
+                 token=None):
     """The paper's linear-attention block output, Eq. 4: normalised ReLU linear attention plus
-    DWC(V).  static_kernel: [C, k, k]; squeeze: (w1, b1, w2, b2) for the dynamic kernel;
+    DWC(V).  static_kernel: [C, k, k]; squeeze: (w1, b1, w2, b2) for the dynamic kernel; token:
+    the same four for the per-token variant (generator and convolution on the grid tokens);
     focus_p > 1: the focused map of Eq. 3 instead of ReLU (the variant Table 1 lists).
     Tokens beyond H * W are prefix tokens in front of the grid (the library's stated rule): they
     are ordinary tokens of the linear attention and of the token average that generates the
@@ -301,6 +342,8 @@ def linear_block(q, k, v, H, W, eps=1e-6, static_kernel=None, squeeze=None, ksiz
         o[:, :, P:] += dwc(vg, np.asarray(static_kernel, dtype=np.float64)[None], H, W)
     if squeeze is not None:
         o[:, :, P:] += dwc(vg, squeeze_kernel(v, *squeeze, ksize), H, W)
+    if token is not None:
+        o[:, :, P:] += dwc_tokenwise(vg, tokenwise_kernels(vg, *token, ksize), H, W)
     return o
 
 
@@ -325,7 +368,7 @@ def encoder_block(x, wts, mixer, H, W, heads, window=(16, 16), ln_eps=1e-6, la_e
         if dwc_cfg or la_focus_p > 1 or n_prefix > 0:
             o = linear_block(q, k, v, H, W, la_eps, static_kernel=dwc_cfg.get("static_kernel"),
                              squeeze=dwc_cfg.get("squeeze"), ksize=dwc_cfg.get("ksize", 3),
-                             focus_p=la_focus_p)
+                             focus_p=la_focus_p, token=dwc_cfg.get("token"))
         else:
             o = linear_attn_quadratic(q, k, v, la_eps)
     elif mixer == MIX_WINDOW:

@@ -25,8 +25,8 @@ EXPORTS = [
     "jv_layernorm_fwd", "jv_gemm_bias_act",
     "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_forward_taps", "jv_encoder_destroy",
 ]
-JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL = 0, 1, 2
-JV_DWC_NONE, JV_DWC_STATIC, JV_DWC_SQUEEZE_DYNAMIC = 0, 1, 2
+JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL, JV_EPI_SILU = 0, 1, 2, 3
+JV_DWC_NONE, JV_DWC_STATIC, JV_DWC_SQUEEZE_DYNAMIC, JV_DWC_TOKEN_DYNAMIC = 0, 1, 2, 3
 
 
 class JvStrides(ctypes.Structure):
@@ -185,12 +185,13 @@ def jv_linear_attn_fwd(q, k, v, o, grid, eps=1e-6, workspace=None, stream=None):
     return workspace
 
 
-def make_dwc_params(static_kernel=None, squeeze=None, ksize=3):
+def make_dwc_params(static_kernel=None, squeeze=None, ksize=3, token=None):
     """jv_dwc_params from device fp32 tensors: static_kernel [C, k, k], or squeeze =
-    (w1 [hidden, C], b1 [hidden], w2 [C*k*k, hidden], b2 [C*k*k]); neither = no convolution."""
-    if static_kernel is not None and squeeze is not None:
-        raise ValueError("give a static kernel or generator weights, not both")
-    for t in ([static_kernel] if static_kernel is not None else []) + list(squeeze or []):
+    (w1 [hidden, C], b1 [hidden], w2 [C*k*k, hidden], b2 [C*k*k]) for per-image filters, or
+    token = the same four tensors for per-token filters; none of them = no convolution."""
+    if (static_kernel is not None) + (squeeze is not None) + (token is not None) > 1:
+        raise ValueError("give a static kernel or one set of generator weights, not several")
+    for t in ([static_kernel] if static_kernel is not None else []) + list(squeeze or []) + list(token or []):
         if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
             raise ValueError("convolution parameters must be contiguous fp32 device tensors")
     if static_kernel is not None:
@@ -198,6 +199,10 @@ def make_dwc_params(static_kernel=None, squeeze=None, ksize=3):
     if squeeze is not None:
         w1, b1, w2, b2 = squeeze
         return JvDwcParams(JV_DWC_SQUEEZE_DYNAMIC, ksize, w1.shape[0], None, w1.data_ptr(),
+                           b1.data_ptr(), w2.data_ptr(), b2.data_ptr())
+    if token is not None:
+        w1, b1, w2, b2 = token
+        return JvDwcParams(JV_DWC_TOKEN_DYNAMIC, ksize, w1.shape[0], None, w1.data_ptr(),
                            b1.data_ptr(), w2.data_ptr(), b2.data_ptr())
     return JvDwcParams(JV_DWC_NONE, ksize, 0, None, None, None, None, None)
 
@@ -207,11 +212,11 @@ def jv_linear_block_workspace_bytes(desc, dwc):
 
 
 def jv_linear_block_fwd(q, k, v, o, grid, eps=1e-6, static_kernel=None, squeeze=None, ksize=3,
-                        workspace=None, stream=None):
+                        workspace=None, stream=None, token=None):
     """o <- linear attention + depth-wise convolution of v (the paper's linear-attention block);
     returns the workspace tensor used."""
     desc = make_desc(q, k, v, o, grid)
-    dwc = make_dwc_params(static_kernel, squeeze, ksize)
+    dwc = make_dwc_params(static_kernel, squeeze, ksize, token)
     if workspace is None:
         need = jv_linear_block_workspace_bytes(desc, dwc)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
@@ -222,11 +227,11 @@ def jv_linear_block_fwd(q, k, v, o, grid, eps=1e-6, static_kernel=None, squeeze=
 
 
 def jv_linear_block_focused_fwd(q, k, v, o, grid, focus_p, eps=1e-6, static_kernel=None, squeeze=None,
-                                ksize=3, workspace=None, stream=None):
+                                ksize=3, workspace=None, stream=None, token=None):
     """The linear-attention block with the focused feature map of power focus_p in place of
     ReLU; returns the workspace tensor used."""
     desc = make_desc(q, k, v, o, grid)
-    dwc = make_dwc_params(static_kernel, squeeze, ksize)
+    dwc = make_dwc_params(static_kernel, squeeze, ksize, token)
     if workspace is None:
         need = jv_linear_block_workspace_bytes(desc, dwc)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
@@ -325,10 +330,10 @@ class Encoder:
             for name in BLOCK_FIELDS:
                 setattr(table[i], name, b[name].data_ptr())
             # optional convolution branch of a linear-attention block: b["dwc"] is a dict with
-            # "static_kernel" or "squeeze" (tuple of device tensors) and "ksize"
+            # "static_kernel", "squeeze" or "token" (tuple of device tensors) and "ksize"
             if b.get("dwc") is not None:
                 d = b["dwc"]
-                params = make_dwc_params(d.get("static_kernel"), d.get("squeeze"), d.get("ksize", 3))
+                params = make_dwc_params(d.get("static_kernel"), d.get("squeeze"), d.get("ksize", 3), d.get("token"))
                 self._dwc.append(params)
                 table[i].dwc = ctypes.pointer(params)
         self._handle = ctypes.c_void_p()

@@ -3,6 +3,9 @@
 //   squeeze_hidden / squeeze_kappa   the generator of the dynamic filters ("Squeeze Dynamic
 //                                    Convolution": token mean of V -> Linear -> SiLU -> Linear)
 //   v_sum_f32, dwc_add_f32           plain fp32 kernels for fp32 tensors
+//   cast_to_bf16, pack_v_rows,       the token-wise dynamic variant the paper rejects for its cost
+//   dwc_token_add                    (Tab. 1): the generator as two matrix products over all
+//                                    tokens, then every token's own filters on its neighbourhood
 #include "jv_linear.h"
 #include "jv_mfma.h"
 
@@ -10,7 +13,7 @@ namespace jv {
 
 static size_t align64f(size_t floats) { return (floats + 63) & ~(size_t)63; }  // 256 bytes
 
-jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int heads, DwcPlan *out) {
+jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int heads, int N, DwcPlan *out) {
     DwcPlan p;
     const size_t base = align64f(linear_workspace_floats(lp, B, heads));
     p.total_floats = base;
@@ -18,7 +21,7 @@ jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int he
         *out = p;
         return JV_OK;
     }
-    if (dwc->mode != JV_DWC_STATIC && dwc->mode != JV_DWC_SQUEEZE_DYNAMIC)
+    if (dwc->mode != JV_DWC_STATIC && dwc->mode != JV_DWC_SQUEEZE_DYNAMIC && dwc->mode != JV_DWC_TOKEN_DYNAMIC)
         return fail(JV_ERR_INVALID_ARG, "unknown convolution mode");
     if (dwc->ksize != 3 && dwc->ksize != 5) return fail(JV_ERR_UNSUPPORTED, "ksize must be 3 or 5");
     const long long C = (long long)heads * kHeadDim;
@@ -39,6 +42,20 @@ jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int he
                 return fail(JV_ERR_INVALID_ARG, "generator weight is null or not 16-byte aligned");
         p.hidden = dwc->hidden;
         p.w1 = dwc->w1; p.b1 = dwc->b1; p.w2 = dwc->w2; p.b2 = dwc->b2;
+        if (dwc->mode == JV_DWC_TOKEN_DYNAMIC) {
+            if (dwc->hidden % 64) return fail(JV_ERR_UNSUPPORTED, "token-wise filters: hidden must be a multiple of 64");
+            if (N <= 0) return fail(JV_ERR_INVALID_ARG, "token-wise filters: token count must be positive");
+            const size_t M = (size_t)B * N, kk = (size_t)dwc->ksize * dwc->ksize;
+            p.w1b_off = base;  // two bf16 per float of offset
+            p.w2b_off = p.w1b_off + align64f((size_t)dwc->hidden * C / 2);
+            p.vt_off = p.w2b_off + align64f((size_t)C * kk * dwc->hidden / 2);
+            p.u_off = p.vt_off + align64f(M * C / 2);
+            p.tok_kappa_off = p.u_off + align64f(M * dwc->hidden / 2);
+            p.la_off = p.tok_kappa_off + align64f(M * C * kk / 2);
+            p.total_floats = p.la_off + align64f(M * C);
+            *out = p;
+            return JV_OK;
+        }
         p.vsum_off = base;
         p.hidden_off = p.vsum_off + align64f((size_t)lp.n_split * B * heads * kHeadDim);
         p.kappa_off = p.hidden_off + align64f((size_t)B * dwc->hidden);
@@ -187,6 +204,138 @@ dwc_add_f32(TensorArg vt, TensorArg ot, DwcArg cv, int ksize, int heads, int N) 
             }
         *(f32x4 *)(op + (long long)n * ot.sn + c4) = acc;
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Token-wise dynamic filters.
+// ---------------------------------------------------------------------------------------
+
+// dst[i] = bf16(src[i]), eight elements per thread; n8 = element count / 8.
+__global__ void __launch_bounds__(256)
+cast_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, long long n8) {
+    const long long i = blockIdx.x * 256ll + threadIdx.x;
+    if (i >= n8) return;
+    const f32x4 a = *(const f32x4 *)(src + 8 * i), b = *(const f32x4 *)(src + 8 * i + 4);
+    u32x4 r = {pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
+    *(u32x4 *)(dst + 8 * i) = r;
+}
+
+// V in any strided layout -> rows [B*N][C] (channel = head*64 + c), 16 bytes per thread.
+__global__ void __launch_bounds__(256)
+pack_v_rows(TensorArg vt, unsigned short *__restrict__ rows, int heads, int N, long long total) {
+    const long long idx = blockIdx.x * 256ll + threadIdx.x;
+    if (idx >= total) return;
+    const int groups = heads * 8, cg = (int)(idx % groups), h = cg >> 3, c8 = (cg & 7) * 8;
+    const long long m = idx / groups;
+    const int b = (int)(m / N), n = (int)(m % N);
+    const unsigned short *src = (const unsigned short *)vt.ptr + b * vt.sb + h * vt.sh + (long long)n * vt.sn + c8;
+    *(u32x4 *)(rows + idx * 8) = *(const u32x4 *)src;
+}
+
+__device__ inline float bf16_elem(const u32x4 &x, int e) {  // e = 0..7, compile-time after unrolling
+    return (e & 1) ? bf16_hi(x[e >> 1]) : bf16_lo(x[e >> 1]);
+}
+
+// o[b, n, c] = la[b, n, c] + sum_taps kappa[b*N + n][c*k*k + tap] * v[b, n + tap, c] on the
+// H x W grid behind P prefix tokens (prefix rows: o = la).  One thread per token and 8 channels;
+// total = B*N*C/8 threads.  la and o may be the same fp32 tensor (each element is read and
+// written by one thread).
+template <int KS, bool O_BF16>
+__global__ void __launch_bounds__(256)
+dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const unsigned short *__restrict__ kappa,
+              int heads, int N, int P, int H, int W, long long total) {
+    constexpr int KK = KS * KS, PAD = KS / 2;
+    const long long idx = blockIdx.x * 256ll + threadIdx.x;
+    if (idx >= total) return;
+    const int groups = heads * 8, cg = (int)(idx % groups), h = cg >> 3, c8 = (cg & 7) * 8;
+    const long long m = idx / groups;
+    const int b = (int)(m / N), n = (int)(m % N);
+    const float *lp = (const float *)la.ptr + b * la.sb + h * la.sh + (long long)n * la.sn + c8;
+    const f32x4 l0 = *(const f32x4 *)lp, l1 = *(const f32x4 *)(lp + 4);
+    float acc[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
+    if (n >= P) {
+        const int g = n - P, r = g / W, col = g - r * W;
+        const u32x4 *kp = (const u32x4 *)(kappa + idx * (8 * KK));
+        u32x4 kv[KK];  // 8 channels x KK taps, element c*KK + tap
+#pragma unroll
+        for (int j = 0; j < KK; ++j) kv[j] = kp[j];
+        const unsigned short *vp = (const unsigned short *)vt.ptr + b * vt.sb + h * vt.sh + c8;
+#pragma unroll
+        for (int di = -PAD; di <= PAD; ++di)
+#pragma unroll
+            for (int dj = -PAD; dj <= PAD; ++dj) {
+                const int tap = (di + PAD) * KS + dj + PAD;
+                const int r2 = r + di, c2 = col + dj;
+                const bool inside = r2 >= 0 && r2 < H && c2 >= 0 && c2 < W;
+                const int nb = inside ? P + r2 * W + c2 : n;
+                u32x4 vv = *(const u32x4 *)(vp + (long long)nb * vt.sn);
+                if (!inside) vv = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const int e = c * KK + tap;
+                    acc[c] = fmaf(bf16_elem(kv[e >> 3], e & 7), bf16_elem(vv, c), acc[c]);
+                }
+            }
+    }
+    if (O_BF16) {
+        unsigned short *op = (unsigned short *)ot.ptr + b * ot.sb + h * ot.sh + (long long)n * ot.sn + c8;
+        u32x4 out = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                     pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7])};
+        *(u32x4 *)op = out;
+    } else {
+        float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)n * ot.sn + c8;
+        *(f32x4 *)op = f32x4{acc[0], acc[1], acc[2], acc[3]};
+        *(f32x4 *)(op + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+    }
+}
+
+template <int KS, bool O_BF16>
+static void launch_token_add(hipStream_t stream, const Problem &pr, const TensorArg &la,
+                             const unsigned short *kappa, long long total) {
+    hipLaunchKernelGGL((dwc_token_add<KS, O_BF16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                       stream, pr.v, la, pr.o, kappa, pr.heads, pr.N, pr.P, pr.H, pr.W, total);
+}
+
+jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPlan &dwc, float *ws,
+                            hipStream_t stream) {
+    const int C = pr.heads * kHeadDim, kk = dwc.ksize * dwc.ksize;
+    const long long M = (long long)pr.B * pr.N;
+    if (M * (C / 8) / 256 >= (1ll << 31) - 1) return fail(JV_ERR_UNSUPPORTED, "token-wise filters: too many tokens");
+    unsigned short *w1b = (unsigned short *)(ws + dwc.w1b_off), *w2b = (unsigned short *)(ws + dwc.w2b_off);
+    unsigned short *rows = (unsigned short *)(ws + dwc.vt_off), *u = (unsigned short *)(ws + dwc.u_off);
+    unsigned short *kappa = (unsigned short *)(ws + dwc.tok_kappa_off);
+    jv_status st;
+    long long n8 = (long long)dwc.hidden * C / 8;
+    hipLaunchKernelGGL(cast_to_bf16, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, dwc.w1, w1b, n8);
+    if ((st = launch_status("cast_to_bf16")) != JV_OK) return st;
+    n8 = (long long)C * kk * dwc.hidden / 8;
+    hipLaunchKernelGGL(cast_to_bf16, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, dwc.w2, w2b, n8);
+    if ((st = launch_status("cast_to_bf16")) != JV_OK) return st;
+    // V as the matrix [B*N][C]: in place when its layout already is one, else a packed copy.
+    const void *a = pr.v.ptr;
+    long long lda = pr.v.sn;
+    const bool in_place = pr.v.sh == kHeadDim && pr.v.sn >= C && pr.v.sn % 8 == 0 &&
+                          pr.v.sb == (long long)pr.N * pr.v.sn && M * pr.v.sn < (1ll << 30);
+    const long long total = M * (C / 8);
+    if (!in_place) {
+        hipLaunchKernelGGL(pack_v_rows, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, pr.v, rows,
+                           pr.heads, pr.N, total);
+        if ((st = launch_status("pack_v_rows")) != JV_OK) return st;
+        a = rows;
+        lda = C;
+    }
+    if ((st = gemm_forward(a, w1b, dwc.b1, nullptr, u, M, dwc.hidden, C, JV_EPI_SILU, true, stream, lda)) != JV_OK)
+        return st;
+    if ((st = gemm_forward(u, w2b, dwc.b2, nullptr, kappa, M, C * kk, dwc.hidden, JV_EPI_NONE, true, stream)) != JV_OK)
+        return st;
+    if (dwc.ksize == 3) {
+        if (pr.o_bf16) launch_token_add<3, true>(stream, pr, la, kappa, total);
+        else launch_token_add<3, false>(stream, pr, la, kappa, total);
+    } else {
+        if (pr.o_bf16) launch_token_add<5, true>(stream, pr, la, kappa, total);
+        else launch_token_add<5, false>(stream, pr, la, kappa, total);
+    }
+    return launch_status("dwc_token_add");
 }
 
 jv_status vsum_f32_launch(const Problem &pr, const LinearPlan &plan, float *vsum, hipStream_t stream) {

@@ -169,7 +169,7 @@ template <int EPI, bool OUT_BF16>
 __global__ void __launch_bounds__(512, 1)
 gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                  const float *__restrict__ bias, const float *residual, void *Y, int M, int N,
-                 int K, int tiles_n, int n_tiles) {
+                 int K, int lda, int tiles_n, int n_tiles) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
     const int per_xcd = (n_tiles + 7) / 8;
@@ -189,7 +189,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         const int r = wave * 32 + j * 8 + lrow;
         const int gchunk = (lane & 7) ^ ((r >> 1) & 7);
         const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);  // edge tiles re-read the last row
-        a_off[j] = 2u * ((unsigned)ar * (unsigned)K + gchunk * 8);
+        a_off[j] = 2u * ((unsigned)ar * (unsigned)lda + gchunk * 8);  // rows of a are lda elements apart
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
     const int n_b = K / kBK, n_parts = 2 * n_b;
@@ -340,6 +340,10 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
                     for (int e = 0; e < 4; ++e) val[e] = gelu_erf(val[e]);
                 }
+                if (EPI == JV_EPI_SILU) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) val[e] = val[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-val[e]));
+                }
                 if (EPI == JV_EPI_RESIDUAL) val += res_reg[mt & 1][nt][q4];
                 if (row_ok && col < N) {
                     const size_t at_out = (size_t)row * N + col;
@@ -356,7 +360,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 
 template <int EPI, bool OUT_BF16>
 static jv_status launch_gemm(const void *a, const void *w, const float *bias, const float *residual,
-                             void *y, long long M, int N, int K, hipStream_t stream) {
+                             void *y, long long M, int N, int K, int lda, hipStream_t stream) {
     static LdsLimit lds_limit;
     jv_status st = ensure_lds_limit(lds_limit, (const void *)gemm_bf16_kernel<EPI, OUT_BF16>, kGemmLds);
     if (st != JV_OK) return st;
@@ -364,15 +368,19 @@ static jv_status launch_gemm(const void *a, const void *w, const float *bias, co
     const int n_tiles = tiles_m * tiles_n;
     dim3 grid(8 * ((n_tiles + 7) / 8));
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16>), grid, dim3(512), kGemmLds, stream,
-                       (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K,
+                       (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K, lda,
                        tiles_n, n_tiles);
     return launch_status("gemm_bf16_kernel");
 }
 
-static jv_status gemm_forward(const void *a, const void *w, const float *bias,
-                              const float *residual, void *y, long long M, int N, int K, int epi,
-                              bool out_bf16, hipStream_t stream) {
+jv_status gemm_forward(const void *a, const void *w, const float *bias, const float *residual,
+                       void *y, long long M, int N, int K, int epi, bool out_bf16,
+                       hipStream_t stream, long long lda_arg) {
     if (M <= 0 || N <= 0 || K <= 0) return fail(JV_ERR_INVALID_ARG, "M, N, K must be positive");
+    const long long lda_ll = lda_arg > 0 ? lda_arg : K;
+    if (lda_ll < K || lda_ll % 8) return fail(JV_ERR_INVALID_ARG, "row stride of a below K or not a multiple of 8");
+    if (M * lda_ll >= (1ll << 30)) return fail(JV_ERR_UNSUPPORTED, "operand above 2^30 elements");
+    const int lda = (int)lda_ll;
     if (!a || !w || !y) return fail(JV_ERR_INVALID_ARG, "a, w, y must be non-null");
     if (((uintptr_t)a | (uintptr_t)w | (uintptr_t)y | (uintptr_t)bias | (uintptr_t)residual) & 15)
         return fail(JV_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
@@ -384,14 +392,17 @@ static jv_status gemm_forward(const void *a, const void *w, const float *bias,
         return fail(JV_ERR_INVALID_ARG, "residual epilogue needs a residual tensor");
     switch (epi) {
         case JV_EPI_NONE:
-            return out_bf16 ? launch_gemm<JV_EPI_NONE, true>(a, w, bias, residual, y, M, N, K, stream)
-                            : launch_gemm<JV_EPI_NONE, false>(a, w, bias, residual, y, M, N, K, stream);
+            return out_bf16 ? launch_gemm<JV_EPI_NONE, true>(a, w, bias, residual, y, M, N, K, lda, stream)
+                            : launch_gemm<JV_EPI_NONE, false>(a, w, bias, residual, y, M, N, K, lda, stream);
         case JV_EPI_GELU:
-            return out_bf16 ? launch_gemm<JV_EPI_GELU, true>(a, w, bias, residual, y, M, N, K, stream)
-                            : launch_gemm<JV_EPI_GELU, false>(a, w, bias, residual, y, M, N, K, stream);
+            return out_bf16 ? launch_gemm<JV_EPI_GELU, true>(a, w, bias, residual, y, M, N, K, lda, stream)
+                            : launch_gemm<JV_EPI_GELU, false>(a, w, bias, residual, y, M, N, K, lda, stream);
         case JV_EPI_RESIDUAL:
-            return out_bf16 ? launch_gemm<JV_EPI_RESIDUAL, true>(a, w, bias, residual, y, M, N, K, stream)
-                            : launch_gemm<JV_EPI_RESIDUAL, false>(a, w, bias, residual, y, M, N, K, stream);
+            return out_bf16 ? launch_gemm<JV_EPI_RESIDUAL, true>(a, w, bias, residual, y, M, N, K, lda, stream)
+                            : launch_gemm<JV_EPI_RESIDUAL, false>(a, w, bias, residual, y, M, N, K, lda, stream);
+        case JV_EPI_SILU:
+            return out_bf16 ? launch_gemm<JV_EPI_SILU, true>(a, w, bias, residual, y, M, N, K, lda, stream)
+                            : launch_gemm<JV_EPI_SILU, false>(a, w, bias, residual, y, M, N, K, lda, stream);
     }
     return fail(JV_ERR_INVALID_ARG, "unknown epilogue");
 }
@@ -421,7 +432,7 @@ static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N) 
     size_t need = linear_workspace_bytes(batch, enc->cfg.heads, N);
     for (int l = 0; l < enc->cfg.n_blocks; ++l) {
         DwcPlan plan;
-        if (plan_dwc(&enc->dwc[l], lp, batch, enc->cfg.heads, &plan) == JV_OK) {
+        if (plan_dwc(&enc->dwc[l], lp, batch, enc->cfg.heads, N, &plan) == JV_OK) {
             const size_t bytes = plan.total_floats * sizeof(float);
             need = bytes > need ? bytes : need;
         }
@@ -484,7 +495,7 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
                 return jv::fail(JV_ERR_INVALID_ARG, "block %d: null or misaligned weight pointer", l);
         if (c.pattern[l] == 0 && b.dwc) {  // validate the convolution parameters now
             jv::DwcPlan plan;
-            jv_status st = jv::plan_dwc(b.dwc, jv::plan_linear(1, c.heads, 256), 1, c.heads, &plan);
+            jv_status st = jv::plan_dwc(b.dwc, jv::plan_linear(1, c.heads, 256), 1, c.heads, 256, &plan);
             if (st != JV_OK) return st;
         }
     }

@@ -26,10 +26,18 @@ struct DwcPlan {
     size_t vsum_off = 0;    // [n_split][B*heads][64] partial token sums of V (dynamic mode)
     size_t hidden_off = 0;  // [B][hidden] generator hidden layer (dynamic mode)
     size_t kappa_off = 0;   // [B][C][k*k] generated filters (dynamic mode)
+    // Token-wise dynamic mode (regions of bf16 elements unless noted, offsets still in floats):
+    size_t w1b_off = 0;     // [hidden][C] generator weights rounded to bf16
+    size_t w2b_off = 0;     // [C*k*k][hidden]
+    size_t vt_off = 0;      // [B*N][C] V as token rows, when its own layout is not such a matrix
+    size_t u_off = 0;       // [B*N][hidden] hidden layer of every token
+    size_t tok_kappa_off = 0;  // [B*N][C*k*k] filters of every token
+    size_t la_off = 0;      // fp32 [B*N][C] linear-attention term before the convolution is added
     size_t total_floats = 0;
 };
-// Fills the offsets for a validated parameter block; dwc may be null (mode none).
-jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int heads, DwcPlan *out);
+// Fills the offsets for a validated parameter block; dwc may be null (mode none).  N = tokens
+// per image (prefix included); only the token-wise mode sizes anything by it.
+jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int heads, int N, DwcPlan *out);
 
 // What the apply kernels need of the convolution: filters [.., C, k*k] with a batch stride
 // (0 for a static bank) on the H x W grid that follows P prefix tokens.
@@ -51,6 +59,12 @@ jv_status squeeze_generate(const DwcPlan &dwc, float *ws, int n_part, int B, int
 // fp32 tensors: partial token sums of V, and o += DWC(v) as a pass of its own.
 jv_status vsum_f32_launch(const Problem &pr, const LinearPlan &plan, float *vsum, hipStream_t stream);
 jv_status dwc_add_f32_launch(const Problem &pr, const DwcArg &cv, int ksize, hipStream_t stream);
+
+// Token-wise dynamic filters (bf16 tensors): generator as two matrix products over all tokens,
+// then o = la + DWC(v) with each token's own filters; la is the fp32 linear-attention term
+// (pr.o itself when O is fp32).
+jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPlan &dwc, float *ws,
+                            hipStream_t stream);
 
 jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params *dwc,
                                void *workspace, size_t workspace_bytes, hipStream_t stream,

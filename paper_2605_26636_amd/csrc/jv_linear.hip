@@ -178,12 +178,27 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
     if (focus_p < 1 || focus_p > 16) return fail(JV_ERR_INVALID_ARG, "focusing power must be 1 .. 16");
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;
-    jv_status st = plan_dwc(dwc, plan, pr.B, pr.heads, &cv);
+    jv_status st = plan_dwc(dwc, plan, pr.B, pr.heads, pr.N, &cv);
     if (st != JV_OK) return st;
     if (workspace_bytes < cv.total_floats * sizeof(float))
         return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes,
                     cv.total_floats * sizeof(float));
     float *ws = (float *)workspace;
+    if (cv.mode == JV_DWC_TOKEN_DYNAMIC) {
+        // Plain linear attention into an fp32 tensor (O itself when it is fp32), then one pass
+        // that adds every token's own convolution term and rounds once.
+        if (!pr.bf16) return fail(JV_ERR_UNSUPPORTED, "token-wise filters are built for bf16 tensors only");
+        Problem la = pr;
+        if (pr.o_bf16) {
+            const long long C = (long long)pr.heads * kHeadDim;
+            la.o = {ws + cv.la_off, (long long)pr.N * C, kHeadDim, C};
+            la.o_bf16 = false;
+        }
+        DwcPlan none = cv;
+        none.mode = JV_DWC_NONE;
+        if ((st = linear_bf16(la, plan, eps, ws, none, focus_p, stream)) != JV_OK) return st;
+        return token_dwc_forward(pr, la.o, cv, ws, stream);
+    }
     if (pr.bf16) return linear_bf16(pr, plan, eps, ws, cv, focus_p, stream);
     const int BH = pr.B * pr.heads;
     hipLaunchKernelGGL(la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v, ws,
@@ -227,8 +242,9 @@ size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_pa
     jv::clear_error();
     if (jv::check_desc(desc) != JV_OK) return 0;
     jv::DwcPlan cv;
-    const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, desc->n_prefix + desc->grid_h * desc->grid_w);
-    if (jv::plan_dwc(dwc, plan, desc->batch, desc->heads, &cv) != JV_OK) return 0;
+    const int N = desc->n_prefix + desc->grid_h * desc->grid_w;
+    const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, N);
+    if (jv::plan_dwc(dwc, plan, desc->batch, desc->heads, N, &cv) != JV_OK) return 0;
     return cv.total_floats * sizeof(float);
 }
 

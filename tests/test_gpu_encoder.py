@@ -60,6 +60,8 @@ def test_gemm_epilogues(M, N, K):
     inplace = dr.clone()
     binding.jv_gemm_bias_act(da, dw, db, inplace, inplace, binding.JV_EPI_RESIDUAL)
     assert torch.equal(inplace, y32)
+    binding.jv_gemm_bias_act(da, dw, db, None, y32, binding.JV_EPI_SILU)
+    check(err_bf16(to_host(y32), plain / (1.0 + np.exp(-plain))), 1e-4)
 
 
 def test_gemm_rejects_unsupported_shapes():
@@ -80,8 +82,9 @@ def _device_blocks(blocks):
                 d[k] = {"ksize": v.get("ksize", 3)}
                 if v.get("static_kernel") is not None:
                     d[k]["static_kernel"] = torch.from_numpy(v["static_kernel"]).cuda()
-                if v.get("squeeze") is not None:
-                    d[k]["squeeze"] = tuple(torch.from_numpy(a).cuda() for a in v["squeeze"])
+                for kind in ("squeeze", "token"):
+                    if v.get(kind) is not None:
+                        d[k][kind] = tuple(torch.from_numpy(a).cuda() for a in v[kind])
                 continue
             t = torch.from_numpy(v).cuda()
             d[k] = t.to(torch.bfloat16) if k.startswith("w_") else t
@@ -200,6 +203,35 @@ def test_encoder_linear_blocks_with_convolution_branch():
     plain = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 5))
     assert err_bf16(to_host(y), plain) > 10 * BF16_TOL
     enc.close()
+
+
+def test_encoder_token_wise_dynamic_filters():
+    """A linear-attention block with per-token dynamic filters (the variant Tab. 1 lists as
+    "Token-wise Dynamic DWC") inside the encoder, where V is read in place from the fused QKV
+    rows; with and without prefix tokens."""
+    H, W, heads, hidden = 9, 11, 2, 256
+    C = heads * 64
+    blocks = [synth.block_weights(C, hidden, 930 + i) for i in range(2)]
+    # generator weights scaled down so that the branch adds about as much as the stream holds
+    # (at full scale it is 5x the stream, and the result is the branch's own bf16 chain)
+    for l, (hid, ks) in enumerate(((64, 3), (128, 5))):
+        w1, b1, w2, b2 = synth.squeeze_weights(C, hid, ks, 940 + l)
+        quarter = np.float32(0.25)
+        blocks[l]["dwc"] = {"token": (w1 * quarter, b1, w2 * quarter, b2 * quarter), "ksize": ks}
+    pattern = [0, 0]
+    dev = _device_blocks(blocks)
+    for B, P in ((2, 0), (1, 3)):
+        x = synth.normal((B, P + H * W, C), 950 + P)
+        enc = binding.Encoder(dev, pattern, heads, hidden, n_prefix=P)
+        dx = torch.from_numpy(x).cuda()
+        y = torch.empty_like(dx)
+        enc.forward(dx, y, (H, W))
+        ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, n_prefix=P)
+        check(err_bf16(to_host(y), ref), BF16_TOL)
+        plain = oracle.encoder_forward(x, [{k: v for k, v in b.items() if k != "dwc"} for b in blocks],
+                                       pattern, H, W, heads, n_prefix=P)
+        assert err_bf16(to_host(y), plain) > 10 * BF16_TOL
+        enc.close()
 
 
 def test_encoder_taps_intermediate_streams():

@@ -103,6 +103,109 @@ def test_config2_block_sampled_rows():
     check_bf16_pair(o32, o16, ref, rows)
 
 
+@pytest.mark.parametrize("ksize", [3, 5])
+@pytest.mark.parametrize("B,heads,H,W,P", [
+    (2, 3, 37, 37, 0),   # ragged matrix tiles
+    (1, 2, 5, 7, 0),
+    (1, 1, 1, 1, 0),     # a single token: only the centre tap is inside the grid
+    (1, 2, 20, 130, 0),
+    (2, 2, 12, 9, 5),    # prefix tokens in front of the grid: no convolution term for them
+])
+def test_bf16_token_wise_dynamic(B, heads, H, W, P, ksize):
+    """Per-token dynamic filters (Tab. 1, "Token-wise Dynamic DWC"): generator on every token's
+    V row, each token's own filters on its neighbourhood.
+
+    The generator runs as a bf16 network does: weights, hidden layer and filters are each rounded
+    to bf16 (2^-9 relative), three roundings in a chain in front of a sum of k*k products that
+    may cancel.  The bar is therefore the usual 2e-2 RMS plus the forward bound of that sum,
+    2^-7 * sum_taps |filter * v| (4 half-ulps: the three roundings and their interaction), taken
+    element-wise from the oracle; the same run is also compared with the oracle evaluated
+    with exactly these three roundings."""
+    C, hidden = heads * 64, 64
+    q, k, v = synth.qkv(33, B, heads, P + H * W, 64, 0.5, True)
+    tok = synth.squeeze_weights(C, hidden, ksize, 3500 + ksize)
+    ref = oracle.linear_block(q, k, v, H, W, 1e-6, ksize=ksize, token=tok)
+    o32 = _block(q, k, v, H, W, True, torch.float32, ksize=ksize, token=_dev(*tok))
+    o16 = _block(q, k, v, H, W, True, torch.bfloat16, ksize=ksize, token=_dev(*tok))
+    assert torch.equal(o32.to(torch.bfloat16), o16), "bf16 output is not RNE(fp32 output)"
+    vg = np.ascontiguousarray(v[:, :, P:])
+    kap = oracle.tokenwise_kernels(vg, *tok, ksize)
+    slack = np.zeros_like(ref)
+    slack[:, :, P:] = 2.0 ** -7 * oracle.dwc_tokenwise(np.abs(vg), np.abs(kap), H, W)
+    rms = np.sqrt(np.mean(ref * ref))
+    g32, g16 = to_host(o32), to_host(o16)
+    check(float(np.max(np.abs(g32 - ref) - slack) / rms), BF16_TOL)
+    check(float(np.max(np.abs(g16 - ref) - slack - np.abs(ref) * 2.0 ** -8) / rms), BF16_TOL)
+    # the same three roundings applied to the oracle's own stages
+    rb = lambda a: synth.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
+    w1, b1, w2, b2 = tok
+    rows = vg.transpose(0, 2, 1, 3).reshape(B, H * W, C).astype(np.float64)
+    pre = rows @ rb(w1).T + b1
+    u = rb(pre / (1.0 + np.exp(-pre)))
+    kap_r = rb(u @ rb(w2).T + b2).reshape(B, H * W, C, ksize, ksize)
+    la = oracle.linear_attn_quadratic(q, k, v, 1e-6)
+    same = la.copy()
+    same[:, :, P:] += oracle.dwc_tokenwise(vg, kap_r, H, W)
+    # fp32 against fp64 accumulation flips the bf16 rounding of a few filter entries by one
+    # ulp: isolated differences of up to ulp(filter) * |v|, none on average
+    check(float(np.sqrt(np.mean((g32 - same) ** 2)) / rms), 3e-4)
+    check(err_bf16(g32, same, rms), 2.0 ** -7 * np.abs(kap).max() * np.abs(vg).max() / rms + 1e-3)
+    if P:           # prefix rows are plain linear attention, bit for bit
+        dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+        plain = torch.empty_like(o32)
+        binding.jv_linear_attn_fwd(dq, dk, dv, plain, (H, W))
+        assert torch.equal(plain[:, :, :P], o32[:, :, :P])
+
+
+def test_token_wise_special_filters():
+    """W2 = 0 makes every token's filters the static bank b2 (chosen bf16-representable, as the
+    generated filters are stored in bf16): the static block's result up to the order of the
+    fp32 additions."""
+    B, heads, H, W = 1, 2, 12, 9
+    C, hidden = heads * 64, 64
+    q, k, v = synth.qkv(34, B, heads, H * W, 64, 0.5, True)
+    w1, b1, w2, b2 = synth.squeeze_weights(C, hidden, 3, 3600)
+    b2 = synth.round_to_bf16(b2)
+    dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+    static = torch.empty_like(dq, dtype=torch.float32)
+    binding.jv_linear_block_fwd(dq, dk, dv, static, (H, W), static_kernel=_dev(b2.reshape(C, 3, 3))[0])
+    tok = torch.empty_like(static)
+    binding.jv_linear_block_fwd(dq, dk, dv, tok, (H, W), token=_dev(w1, b1, np.zeros_like(w2), b2))
+    assert float((tok - static).abs().max()) <= 1e-5 * float(static.abs().max())
+
+
+def test_token_wise_reads_v_in_place_from_fused_rows():
+    """Q, K, V as strided views of one [B, N, 3, heads, 64] buffer (the layout a fused QKV
+    projection leaves): the generator reads V's rows in place; same bits as from packed tensors."""
+    B, heads, H, W, P = 2, 3, 13, 11, 2
+    N = P + H * W
+    q, k, v = synth.qkv(35, B, heads, N, 64, 0.5, True)
+    tok = _dev(*synth.squeeze_weights(heads * 64, 64, 3, 3700))
+    dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+    packed = torch.empty(dq.shape, dtype=torch.float32, device="cuda")
+    binding.jv_linear_block_fwd(dq, dk, dv, packed, (H, W), token=tok)
+    fused = torch.empty(B, N, 3, heads, 64, dtype=torch.bfloat16, device="cuda")
+    for i, t in enumerate((dq, dk, dv)):
+        fused[:, :, i] = t.permute(0, 2, 1, 3)
+    fq, fk, fv = (fused[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    in_place = torch.full_like(packed, float("nan"))
+    binding.jv_linear_block_fwd(fq, fk, fv, in_place, (H, W), token=tok)
+    assert torch.equal(packed, in_place)
+
+
+def test_token_wise_rejects_unsupported():
+    q = torch.zeros(1, 1, 16, 64, device="cuda")
+    tok = _dev(*synth.squeeze_weights(64, 64, 3, 1))
+    with pytest.raises(binding.JvError) as e:     # fp32 tensors
+        binding.jv_linear_block_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (4, 4), token=tok)
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
+    qb = q.to(torch.bfloat16)
+    with pytest.raises(binding.JvError) as e:     # hidden not a multiple of 64
+        binding.jv_linear_block_fwd(qb, qb.clone(), qb.clone(), torch.empty_like(qb), (4, 4),
+                                    token=_dev(*synth.squeeze_weights(64, 8, 3, 2)))
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
+
+
 def test_block_rejects_bad_parameters():
     q = torch.zeros(1, 1, 16, 64, device="cuda")
     o = torch.empty_like(q)

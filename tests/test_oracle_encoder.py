@@ -147,3 +147,64 @@ def test_linear_block_with_prefix_tokens():
     u = u / (1.0 + np.exp(-u))
     want = (sq[2].astype(np.float64) @ u + sq[3]).reshape(C, 3, 3)
     assert np.abs(ka[0] - want).max() < 1e-12
+
+
+def test_tokenwise_dynamic_filters():
+    """Pins of the per-token dynamic convolution (Sec. 3.2.1; Tab. 1, "Token-wise Dynamic DWC")."""
+    B, heads, H, W, d, k, hidden = 2, 2, 4, 5, 4, 3, 6
+    C, N = heads * d, H * W
+    v = synth.normal((B, heads, N, d), 70)
+    w1, b1 = synth.normal((hidden, C), 71), synth.normal((hidden,), 72)
+    w2, b2 = synth.normal((C * k * k, hidden), 73), synth.normal((C * k * k,), 74)
+    # (1) W2 = 0: every token's filters are the static bank b2 -> the static convolution
+    kap0 = oracle.tokenwise_kernels(v, w1, b1, np.zeros_like(w2), b2, k)
+    static = b2.astype(np.float64).reshape(1, C, k, k)
+    assert np.abs(oracle.dwc_tokenwise(v, kap0, H, W) - oracle.dwc(v, static, H, W)).max() < 1e-14
+    # (2) an image whose tokens are all equal: each token equals the token average, so the
+    # per-token filters are the per-image filters of the squeeze generator
+    flat = np.ascontiguousarray(np.broadcast_to(v[:, :, :1], v.shape))
+    kap = oracle.tokenwise_kernels(flat, w1, b1, w2, b2, k)
+    per_image = oracle.squeeze_kernel(flat, w1, b1, w2, b2, k)
+    assert np.abs(kap - per_image[:, None]).max() < 1e-6      # squeeze_kernel reads V as fp32
+    assert np.abs(oracle.dwc_tokenwise(flat, kap, H, W) - oracle.dwc(flat, per_image, H, W)).max() < 1e-5
+    # (3) the generator against library modules, token by token
+    rows = torch.from_numpy(v).double().permute(0, 2, 1, 3).reshape(B, N, C)
+    u = F.silu(rows @ torch.from_numpy(w1).double().T + torch.from_numpy(b1).double())
+    ref = (u @ torch.from_numpy(w2).double().T + torch.from_numpy(b2).double()).reshape(B, N, C, k, k)
+    full = oracle.tokenwise_kernels(v, w1, b1, w2, b2, k)
+    assert np.abs(full - ref.numpy()).max() < 1e-13
+    # (4) brute force of the convolution: the OUTPUT token's filters weight its neighbourhood
+    want = np.zeros((B, heads, N, d))
+    for b in range(B):
+        for n in range(N):
+            r, s = divmod(n, W)
+            for ch in range(C):
+                hh, c = divmod(ch, d)
+                for di in range(k):
+                    for dj in range(k):
+                        r2, s2 = r + di - k // 2, s + dj - k // 2
+                        if 0 <= r2 < H and 0 <= s2 < W:
+                            want[b, hh, n, c] += full[b, n, ch, di, dj] * float(v[b, hh, r2 * W + s2, c])
+    assert np.abs(oracle.dwc_tokenwise(v, full, H, W) - want).max() < 1e-13
+    # (5) closed form with one live path: hidden unit 0 reads channel c0, filter entry
+    # (channel c1, tap (0, 2)) reads hidden unit 0 -> out[n, c1] = w silu(a v[n, c0] + bias) v[n - W + 1, c1]
+    c0, c1, a, bias, w = 1, 6, 0.7, -0.2, 1.3
+    w1s = np.zeros((hidden, C)); w1s[0, c0] = a
+    b1s = np.zeros(hidden); b1s[0] = bias
+    w2s = np.zeros((C * k * k, hidden)); w2s[c1 * k * k + 0 * k + 2, 0] = w
+    got = oracle.dwc_tokenwise(v, oracle.tokenwise_kernels(v, w1s, b1s, w2s, np.zeros(C * k * k), k), H, W)
+    for n in range(N):
+        r, s = divmod(n, W)
+        pre = a * float(v[0, c0 // d, n, c0 % d]) + bias
+        nb = float(v[0, c1 // d, (r - 1) * W + s + 1, c1 % d]) if r >= 1 and s + 1 < W else 0.0
+        assert abs(got[0, c1 // d, n, c1 % d] - w * pre / (1 + np.exp(-pre)) * nb) < 1e-14
+    assert np.count_nonzero(np.delete(got.transpose(0, 2, 1, 3).reshape(B, N, C), c1, axis=2)) == 0
+    # (6) in the block: added on the grid tokens only; a prefix token changes nothing there
+    q, kk_, vv = synth.qkv(75, 1, heads, 2 + N, d, 1.0, False)
+    tok = (w1, b1, w2, b2)
+    out = oracle.linear_block(q, kk_, vv, H, W, token=tok)
+    la = oracle.linear_attn_quadratic(q, kk_, vv, 1e-6)
+    assert np.array_equal(out[:, :, :2], la[:, :, :2])
+    vg = np.ascontiguousarray(vv[:, :, 2:])
+    conv = oracle.dwc_tokenwise(vg, oracle.tokenwise_kernels(vg, *tok, k), H, W)
+    assert np.abs(out[:, :, 2:] - la[:, :, 2:] - conv).max() < 1e-13
