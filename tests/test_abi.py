@@ -74,3 +74,33 @@ def test_argument_validation_launches_nothing():
     with pytest.raises(binding.JvError):
         binding.jv_window_geometry(4, 4, 0, 2)
     assert L.jv_status_string(3) == b"workspace too small"
+
+
+def test_block_workspace_query_by_convolution_mode():
+    """jv_linear_block_workspace_bytes (host only): grows with the mode's buffers; the token-wise
+    mode holds the bf16 filters of every token; parameter blocks the library does not support
+    answer 0."""
+    B, heads, H, W, P = 2, 3, 10, 12, 4
+    C, N, hidden, k = heads * 64, P + H * W, 64, 3
+    s = binding.JvStrides(heads * N * 64, N * 64, 64)
+    d = binding.JvAttnDesc(B, heads, H, W, 64, binding.JV_BF16, binding.JV_BF16, s, s, s, s, P)
+    fake = ctypes.c_void_p(4096)   # 16-byte aligned, never dereferenced by the query
+
+    def params(mode, ksize=k, hid=hidden):
+        return binding.JvDwcParams(mode, ksize, hid, fake, fake, fake, fake, fake)
+
+    plain = binding.jv_linear_attn_workspace_bytes(d)
+    assert plain > 0 and plain % 256 == 0
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_NONE)) == plain
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_STATIC)) == plain
+    squeeze = binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_SQUEEZE_DYNAMIC))
+    assert plain + 4 * (B * C * k * k + B * hidden) <= squeeze < plain + (1 << 20)
+    token = binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_TOKEN_DYNAMIC))
+    M = B * N
+    exact = (2 * hidden * C + 2 * C * k * k * hidden      # bf16 generator weights
+             + 2 * M * C + 2 * M * hidden                 # V rows, hidden layer
+             + 2 * M * C * k * k + 4 * M * C)             # filters of every token, fp32 attention term
+    assert plain + exact <= token <= plain + exact + 6 * 256
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_TOKEN_DYNAMIC, hid=40)) == 0
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_STATIC, ksize=4)) == 0
+    assert binding.jv_linear_block_workspace_bytes(d, params(4)) == 0
