@@ -58,12 +58,15 @@ def main():
     ap.add_argument("--paper-ratio", action="store_true",
                     help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
                          "(the resolution of the paper's speed tables), as ratios")
-    ap.add_argument("--model", choices=["L", "B", "H"], default="L", help="ViT size for --paper-ratio")
+    ap.add_argument("--model", choices=["L", "B", "H", "G"], default="L", help="ViT size for --paper-ratio")
     ap.add_argument("--graph", action="store_true",
                     help="--paper-ratio: replay each forward pass as one captured HIP graph")
     ap.add_argument("--la-ablation", action="store_true",
                     help="time the linear-attention block variants of the paper's Tab. 1 in a pure "
                          "linear-attention ViT-L and print their ratios")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time linear, window 16x16 (and full, up to 16 384 tokens) attention over the "
+                         "token-count sweep at 32 768 tokens per call: 1 024 ... 65 536 tokens per image")
     ap.add_argument("--only", choices=["linear", "window", "full", "block"], default=None,
                     help="run only this mixer's launches (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -88,6 +91,9 @@ def main():
         del src, dst
     if args.la_ablation:
         print(json.dumps(bench_la_ablation(args.steps, args.warmup)))
+        return
+    if args.sweep:
+        print(json.dumps(bench_sweep(args.steps, args.warmup, args.buffers)))
         return
     if args.paper_ratio:
         print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model, args.graph)))
@@ -288,13 +294,14 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
     block is linear attention, the others alternate window 16x16 and linear attention; linear
     blocks carry the squeeze-dynamic 3x3 convolution branch (hidden width C/16).  model "B": the
     same with ViT-B (12 blocks, width 768, 12 heads), full attention kept at blocks 7 and 11, or
-    "H" (32 blocks, width 1280, 20 heads, MLP 5120), blocks 19 and 29 (the paper prints positions
-    for ViT-L only: scaled to the other depths)."""
+    "H" (32 blocks, width 1280, 20 heads, MLP 5120), blocks 19 and 29, or "G" (40 blocks, width
+    1536, 24 heads, MLP 6144), blocks 24 and 37 (the paper prints positions for ViT-L only: scaled
+    to the other depths)."""
     import torch
     from paper_2605_26636_amd import binding, synth
     B, H, W = 1, 64, 128
     heads, hidden, L, full_at_two = {"L": (16, 4096, 24, (14, 22)), "B": (12, 3072, 12, (7, 11)),
-                                     "H": (20, 5120, 32, (19, 29))}[model]
+                                     "H": (20, 5120, 32, (19, 29)), "G": (24, 6144, 40, (24, 37))}[model]
     C, N = heads * 64, H * W
     dev = []
     for l in range(L):
@@ -350,6 +357,61 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
             "data": "synthetic", "hip_graph": bool(graph), "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
             "paper_context_h100": {"DINOv3-L -> JetViT-L (2 full-attention blocks), whole model": "35.07 ms -> 18.77 ms (1.87x)",
                                    "DINOv3-B -> JetViT-B 0/1/2 full-attention blocks": "12.86 ms -> 7.37 / 7.69 / 8.27 ms"}}
+
+
+def bench_sweep(steps, warmup, buffers):
+    """Token-count sweep of the crossover experiment (bf16, 16 heads x 64): 32 768 tokens per call
+    as 32 images of 1 024 tokens ... 2 images of 16 384, and one image of 65 536 tokens.  Linear and
+    16x16 window attention move the same bytes per token at every size; full attention (timed up
+    to 16 384 tokens per image) grows with the image.  Events on the launch stream, rotating
+    buffer sets."""
+    import torch
+    from paper_2605_26636_amd import binding, synth
+    heads, d = 16, 64
+    stream = torch.cuda.current_stream()
+    rows = []
+    for B, H, W in synth.SWEEP:
+        N = H * W
+        q, k, v = synth.qkv(3, B, heads, N, d, 0.125, True)
+        base = [torch.from_numpy(x).cuda().to(torch.bfloat16) for x in (q, k, v)]
+        sets = []
+        for i in range(buffers):
+            qs, ks, vs = (t.clone() if i else t for t in base)
+            sets.append((qs, ks, vs, torch.empty_like(qs)))
+        ws = torch.empty(max(256, binding.jv_linear_attn_workspace_bytes(binding.make_desc(*sets[0], (H, W)))),
+                         dtype=torch.uint8, device="cuda")
+        mixers = {"linear": lambda s_: binding.jv_linear_attn_fwd(s_[0], s_[1], s_[2], s_[3], (H, W), 1e-6, ws, stream),
+                  "window": lambda s_: binding.jv_window_attn_fwd(s_[0], s_[1], s_[2], s_[3], (H, W), (16, 16), 0.0, stream)}
+        if N <= 16384:
+            mixers["full"] = lambda s_: binding.jv_full_attn_fwd(s_[0], s_[1], s_[2], s_[3], (H, W), 0.0, stream)
+        tokens = B * N
+        bytes_layer = 4 * tokens * heads * d * 2
+        row = {"tokens_per_image": N, "batch": B, "grid": [H, W]}
+        for name, fn in mixers.items():
+            n_timed = steps if name != "full" else max(3, min(steps, 10))
+            for i in range(warmup):
+                fn(sets[i % len(sets)])
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                   for _ in range(n_timed)]
+            torch.cuda.synchronize()
+            for i, (a, b) in enumerate(evs):
+                a.record(stream); fn(sets[i % len(sets)]); b.record(stream)
+            torch.cuda.synchronize()
+            t = np.array([a.elapsed_time(b) for a, b in evs])
+            ms = float(np.median(t))
+            row[name] = {"ms_median": ms, "ms_min": float(t.min()), "ns_per_token": ms * 1e6 / tokens}
+            if name == "full":
+                tf = 4.0 * N * N * d * B * heads / (ms * 1e-3) / 1e12
+                row[name].update({"TFLOPs": tf, "mfma_frac": tf / MFMA_BF16_PEAK_TFLOPS})
+            else:
+                gbs = bytes_layer / (ms * 1e-3) / 1e9
+                row[name].update({"hbm_GBs": gbs, "hbm_frac": gbs / HBM_PEAK_GBS})
+        rows.append(row)
+        del sets, base, ws
+        torch.cuda.empty_cache()
+    return {"metric": "mixer time over the token-count sweep (bf16, 16 heads x 64, 16x16 windows)",
+            "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16",
+            "data": "synthetic", "sweep": rows}
 
 
 def bench_la_ablation(steps, warmup):
