@@ -239,7 +239,7 @@ __device__ inline void wave_store(const WaveState<NT> &w, const AttnArgs &a, int
                 const int orow = r * 8 + lrow;
                 const int tok = slot_token(a, wy, wx, q0 + 32 * nt + orow);
                 const u32x4 val = *(const u32x4 *)(stage + tile_off_row(orow, lchunk));
-                if (tok >= 0) *(u32x4 *)(op + (long long)tok * a.o.sn + lchunk * 8) = val;
+                if (tok >= 0) st_stream((u32x4 *)(op + (long long)tok * a.o.sn + lchunk * 8), val);
             }
         } else {
             float *op = (float *)a.o.ptr + obase;
@@ -447,10 +447,10 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
                 const int vchunk = lslot ^ (((row ^ (row >> 1)) & 1) << 2);
                 __builtin_amdgcn_global_load_lds(
                     (attn_global_cvoid *)(kptr + (long long)src * a.k.sn + kchunk * 8),
-                    (attn_lds_void *)(ktile + row0 * 128), 16, 0, 0);
+                    (attn_lds_void *)(ktile + row0 * 128), 16, 0, kDmaStreamAux);
                 __builtin_amdgcn_global_load_lds(
                     (attn_global_cvoid *)(vptr + (long long)src * a.v.sn + vchunk * 8),
-                    (attn_lds_void *)(vtile + row0 * 128), 16, 0, 0);
+                    (attn_lds_void *)(vtile + row0 * 128), 16, 0, kDmaStreamAux);
                 if (lslot == 0) bias[row] = tok >= 0 ? 0.f : -INFINITY;
             }
         }
@@ -552,9 +552,9 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
         for (int jj = 0; jj < 4; ++jj) {
             const int j = 4 * half + jj, row0 = 32 * j + 8 * wave;
             __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.k + (koff0 + j * kstep)),
-                                             (attn_lds_void *)(ktile + row0 * 128), 16, 0, 0);
+                                             (attn_lds_void *)(ktile + row0 * 128), 16, 0, kDmaStreamAux);
             __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.v + (voff0 + j * vstep)),
-                                             (attn_lds_void *)(vtile + row0 * 128), 16, 0, 0);
+                                             (attn_lds_void *)(vtile + row0 * 128), 16, 0, kDmaStreamAux);
         }
     };
     bf16x8 qreg[2][4];
@@ -625,7 +625,7 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
                 for (int r = 0; r < 4; ++r) {
                     const u32x4 val = *(const u32x4 *)(stage + tile_off_row(r * 8 + lrow, lslot));
                     const unsigned ooff = 2u * ((unsigned)rel_token(q0 + 32 * nt + r * 8 + lrow + fresh) * (unsigned)a.o.sn + lslot * 8);
-                    *(u32x4 *)(cur.o + ooff) = val;
+                    st_stream((u32x4 *)(cur.o + ooff), val);
                 }
             } else {
                 const unsigned ooff = 4u * (unsigned)rel_token(q0 + 32 * nt + li + fresh) * (unsigned)a.o.sn;

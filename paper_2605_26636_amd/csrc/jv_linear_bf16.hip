@@ -80,7 +80,9 @@ constexpr int kStateLds = 4 * kWaveLds + 2 * 8 * kHeadDim * 4;
 // grid (n_split, B*heads), 256 threads, kStateLds bytes of dynamic LDS.
 // VSUM: also write the chunk's token sum of V (the input of the dynamic-filter generator of
 // the block's convolution branch) to vsum[part][bh][64]; it falls out of the V operands.
-template <bool VSUM>
+// KEEP_V: the apply pass reads V again (convolution branch), so V is loaded with the default
+// cache policy; K, and V otherwise, are read once and loaded as a stream.
+template <bool VSUM, bool KEEP_V>
 __global__ void __launch_bounds__(256, 2)
 la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restrict__ vsum,
               int heads, int N, int chunk, int focus_p) {
@@ -113,8 +115,9 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restr
             kreg[r] = zero;
             vreg[r] = zero;
             if (n < n1) {
-                kreg[r] = *(const u32x4 *)(kp + (long long)n * kt.sn + lchunk * 8);
-                vreg[r] = *(const u32x4 *)(vp + (long long)n * vt.sn + lchunk * 8);
+                kreg[r] = ld_stream((const u32x4 *)(kp + (long long)n * kt.sn + lchunk * 8));
+                const u32x4 *vsrc = (const u32x4 *)(vp + (long long)n * vt.sn + lchunk * 8);
+                vreg[r] = KEEP_V ? *vsrc : ld_stream(vsrc);
             }
         }
     };
@@ -259,7 +262,7 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
             const int n = t0 + r * 8 + lrow;
             u32x4 zero = {0u, 0u, 0u, 0u};
             qreg[r] = zero;
-            if (n < n1) qreg[r] = *(const u32x4 *)(qp + (long long)n * qt.sn + lchunk * 8);
+            if (n < n1) qreg[r] = ld_stream((const u32x4 *)(qp + (long long)n * qt.sn + lchunk * 8));
         }
     };
     int t = n0 + wave * 64;
@@ -439,7 +442,7 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
                             __bf16 *op = (__bf16 *)ot.ptr + b * ot.sb + h * ot.sh;
                             u32x4 pk = {pack_bf16x2(sum[r][0], sum[r][1]), pack_bf16x2(sum[r][2], sum[r][3]),
                                         pack_bf16x2(sum[r][4], sum[r][5]), pack_bf16x2(sum[r][6], sum[r][7])};
-                            *(u32x4 *)(op + (long long)on * ot.sn + lchunk * 8) = pk;
+                            st_stream((u32x4 *)(op + (long long)on * ot.sn + lchunk * 8), pk);
                         } else {
                             float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)on * ot.sn + lchunk * 8;
                             f32x4 s0 = {sum[r][0], sum[r][1], sum[r][2], sum[r][3]};
@@ -463,7 +466,7 @@ la_apply_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int 
                 for (int r = 0; r < 4; ++r) {
                     const int orow = r * 8 + lrow, on = t + 32 * nt + orow;
                     const u32x4 val = *(const u32x4 *)(otile + tile_off_row(orow, lchunk));
-                    if (on < n1) *(u32x4 *)(op + (long long)on * ot.sn + lchunk * 8) = val;
+                    if (on < n1) st_stream((u32x4 *)(op + (long long)on * ot.sn + lchunk * 8), val);
                 }
             } else {
                 float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh;
@@ -494,17 +497,21 @@ static void launch_apply(hipStream_t stream, const Problem &pr, const float *sta
 
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
                       const DwcPlan &dwc, int focus_p, hipStream_t stream) {
-    static LdsLimit lds_limit[2];
-    jv_status st = ensure_lds_limit(lds_limit[0], (const void *)la_state_bf16<false>, kStateLds);
-    if (st == JV_OK) st = ensure_lds_limit(lds_limit[1], (const void *)la_state_bf16<true>, kStateLds);
+    static LdsLimit lds_limit[3];
+    jv_status st = ensure_lds_limit(lds_limit[0], (const void *)la_state_bf16<false, false>, kStateLds);
+    if (st == JV_OK) st = ensure_lds_limit(lds_limit[1], (const void *)la_state_bf16<false, true>, kStateLds);
+    if (st == JV_OK) st = ensure_lds_limit(lds_limit[2], (const void *)la_state_bf16<true, true>, kStateLds);
     if (st != JV_OK) return st;
     const int BH = pr.B * pr.heads;
     const bool dynamic = dwc.mode == JV_DWC_SQUEEZE_DYNAMIC;
     if (dynamic)
-        hipLaunchKernelGGL(la_state_bf16<true>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
+        hipLaunchKernelGGL((la_state_bf16<true, true>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
                            pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p);
+    else if (dwc.mode != JV_DWC_NONE)
+        hipLaunchKernelGGL((la_state_bf16<false, true>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
     else
-        hipLaunchKernelGGL(la_state_bf16<false>, dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
+        hipLaunchKernelGGL((la_state_bf16<false, false>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
                            pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
     if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
     const float *states = ws;

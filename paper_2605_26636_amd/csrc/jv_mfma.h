@@ -30,6 +30,37 @@ __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Loads and stores of data that is touched once per launch (the Q/K/V/O streams of the
+// HBM-bound mixers), marked non-temporal so that they do not displace what is reused.  Only for
+// accesses that cover whole 128-byte lines within one instruction: a line that several
+// non-temporal instructions touch in parts is fetched again for each of them.
+// JV_STREAM_HINTS=0 builds the plain forms (for A/B timing).
+#ifndef JV_STREAM_HINTS
+#define JV_STREAM_HINTS 1
+#endif
+constexpr int kDmaStreamAux = JV_STREAM_HINTS ? 2 : 0;  // cache-policy bits of the LDS-DMA load: nt
+__device__ inline u32x4 ld_stream(const u32x4 *p) {
+#if JV_STREAM_HINTS
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+__device__ inline void st_stream(u32x4 *p, u32x4 v) {
+#if JV_STREAM_HINTS
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+__device__ inline void st_stream(f32x4 *p, f32x4 v) {
+#if JV_STREAM_HINTS
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
 __device__ inline bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 __device__ inline u32x4 as_u32x4(bf16x8 x) { return __builtin_bit_cast(u32x4, x); }
 
