@@ -294,9 +294,15 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     }
 
     // Epilogue: accumulator register v of block (nt, mt) is output feature
-    // n0 + 64 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li.
-    // Loads are batched ahead of their use (all bias pieces once, the residual pieces of a
-    // token block together, one block ahead) so that their latencies overlap.
+    // n0 + 64 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li: a lane holds
+    // 4 consecutive features of one token.  Stored from there, an instruction would touch 32
+    // token rows with 16 or 32 bytes each, and every 128-byte line of y would be written by 4 to
+    // 8 different instructions.  Instead each wavefront turns its 32 x 64 blocks into token rows
+    // in 8 KB of LDS of its own and stores whole rows (128 or 256 contiguous bytes per token);
+    // the residual is read in the same row layout.  The LDS comes from the operand ring: the
+    // last block occupies two of the five slots, and every wavefront has passed the barrier
+    // after which nobody reads the other three (a_slot points at the first of them here).
+    unsigned char *stage = smem + next_slot(a_slot, 1 + (wave >> 2)) * kGemmPart + (wave & 3) * 8192;
     f32x4 bias_reg[2][4];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
@@ -306,33 +312,42 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             bias_reg[nt][q4] = (bias && col < N) ? *(const f32x4 *)(bias + col) : zero;
         }
+    constexpr bool kRowResidual = EPI == JV_EPI_RESIDUAL && !OUT_BF16;  // added in the row layout
+    // Row layout of the fp32 tile: 16 lanes per token row (256 bytes), 4 rows per instruction.
+    const int frow = lane >> 4, fchunk = lane & 15;
+    const int fcol = n0 + wn * 64 + 4 * fchunk;
     // The residual rows of token block mt+1 are fetched before block mt is stored (different
     // rows, so this is safe although the residual may be y itself): one round trip is exposed
     // instead of four.
-    f32x4 res_reg[2][2][4];
+    f32x4 res_reg[2][8];
     auto load_residual = [&](int mt, int set) {
-        const int row = m0 + wm * 128 + mt * 32 + li;
+        if (kRowResidual) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
+            for (int r = 0; r < 8; ++r) {
+                const int row = m0 + wm * 128 + mt * 32 + 4 * r + frow;
                 f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                res_reg[set][nt][q4] = (row < M && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
+                res_reg[set][r] = (row < M && fcol < N) ? *(const f32x4 *)(residual + (size_t)row * N + fcol) : zero;
             }
+        } else {  // accumulator layout (bf16 output with a residual: not a shape the encoder uses)
+            const int row = m0 + wm * 128 + mt * 32 + li;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
+                    f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    res_reg[set][4 * nt + q4] = (row < M && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
+                }
+        }
     };
     if (EPI == JV_EPI_RESIDUAL) load_residual(0, 0);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-        const int row = m0 + wm * 128 + mt * 32 + li;
-        const bool row_ok = row < M;
         if (EPI == JV_EPI_RESIDUAL && mt + 1 < 4) load_residual(mt + 1, (mt + 1) & 1);
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
-                // N % 8 == 0: the four features of a piece are in or out together
                 f32x4 val = {acc[nt][mt][4 * q4], acc[nt][mt][4 * q4 + 1], acc[nt][mt][4 * q4 + 2],
                              acc[nt][mt][4 * q4 + 3]};
                 val += bias_reg[nt][q4];
@@ -344,17 +359,32 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
                     for (int e = 0; e < 4; ++e) val[e] = val[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-val[e]));
                 }
-                if (EPI == JV_EPI_RESIDUAL) val += res_reg[mt & 1][nt][q4];
-                if (row_ok && col < N) {
-                    const size_t at_out = (size_t)row * N + col;
-                    if (OUT_BF16) {
-                        u32x2 pk = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
-                        *(u32x2 *)((__bf16 *)Y + at_out) = pk;
-                    } else {
-                        *(f32x4 *)((float *)Y + at_out) = val;
-                    }
+                if (EPI == JV_EPI_RESIDUAL && !kRowResidual) val += res_reg[mt & 1][4 * nt + q4];
+                if (OUT_BF16) {
+                    u32x2 pk = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
+                    *(u32x2 *)(stage + tile_off_row(li, 4 * nt + q4) + 8 * g) = pk;
+                } else {
+                    *(f32x4 *)(stage + li * 256 + (((8 * nt + 2 * q4 + g) ^ (li & 15)) << 4)) = val;
                 }
             }
+        if (OUT_BF16) {  // 8 lanes per token row (128 bytes), 8 rows per instruction
+            const int col = n0 + wn * 64 + 8 * (lane & 7);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int orow = 8 * r + lrow, row = m0 + wm * 128 + mt * 32 + orow;
+                const u32x4 out = *(const u32x4 *)(stage + tile_off_row(orow, lane & 7));
+                // N % 8 == 0: the eight features of a piece are in or out together
+                if (row < M && col < N) *(u32x4 *)((__bf16 *)Y + (size_t)row * N + col) = out;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int orow = 4 * r + frow, row = m0 + wm * 128 + mt * 32 + orow;
+                f32x4 out = *(const f32x4 *)(stage + orow * 256 + ((fchunk ^ (orow & 15)) << 4));
+                if (kRowResidual) out += res_reg[mt & 1][r];
+                if (row < M && fcol < N) *(f32x4 *)((float *)Y + (size_t)row * N + fcol) = out;
+            }
+        }
     }
 }
 
