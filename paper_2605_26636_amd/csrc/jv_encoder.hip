@@ -265,13 +265,16 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         if (next) load_ops(next_slot(a_slot, 2), next_slot(w_slot, 2), 0, 0);
         products(1);
         if (n_issue >= 2) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x010, 2 * kPartLoads, 0);
+            // after the barrier: the six LDS reads of the next block's first step and the eight
+            // loads that refill this block's slots, spread among the eight matrix instructions
 #pragma unroll
             for (int i = 0; i < 6; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
     };

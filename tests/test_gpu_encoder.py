@@ -60,6 +60,8 @@ def test_gemm_epilogues(M, N, K):
     inplace = dr.clone()
     binding.jv_gemm_bias_act(da, dw, db, inplace, inplace, binding.JV_EPI_RESIDUAL)
     assert torch.equal(inplace, y32)
+    binding.jv_gemm_bias_act(da, dw, db, dr, y16, binding.JV_EPI_RESIDUAL)   # bf16 output with a residual
+    assert torch.equal(y32.to(torch.bfloat16), y16)
     binding.jv_gemm_bias_act(da, dw, db, None, y32, binding.JV_EPI_SILU)
     check(err_bf16(to_host(y32), plain / (1.0 + np.exp(-plain))), 1e-4)
 
