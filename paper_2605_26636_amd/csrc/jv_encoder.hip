@@ -125,8 +125,8 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // Rows are 128 bytes in LDS; the 16-byte chunk index is rotated by the row pair, which
 // spreads the sixteen rows that one pass of a row-per-lane read touches over all 64 banks.
 // The product is formed transposed (features x tokens): a lane then holds 4 consecutive output
-// features of one token, which makes the epilogue loads (bias, residual) and stores 8 or 16
-// bytes wide.
+// features of one token (bias pieces are 16-byte loads); the epilogue regroups the blocks into
+// token rows through LDS before it touches global memory.
 // Tiles are assigned so that the workgroups an XCD receives (every eighth) walk a contiguous
 // range of tiles, feature-tile fastest: they share the a row-tile and keep w in that L2.
 // grid (8 * ceil(tiles / 8)), 512 threads, kGemmLds bytes of dynamic LDS.
