@@ -139,15 +139,18 @@ constexpr int kGemmLds = kGemmSlots * kGemmPart;       // 160 KB
 typedef __attribute__((address_space(1))) const void global_cvoid;
 typedef __attribute__((address_space(3))) void lds_void;
 
-// erf(z) by Abramowitz-Stegun 7.1.25 (absolute error below 2.5e-5), exp through exp2.
+// gelu(x) = x/2 (1 + erf(x / sqrt 2)) with erf(z) by Abramowitz-Stegun 7.1.25 (absolute error
+// below 2.5e-5):  erf(z) = 1 - (a1 t + a2 t^2 + a3 t^3) exp(-z^2),  t = 1 / (1 + p z),  z >= 0.
+// Constants are folded so that one scaled argument serves both factors: w = |x| sqrt(log2(e) / 2)
+// gives exp(-z^2) = exp2(-w^2) and p z = p' w.
 __device__ inline float gelu_erf(float x) {
-    const float z = fabsf(x) * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.47047f, z, 1.0f));
+    const float w = fabsf(x) * 0.8493218002880191f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3916919679f, w, 1.0f));
     const float poly = t * fmaf(t, fmaf(t, 0.7478556f, -0.0958798f), 0.3480242f);
-    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
-    const float erf_abs = fmaf(-poly, e, 1.0f);
-    const float erf_x = copysignf(erf_abs, x);
-    return 0.5f * x * (1.0f + erf_x);
+    const float e = __builtin_amdgcn_exp2f(-(w * w));
+    const float erf_x = copysignf(fmaf(-poly, e, 1.0f), x);
+    const float h = 0.5f * x;
+    return fmaf(h, erf_x, h);
 }
 
 // Byte offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 LDS part.
