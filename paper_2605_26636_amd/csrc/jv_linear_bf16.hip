@@ -202,15 +202,20 @@ la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restr
     }
 }
 
-// grid (B*heads, ceil(kStateFloats / 1024)), 256 threads: dst[bh] = sum_p ws[p][bh], one
-// 16-byte piece per thread, the loads of eight partials in flight at a time.
+// grid (B*heads, ceil((kStateFloats + 64) / 1024)), 256 threads: dst[bh] = sum_p ws[p][bh], one
+// 16-byte piece per thread, the loads of eight partials in flight at a time.  With vsum (the
+// partial token sums of V, [n_split][B*heads][64]) the sixteen threads after the state's last
+// piece sum those too, into partial 0 (each element is read and written by one thread).
 __global__ void __launch_bounds__(256)
-la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
+la_combine(const float *__restrict__ ws, float *__restrict__ dst, float *vsum, int n_split) {
     const int bh = blockIdx.x, BH = gridDim.x;
     const int e4 = blockIdx.y * 256 + threadIdx.x;
-    if (e4 >= kStateFloats / 4) return;
-    const f32x4 *src = (const f32x4 *)ws + (size_t)bh * (kStateFloats / 4) + e4;
-    const size_t stride4 = (size_t)BH * (kStateFloats / 4);
+    constexpr int kStateVec = kStateFloats / 4, kSumVec = kHeadDim / 4;
+    if (e4 >= kStateVec + kSumVec || (e4 >= kStateVec && !vsum)) return;
+    const bool state = e4 < kStateVec;
+    const f32x4 *src = state ? (const f32x4 *)ws + (size_t)bh * kStateVec + e4
+                             : (const f32x4 *)vsum + (size_t)bh * kSumVec + (e4 - kStateVec);
+    const size_t stride4 = (size_t)BH * (state ? kStateVec : kSumVec);
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     for (int p0 = 0; p0 < n_split; p0 += 8) {
         f32x4 part[8];
@@ -222,7 +227,8 @@ la_combine(const float *__restrict__ ws, float *__restrict__ dst, int n_split) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) sum += part[i];
     }
-    ((f32x4 *)dst)[(size_t)bh * (kStateFloats / 4) + e4] = sum;
+    if (state) ((f32x4 *)dst)[(size_t)bh * kStateVec + e4] = sum;
+    else ((f32x4 *)vsum)[(size_t)bh * kSumVec + (e4 - kStateVec)] = sum;
 }
 
 // grid (8 * ceil(n_chunks * B*heads / 8)), 256 threads.  Workgroups are dealt to the eight XCDs
@@ -519,15 +525,15 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
     long long part_stride = (long long)BH * kStateFloats;
     if (plan.combine) {
         float *dst = ws + (size_t)plan.n_split * BH * kStateFloats;
-        hipLaunchKernelGGL(la_combine, dim3(BH, (kStateFloats / 4 + 255) / 256), dim3(256), 0, stream, ws, dst,
-                           plan.n_split);
+        hipLaunchKernelGGL(la_combine, dim3(BH, ((kStateFloats + kHeadDim) / 4 + 255) / 256), dim3(256), 0,
+                           stream, ws, dst, dynamic ? ws + dwc.vsum_off : (float *)nullptr, plan.n_split);
         if ((st = launch_status("la_combine")) != JV_OK) return st;
         states = dst;
         n_part = 1;
     }
     DwcArg cv = {dwc.static_kernel, 0, pr.H, pr.W, pr.P};
     if (dynamic) {
-        if ((st = squeeze_generate(dwc, ws, plan.n_split, pr.B, pr.heads, pr.N, stream)) != JV_OK) return st;
+        if ((st = squeeze_generate(dwc, ws, n_part, pr.B, pr.heads, pr.N, stream)) != JV_OK) return st;
         cv.kappa = ws + dwc.kappa_off;
         cv.kappa_sb = (long long)pr.heads * kHeadDim * dwc.ksize * dwc.ksize;
     }
