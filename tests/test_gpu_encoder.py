@@ -329,3 +329,36 @@ def test_encoder_forward_under_graph_capture():
             torch.cuda.synchronize()
             assert torch.equal(scratch, want)
     enc.close()
+
+
+def test_gemm_random_shapes_all_epilogues():
+    """Seeded sweep of ragged GEMM shapes (M arbitrary, N a multiple of 8, K a multiple of 64:
+    edge tiles in both directions, one to nine K blocks, one or several tiles per workgroup
+    slot), every epilogue with both output types, against the oracle's fp64 product."""
+    rng = np.random.Generator(np.random.Philox(20260527))
+    for case in range(10):
+        M = int(rng.integers(1, 900))
+        N = 8 * int(rng.integers(1, 110))
+        K = 64 * int(rng.integers(1, 10))
+        a = synth.round_to_bf16(synth.normal((M, K), 7000 + case))
+        w = synth.round_to_bf16(synth.normal((N, K), 7100 + case, 1.0 / np.sqrt(K)))
+        bias = synth.normal((N,), 7200 + case) * 0.5
+        res = synth.normal((M, N), 7300 + case)
+        da, dw = (torch.from_numpy(t).cuda().to(torch.bfloat16) for t in (a, w))
+        db, dr = torch.from_numpy(bias).cuda(), torch.from_numpy(res).cuda()
+        plain = oracle.linear(a.astype(np.float64), w, bias)
+        want = {binding.JV_EPI_NONE: plain, binding.JV_EPI_GELU: oracle.gelu(plain),
+                binding.JV_EPI_RESIDUAL: plain + res, binding.JV_EPI_SILU: plain / (1.0 + np.exp(-plain))}
+        print(f"  case {case}: M {M} N {N} K {K}", flush=True)
+        for epi, ref in want.items():
+            # guard rows around y: nothing may be written outside [M, N]
+            pad32 = torch.full((M + 2, N), 768.0, device="cuda")
+            y32 = pad32[1:M + 1]
+            binding.jv_gemm_bias_act(da, dw, db, dr if epi == binding.JV_EPI_RESIDUAL else None, y32, epi)
+            check(err_bf16(to_host(y32), ref), 2e-4)
+            assert float(pad32[0].min()) == 768.0 and float(pad32[M + 1].max()) == 768.0
+            pad16 = torch.full((M + 2, N), 768.0, device="cuda", dtype=torch.bfloat16)
+            y16 = pad16[1:M + 1]
+            binding.jv_gemm_bias_act(da, dw, db, dr if epi == binding.JV_EPI_RESIDUAL else None, y16, epi)
+            assert torch.equal(y32.to(torch.bfloat16), y16)
+            assert float(pad16[0].float().min()) == 768.0 and float(pad16[M + 1].float().max()) == 768.0
