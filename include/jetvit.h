@@ -237,7 +237,7 @@ jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *
  * jv_gemm_bias_act: y = epilogue(a w^T + bias), a [M, K] bf16 and w [N, K] bf16 both row-major
  * (K contiguous), fp32 accumulation on the matrix cores.  bias is fp32 [N] or NULL.
  *   JV_EPI_NONE      y = acc + bias
- *   JV_EPI_GELU      y = gelu(acc + bias), the exact (erf) GELU, erf to 3e-5 absolute
+ *   JV_EPI_GELU      y = gelu(acc + bias), the exact (erf) GELU x Phi(x), Phi to 5e-6 absolute
  *   JV_EPI_RESIDUAL  y = acc + bias + residual, residual fp32 [M, N] (may be y itself)
  *   JV_EPI_SILU      y = silu(acc + bias), silu(x) = x / (1 + exp(-x))
  * y is [M, N] of y_dtype (JV_BF16 or JV_F32).  K % 64 == 0 and N % 8 == 0 are required

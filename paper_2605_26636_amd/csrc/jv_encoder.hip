@@ -139,18 +139,28 @@ constexpr int kGemmLds = kGemmSlots * kGemmPart;       // 160 KB
 typedef __attribute__((address_space(1))) const void global_cvoid;
 typedef __attribute__((address_space(3))) void lds_void;
 
-// gelu(x) = x/2 (1 + erf(x / sqrt 2)) with erf(z) by Abramowitz-Stegun 7.1.25 (absolute error
-// below 2.5e-5):  erf(z) = 1 - (a1 t + a2 t^2 + a3 t^3) exp(-z^2),  t = 1 / (1 + p z),  z >= 0.
-// Constants are folded so that one scaled argument serves both factors: w = |x| sqrt(log2(e) / 2)
-// gives exp(-z^2) = exp2(-w^2) and p z = p' w.
-__device__ inline float gelu_erf(float x) {
-    const float w = fabsf(x) * 0.8493218002880191f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3916919679f, w, 1.0f));
-    const float poly = t * fmaf(t, fmaf(t, 0.7478556f, -0.0958798f), 0.3480242f);
-    const float e = __builtin_amdgcn_exp2f(-(w * w));
-    const float erf_x = copysignf(fmaf(-poly, e, 1.0f), x);
-    const float h = 0.5f * x;
-    return fmaf(h, erf_x, h);
+// gelu(x) = x Phi(x), Phi the standard normal distribution function.  The GEMM epilogue reads
+// Phi from a table in LDS (kPhiSteps intervals on [-6, 6], linear interpolation: absolute error
+// below 5e-6; outside the range Phi is 0 or 1 to 1e-9) that every workgroup builds for itself
+// from  Phi(x) = 1 - erfc(x / sqrt 2) / 2,  erfc(z) = (a1 t + ... + a5 t^5) exp(-z^2),
+// t = 1 / (1 + p z), z >= 0  (Abramowitz-Stegun 7.1.26, absolute error 1.5e-7).
+constexpr int kPhiSteps = 1024;
+constexpr float kPhiLo = -6.0f, kPhiStep = 12.0f / kPhiSteps;
+__device__ inline float normal_cdf(float x) {
+    const float z = fabsf(x) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+    const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f),
+                                        -0.284496736f), 0.254829592f);
+    const float half_erfc = 0.5f * poly * __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
+    return x < 0.f ? half_erfc : 1.0f - half_erfc;
+}
+// table[2 i] = Phi(x_i), table[2 i + 1] = Phi(x_i+1) - Phi(x_i), x_i = kPhiLo + i kPhiStep.
+__device__ inline float gelu_from_table(float x, const float *table) {
+    const float t = __builtin_amdgcn_fmed3f(fmaf(x, 1.0f / kPhiStep, -kPhiLo / kPhiStep), 0.0f,
+                                            (float)kPhiSteps - 0.004f);
+    const unsigned i = (unsigned)t;
+    const float2 pd = *(const float2 *)(table + 2 * i);
+    return x * fmaf(t - (float)i, pd.y, pd.x);
 }
 
 // Byte offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 LDS part.
@@ -309,6 +319,17 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     // last block occupies two of the five slots, and every wavefront has passed the barrier
     // after which nobody reads the other three (a_slot points at the first of them here).
     unsigned char *stage = smem + next_slot(a_slot, 1 + (wave >> 2)) * kGemmPart + (wave & 3) * 8192;
+    // GELU reads the normal distribution function from a table in the third free slot, built
+    // here by all threads (two or three entries each; see gelu_from_table).
+    float *phi_table = (float *)(smem + a_slot * kGemmPart);
+    if (EPI == JV_EPI_GELU) {
+        for (int i = tid; i <= kPhiSteps; i += 512) {
+            const float p0 = normal_cdf(kPhiLo + (float)i * kPhiStep);
+            phi_table[2 * i] = p0;
+            phi_table[2 * i + 1] = normal_cdf(kPhiLo + (float)(i + 1) * kPhiStep) - p0;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
     f32x4 bias_reg[2][4];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
@@ -359,7 +380,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                 val += bias_reg[nt][q4];
                 if (EPI == JV_EPI_GELU) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) val[e] = gelu_erf(val[e]);
+                    for (int e = 0; e < 4; ++e) val[e] = gelu_from_table(val[e], phi_table);
                 }
                 if (EPI == JV_EPI_SILU) {
 #pragma unroll
