@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--la-ablation", action="store_true",
                     help="time the linear-attention block variants of the paper's Tab. 1 in a pure "
                          "linear-attention ViT-L and print their ratios")
+    ap.add_argument("--gemm", action="store_true",
+                    help="time the encoder's four GEMM shapes alone (this library, and the vendor "
+                         "library's plain GEMM through torch as a reference point)")
     ap.add_argument("--sweep", action="store_true",
                     help="time linear, window 16x16 (and full, up to 16 384 tokens) attention over the "
                          "token-count sweep at 32 768 tokens per call: 1 024 ... 65 536 tokens per image")
@@ -94,6 +97,9 @@ def main():
         return
     if args.sweep:
         print(json.dumps(bench_sweep(args.steps, args.warmup, args.buffers)))
+        return
+    if args.gemm:
+        print(json.dumps(bench_gemm(args.steps, args.warmup)))
         return
     if args.paper_ratio:
         print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model, args.graph)))
@@ -360,6 +366,48 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
             "data": "synthetic", "hip_graph": bool(graph), "ms": ms, "speedup_vs_all_full": {k: base / v for k, v in ms.items()},
             "paper_context_h100": {"DINOv3-L -> JetViT-L (2 full-attention blocks), whole model": "35.07 ms -> 18.77 ms (1.87x)",
                                    "DINOv3-B -> JetViT-B 0/1/2 full-attention blocks": "12.86 ms -> 7.37 / 7.69 / 8.27 ms"}}
+
+
+def bench_gemm(steps, warmup):
+    """The four GEMMs of a ViT-L block at 16 384 tokens (batch 4, 64x64 grid), each alone, same
+    buffers every launch (operands warm in the last-level cache, as inside the encoder): QKV
+    (bias), fc1 (bias + GELU), output projection and fc2 (bias + fp32 residual, fp32 out).  The
+    vendor library's plain bf16 GEMM (torch.nn.functional.linear: no GELU, no residual) is timed
+    on the same shapes as a reference point."""
+    import torch
+    from paper_2605_26636_amd import binding
+    M = 16384
+    shapes = [("qkv", 3072, 1024, binding.JV_EPI_NONE), ("fc1_gelu", 4096, 1024, binding.JV_EPI_GELU),
+              ("proj_residual", 1024, 1024, binding.JV_EPI_RESIDUAL), ("fc2_residual", 1024, 4096, binding.JV_EPI_RESIDUAL)]
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    out = {}
+    for name, N, K, epi in shapes:
+        a = torch.randn(M, K, device="cuda", generator=gen).to(torch.bfloat16)
+        w = (torch.randn(N, K, device="cuda", generator=gen) / K ** 0.5).to(torch.bfloat16)
+        bias = torch.zeros(N, device="cuda")
+        res = torch.zeros(M, N, device="cuda") if epi == binding.JV_EPI_RESIDUAL else None
+        y = torch.empty(M, N, device="cuda", dtype=torch.float32 if res is not None else torch.bfloat16)
+
+        def timed(fn):
+            for _ in range(warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+        ms = timed(lambda: binding.jv_gemm_bias_act(a, w, bias, res, y, epi))
+        ms_ref = timed(lambda: torch.nn.functional.linear(a, w))
+        flops = 2.0 * M * N * K
+        out[name] = {"M": M, "N": N, "K": K, "us": ms * 1e3, "TFLOPs": flops / (ms * 1e-3) / 1e12,
+                     "mfma_frac": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "vendor_plain_gemm_us": ms_ref * 1e3, "vendor_plain_gemm_TFLOPs": flops / (ms_ref * 1e-3) / 1e12}
+    return {"metric": "GEMMs of a ViT-L block at 16 384 tokens, each alone", "unit": "us", "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "dtype": "bf16", "data": "synthetic", "gemm": out}
 
 
 def bench_sweep(steps, warmup, buffers):
