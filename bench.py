@@ -113,7 +113,7 @@ def main():
             "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": enc["workload"]},
             "roofline": {"bound": "mfma", "achieved": enc["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": enc["mfma_frac"], "traffic": None},
+                         "unit": "TFLOP/s", "frac": enc["mfma_frac"], "traffic": read_traffic().get("encoder")},
             "encoder": enc, "cpu_baseline": None}))
         return
     c = synth.CONFIGS[args.config]
@@ -231,7 +231,7 @@ def main():
         encoder = bench_encoder(10, 3)
         rooflines["encoder"] = {"kernel": "gemm_bf16_kernel (+ mixers, LayerNorm)", "bound": "mfma",
                                 "achieved": encoder["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                                "unit": "TFLOP/s", "frac": encoder["mfma_frac"], "traffic": None}
+                                "unit": "TFLOP/s", "frac": encoder["mfma_frac"], "traffic": traffic.get("encoder")}
 
     cpu = None
     if not args.no_cpu_baseline:
