@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--la-ablation", action="store_true",
                     help="time the linear-attention block variants of the paper's Tab. 1 in a pure "
                          "linear-attention ViT-L and print their ratios")
+    ap.add_argument("--stream-bf16", action="store_true",
+                    help="--encoder: carry the residual stream in bf16 instead of fp32")
     ap.add_argument("--gemm", action="store_true",
                     help="time the encoder's four GEMM shapes alone (this library, and the vendor "
                          "library's plain GEMM through torch as a reference point)")
@@ -105,7 +107,7 @@ def main():
         print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model, args.graph)))
         return
     if args.encoder:
-        enc = bench_encoder(args.steps, args.warmup)
+        enc = bench_encoder(args.steps, args.warmup, args.stream_bf16)
         print(json.dumps({
             "metric": "hybrid ViT-L encoder forward, tokens/s per encoder",
             "value": enc["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -229,6 +231,8 @@ def main():
         del sets, base
         torch.cuda.empty_cache()
         encoder = bench_encoder(10, 3)
+        encoder["bf16_residual_stream"] = {k: v for k, v in bench_encoder(10, 3, stream_bf16=True).items()
+                                           if k in ("ms_per_encoder", "tokens_per_s", "TFLOPs", "mfma_frac")}
         rooflines["encoder"] = {"kernel": "gemm_bf16_kernel (+ mixers, LayerNorm)", "bound": "mfma",
                                 "achieved": encoder["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
                                 "unit": "TFLOP/s", "frac": encoder["mfma_frac"], "traffic": traffic.get("encoder")}
@@ -253,10 +257,11 @@ def main():
     print(json.dumps(out))
 
 
-def bench_encoder(steps, warmup):
+def bench_encoder(steps, warmup, stream_bf16=False):
     """Config 5: 24 pre-LN blocks of width 1024 (16 heads, MLP 4096), batch 4 on a 64x64 grid;
     full attention at blocks 5, 11, 17, 23, window 16x16 at the other even blocks, linear
-    attention at the rest.  Random-init (Xavier-normal, seeded) bf16 weights, fp32 residual."""
+    attention at the rest.  Random-init (Xavier-normal, seeded) bf16 weights; the residual stream
+    in fp32, or in bf16 with stream_bf16 (what a network converted to bf16 as a whole carries)."""
     import torch
     from paper_2605_26636_amd import binding, synth
     B, H, W, heads, hidden, L = 4, 64, 64, 16, 4096, 24
@@ -267,8 +272,9 @@ def bench_encoder(steps, warmup):
         wts = synth.block_weights(C, hidden, 5000 + l)
         blocks.append({k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_")
                            else torch.from_numpy(v).cuda()) for k, v in wts.items()})
-    enc = binding.Encoder(blocks, pattern, heads, hidden, window=(16, 16))
-    x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda()
+    sd = torch.bfloat16 if stream_bf16 else torch.float32
+    enc = binding.Encoder(blocks, pattern, heads, hidden, window=(16, 16), stream_dtype=sd)
+    x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda().to(sd)
     y = torch.empty_like(x)
     ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
@@ -289,7 +295,8 @@ def bench_encoder(steps, warmup):
     flops = gemm_flops + mix_flops
     tf = flops / (ms * 1e-3) / 1e12
     return {"workload": f"config5: 24-block hybrid ViT-L encoder, B{B} {H}x{W} grid, width {C}, "
-                        f"{n_full} full / {n_win} window16x16 / {n_lin} linear blocks",
+                        f"{n_full} full / {n_win} window16x16 / {n_lin} linear blocks, "
+                        f"{'bf16' if stream_bf16 else 'fp32'} residual stream",
             "ms_per_encoder": ms, "ms_per_layer": ms / L, "tokens_per_s": T / (ms * 1e-3),
             "steps": steps, "warmup": warmup, "flops_per_encoder": flops, "gemm_flops": gemm_flops,
             "TFLOPs": tf, "mfma_frac": tf / MFMA_BF16_PEAK_TFLOPS}
@@ -371,22 +378,24 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
 def bench_gemm(steps, warmup):
     """The four GEMMs of a ViT-L block at 16 384 tokens (batch 4, 64x64 grid), each alone, same
     buffers every launch (operands warm in the last-level cache, as inside the encoder): QKV
-    (bias), fc1 (bias + GELU), output projection and fc2 (bias + fp32 residual, fp32 out).  The
+    (bias), fc1 (bias + GELU), output projection and fc2 (bias + residual, in fp32 and in bf16).  The
     vendor library's plain bf16 GEMM (torch.nn.functional.linear: no GELU, no residual) is timed
     on the same shapes as a reference point."""
     import torch
     from paper_2605_26636_amd import binding
     M = 16384
     shapes = [("qkv", 3072, 1024, binding.JV_EPI_NONE), ("fc1_gelu", 4096, 1024, binding.JV_EPI_GELU),
-              ("proj_residual", 1024, 1024, binding.JV_EPI_RESIDUAL), ("fc2_residual", 1024, 4096, binding.JV_EPI_RESIDUAL)]
+              ("proj_residual", 1024, 1024, binding.JV_EPI_RESIDUAL), ("fc2_residual", 1024, 4096, binding.JV_EPI_RESIDUAL),
+              ("proj_residual_bf16", 1024, 1024, binding.JV_EPI_RESIDUAL), ("fc2_residual_bf16", 1024, 4096, binding.JV_EPI_RESIDUAL)]
     gen = torch.Generator(device="cuda").manual_seed(5)
     out = {}
     for name, N, K, epi in shapes:
         a = torch.randn(M, K, device="cuda", generator=gen).to(torch.bfloat16)
         w = (torch.randn(N, K, device="cuda", generator=gen) / K ** 0.5).to(torch.bfloat16)
         bias = torch.zeros(N, device="cuda")
-        res = torch.zeros(M, N, device="cuda") if epi == binding.JV_EPI_RESIDUAL else None
-        y = torch.empty(M, N, device="cuda", dtype=torch.float32 if res is not None else torch.bfloat16)
+        rd = torch.bfloat16 if name.endswith("_bf16") else torch.float32      # residual and output alike
+        res = torch.zeros(M, N, device="cuda", dtype=rd) if epi == binding.JV_EPI_RESIDUAL else None
+        y = torch.empty(M, N, device="cuda", dtype=rd if res is not None else torch.bfloat16)
 
         def timed(fn):
             for _ in range(warmup):

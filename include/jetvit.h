@@ -238,7 +238,8 @@ jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *
  * (K contiguous), fp32 accumulation on the matrix cores.  bias is fp32 [N] or NULL.
  *   JV_EPI_NONE      y = acc + bias
  *   JV_EPI_GELU      y = gelu(acc + bias), the exact (erf) GELU x Phi(x), Phi to 5e-6 absolute
- *   JV_EPI_RESIDUAL  y = acc + bias + residual, residual fp32 [M, N] (may be y itself)
+ *   JV_EPI_RESIDUAL  y = acc + bias + residual, residual [M, N] of y's element type (may be y
+ *                    itself); the sum is formed in fp32 and rounded once
  *   JV_EPI_SILU      y = silu(acc + bias), silu(x) = x / (1 + exp(-x))
  * y is [M, N] of y_dtype (JV_BF16 or JV_F32).  K % 64 == 0 and N % 8 == 0 are required
  * (JV_ERR_UNSUPPORTED otherwise); M is arbitrary.  All pointers device, 16-byte aligned.
@@ -248,7 +249,7 @@ typedef enum { JV_EPI_NONE = 0, JV_EPI_GELU = 1, JV_EPI_RESIDUAL = 2, JV_EPI_SIL
 jv_status jv_layernorm_fwd(const void *x, const float *gamma, const float *beta, void *y,
                            int64_t rows, int32_t cols, float eps, jv_dtype x_dtype,
                            jv_dtype y_dtype, void *hip_stream);
-jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, const float *residual,
+jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, const void *residual,
                            void *y, int64_t M, int32_t N, int32_t K, jv_epilogue epilogue,
                            jv_dtype y_dtype, void *hip_stream);
 
@@ -258,7 +259,10 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  *     a = LN(x; ln1);  [Q K V] = a W_qkv^T + b_qkv, split into heads of 64;
  *     x += mix_{pattern[l]}(Q, K, V) W_o^T + b_o;
  *     x += gelu(LN(x; ln2) W_fc1^T + b_fc1) W_fc2^T + b_fc2.
- * The residual stream x is fp32; GEMM operands and the tensors between kernels are bf16.
+ * The residual stream x is fp32 (stream_dtype JV_F32, the default) or bf16 (JV_BF16: what a
+ * network converted to bf16 as a whole carries; every block then rounds the stream twice, and
+ * each residual GEMM and LayerNorm moves half the bytes); GEMM operands and the tensors between
+ * kernels are bf16.
  * No final norm: the output is the residual stream after the last block.
  *
  * jv_encoder_create copies the configuration and the table of weight POINTERS into a host
@@ -270,7 +274,8 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * w_fc2 bf16 [width, mlp_hidden], b_fc2 fp32.  width = heads * 64, width and mlp_hidden
  * multiples of 64.
  *
- * jv_encoder_forward: x and y are device fp32 [batch, n_prefix + grid_h*grid_w, width] (y may be x);
+ * jv_encoder_forward: x and y are device [batch, n_prefix + grid_h*grid_w, width] of stream_dtype
+ * (y may be x);
  * workspace is device memory of at least jv_encoder_workspace_bytes(...) bytes, 256-byte
  * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.
  *
@@ -278,7 +283,7 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * chosen blocks, which is what a dense-prediction head attached to the encoder reads (the
  * paper's depth and segmentation heads take features of four intermediate layers, Sec. 4.1
  * and 4.2).  tap_blocks is a host array of n_taps block indices (0-based, strictly increasing,
- * each < n_blocks); tap_out is a host array of n_taps device pointers, each fp32
+ * each < n_blocks); tap_out is a host array of n_taps device pointers, each of stream_dtype,
  * [batch, grid_h*grid_w, width], 16-byte aligned, distinct from each other and from x and y.
  * tap_out[i] receives the stream after block tap_blocks[i].  The block's last GEMM writes
  * there directly and the next block reads it from there, so a tap costs no extra pass over the
@@ -296,6 +301,7 @@ typedef struct {
     int32_t n_prefix;       /* prefix tokens in front of the grid tokens of every image, 0 .. 64
                                (see "Prefix tokens" at jv_attn_desc); x and y are then
                                [batch, n_prefix + grid_h*grid_w, width] */
+    jv_dtype stream_dtype;  /* element type of the residual stream: x, y and the taps */
 } jv_encoder_config;
 
 typedef struct {
@@ -317,12 +323,12 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
                             jv_encoder **out);
 size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
                                   int32_t grid_w);
-jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
                              int32_t grid_h, int32_t grid_w, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
-jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y, int32_t batch,
                                   int32_t grid_h, int32_t grid_w, int32_t n_taps,
-                                  const int32_t *tap_blocks, float *const *tap_out,
+                                  const int32_t *tap_blocks, void *const *tap_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 void jv_encoder_destroy(jv_encoder *enc);
 

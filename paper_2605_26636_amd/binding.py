@@ -53,7 +53,7 @@ class JvEncoderConfig(ctypes.Structure):
                 ("mlp_hidden", ctypes.c_int32), ("win_h", ctypes.c_int32), ("win_w", ctypes.c_int32),
                 ("ln_eps", ctypes.c_float), ("la_eps", ctypes.c_float),
                 ("pattern", ctypes.POINTER(ctypes.c_uint8)), ("la_focus_p", ctypes.c_int32),
-                ("n_prefix", ctypes.c_int32)]
+                ("n_prefix", ctypes.c_int32), ("stream_dtype", ctypes.c_int32)]
 
 
 BLOCK_FIELDS = ["ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_fc1", "b_fc1",
@@ -296,7 +296,7 @@ def jv_layernorm_fwd(x, gamma, beta, y, eps=1e-6, stream=None):
 
 def jv_gemm_bias_act(a, w, bias, residual, y, epilogue=JV_EPI_NONE, stream=None):
     """y <- epilogue(a w^T + bias); a bf16 [M, K], w bf16 [N, K], bias fp32 [N] or None,
-    residual fp32 [M, N] or None, y bf16 or fp32 [M, N]."""
+    y bf16 or fp32 [M, N], residual None or [M, N] of y's element type."""
     M, K = a.shape
     N = w.shape[0]
     if w.shape[1] != K or tuple(y.shape) != (M, N):
@@ -306,6 +306,9 @@ def jv_gemm_bias_act(a, w, bias, residual, y, epilogue=JV_EPI_NONE, stream=None)
             raise ValueError("operands must be contiguous")
     if a.dtype != torch.bfloat16 or w.dtype != torch.bfloat16:
         raise TypeError("a and w must be bf16")
+    if residual is not None and (residual.dtype != y.dtype or tuple(residual.shape) != (M, N)
+                                 or not residual.is_contiguous()):
+        raise TypeError("residual must be a contiguous [M, N] tensor of y's element type")
     _check(lib().jv_gemm_bias_act(a.data_ptr(), w.data_ptr(),
                                   None if bias is None else bias.data_ptr(),
                                   None if residual is None else residual.data_ptr(), y.data_ptr(),
@@ -317,13 +320,17 @@ class Encoder:
     weights bf16, biases and LayerNorm parameters fp32); the tensors are kept alive here."""
 
     def __init__(self, blocks, pattern, heads, mlp_hidden, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
-                 la_focus_p=1, n_prefix=0):
+                 la_focus_p=1, n_prefix=0, stream_dtype=torch.float32):
         self.blocks = blocks
         self.width = blocks[0]["w_o"].shape[0]
         n = len(blocks)
         self._pattern = (ctypes.c_uint8 * n)(*pattern)
         cfg = JvEncoderConfig(n, self.width, heads, mlp_hidden, window[0], window[1], ln_eps, la_eps,
-                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)), la_focus_p, n_prefix)
+                              ctypes.cast(self._pattern, ctypes.POINTER(ctypes.c_uint8)), la_focus_p, n_prefix,
+                              JV_BF16 if stream_dtype == torch.bfloat16 else JV_F32)
+        if stream_dtype not in (torch.float32, torch.bfloat16):
+            raise TypeError("the residual stream is fp32 or bf16")
+        self.stream_dtype = stream_dtype
         table = (JvBlockWeights * n)()
         self._dwc = []   # parameter structs stay alive until the encoder has copied them
         for i, b in enumerate(blocks):
@@ -343,12 +350,13 @@ class Encoder:
         return int(lib().jv_encoder_workspace_bytes(self._handle, batch, grid[0], grid[1]))
 
     def forward(self, x, y, grid, workspace=None, stream=None, taps=None):
-        """y <- encoder(x); x, y fp32 [batch, N, width] on the GPU; returns the workspace used.
-        taps: optional dict {block index: fp32 tensor like y} that receives the residual stream
-        after those blocks (jv_encoder_forward_taps)."""
+        """y <- encoder(x); x, y [batch, N, width] of the stream's element type on the GPU; returns
+        the workspace used.  taps: optional dict {block index: tensor like y} that receives the
+        residual stream after those blocks (jv_encoder_forward_taps)."""
         batch = x.shape[0]
-        if x.dtype != torch.float32 or y.dtype != torch.float32 or not x.is_contiguous() or not y.is_contiguous():
-            raise ValueError("x and y must be contiguous fp32")
+        sd = self.stream_dtype
+        if x.dtype != sd or y.dtype != sd or not x.is_contiguous() or not y.is_contiguous():
+            raise ValueError("x and y must be contiguous tensors of the stream's element type")
         if workspace is None:
             workspace = torch.empty(self.workspace_bytes(batch, grid), dtype=torch.uint8, device=x.device)
         if not taps:
@@ -359,8 +367,8 @@ class Encoder:
         order = sorted(taps)
         for l in order:
             t = taps[l]
-            if t.dtype != torch.float32 or not t.is_contiguous() or t.shape != y.shape:
-                raise ValueError("tap tensors must be contiguous fp32 of the shape of y")
+            if t.dtype != sd or not t.is_contiguous() or t.shape != y.shape:
+                raise ValueError("tap tensors must be contiguous, of the type and shape of y")
         blocks = (ctypes.c_int32 * len(order))(*order)
         outs = (ctypes.c_void_p * len(order))(*[taps[l].data_ptr() for l in order])
         _check(lib().jv_encoder_forward_taps(self._handle, x.data_ptr(), y.data_ptr(), batch, grid[0],

@@ -81,7 +81,7 @@ jv_status full_forward(const Problem &pr, float scale, hipStream_t stream);
 
 // y = epilogue(a w^T + bias) on the matrix cores (see jv_gemm_bias_act); lda: elements between
 // rows of a (0 = K, i.e. contiguous rows), a multiple of 8.
-jv_status gemm_forward(const void *a, const void *w, const float *bias, const float *residual,
+jv_status gemm_forward(const void *a, const void *w, const float *bias, const void *residual,
                        void *y, long long M, int N, int K, int epi, bool out_bf16,
                        hipStream_t stream, long long lda = 0);
 

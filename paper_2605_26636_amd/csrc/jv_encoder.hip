@@ -181,7 +181,7 @@ __device__ inline void wait_loads_and_barrier(int pending) {
 template <int EPI, bool OUT_BF16>
 __global__ void __launch_bounds__(512, 1)
 gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
-                 const float *__restrict__ bias, const float *residual, void *Y, int M, int N,
+                 const float *__restrict__ bias, const void *residual, void *Y, int M, int N,
                  int K, int lda, int tiles_n, int n_tiles) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
@@ -339,7 +339,10 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             bias_reg[nt][q4] = (bias && col < N) ? *(const f32x4 *)(bias + col) : zero;
         }
-    constexpr bool kRowResidual = EPI == JV_EPI_RESIDUAL && !OUT_BF16;  // added in the row layout
+    // The residual has y's element type and is added in the row layout; with bf16 tensors the
+    // blocks are staged in fp32 all the same, so that the sum is rounded once.
+    constexpr bool kResidual = EPI == JV_EPI_RESIDUAL;
+    constexpr bool kStageF32 = !OUT_BF16 || kResidual;
     // Row layout of the fp32 tile: 16 lanes per token row (256 bytes), 4 rows per instruction.
     const int frow = lane >> 4, fchunk = lane & 15;
     const int fcol = n0 + wn * 64 + 4 * fchunk;
@@ -347,30 +350,25 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     // rows, so this is safe although the residual may be y itself): one round trip is exposed
     // instead of four.
     f32x4 res_reg[2][8];
+    u32x2 res16_reg[2][8];
     auto load_residual = [&](int mt, int set) {
-        if (kRowResidual) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const int row = m0 + wm * 128 + mt * 32 + 4 * r + frow;
+        for (int r = 0; r < 8; ++r) {
+            const int row = m0 + wm * 128 + mt * 32 + 4 * r + frow;
+            const bool inside = row < M && fcol < N;
+            if (OUT_BF16) {
+                u32x2 zero = {0u, 0u};
+                res16_reg[set][r] = inside ? *(const u32x2 *)((const __bf16 *)residual + (size_t)row * N + fcol) : zero;
+            } else {
                 f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                res_reg[set][r] = (row < M && fcol < N) ? *(const f32x4 *)(residual + (size_t)row * N + fcol) : zero;
+                res_reg[set][r] = inside ? *(const f32x4 *)((const float *)residual + (size_t)row * N + fcol) : zero;
             }
-        } else {  // accumulator layout (bf16 output with a residual: not a shape the encoder uses)
-            const int row = m0 + wm * 128 + mt * 32 + li;
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
-                    f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                    res_reg[set][4 * nt + q4] = (row < M && col < N) ? *(const f32x4 *)(residual + (size_t)row * N + col) : zero;
-                }
         }
     };
-    if (EPI == JV_EPI_RESIDUAL) load_residual(0, 0);
+    if (kResidual) load_residual(0, 0);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-        if (EPI == JV_EPI_RESIDUAL && mt + 1 < 4) load_residual(mt + 1, (mt + 1) & 1);
+        if (kResidual && mt + 1 < 4) load_residual(mt + 1, (mt + 1) & 1);
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -386,15 +384,14 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
                     for (int e = 0; e < 4; ++e) val[e] = val[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-val[e]));
                 }
-                if (EPI == JV_EPI_RESIDUAL && !kRowResidual) val += res_reg[mt & 1][4 * nt + q4];
-                if (OUT_BF16) {
+                if (kStageF32) {
+                    *(f32x4 *)(stage + li * 256 + (((8 * nt + 2 * q4 + g) ^ (li & 15)) << 4)) = val;
+                } else {
                     u32x2 pk = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
                     *(u32x2 *)(stage + tile_off_row(li, 4 * nt + q4) + 8 * g) = pk;
-                } else {
-                    *(f32x4 *)(stage + li * 256 + (((8 * nt + 2 * q4 + g) ^ (li & 15)) << 4)) = val;
                 }
             }
-        if (OUT_BF16) {  // 8 lanes per token row (128 bytes), 8 rows per instruction
+        if (!kStageF32) {  // 8 lanes per token row (128 bytes), 8 rows per instruction
             const int col = n0 + wn * 64 + 8 * (lane & 7);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -408,15 +405,22 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             for (int r = 0; r < 8; ++r) {
                 const int orow = 4 * r + frow, row = m0 + wm * 128 + mt * 32 + orow;
                 f32x4 out = *(const f32x4 *)(stage + orow * 256 + ((fchunk ^ (orow & 15)) << 4));
-                if (kRowResidual) out += res_reg[mt & 1][r];
-                if (row < M && fcol < N) *(f32x4 *)((float *)Y + (size_t)row * N + fcol) = out;
+                if (OUT_BF16) {  // bf16 tensors with a residual: 16 lanes x 8 bytes = one 128-byte row
+                    const u32x2 rr = res16_reg[mt & 1][r];
+                    u32x2 pk = {pack_bf16x2(out[0] + bf16_lo(rr[0]), out[1] + bf16_hi(rr[0])),
+                                pack_bf16x2(out[2] + bf16_lo(rr[1]), out[3] + bf16_hi(rr[1]))};
+                    if (row < M && fcol < N) *(u32x2 *)((__bf16 *)Y + (size_t)row * N + fcol) = pk;
+                } else {
+                    if (kResidual) out += res_reg[mt & 1][r];
+                    if (row < M && fcol < N) *(f32x4 *)((float *)Y + (size_t)row * N + fcol) = out;
+                }
             }
         }
     }
 }
 
 template <int EPI, bool OUT_BF16>
-static jv_status launch_gemm(const void *a, const void *w, const float *bias, const float *residual,
+static jv_status launch_gemm(const void *a, const void *w, const float *bias, const void *residual,
                              void *y, long long M, int N, int K, int lda, hipStream_t stream) {
     static LdsLimit lds_limit;
     jv_status st = ensure_lds_limit(lds_limit, (const void *)gemm_bf16_kernel<EPI, OUT_BF16>, kGemmLds);
@@ -430,7 +434,7 @@ static jv_status launch_gemm(const void *a, const void *w, const float *bias, co
     return launch_status("gemm_bf16_kernel");
 }
 
-jv_status gemm_forward(const void *a, const void *w, const float *bias, const float *residual,
+jv_status gemm_forward(const void *a, const void *w, const float *bias, const void *residual,
                        void *y, long long M, int N, int K, int epi, bool out_bf16,
                        hipStream_t stream, long long lda_arg) {
     if (M <= 0 || N <= 0 || K <= 0) return fail(JV_ERR_INVALID_ARG, "M, N, K must be positive");
@@ -518,7 +522,7 @@ jv_status jv_layernorm_fwd(const void *x, const float *gamma, const float *beta,
                                  y_dtype == JV_BF16, (hipStream_t)hip_stream);
 }
 
-jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, const float *residual,
+jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, const void *residual,
                            void *y, int64_t M, int32_t N, int32_t K, jv_epilogue epilogue,
                            jv_dtype y_dtype, void *hip_stream) {
     jv::clear_error();
@@ -542,6 +546,7 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
     if (!(c.ln_eps >= 0.f) || !(c.la_eps >= 0.f)) return jv::fail(JV_ERR_INVALID_ARG, "bad epsilon");
     if (c.la_focus_p < 0 || c.la_focus_p > 16) return jv::fail(JV_ERR_INVALID_ARG, "la_focus_p must be 0 .. 16");
     if (c.n_prefix < 0 || c.n_prefix > 64) return jv::fail(JV_ERR_INVALID_ARG, "n_prefix must be 0 .. 64");
+    if (c.stream_dtype != JV_F32 && c.stream_dtype != JV_BF16) return jv::fail(JV_ERR_INVALID_ARG, "bad stream_dtype");
     for (int l = 0; l < c.n_blocks; ++l) {
         if (c.pattern[l] > 2) return jv::fail(JV_ERR_INVALID_ARG, "pattern[%d] is not 0, 1 or 2", l);
         const jv_block_weights &b = blocks[l];
@@ -601,16 +606,16 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
            jv::align256(jv::encoder_linear_workspace(enc, batch, enc->cfg.n_prefix + grid_h * grid_w));
 }
 
-jv_status jv_encoder_forward(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
                              int32_t grid_h, int32_t grid_w, void *workspace,
                              size_t workspace_bytes, void *hip_stream) {
     return jv_encoder_forward_taps(enc, x, y, batch, grid_h, grid_w, 0, nullptr, nullptr, workspace,
                                    workspace_bytes, hip_stream);
 }
 
-jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *y, int32_t batch,
+jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y, int32_t batch,
                                   int32_t grid_h, int32_t grid_w, int32_t n_taps,
-                                  const int32_t *tap_blocks, float *const *tap_out,
+                                  const int32_t *tap_blocks, void *const *tap_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
     jv::clear_error();
     if (!enc || !x || !y || !workspace) return jv::fail(JV_ERR_INVALID_ARG, "null argument");
@@ -655,11 +660,12 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *
     pr.o = {narrow, (long long)N * C, jv::kHeadDim, C};
 
     jv_status st;
-    const float *resid = x;  // the first residual add reads the input and writes y
+    const bool s16 = c.stream_dtype == JV_BF16;  // element type of the residual stream
+    const void *resid = x;  // the first residual add reads the input and writes y
     int next_tap = 0;
     for (int l = 0; l < c.n_blocks; ++l) {
         const jv_block_weights &b = enc->blocks[l];
-        if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
+        if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
         if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
         switch (enc->pattern[l]) {
             case 0:
@@ -670,16 +676,16 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const float *x, float *
             default: st = jv::full_forward(pr, 0.f, stream); break;
         }
         if (st != JV_OK) return st;
-        if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
-        if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, false, true, stream)) != JV_OK) return st;
+        if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
+        if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
         if ((st = jv::gemm_forward(narrow, b.w_fc1, b.b_fc1, nullptr, widebuf, T, c.mlp_hidden, C, JV_EPI_GELU, true, stream)) != JV_OK) return st;
         // A tapped block leaves its result in the tap buffer and the next block picks the stream
         // up from there; the last block's result has to be in y as well.
         const bool tapped = next_tap < n_taps && tap_blocks[next_tap] == l;
-        float *out = tapped && l + 1 < c.n_blocks ? tap_out[next_tap] : y;
-        if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, false, stream)) != JV_OK) return st;
+        void *out = tapped && l + 1 < c.n_blocks ? tap_out[next_tap] : y;
+        if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
         if (tapped && out == y) {
-            hipError_t e = hipMemcpyAsync(tap_out[next_tap], y, (size_t)T * C * sizeof(float), hipMemcpyDeviceToDevice, stream);
+            hipError_t e = hipMemcpyAsync(tap_out[next_tap], y, (size_t)T * C * (s16 ? 2 : 4), hipMemcpyDeviceToDevice, stream);
             if (e != hipSuccess) return jv::fail(JV_ERR_HIP, "hipMemcpyAsync: %s", hipGetErrorString(e));
         }
         if (tapped) ++next_tap;
