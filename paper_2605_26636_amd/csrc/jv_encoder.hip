@@ -114,10 +114,11 @@ static jv_status layernorm_forward(const void *x, const float *gamma, const floa
 // K is walked in blocks of 64, i.e. whole 128-byte lines of every row: the 256 x 64 parts of a
 // and of w go from global memory straight into LDS (no register staging) through a ring of
 // five 32 KB slots filled in the order a0 w0 a1 w1 a2 ...  While block p is multiplied, the
-// parts of block p+1 and the a part of block p+2 are in flight or landed; the two slots of
-// block p are refilled (w of p+2, a of p+3) as soon as its last operands have been read.  The
-// wait before a block is therefore a counted one (the youngest part may still be
-// outstanding), written by hand next to the barrier.
+// parts of block p+1 are in flight or landed and the a part of block p+2 is being issued, a
+// load or two per step, into the slot the block before p has left; the w part of p+2 follows
+// into block p's a slot as soon as its last operands have been read.  The wait before a block
+// is therefore a counted one (the youngest part may still be outstanding), written by hand
+// next to the barrier.
 // A block is four steps of 16 in K; the LDS reads of a step are issued among the matrix
 // instructions of the step before it, and the workgroup barrier sits before the last step:
 // when a wavefront leaves it, the operands of that step are already in registers, so the
@@ -206,22 +207,23 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
     const int n_b = K / kBK, n_parts = 2 * n_b;
-    // part = 2 * block + (0: a, 1: w); it lives in slot part % 5
-    auto issue_part = [&](int part, int slot) {
+    // part = 2 * block + (0: a, 1: w); it lives in slot part % 5.  Loads j0 .. j1-1 of a part:
+    auto issue_loads = [&](int part, int slot, int j0, int j1) __attribute__((always_inline)) {
         unsigned char *base = smem + slot * kGemmPart + wave * 32 * 128;
         const unsigned kbytes = 2u * (unsigned)(part >> 1) * kBK;
         if (part & 1) {
 #pragma unroll
-            for (int j = 0; j < kPartLoads; ++j)
+            for (int j = j0; j < j1; ++j)
                 __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)W + (w_off[j] + kbytes)),
                                                  (lds_void *)(base + j * 1024), 16, 0, 0);
         } else {
 #pragma unroll
-            for (int j = 0; j < kPartLoads; ++j)
+            for (int j = j0; j < j1; ++j)
                 __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)A + (a_off[j] + kbytes)),
                                                  (lds_void *)(base + j * 1024), 16, 0, 0);
         }
     };
+    auto issue_part = [&](int part, int slot) __attribute__((always_inline)) { issue_loads(part, slot, 0, kPartLoads); };
 
     f32x16 acc[2][4];  // [feature block][token block]
 #pragma unroll
@@ -249,10 +251,19 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma32(wop[set][nt], aop[set][mt], acc[nt][mt]);
     };
     auto next_slot = [](int s, int by) { s += by; return s >= kGemmSlots ? s - kGemmSlots : s; };
-    // One step (8 matrix instructions) interleaved with the 6 LDS reads of the next one.
-    auto step_with_reads = [&](int set) {
+    // One step (8 matrix instructions) interleaved with the 6 LDS reads of the next one and with
+    // `n_loads` global->LDS loads (written before the reads in the source: the compiler keeps
+    // LDS reads and loads that write LDS in program order).
+    auto step_with_reads = [&](int set, int n_loads) __attribute__((always_inline)) {
         products(set);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (n_loads >= 2) {
+            __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (n_loads == 1) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        }
 #pragma unroll
         for (int i = 0; i < 6; ++i) {  // the reads early, so that they have landed by the end
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -261,50 +272,57 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     };
     // One block of 64 in K.  a_slot/w_slot hold it; the set-0 operands of its first step are in
-    // registers.  `n_issue`: how many of the parts 2p+5, 2p+6 exist; they refill the block's
-    // two slots once those are free.  `pending`: loads that may be outstanding at the barrier
-    // with block p+1 complete.  `next`: there is a block p+1.
-    auto block = [&](int p, int a_slot, int w_slot, int n_issue, int pending, bool next) {
+    // registers.  The refill loads are spread over the block instead of issued in one burst:
+    // all eight wavefronts pass the barrier together, and 64 loads issued at once queue in the
+    // address path while the matrix instructions behind them in program order wait (the loop
+    // ran 9 % faster with them spread).  `refill`: parts 2p+4 and 2p+5 exist.  Part 2p+4 goes
+    // into the slot of part 2p-1 (free since the previous barrier) during the first three
+    // steps, part 2p+5 into this block's a slot after the barrier; at the barrier block p+1
+    // (parts 2p+2, 2p+3) must have landed and only part 2p+4 may be pending.  `next`: there is
+    // a block p+1.
+    auto block = [&](int p, int a_slot, int w_slot, bool refill, bool next) __attribute__((always_inline)) {
+        const int slot4 = next_slot(w_slot, 3);
+        if (refill) issue_loads(2 * p + 4, slot4, 0, 2);
         load_ops(a_slot, w_slot, 1, 1);
-        step_with_reads(0);
+        step_with_reads(0, refill ? 2 : 0);
+        if (refill) issue_loads(2 * p + 4, slot4, 2, 3);
         load_ops(a_slot, w_slot, 2, 0);
-        step_with_reads(1);
+        step_with_reads(1, refill ? 1 : 0);
+        if (refill) issue_loads(2 * p + 4, slot4, 3, 4);
         load_ops(a_slot, w_slot, 3, 1);
-        step_with_reads(0);
+        step_with_reads(0, refill ? 1 : 0);
         // every wavefront is done reading this block once it arrives here
-        if (next) wait_loads_and_barrier(pending);
-        if (n_issue >= 1) issue_part(2 * p + 5, a_slot);
-        if (n_issue >= 2) issue_part(2 * p + 6, w_slot);
+        if (next) wait_loads_and_barrier(refill ? kPartLoads : 0);
         if (next) load_ops(next_slot(a_slot, 2), next_slot(w_slot, 2), 0, 0);
+        if (refill) issue_part(2 * p + 5, a_slot);
         products(1);
-        if (n_issue >= 2) {
-            // after the barrier: the six LDS reads of the next block's first step and the eight
-            // loads that refill this block's slots, spread among the eight matrix instructions
+        if (refill) {
+            // after the barrier: the six LDS reads of the next block's first step, then the
+            // four loads of part 2p+5 among the last matrix instructions
 #pragma unroll
             for (int i = 0; i < 6; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
     };
-    for (int part = 0; part < kGemmSlots && part < n_parts; ++part) issue_part(part, part);
-    wait_loads_and_barrier(kPartLoads * min(n_parts - 2, kGemmSlots - 2));  // block 0 has landed
+    static_assert(kPartLoads == 4, "the block spreads four loads per part over its steps");
+    const int n_first = min(n_parts, kGemmSlots - 1);  // parts 0..3 go out at once, part 4 with block 0
+    for (int part = 0; part < n_first; ++part) issue_part(part, part);
+    wait_loads_and_barrier(kPartLoads * (n_first - 2));  // block 0 has landed
     load_ops(0, 1, 0, 0);
     int p = 0, a_slot = 0, w_slot = 1;
-    // Steady state: parts 2p+5 and 2p+6 exist; at the barrier only part 2p+4 may be pending.
-    for (; 2 * p + 6 < n_parts; ++p) {
-        block(p, a_slot, w_slot, 2, kPartLoads, true);
+    for (; 2 * p + 5 < n_parts; ++p) {  // steady state
+        block(p, a_slot, w_slot, true, true);
         a_slot = next_slot(a_slot, 2);
         w_slot = next_slot(w_slot, 2);
     }
-    for (; p < n_b; ++p) {
-        // everything up to part 2p+4 has been issued; block p+1 is complete when at most that
-        // part is pending.  The last w part (2p+5) may still have to be issued here.
-        block(p, a_slot, w_slot, 2 * p + 5 < n_parts ? 1 : 0, 2 * p + 4 < n_parts ? kPartLoads : 0, p + 1 < n_b);
+    for (; p < n_b; ++p) {  // the last two blocks: everything has been issued
+        block(p, a_slot, w_slot, false, p + 1 < n_b);
         a_slot = next_slot(a_slot, 2);
         w_slot = next_slot(w_slot, 2);
     }
