@@ -52,18 +52,36 @@ __device__ inline int slot_token(const AttnArgs &a, int wy, int wx, int slot) {
     return (r < g.H && c < g.W) ? r * g.W + c : -1;
 }
 
-// A operand of O^T += V^T P^T: channels 32*blk32 .. +31 (one per lane), k-slot (g, 4r + e)
-// stands for key key0 + 8r + 4g + e, the order in which a lane holds its scores.
-__device__ inline bf16x8 load_vt_operand(const unsigned char *tile, int key0, int blk32,
-                                         int lane) {
+// A operands of O^T += V^T P^T for one tile of 32 keys: va[kk][mi] holds channels 32*mi .. +31
+// (one per lane) of keys 16*kk .. +15 of the tile, k-slot (g, 4r + e) standing for key
+// 16*kk + 8r + 4g + e, the order in which a lane holds its scores.  `vaddr[mi]` is this lane's
+// LDS byte address for the tile's first key (vt_lane_address), OFF a compile-time byte offset
+// on top of it: because a tile starts at a multiple of 16 rows, the chunk flips of tile_off_tr
+// are the same for every 8-row step, so all eight reads are constant offsets from two
+// per-lane addresses.  The reads are written in assembly (see lds_read_tr16_at): wait with
+// lds_reads_landed before use.
+__device__ inline unsigned vt_lane_address(const unsigned char *vrow0, int mi, int lane) {
     const int b = lane >> 4, j = lane & 15, g = b >> 1;
-    const int chunk16 = blk32 * 4 + (b & 1) * 2 + ((j & 3) >> 1);
-    const int half = (j & 1) * 8;
-    const int row0 = key0 + 4 * g + (j >> 2);
-    u32x2 r0 = lds_read_tr16(tile + tile_off_tr(row0, chunk16) + half);
-    u32x2 r1 = lds_read_tr16(tile + tile_off_tr(row0 + 8, chunk16) + half);
-    u32x4 r = {r0[0], r0[1], r1[0], r1[1]};
-    return as_bf16x8(r);
+    const int chunk16 = mi * 4 + (b & 1) * 2 + ((j & 3) >> 1);
+    return lds_address(vrow0) + tile_off_tr(4 * g + (j >> 2), chunk16) + (j & 1) * 8;
+}
+template <int OFF>
+__device__ inline void load_vt_operands(u32x4 (&va)[2][2], const unsigned (&vaddr)[2]) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            u32x2 r0, r1;
+            if (kk == 0) {
+                r0 = lds_read_tr16_at<OFF>(vaddr[mi]);
+                r1 = lds_read_tr16_at<OFF + 1024>(vaddr[mi]);
+            } else {
+                r0 = lds_read_tr16_at<OFF + 2048>(vaddr[mi]);
+                r1 = lds_read_tr16_at<OFF + 3072>(vaddr[mi]);
+            }
+            u32x4 r = {r0[0], r0[1], r1[0], r1[1]};
+            va[kk][mi] = r;
+        }
 }
 
 // Running softmax state of one wavefront: NT blocks of 32 query columns, 64 channels.
@@ -145,32 +163,33 @@ __device__ inline void add_key_bias(f32x16 &s, const float *bias, int g) {
 }
 
 // K operands of one tile of 32 keys (A of S^T = K Q^T): lane holds channels 16*ks + 8g .. +7
-// of key row krow0 + lane%32.
-__device__ inline void load_k_operands(bf16x8 (&ka)[4], const unsigned char *kstage, int krow0,
-                                       int lane) {
+// of key row lane%32 of the tile.  `kaddr[ks]` is this lane's LDS byte address of that piece in
+// a tile that starts at row 0 of a K stage laid out with tile_off_row (k_lane_addresses); a
+// tile that starts at another multiple of 16 rows has the same chunk rotation, so it is a
+// constant number of bytes (OFF) further on.  Read in assembly, like the V operands: wait with
+// lds_reads_landed before use.
+__device__ inline void k_lane_addresses(unsigned (&kaddr)[4], const unsigned char *krow0, int lane) {
     const int g = lane >> 5, li = lane & 31;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-        ka[ks] = as_bf16x8(*(const u32x4 *)(kstage + tile_off_row(krow0 + li, 2 * ks + g)));
+    for (int ks = 0; ks < 4; ++ks) kaddr[ks] = lds_address(krow0) + tile_off_row(li, 2 * ks + g);
 }
+template <int OFF>
+__device__ inline void load_k_operands(u32x4 (&ka)[4], const unsigned (&kaddr)[4]) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ka[ks] = lds_read_b128_at<OFF>(kaddr[ks]);
+}
+__device__ inline void k_operands_landed(u32x4 (&ka)[4]) { lds_reads_landed(ka[0], ka[1], ka[2], ka[3]); }
 
-// One tile of 32 keys.  kstage/vstage point at row 0 of an LDS stage (K rows laid out with
-// tile_off_row, V rows with tile_off_tr), the tile starts at row krow0 (a multiple of 32).
-// `ka` holds this tile's K operands on entry; if k_next is non-null the K operands of the tile
-// at (k_next, krow_next) are read into it as soon as the scores are issued, so that their LDS
-// latency hides behind the exponentials.  The V operands are read before the scores for the
-// same reason.  bias, if non-null, holds 0 / -inf per key of the tile.
-template <int NT>
-__device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4], bf16x8 (&ka)[4],
-                                   const unsigned char *k_next, int krow_next,
-                                   const unsigned char *vstage, int krow0, const float *bias,
-                                   float c, int lane) {
+// One tile of 32 keys.  `ka` holds the tile's K operands on entry (landed); its V rows (laid
+// out with tile_off_tr) are addressed by vaddr + VOFF (load_vt_operands).  If KNEXT >= 0 the K
+// operands of the tile at kaddr + KNEXT are read into `ka` as soon as the scores are issued, so
+// that their LDS latency hides behind the exponentials, like that of the V operands; they have
+// landed when the function returns.  bias, if non-null, holds 0 / -inf per key of the tile.
+template <int NT, int KNEXT, int VOFF>
+__device__ __forceinline__ void attn_tile32(WaveState<NT> &w, const u32x4 (&qreg)[NT][4], u32x4 (&ka)[4],
+                                   const unsigned (&kaddr)[4], const unsigned (&vaddr)[2],
+                                   const float *bias, float c, int lane) {
     const int g = lane >> 5;
-    bf16x8 va[2][2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) va[kk][mi] = load_vt_operand(vstage, krow0 + 16 * kk, mi, lane);
     f32x16 s[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -179,8 +198,12 @@ __device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4]
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) s[nt] = mfma32(ka[ks], qreg[nt][ks], s[nt]);
-    if (k_next) load_k_operands(ka, k_next, krow_next, lane);  // wave-uniform
+        for (int nt = 0; nt < NT; ++nt) s[nt] = mfma32(as_bf16x8(ka[ks]), as_bf16x8(qreg[nt][ks]), s[nt]);
+    __builtin_amdgcn_sched_barrier(0);  // the score products are issued before the reads below
+    u32x4 va[2][2];
+    load_vt_operands<VOFF>(va, vaddr);
+    if (KNEXT >= 0) load_k_operands<KNEXT >= 0 ? KNEXT : 0>(ka, kaddr);
+    __builtin_amdgcn_sched_barrier(0);  // ... and the reads before the softmax arithmetic
     if (bias) {  // wave-uniform
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) add_key_bias(s[nt], bias, g);
@@ -201,6 +224,8 @@ __device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4]
         }
         w.l[nt] += tile_sum;
     }
+    if (KNEXT >= 0) lds_reads_landed(va[0], va[1], ka);  // (va[kk] is the pair of channel blocks)
+    else lds_reads_landed(va[0][0], va[0][1], va[1][0], va[1][1]);
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -208,7 +233,7 @@ __device__ inline void attn_tile32(WaveState<NT> &w, const bf16x8 (&qreg)[NT][4]
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
-                w.acc[mi][nt] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][nt]);
+                w.acc[mi][nt] = mfma32(as_bf16x8(va[kk][mi]), as_bf16x8(pb), w.acc[mi][nt]);
             }
 }
 
@@ -259,23 +284,31 @@ __device__ inline void wave_store(const WaveState<NT> &w, const AttnArgs &a, int
     }
 }
 
-// Query operands (B of S^T = K Q^T): lane holds channels 16*ks + 8g .. +7 of query li.
+// Query operands (B of S^T = K Q^T): lane holds channels 16*ks + 8g .. +7 of query li.  Padding
+// slots fetch token 0 of the slice (their columns are computed and never stored).  The loads
+// are written in assembly: the compiler, which cannot tell which of the loads in flight write
+// LDS, would otherwise wait for all of them before the first use of a query register, inside
+// the key loop.  They are the oldest loads of the wavefront, so any wait for a later load
+// covers them; the caller puts queries_landed() behind that wait.
 template <int NT>
-__device__ inline void load_queries(bf16x8 (&qreg)[NT][4], const AttnArgs &a, int wy, int wx,
+__device__ inline void load_queries(u32x4 (&qreg)[NT][4], const AttnArgs &a, int wy, int wx,
                                     int q0, long long qbase, int lane) {
     const int g = lane >> 5, li = lane & 31;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int tok = slot_token(a, wy, wx, q0 + 32 * nt + li);
+        const int tok = max(slot_token(a, wy, wx, q0 + 32 * nt + li), 0);
+        const __bf16 *row = (const __bf16 *)a.q.ptr + qbase + (long long)tok * a.q.sn + g * 8;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 x = {0u, 0u, 0u, 0u};
-            if (tok >= 0)
-                x = *(const u32x4 *)((const __bf16 *)a.q.ptr + qbase + (long long)tok * a.q.sn +
-                                     (2 * ks + g) * 8);
-            qreg[nt][ks] = as_bf16x8(x);
-        }
+        for (int ks = 0; ks < 4; ++ks)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qreg[nt][ks]) : "v"(row), "n"(32 * ks));
     }
+}
+// Nothing that uses the query registers may be scheduled above this point (no instruction).
+template <int NT>
+__device__ inline void queries_landed(u32x4 (&qreg)[NT][4]) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+        asm volatile("" : "+v"(qreg[nt][0]), "+v"(qreg[nt][1]), "+v"(qreg[nt][2]), "+v"(qreg[nt][3]));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -289,6 +322,9 @@ constexpr int kStageBytes = 2 * kStage * 128;  // K rows then V rows
 
 template <bool O_BF16, int NT>
 __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a) {
+    // the logit scale, fetched (a kernel argument) and waited for here, not inside the key loop
+    float c_log2 = a.c;
+    asm volatile("" : "+s"(c_log2));
     __shared__ __align__(16) unsigned char smem[2 * kStageBytes];
     __shared__ __align__(16) float bias[2][kStage];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -299,7 +335,7 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
     const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
     const bool wave_live = q0 < a.q_slots;
 
-    bf16x8 qreg[NT][4];
+    u32x4 qreg[NT][4];
     load_queries<NT>(qreg, a, wy, wx, q0, qbase, lane);
     WaveState<NT> w;
     wave_state_init<NT>(w);
@@ -339,6 +375,10 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
             if (lchunk == 0) bias[buf][row] = live[i] ? 0.f : -INFINITY;
         }
     };
+    const unsigned vaddr[2] = {vt_lane_address(smem + kStage * 128, 0, lane),
+                               vt_lane_address(smem + kStage * 128, 1, lane)};  // V rows of buffer 0
+    unsigned kaddr[4];
+    k_lane_addresses(kaddr, smem, lane);  // K rows of buffer 0
     // One stage: prefetch the next one, run the two tiles of this one, publish the next one.
     // `buf` is a compile-time constant so that every LDS offset folds into the instruction.
     auto run_stage = [&](int st, auto buf_tag) {
@@ -346,13 +386,14 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
         const bool more = st + 1 < n_stage;
         if (more) fetch(st + 1);
         if (wave_live) {
-            const unsigned char *kt = smem + buf * kStageBytes, *vt = kt + kStage * 128;
             const bool masked = ragged || (st + 1) * kStage > a.g.slots;
-            bf16x8 ka[4];
-            load_k_operands(ka, kt, 0, lane);
-            attn_tile32<NT>(w, qreg, ka, kt, 32, vt, 0, masked ? &bias[buf][0] : nullptr, a.c, lane);
-            attn_tile32<NT>(w, qreg, ka, nullptr, 0, vt, 32, masked ? &bias[buf][32] : nullptr, a.c,
-                            lane);
+            u32x4 ka[4];
+            load_k_operands<buf * kStageBytes>(ka, kaddr);
+            k_operands_landed(ka);
+            attn_tile32<NT, buf * kStageBytes + 32 * 128, buf * kStageBytes>(
+                w, qreg, ka, kaddr, vaddr, masked ? &bias[buf][0] : nullptr, c_log2, lane);
+            attn_tile32<NT, -1, buf * kStageBytes + 32 * 128>(
+                w, qreg, ka, kaddr, vaddr, masked ? &bias[buf][32] : nullptr, c_log2, lane);
         }
         if (more) stash(buf ^ 1);
         __syncthreads();
@@ -360,6 +401,8 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
 
     fetch(0);
     stash(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the queries (the first stage has been waited for already)
+    queries_landed<NT>(qreg);
     __syncthreads();
     for (int st = 0; st < n_stage; st += 2) {
         run_stage(st, std::integral_constant<int, 0>());
@@ -406,6 +449,9 @@ __device__ inline void wait_vm_loads(int pending) {
 
 template <bool O_BF16, int WPW>
 __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
+    // the logit scale, fetched (a kernel argument) and waited for here, not inside the key loop
+    float c_log2 = a.c;
+    asm volatile("" : "+s"(c_log2));
     extern __shared__ __align__(16) unsigned char wsm[];
     constexpr int R = 64 * WPW;       // LDS rows per window
     constexpr int kIpt = 4 / WPW;     // load instructions per tile, tensor and wavefront (8 rows each)
@@ -424,7 +470,7 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     const int n_tile = (a.g.slots + 31) >> 5;
     const bool wave_live = win_live && q0 < a.g.slots;
 
-    bf16x8 qreg[2][4];
+    u32x4 qreg[2][4];
     if (wave_live) load_queries<2>(qreg, a, wy, wx, q0, qbase, lane);
 
     // Loads, tile by tile: lane = 8 * (row in the group of 8) + 16-byte slot of the LDS row; it
@@ -458,7 +504,7 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     // Tiles 0 .. upto have landed for every wavefront of the window.
     auto tiles_ready = [&](int upto) {
         wait_vm_loads(2 * kIpt * max(n_tile - 1 - upto, 0));
-        if (WPW == 4) __syncthreads();
+        if (WPW == 4) lds_barrier();
         else __builtin_amdgcn_wave_barrier();
     };
 
@@ -466,15 +512,35 @@ __global__ void __launch_bounds__(256, 2) attn_window_bf16(AttnArgs a) {
     wave_state_init<2>(w);
     const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
     tiles_ready(0);
-    bf16x8 ka[4];
-    if (wave_live) load_k_operands(ka, ktile, 0, lane);
-    for (int tile = 0; tile < n_tile; ++tile) {
+    queries_landed<2>(qreg);  // (older than the loads of tile 0)
+    const unsigned vaddr[2] = {vt_lane_address(vtile, 0, lane), vt_lane_address(vtile, 1, lane)};
+    unsigned kaddr[4];
+    k_lane_addresses(kaddr, ktile, lane);
+    u32x4 ka[4];
+    load_k_operands<0>(ka, kaddr);
+    k_operands_landed(ka);
+    // The tile loop, unrolled so that every LDS offset is a constant of the instruction.  While
+    // tile j is multiplied the K operands of tile j + 1 are read (it has landed); after the
+    // window's last tile that read fetches bytes nobody uses (rows of the V tile).
+    auto run_tile = [&](auto tile_tag) __attribute__((always_inline)) {
+        constexpr int tile = decltype(tile_tag)::value;
+        if (tile >= n_tile) return;  // uniform
         if (tile + 1 < n_tile) tiles_ready(tile + 1);  // all wavefronts of the workgroup take part
         if (wave_live) {
             const bool masked = ragged || 32 * (tile + 1) > a.g.slots;
-            attn_tile32<2>(w, qreg, ka, tile + 1 < n_tile ? ktile : nullptr, 32 * (tile + 1), vtile,
-                           32 * tile, masked ? bias + 32 * tile : nullptr, a.c, lane);
+            attn_tile32<2, (tile + 1) * 32 * 128, tile * 32 * 128>(w, qreg, ka, kaddr, vaddr,
+                                                                   masked ? bias + 32 * tile : nullptr, c_log2, lane);
         }
+    };
+    run_tile(std::integral_constant<int, 0>());
+    run_tile(std::integral_constant<int, 1>());
+    if (WPW == 4) {
+        run_tile(std::integral_constant<int, 2>());
+        run_tile(std::integral_constant<int, 3>());
+        run_tile(std::integral_constant<int, 4>());
+        run_tile(std::integral_constant<int, 5>());
+        run_tile(std::integral_constant<int, 6>());
+        run_tile(std::integral_constant<int, 7>());
     }
     if (WPW == 4) __syncthreads();  // all waves are done with the tiles: reuse them as staging
     else __builtin_amdgcn_wave_barrier();
@@ -507,6 +573,9 @@ constexpr int kWindow8Lds = 2 * 256 * 128;
 
 template <bool O_BF16>
 __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_items) {
+    // the logit scale, fetched (a kernel argument) and waited for here, not inside the key loop
+    float c_log2 = a.c;
+    asm volatile("" : "+s"(c_log2));
     extern __shared__ __align__(16) unsigned char wsm[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
     unsigned char *ktile = wsm, *vtile = wsm + 256 * 128;
@@ -518,13 +587,15 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
     // width is a power of two)
     const int ww_shift = __builtin_ctz(a.g.ww);
     auto rel_token = [&](int row) { return (row >> ww_shift) * a.g.W + (row & (a.g.ww - 1)); };
-    // K/V loads: byte offset of this lane's 16 bytes in key tile 0; 32 slots further on (the next
-    // tile) is a fixed number of tokens, and the chunk rotations repeat every 16 rows.
+    // K/V loads: byte offset of this lane's 16 bytes in key tile 0.  Key tile j starts at window
+    // slot 32 j, and a tile never straddles a window row unevenly (the window width is a power of
+    // two: either whole rows make up a tile, or a tile lies inside one row), so tile j is tile 0
+    // moved by rel_token(32 j) tokens, the same for every lane; the chunk rotations repeat every
+    // 16 rows.
     const int row_kv = 8 * wave + lrow;
-    const unsigned tile_tokens = a.g.ww >= 32 ? 32u : (unsigned)(32 >> ww_shift) * (unsigned)a.g.W;
     const unsigned koff0 = 2u * ((unsigned)rel_token(row_kv) * (unsigned)a.k.sn + (lslot ^ tile_row_rotation(row_kv)) * 8);
     const unsigned voff0 = 2u * ((unsigned)rel_token(row_kv) * (unsigned)a.v.sn + (lslot ^ (((row_kv ^ (row_kv >> 1)) & 1) << 2)) * 8);
-    const unsigned kstep = 2u * tile_tokens * (unsigned)a.k.sn, vstep = 2u * tile_tokens * (unsigned)a.v.sn;
+    const unsigned ksn2 = 2u * (unsigned)a.k.sn, vsn2 = 2u * (unsigned)a.v.sn;
 
     struct Item {
         const char *q, *k, *v;
@@ -551,13 +622,14 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int j = 4 * half + jj, row0 = 32 * j + 8 * wave;
-            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.k + (koff0 + j * kstep)),
+            const unsigned tile_tok = (unsigned)rel_token(32 * j);  // uniform
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.k + (koff0 + tile_tok * ksn2)),
                                              (attn_lds_void *)(ktile + row0 * 128), 16, 0, kDmaStreamAux);
-            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.v + (voff0 + j * vstep)),
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(it.v + (voff0 + tile_tok * vsn2)),
                                              (attn_lds_void *)(vtile + row0 * 128), 16, 0, kDmaStreamAux);
         }
     };
-    bf16x8 qreg[2][4];
+    u32x4 qreg[2][4];
     // `fresh` is zero, but opaque to the compiler: the offsets are then recomputed per window (a
     // few integer operations) instead of being kept, loop-invariant, in registers that the
     // loop does not have to spare (they were spilled to scratch memory and reloaded per window).
@@ -566,14 +638,23 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
         for (int nt = 0; nt < 2; ++nt) {
             const unsigned qoff = 2u * ((unsigned)rel_token(q0 + 32 * nt + li + fresh) * (unsigned)a.q.sn + g * 8);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) qreg[nt][ks] = as_bf16x8(*(const u32x4 *)(it.q + (qoff + 32 * ks)));
+            for (int ks = 0; ks < 4; ++ks)  // (in assembly, as in load_queries)
+                asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"
+                             : "=v"(qreg[nt][ks]) : "v"(qoff), "s"(it.q), "n"(32 * ks)
+                             : "memory");  // the stores and loads counted below stay behind it
         }
     };
+    // Vector-memory operations a wavefront issues per window after its query loads: the output
+    // stores, then the loads of half B.  (Loads and stores complete in issue order.)
+    constexpr int kAfterQueries = (O_BF16 ? 8 : 16) + 8;
     auto drain_and_sync = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        lds_barrier();
     };
 
+    const unsigned vaddr[2] = {vt_lane_address(vtile, 0, lane), vt_lane_address(vtile, 1, lane)};
+    unsigned kaddr[4];
+    k_lane_addresses(kaddr, ktile, lane);
     int item = blockIdx.x;
     if (item >= n_items) return;  // whole workgroup
     Item cur = make_item(item);
@@ -582,14 +663,18 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
     drain_and_sync();
     for (;;) {
         issue_half(cur, 1);
+        if (kAfterQueries == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        queries_landed<2>(qreg);
         const int next = item + gridDim.x;
         const bool has_next = next < n_items;
         Item nxt = cur;
         WaveState<2> w;
         wave_state_init<2>(w);
-        bf16x8 ka[4];
-#pragma unroll 1
-        for (int tile = 0; tile < 8; ++tile) {
+        u32x4 ka[4];
+        // (unrolled: every LDS offset is a constant of the instruction)
+        auto run_tile = [&](auto tile_tag) __attribute__((always_inline)) {
+            constexpr int tile = decltype(tile_tag)::value;
             if (tile == 4) {
                 drain_and_sync();  // half B has landed; every wavefront is done with half A
                 if (has_next) {
@@ -597,10 +682,21 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
                     issue_half(nxt, 0);
                 }
             }
-            if ((tile & 3) == 0) load_k_operands(ka, ktile, 32 * tile, lane);
-            attn_tile32<2>(w, qreg, ka, (tile & 3) != 3 ? ktile : nullptr, 32 * (tile + 1), vtile, 32 * tile,
-                           nullptr, a.c, lane);
-        }
+            if ((tile & 3) == 0) {
+                load_k_operands<tile * 32 * 128>(ka, kaddr);
+                k_operands_landed(ka);
+            }
+            attn_tile32<2, (tile & 3) != 3 ? (tile + 1) * 32 * 128 : -1, tile * 32 * 128>(w, qreg, ka, kaddr, vaddr,
+                                                                                       nullptr, c_log2, lane);
+        };
+        run_tile(std::integral_constant<int, 0>());
+        run_tile(std::integral_constant<int, 1>());
+        run_tile(std::integral_constant<int, 2>());
+        run_tile(std::integral_constant<int, 3>());
+        run_tile(std::integral_constant<int, 4>());
+        run_tile(std::integral_constant<int, 5>());
+        run_tile(std::integral_constant<int, 6>());
+        run_tile(std::integral_constant<int, 7>());
         drain_and_sync();  // the next window's half A has landed; half B is free
         int fresh = 0;
         asm volatile("" : "+v"(fresh));
@@ -621,11 +717,16 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
                                     pack_bf16x2(x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv)};
                         *(u32x2 *)(stage + tile_off_row(li, 4 * mi + q4) + 8 * g) = pk;
                     }
+                // (read back in assembly, so that the compiler does not wait for the query loads
+                // of the next window, which it cannot tell from loads that write LDS)
+                u32x4 val[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) val[r] = lds_read_b128_ordered(lds_address(stage + tile_off_row(r * 8 + lrow, lslot)));
+                lds_reads_landed(val[0], val[1], val[2], val[3]);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const u32x4 val = *(const u32x4 *)(stage + tile_off_row(r * 8 + lrow, lslot));
                     const unsigned ooff = 2u * ((unsigned)rel_token(q0 + 32 * nt + r * 8 + lrow + fresh) * (unsigned)a.o.sn + lslot * 8);
-                    st_stream((u32x4 *)(cur.o + ooff), val);
+                    st_stream((u32x4 *)(cur.o + ooff), val[r]);
                 }
             } else {
                 const unsigned ooff = 4u * (unsigned)rel_token(q0 + 32 * nt + li + fresh) * (unsigned)a.o.sn;
@@ -640,7 +741,7 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
                     }
             }
         }
-        __syncthreads();  // staging bytes are read out: half B may be refilled
+        lds_barrier();  // staging bytes are read out: half B may be refilled (the stores drain on their own)
         if (!has_next) break;
         cur = nxt;
         item = next;
@@ -653,29 +754,27 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
 // Same tiling as attn_stream_bf16 (a workgroup holds 256 query slots, keys pass through LDS
 // in stages of 64), but built so that the inner loop is nothing but matrix instructions,
 // exponentials and LDS operand reads:
-//   * K/V stages go from global memory straight into a ring of three LDS stages (no register
+//   * K/V stages go from global memory straight into a ring of four LDS stages (no register
 //     staging, no LDS stores, no per-row selects), two stages ahead of the arithmetic; a
-//     stage costs each wavefront four load instructions, one counted wait and one barrier;
+//     stage costs each wavefront four load instructions, one counted wait and one barrier,
+//     which sits between the stage's two tiles so that the K operands of the next stage's
+//     first tile are read under this stage's second tile;
 //   * every full stage runs the unmasked tile code, which is one basic block per tile apart
 //     from the (rarely taken) branch that raises the softmax reference; only the last,
 //     partial stage of a window masks keys, and it does so by key index, not through LDS.
 // grid (ceil(slots/256), n_win, B*heads), 256 threads.
 // ---------------------------------------------------------------------------------------
-constexpr int kRing = 3;
+constexpr int kRing = 4;
 
-// One tile of 32 keys of the ring kernel.  NEXT: the stage holds another tile after this one,
-// whose K operands are read into `ka` once the scores are issued.  MASKED: keys with index
-// (inside the stage) >= key_limit are padding.
-template <bool NEXT, bool MASKED>
-__device__ inline void ring_tile32(WaveState<2> &w, const bf16x8 (&qreg)[2][4], bf16x8 (&ka)[4],
-                                   const unsigned char *kstage, const unsigned char *vstage,
+// One tile of 32 keys of the ring kernel, as attn_tile32: `ka` holds its K operands, its V rows
+// are at vaddr + VOFF, and if KNEXT >= 0 the K operands at kaddr + KNEXT are read into `ka`
+// under the exponentials.  MASKED: the tile's keys are keys krow0 .. +31 of their stage, and
+// keys with index (inside the stage) >= key_limit are padding.
+template <int KNEXT, bool MASKED, int VOFF>
+__device__ __forceinline__ void ring_tile32(WaveState<2> &w, const u32x4 (&qreg)[2][4], u32x4 (&ka)[4],
+                                   const unsigned (&kaddr)[4], const unsigned (&vaddr)[2],
                                    int krow0, int key_limit, float c, int lane) {
     const int g = lane >> 5;
-    bf16x8 va[2][2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) va[kk][mi] = load_vt_operand(vstage, krow0 + 16 * kk, mi, lane);
     f32x16 s[2];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
@@ -684,8 +783,12 @@ __device__ inline void ring_tile32(WaveState<2> &w, const bf16x8 (&qreg)[2][4], 
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) s[nt] = mfma32(ka[ks], qreg[nt][ks], s[nt]);
-    if (NEXT) load_k_operands(ka, kstage, krow0 + 32, lane);
+        for (int nt = 0; nt < 2; ++nt) s[nt] = mfma32(as_bf16x8(ka[ks]), as_bf16x8(qreg[nt][ks]), s[nt]);
+    __builtin_amdgcn_sched_barrier(0);  // the score products are issued before the reads below
+    u32x4 va[2][2];
+    load_vt_operands<VOFF>(va, vaddr);
+    if (KNEXT >= 0) load_k_operands<KNEXT >= 0 ? KNEXT : 0>(ka, kaddr);
+    __builtin_amdgcn_sched_barrier(0);  // ... and the reads before the softmax arithmetic
     if (MASKED) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -710,6 +813,8 @@ __device__ inline void ring_tile32(WaveState<2> &w, const bf16x8 (&qreg)[2][4], 
     }
     w.l[0] += sum0;
     w.l[1] += sum1;
+    if (KNEXT >= 0) lds_reads_landed(va[0], va[1], ka);
+    else lds_reads_landed(va[0][0], va[0][1], va[1][0], va[1][1]);
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -717,12 +822,15 @@ __device__ inline void ring_tile32(WaveState<2> &w, const bf16x8 (&qreg)[2][4], 
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
-                w.acc[mi][nt] = mfma32(va[kk][mi], as_bf16x8(pb), w.acc[mi][nt]);
+                w.acc[mi][nt] = mfma32(as_bf16x8(va[kk][mi]), as_bf16x8(pb), w.acc[mi][nt]);
             }
 }
 
 template <bool O_BF16>
 __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
+    // the logit scale, fetched (a kernel argument) and waited for here, not inside the key loop
+    float c_log2 = a.c;
+    asm volatile("" : "+s"(c_log2));
     __shared__ __align__(16) unsigned char smem[kRing * kStageBytes];
     constexpr int WAVES = 4;
     constexpr int kLoads = 8 / WAVES;  // load instructions per stage, tensor and wavefront (8 rows each)
@@ -734,7 +842,7 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
     const long long qbase = b * a.q.sb + h * a.q.sh, obase = b * a.o.sb + h * a.o.sh;
     const bool wave_live = q0 < a.q_slots;
 
-    bf16x8 qreg[2][4];
+    u32x4 qreg[2][4];
     load_queries<2>(qreg, a, wy, wx, q0, qbase, lane);
     WaveState<2> w;
     wave_state_init<2>(w);
@@ -788,39 +896,50 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
             vcur[i] += vstep;
         }
     };
-    // Stage `st` has landed for every wavefront, and every wavefront is done with stage st - 1,
-    // whose ring slot takes stage st + 2.
-    auto stage_ready = [&](int st) {
-        if (st + 1 < n_stage) {
-            static_assert(kLoads == 2, "the wait below leaves one stage (2 * kLoads loads) in flight");
-            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
-        __syncthreads();
-        if (st + 2 < n_stage) issue(st + 2);
+    static_assert(kLoads == 2 && kRing == 4, "the waits below count 2 * kLoads loads per stage in flight");
+    // Between the two tiles of stage st: stage st + 1 has landed for every wavefront (one more
+    // stage may be in flight), and every wavefront has left stage st - 1, whose ring slot takes
+    // stage st + 3.  The second tile of stage st may then read the first K operands of stage
+    // st + 1, so no tile waits for its operands at a stage boundary.
+    auto next_stage_ready = [&](int st) {
+        if (st + 1 >= n_stage) return;  // uniform
+        if (st + 2 < n_stage) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        if (st + 3 < n_stage) issue(st + 3);
     };
-    // A full stage in ring slot `slot` (a compile-time constant, so that every LDS offset folds
-    // into the instruction).
+    const unsigned vaddr[2] = {vt_lane_address(smem + kStage * 128, 0, lane),
+                               vt_lane_address(smem + kStage * 128, 1, lane)};  // V rows of ring slot 0
+    unsigned kaddr[4];
+    k_lane_addresses(kaddr, smem, lane);  // K rows of ring slot 0
+    u32x4 ka[4];
+    // A full stage in ring slot `slot` (a compile-time constant, so that every LDS offset is a
+    // constant of the instruction).
     auto full_stage = [&](int st, auto slot_tag) {
-        constexpr int slot = decltype(slot_tag)::value;
-        stage_ready(st);
-        if (wave_live) {
-            const unsigned char *kt = smem + slot * kStageBytes, *vt = kt + kStage * 128;
-            bf16x8 ka[4];
-            load_k_operands(ka, kt, 0, lane);
-            ring_tile32<true, false>(w, qreg, ka, kt, vt, 0, 0, a.c, lane);
-            ring_tile32<false, false>(w, qreg, ka, kt, vt, 32, 0, a.c, lane);
-        }
+        constexpr int slot = decltype(slot_tag)::value, after = (slot + 1) % kRing;
+        if (wave_live)
+            ring_tile32<slot * kStageBytes + 32 * 128, false, slot * kStageBytes>(w, qreg, ka, kaddr, vaddr, 0, 0, c_log2, lane);
+        next_stage_ready(st);
+        if (wave_live)  // (after the window's last stage the K operands read here are not used)
+            ring_tile32<after * kStageBytes, false, slot * kStageBytes + 32 * 128>(w, qreg, ka, kaddr, vaddr, 32, 0, c_log2, lane);
     };
 
     if (n_stage > 0) issue(0);
     if (n_stage > 1) issue(1);
+    if (n_stage > 2) issue(2);
+    if (n_stage > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (n_stage > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();  // stage 0 has landed
+    queries_landed<2>(qreg);  // (older than the loads of stage 0)
+    load_k_operands<0>(ka, kaddr);
+    k_operands_landed(ka);
     int st = 0;
-    for (; st + 2 < n_full; st += 3) {
+    for (; st + 3 < n_full; st += 4) {
         full_stage(st, std::integral_constant<int, 0>());
         full_stage(st + 1, std::integral_constant<int, 1>());
         full_stage(st + 2, std::integral_constant<int, 2>());
+        full_stage(st + 3, std::integral_constant<int, 3>());
     }
     if (st < n_full) {
         full_stage(st, std::integral_constant<int, 0>());
@@ -828,21 +947,22 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
         if (st < n_full) {
             full_stage(st, std::integral_constant<int, 1>());
             ++st;
+            if (st < n_full) {
+                full_stage(st, std::integral_constant<int, 2>());
+                ++st;
+            }
         }
     }
-    if (st < n_stage) {  // the partial stage that ends the window
-        stage_ready(st);
-        if (wave_live) {
-            const unsigned char *kt = smem + (st % kRing) * kStageBytes, *vt = kt + kStage * 128;
-            const int key_limit = tok_limit - st * kStage;  // 1 .. 63
-            bf16x8 ka[4];
-            load_k_operands(ka, kt, 0, lane);
-            if (key_limit > 32) {
-                ring_tile32<true, true>(w, qreg, ka, kt, vt, 0, key_limit, a.c, lane);
-                ring_tile32<false, true>(w, qreg, ka, kt, vt, 32, key_limit, a.c, lane);
-            } else {
-                ring_tile32<false, true>(w, qreg, ka, kt, vt, 0, key_limit, a.c, lane);
-            }
+    if (st < n_stage && wave_live) {  // the partial stage that ends the window (its first K operands are in ka)
+        const unsigned at = (st % kRing) * kStageBytes;
+        const unsigned vlast[2] = {vaddr[0] + at, vaddr[1] + at};
+        const unsigned klast[4] = {kaddr[0] + at, kaddr[1] + at, kaddr[2] + at, kaddr[3] + at};
+        const int key_limit = tok_limit - st * kStage;  // 1 .. 63
+        if (key_limit > 32) {
+            ring_tile32<32 * 128, true, 0>(w, qreg, ka, klast, vlast, 0, key_limit, c_log2, lane);
+            ring_tile32<-1, true, 32 * 128>(w, qreg, ka, klast, vlast, 32, key_limit, c_log2, lane);
+        } else {
+            ring_tile32<-1, true, 0>(w, qreg, ka, klast, vlast, 0, key_limit, c_log2, lane);
         }
     }
     __syncthreads();  // every wavefront is done with the ring: reuse it as staging
@@ -868,6 +988,9 @@ constexpr int kPrefixLds = kPrefixWaves * kStageBytes + 2 * kPrefixWaves * 64 * 
 
 template <bool O_BF16>
 __global__ void __launch_bounds__(512, 1) attn_prefix_bf16(AttnArgs a) {
+    // the logit scale, fetched (a kernel argument) and waited for here, not inside the key loop
+    float c_log2 = a.c;
+    asm volatile("" : "+s"(c_log2));
     extern __shared__ __align__(16) unsigned char psm[];
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, li = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -875,7 +998,7 @@ __global__ void __launch_bounds__(512, 1) attn_prefix_bf16(AttnArgs a) {
     const long long qbase = b * a.q.sb + h * a.q.sh;
     const int N = a.g.slots;
 
-    bf16x8 qreg[2][4];
+    u32x4 qreg[2][4];
     load_queries<2>(qreg, a, 0, 0, 0, qbase, lane);
     WaveState<2> w;
     wave_state_init<2>(w);
@@ -906,18 +1029,23 @@ __global__ void __launch_bounds__(512, 1) attn_prefix_bf16(AttnArgs a) {
                                              (attn_lds_void *)(vt + 8 * i * 128), 16, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        queries_landed<2>(qreg);
         const int key_limit = N - st * kStage;
         // The operand addresses depend on the lane only; `ln` is the lane, but opaque to the
         // compiler, which would otherwise keep every address of every tile variant in a
         // register of its own across the loop (and spill them).
         int ln = lane;
         asm volatile("" : "+v"(ln));
-        bf16x8 ka[4];
-        load_k_operands(ka, kt, 0, ln);
+        const unsigned vaddr[2] = {vt_lane_address(vt, 0, ln), vt_lane_address(vt, 1, ln)};
+        unsigned kaddr[4];
+        k_lane_addresses(kaddr, kt, ln);
+        u32x4 ka[4];
+        load_k_operands<0>(ka, kaddr);
+        k_operands_landed(ka);
         // (one masked tile code for whole and partial stages: this kernel waits for its loads,
         // not for its arithmetic)
-        ring_tile32<true, true>(w, qreg, ka, kt, vt, 0, key_limit, a.c, ln);
-        if (key_limit > 32) ring_tile32<false, true>(w, qreg, ka, kt, vt, 32, key_limit, a.c, ln);
+        ring_tile32<32 * 128, true, 0>(w, qreg, ka, kaddr, vaddr, 0, key_limit, c_log2, ln);
+        if (key_limit > 32) ring_tile32<-1, true, 32 * 128>(w, qreg, ka, kaddr, vaddr, 32, key_limit, c_log2, ln);
     }
 
     // Partial results into LDS: the accumulators as [query][channel] fp32 in the wavefront's own

@@ -104,6 +104,58 @@ __device__ inline u32x2 lds_read_tr16(const unsigned char *lds_ptr) {
     return __builtin_bit_cast(u32x2, r);
 }
 
+// The same read written in assembly, at `addr` + OFF bytes (addr: LDS byte address, OFF: a
+// compile-time constant that goes into the instruction's offset field).  The compiler's wait
+// insertion treats the builtin above as a read of unknown LDS bytes and puts a wait for ALL
+// outstanding vector-memory loads (vmcnt 0) in front of it whenever loads that write LDS
+// (global_load_lds) are in flight, which serialises a kernel that keeps such loads in flight
+// across its arithmetic.  Written this way the read is invisible to that pass: the caller
+// orders it against the loads with its own counted waits and barriers, and must wait for the
+// result itself (lds_reads_landed) before using it.
+__device__ inline unsigned lds_address(const void *p) {
+    return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const unsigned char *)p;
+}
+template <int OFF>
+__device__ inline u32x2 lds_read_tr16_at(unsigned addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "offset field is 16 bits");
+    u32x2 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+// Plain 16-byte LDS read in the same style (ds_read_b128), for kernels whose operand reads
+// use run-time addresses: the compiler cannot tell those from the bytes that in-flight loads
+// into LDS are writing and waits for all of them.
+template <int OFF>
+__device__ inline u32x4 lds_read_b128_at(unsigned addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "offset field is 16 bits");
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+// The same read, ordered after the compiler's own LDS stores that precede it in the source
+// (for reading back what the wavefront has just staged in LDS).
+__device__ inline u32x4 lds_read_b128_ordered(unsigned addr) {
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr) : "memory");
+    return r;
+}
+// Wait for every LDS read this wavefront has issued; the operands are tied to the wait so
+// that no instruction using them can be scheduled above it.
+__device__ inline void lds_reads_landed(u32x4 &a, u32x4 &b, u32x4 &c, u32x4 &d) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+__device__ inline void lds_reads_landed(u32x4 (&a)[2], u32x4 (&b)[2], u32x4 (&c)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]), "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3]));
+}
+
+// Workgroup barrier for kernels that order their LDS traffic with their own counted waits:
+// this wavefront's LDS operations have completed, then the barrier.  Unlike __syncthreads()
+// it carries no memory fence, which the compiler implements by waiting for every outstanding
+// vector-memory operation as well: loads into LDS that are meant to stay in flight across
+// the barrier, and output stores that no one in the workgroup reads.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Exchange between lane l and lane l^32: returns {value of the lower lane, value of the upper
 // lane} in both lanes (v_permlane32_swap).
 __device__ inline void pair_values(float x, float *lo, float *hi) {
