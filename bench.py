@@ -28,20 +28,45 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
+def kernel_sources_hash():
+    """sha256 over the HIP sources of the library (file names and bytes, sorted): the build the
+    counter traffic in profiles/hbm_traffic.txt was measured on is identified by it."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2605_26636_amd", "csrc")
+    for path in sorted(glob.glob(os.path.join(csrc, "*.hip")) + glob.glob(os.path.join(csrc, "*.h"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+TRAFFIC_SOURCE = {"file": "profiles/hbm_traffic.txt"}
+
+
 def read_traffic():
     """HBM bytes per launch measured with rocprofv3 counters (profiles/hbm_traffic.txt holds
-    'kernel-key: bytes' lines and the commands that produced them); {} when absent."""
-    out = {}
+    'kernel-key: bytes' lines, the commands that produced them and the hash of the kernel sources
+    they were measured on).  The figures are handed out only while that hash is the hash of the
+    present sources: after a kernel change the file is stale and every traffic is null until
+    the counters are collected again.  {} when absent or stale; TRAFFIC_SOURCE says which."""
+    out, measured_on = {}, None
     if os.path.exists(TRAFFIC_FILE):
         for line in open(TRAFFIC_FILE):
             line = line.split("#", 1)[0].strip()
             if ":" in line:
                 key, val = line.split(":", 1)
+                if key.strip() == "sources_sha256":
+                    measured_on = val.strip()
+                    continue
                 try:
                     out[key.strip()] = float(val)
                 except ValueError:
                     pass
-    return out
+    now = kernel_sources_hash()
+    TRAFFIC_SOURCE.update({"measured_on_sources": measured_on, "present_sources": now,
+                           "stale": measured_on != now})
+    return out if measured_on == now else {}
 
 
 def main():
@@ -218,6 +243,7 @@ def main():
     roofline = {"kernel": "attn_ring_bf16 (full attention)", "bound": "mfma",
                 "achieved": per["full"]["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": per["full"]["mfma_frac"], "traffic": traffic.get("full"),
+                "traffic_source": dict(TRAFFIC_SOURCE),
                 "algorithmic_flops": flops["full"], "avg_launch_ms": per["full"]["ms_avg"]}
     rooflines = {
         "linear": hbm_roof("linear", "la_state_bf16 + la_apply_bf16"),

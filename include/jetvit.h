@@ -25,7 +25,8 @@
  *    [batch, N, 3, heads, head_dim] can be consumed without a transpose.
  *    Base pointers and all strides must keep every (b, h, n) row 16-byte aligned.
  *  - head_dim must be 64.
- *  - Inputs are never written.  O must not alias Q, K or V.
+ *  - Inputs are never written.  O must not overlap Q, K or V: the byte range that O's
+ *    strides span may not intersect the range of any input (JV_ERR_INVALID_ARG).
  *  - Arithmetic: JV_F32 tensors are processed in fp32 throughout.  JV_BF16
  *    tensors feed bf16 matrix instructions with fp32 accumulation; softmax,
  *    normalisers and divisions are fp32.  O is rounded to `o_dtype` once, at the
@@ -136,12 +137,14 @@ jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void
  *           u_n = silu(w1 V[b, :, n] + b1);  kernel[b, n] = reshape(w2 u_n + b2, [C, k, k]);
  *           DWC(V)[b, c, n] = sum_taps kernel[b, n][c, tap] * V[b, c, n + tap]
  *       Weights as for the squeeze-dynamic mode.  bf16 tensors only, hidden a multiple of 64
- *       (JV_ERR_UNSUPPORTED otherwise).  The generator runs as two matrix products in bf16 with
- *       fp32 accumulation (weights, hidden layer and filters are rounded to bf16) over V as the
- *       matrix [batch * tokens, C] -- read in place when V's strides already describe one (head
- *       stride 64, batch stride = tokens * token stride), from a packed copy otherwise; the
- *       workspace holds the filters of all tokens (batch * tokens * C * k * k bf16), the cost
- *       the paper rejects the variant for.  Prefix tokens get no convolution term.
+ *       (JV_ERR_UNSUPPORTED otherwise).  The generator runs as two matrix products with bf16
+ *       operands and fp32 accumulation (w1, w2 and the hidden layer are rounded to bf16: pass
+ *       weights that are bf16 values already and only the hidden layer is rounded; the filters
+ *       stay fp32) over V as the matrix [batch * tokens, C] -- read in place when V's strides
+ *       already describe one (head stride 64, batch stride = tokens * token stride), from a
+ *       packed copy otherwise; the workspace holds the filters of all tokens (batch * tokens *
+ *       C * k * k fp32), the cost the paper rejects the variant for.  Prefix tokens get no
+ *       convolution term.
  * ksize is 3 or 5; C <= 8192 and hidden <= 1024 (JV_ERR_UNSUPPORTED otherwise).  Pointers the
  * mode does not use are ignored.  workspace as for jv_linear_attn_fwd, sized by
  * jv_linear_block_workspace_bytes (0 for an invalid descriptor or parameter block).
@@ -242,7 +245,8 @@ jv_status jv_full_attn_fwd(const jv_attn_desc *desc, const void *q, const void *
  *                    itself); the sum is formed in fp32 and rounded once
  *   JV_EPI_SILU      y = silu(acc + bias), silu(x) = x / (1 + exp(-x))
  * y is [M, N] of y_dtype (JV_BF16 or JV_F32).  K % 64 == 0 and N % 8 == 0 are required
- * (JV_ERR_UNSUPPORTED otherwise); M is arbitrary.  All pointers device, 16-byte aligned.
+ * (JV_ERR_UNSUPPORTED otherwise); M is arbitrary up to 2^30, K up to 2^21.  All pointers
+ * device, 16-byte aligned.
  * ------------------------------------------------------------------------- */
 typedef enum { JV_EPI_NONE = 0, JV_EPI_GELU = 1, JV_EPI_RESIDUAL = 2, JV_EPI_SILU = 3 } jv_epilogue;
 
@@ -277,7 +281,10 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * jv_encoder_forward: x and y are device [batch, n_prefix + grid_h*grid_w, width] of stream_dtype
  * (y may be x);
  * workspace is device memory of at least jv_encoder_workspace_bytes(...) bytes, 256-byte
- * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.
+ * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.  Every shape the
+ * pass would launch (its four matrix products, the window partition, the token counts) is
+ * checked before the first launch; jv_encoder_workspace_bytes returns 0 for a (batch, grid) that
+ * jv_encoder_forward would refuse.
  *
  * jv_encoder_forward_taps: the same forward pass that also hands out the residual stream after
  * chosen blocks, which is what a dense-prediction head attached to the encoder reads (the

@@ -64,7 +64,19 @@ jv_status make_problem(const jv_attn_desc *d, const void *q, const void *k, cons
     if (!q || !k || !v || !o) return fail(JV_ERR_INVALID_ARG, "q, k, v, o must be non-null");
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15)
         return fail(JV_ERR_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
-    if (o == q || o == k || o == v) return fail(JV_ERR_INVALID_ARG, "o must not alias an input");
+    // O may not overlap an input: compare the byte ranges the four tensors span.
+    const int64_t N = d->n_prefix + (int64_t)d->grid_h * d->grid_w;
+    auto span = [&](const jv_strides &t, int64_t esz) {
+        return ((d->batch - 1) * t.stride_b + (d->heads - 1) * t.stride_h + (N - 1) * t.stride_n + kHeadDim) * esz;
+    };
+    const int64_t in_esz = d->dtype == JV_BF16 ? 2 : 4, out_esz = d->o_dtype == JV_BF16 ? 2 : 4;
+    const uintptr_t o0 = (uintptr_t)o, o1 = o0 + (uintptr_t)span(d->o, out_esz);
+    const void *ins[3] = {q, k, v};
+    const jv_strides *in_strides[3] = {&d->q, &d->k, &d->v};
+    for (int i = 0; i < 3; ++i) {
+        const uintptr_t i0 = (uintptr_t)ins[i], i1 = i0 + (uintptr_t)span(*in_strides[i], in_esz);
+        if (o0 < i1 && i0 < o1) return fail(JV_ERR_INVALID_ARG, "o must not overlap an input");
+    }
     p->B = d->batch;
     p->heads = d->heads;
     p->H = d->grid_h;
@@ -91,8 +103,10 @@ jv_status make_window_geom(int H, int W, int wh, int ww, WindowGeom *g) {
     g->wins_x = (W + ww - 1) / ww;
     g->Hp = g->wins_y * wh;
     g->Wp = g->wins_x * ww;
+    if ((int64_t)g->Hp * g->Wp > 0x7fffffffll)
+        return fail(JV_ERR_UNSUPPORTED, "padded grid above 2^31 - 1 cells");
     g->n_win = g->wins_x * g->wins_y;
-    g->slots = wh * ww;
+    g->slots = wh * ww;  // at most 2^28
     return JV_OK;
 }
 

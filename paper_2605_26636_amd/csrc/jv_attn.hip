@@ -112,10 +112,19 @@ static TensorArg from_token(const TensorArg &t, int first, bool bf16) {
     return r;
 }
 
-jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStream_t stream) {
+jv_status window_check(const Problem &pr, int wh, int ww) {
     WindowGeom g;
     jv_status st = make_window_geom(pr.H, pr.W, wh, ww, &g);
     if (st != JV_OK) return st;
+    if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
+    return JV_OK;
+}
+
+jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStream_t stream) {
+    WindowGeom g;
+    jv_status st = window_check(pr, wh, ww);
+    if (st != JV_OK) return st;
+    make_window_geom(pr.H, pr.W, wh, ww, &g);
     if (pr.P == 0) return attn_dispatch(pr, g, resolve_scale(scale), g.slots, stream);
     // Prefix tokens: the grid tokens run window attention among themselves; the prefix
     // tokens (the first P query slots of the whole sequence) attend to every token.

@@ -79,6 +79,11 @@ jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStrea
 jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStream_t stream);
 jv_status full_forward(const Problem &pr, float scale, hipStream_t stream);
 
+// Host-only checks of what the launchers above would refuse, so that a caller with several
+// launches ahead (the encoder) can refuse before the first one.
+jv_status window_check(const Problem &pr, int wh, int ww);
+jv_status gemm_check_shape(long long M, int N, int K, long long lda = 0);
+
 // y = epilogue(a w^T + bias) on the matrix cores (see jv_gemm_bias_act); lda: elements between
 // rows of a (0 = K, i.e. contiguous rows), a multiple of 8.
 jv_status gemm_forward(const void *a, const void *w, const float *bias, const void *residual,

@@ -48,10 +48,11 @@ jv_status plan_dwc(const jv_dwc_params *dwc, const LinearPlan &lp, int B, int he
             const size_t M = (size_t)B * N, kk = (size_t)dwc->ksize * dwc->ksize;
             p.w1b_off = base;  // two bf16 per float of offset
             p.w2b_off = p.w1b_off + align64f((size_t)dwc->hidden * C / 2);
-            p.vt_off = p.w2b_off + align64f((size_t)C * kk * dwc->hidden / 2);
+            p.b2p_off = p.w2b_off + align64f((size_t)C * kk * dwc->hidden / 2);
+            p.vt_off = p.b2p_off + align64f((size_t)C * kk);
             p.u_off = p.vt_off + align64f(M * C / 2);
             p.tok_kappa_off = p.u_off + align64f(M * dwc->hidden / 2);
-            p.la_off = p.tok_kappa_off + align64f(M * C * kk / 2);
+            p.la_off = p.tok_kappa_off + align64f(M * C * kk);  // the filters stay fp32
             p.total_floats = p.la_off + align64f(M * C);
             *out = p;
             return JV_OK;
@@ -220,6 +221,23 @@ cast_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, lo
     *(u32x4 *)(dst + 8 * i) = r;
 }
 
+// Second generator layer, reordered so that the filters come out tap-major: row c*kk + tap of
+// w2 [C*kk][hidden] becomes row tap*C + c of dst (bf16), and b2 likewise (fp32).  One thread per
+// 8 elements of a row; n8 = C*kk*hidden / 8.
+__global__ void __launch_bounds__(256)
+reorder_w2(const float *__restrict__ w2, const float *__restrict__ b2, unsigned short *__restrict__ dst,
+           float *__restrict__ b2p, int C, int kk, int hidden, long long n8) {
+    const long long i = blockIdx.x * 256ll + threadIdx.x;
+    if (i >= n8) return;
+    const int per_row = hidden / 8, j8 = (int)(i % per_row);
+    const int row = (int)(i / per_row), c = row / kk, tap = row % kk, to = tap * C + c;
+    const float *src = w2 + (size_t)row * hidden + 8 * j8;
+    const f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
+    u32x4 r = {pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
+    *(u32x4 *)(dst + (size_t)to * hidden + 8 * j8) = r;
+    if (j8 == 0) b2p[to] = b2[row];
+}
+
 // V in any strided layout -> rows [B*N][C] (channel = head*64 + c), 16 bytes per thread.
 __global__ void __launch_bounds__(256)
 pack_v_rows(TensorArg vt, unsigned short *__restrict__ rows, int heads, int N, long long total) {
@@ -236,13 +254,13 @@ __device__ inline float bf16_elem(const u32x4 &x, int e) {  // e = 0..7, compile
     return (e & 1) ? bf16_hi(x[e >> 1]) : bf16_lo(x[e >> 1]);
 }
 
-// o[b, n, c] = la[b, n, c] + sum_taps kappa[b*N + n][c*k*k + tap] * v[b, n + tap, c] on the
-// H x W grid behind P prefix tokens (prefix rows: o = la).  One thread per token and 8 channels;
-// total = B*N*C/8 threads.  la and o may be the same fp32 tensor (each element is read and
-// written by one thread).
+// o[b, n, c] = la[b, n, c] + sum_taps kappa[b*N + n][tap][c] * v[b, n + tap, c] on the H x W
+// grid behind P prefix tokens (prefix rows: o = la); kappa fp32, tap-major.  One thread per
+// token and 8 channels; total = B*N*C/8 threads.  la and o may be the same fp32 tensor (each
+// element is read and written by one thread).
 template <int KS, bool O_BF16>
 __global__ void __launch_bounds__(256)
-dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const unsigned short *__restrict__ kappa,
+dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const float *__restrict__ kappa,
               int heads, int N, int P, int H, int W, long long total) {
     constexpr int KK = KS * KS, PAD = KS / 2;
     const long long idx = blockIdx.x * 256ll + threadIdx.x;
@@ -255,10 +273,8 @@ dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const unsigned short *__
     float acc[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
     if (n >= P) {
         const int g = n - P, r = g / W, col = g - r * W;
-        const u32x4 *kp = (const u32x4 *)(kappa + idx * (8 * KK));
-        u32x4 kv[KK];  // 8 channels x KK taps, element c*KK + tap
-#pragma unroll
-        for (int j = 0; j < KK; ++j) kv[j] = kp[j];
+        const int C = heads * kHeadDim;
+        const float *kp = kappa + (size_t)m * C * KK + cg * 8;  // this thread's 8 channels, tap 0
         const unsigned short *vp = (const unsigned short *)vt.ptr + b * vt.sb + h * vt.sh + c8;
 #pragma unroll
         for (int di = -PAD; di <= PAD; ++di)
@@ -270,10 +286,11 @@ dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const unsigned short *__
                 const int nb = inside ? P + r2 * W + c2 : n;
                 u32x4 vv = *(const u32x4 *)(vp + (long long)nb * vt.sn);
                 if (!inside) vv = u32x4{0u, 0u, 0u, 0u};
+                const f32x4 k0 = *(const f32x4 *)(kp + (size_t)tap * C), k1 = *(const f32x4 *)(kp + (size_t)tap * C + 4);
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const int e = c * KK + tap;
-                    acc[c] = fmaf(bf16_elem(kv[e >> 3], e & 7), bf16_elem(vv, c), acc[c]);
+                for (int c = 0; c < 4; ++c) {
+                    acc[c] = fmaf(k0[c], bf16_elem(vv, c), acc[c]);
+                    acc[c + 4] = fmaf(k1[c], bf16_elem(vv, c + 4), acc[c + 4]);
                 }
             }
     }
@@ -291,7 +308,7 @@ dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const unsigned short *__
 
 template <int KS, bool O_BF16>
 static void launch_token_add(hipStream_t stream, const Problem &pr, const TensorArg &la,
-                             const unsigned short *kappa, long long total) {
+                             const float *kappa, long long total) {
     hipLaunchKernelGGL((dwc_token_add<KS, O_BF16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        stream, pr.v, la, pr.o, kappa, pr.heads, pr.N, pr.P, pr.H, pr.W, total);
 }
@@ -303,19 +320,20 @@ jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPla
     if (M * (C / 8) / 256 >= (1ll << 31) - 1) return fail(JV_ERR_UNSUPPORTED, "token-wise filters: too many tokens");
     unsigned short *w1b = (unsigned short *)(ws + dwc.w1b_off), *w2b = (unsigned short *)(ws + dwc.w2b_off);
     unsigned short *rows = (unsigned short *)(ws + dwc.vt_off), *u = (unsigned short *)(ws + dwc.u_off);
-    unsigned short *kappa = (unsigned short *)(ws + dwc.tok_kappa_off);
+    float *kappa = ws + dwc.tok_kappa_off, *b2p = ws + dwc.b2p_off;
     jv_status st;
     long long n8 = (long long)dwc.hidden * C / 8;
     hipLaunchKernelGGL(cast_to_bf16, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, dwc.w1, w1b, n8);
     if ((st = launch_status("cast_to_bf16")) != JV_OK) return st;
     n8 = (long long)C * kk * dwc.hidden / 8;
-    hipLaunchKernelGGL(cast_to_bf16, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, dwc.w2, w2b, n8);
-    if ((st = launch_status("cast_to_bf16")) != JV_OK) return st;
+    hipLaunchKernelGGL(reorder_w2, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, dwc.w2, dwc.b2, w2b,
+                       b2p, C, kk, dwc.hidden, n8);
+    if ((st = launch_status("reorder_w2")) != JV_OK) return st;
     // V as the matrix [B*N][C]: in place when its layout already is one, else a packed copy.
     const void *a = pr.v.ptr;
     long long lda = pr.v.sn;
     const bool in_place = pr.v.sh == kHeadDim && pr.v.sn >= C && pr.v.sn % 8 == 0 &&
-                          pr.v.sb == (long long)pr.N * pr.v.sn && M * pr.v.sn < (1ll << 30);
+                          pr.v.sb == (long long)pr.N * pr.v.sn && pr.v.sn <= (1 << 21);
     const long long total = M * (C / 8);
     if (!in_place) {
         hipLaunchKernelGGL(pack_v_rows, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, pr.v, rows,
@@ -326,7 +344,7 @@ jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPla
     }
     if ((st = gemm_forward(a, w1b, dwc.b1, nullptr, u, M, dwc.hidden, C, JV_EPI_SILU, true, stream, lda)) != JV_OK)
         return st;
-    if ((st = gemm_forward(u, w2b, dwc.b2, nullptr, kappa, M, C * kk, dwc.hidden, JV_EPI_NONE, true, stream)) != JV_OK)
+    if ((st = gemm_forward(u, w2b, b2p, nullptr, kappa, M, C * kk, dwc.hidden, JV_EPI_NONE, false, stream)) != JV_OK)
         return st;
     if (dwc.ksize == 3) {
         if (pr.o_bf16) launch_token_add<3, true>(stream, pr, la, kappa, total);

@@ -197,12 +197,15 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     // instruction; lane = 8 * (row in group) + LDS chunk slot, and it fetches the global chunk
     // that belongs in that slot under the row rotation.  Four loads per wavefront and part.
     const int lrow = lane >> 3;
+    // The tile's first rows are 64-bit bases (the same in every lane); the offsets inside the
+    // tile, 255 rows at most, fit 32 bits (the launcher bounds lda and K).
+    const char *a_tile = (const char *)(A + (size_t)m0 * lda), *w_tile = (const char *)(W + (size_t)n0 * K);
     unsigned a_off[kPartLoads], w_off[kPartLoads];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
     for (int j = 0; j < kPartLoads; ++j) {
         const int r = wave * 32 + j * 8 + lrow;
         const int gchunk = (lane & 7) ^ ((r >> 1) & 7);
-        const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);  // edge tiles re-read the last row
+        const int ar = min(r, M - 1 - m0), wr = min(r, N - 1 - n0);  // edge tiles re-read the last row
         a_off[j] = 2u * ((unsigned)ar * (unsigned)lda + gchunk * 8);  // rows of a are lda elements apart
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
@@ -214,12 +217,12 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         if (part & 1) {
 #pragma unroll
             for (int j = j0; j < j1; ++j)
-                __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)W + (w_off[j] + kbytes)),
+                __builtin_amdgcn_global_load_lds((global_cvoid *)(w_tile + (w_off[j] + kbytes)),
                                                  (lds_void *)(base + j * 1024), 16, 0, 0);
         } else {
 #pragma unroll
             for (int j = j0; j < j1; ++j)
-                __builtin_amdgcn_global_load_lds((global_cvoid *)((const char *)A + (a_off[j] + kbytes)),
+                __builtin_amdgcn_global_load_lds((global_cvoid *)(a_tile + (a_off[j] + kbytes)),
                                                  (lds_void *)(base + j * 1024), 16, 0, 0);
         }
     };
@@ -452,21 +455,31 @@ static jv_status launch_gemm(const void *a, const void *w, const float *bias, co
     return launch_status("gemm_bf16_kernel");
 }
 
+// Shape limits of the GEMM (no pointers): what jv_gemm_bias_act documents.  The kernel addresses
+// a tile's rows with 32-bit byte offsets from the tile's first row (256 rows of at most 2^21
+// elements) and counts tiles and rows in 32-bit integers.
+jv_status gemm_check_shape(long long M, int N, int K, long long lda_arg) {
+    if (M <= 0 || N <= 0 || K <= 0) return fail(JV_ERR_INVALID_ARG, "M, N, K must be positive");
+    const long long lda = lda_arg > 0 ? lda_arg : K;
+    if (lda < K || lda % 8) return fail(JV_ERR_INVALID_ARG, "row stride of a below K or not a multiple of 8");
+    if (K % 64) return fail(JV_ERR_UNSUPPORTED, "K must be a multiple of 64");
+    if (N % 8) return fail(JV_ERR_UNSUPPORTED, "N must be a multiple of 8");
+    if (lda > (1 << 21)) return fail(JV_ERR_UNSUPPORTED, "rows of a above 2^21 elements");
+    if (M > (1ll << 30) || N > (1 << 30)) return fail(JV_ERR_UNSUPPORTED, "M or N above 2^30");
+    const long long tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
+    if (tiles > (1ll << 30)) return fail(JV_ERR_UNSUPPORTED, "more than 2^30 output tiles");
+    return JV_OK;
+}
+
 jv_status gemm_forward(const void *a, const void *w, const float *bias, const void *residual,
                        void *y, long long M, int N, int K, int epi, bool out_bf16,
                        hipStream_t stream, long long lda_arg) {
-    if (M <= 0 || N <= 0 || K <= 0) return fail(JV_ERR_INVALID_ARG, "M, N, K must be positive");
-    const long long lda_ll = lda_arg > 0 ? lda_arg : K;
-    if (lda_ll < K || lda_ll % 8) return fail(JV_ERR_INVALID_ARG, "row stride of a below K or not a multiple of 8");
-    if (M * lda_ll >= (1ll << 30)) return fail(JV_ERR_UNSUPPORTED, "operand above 2^30 elements");
-    const int lda = (int)lda_ll;
+    jv_status shape = gemm_check_shape(M, N, K, lda_arg);
+    if (shape != JV_OK) return shape;
+    const int lda = (int)(lda_arg > 0 ? lda_arg : K);
     if (!a || !w || !y) return fail(JV_ERR_INVALID_ARG, "a, w, y must be non-null");
     if (((uintptr_t)a | (uintptr_t)w | (uintptr_t)y | (uintptr_t)bias | (uintptr_t)residual) & 15)
         return fail(JV_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
-    if (K % 64) return fail(JV_ERR_UNSUPPORTED, "K must be a multiple of 64");
-    if (N % 8) return fail(JV_ERR_UNSUPPORTED, "N must be a multiple of 8");
-    if (M * (long long)K >= (1ll << 30) || (long long)N * K >= (1ll << 30) || M > (1 << 24))
-        return fail(JV_ERR_UNSUPPORTED, "operand above 2^30 elements");
     if (epi == JV_EPI_RESIDUAL && !residual)
         return fail(JV_ERR_INVALID_ARG, "residual epilogue needs a residual tensor");
     switch (epi) {
@@ -518,6 +531,30 @@ static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N) 
     }
     return need;
 }
+// Everything a forward pass over (batch, grid) would be refused for after its first launch,
+// checked on the host: the four GEMM shapes, the window partition, the token-count limits of
+// the mixers.
+static jv_status encoder_check_shapes(const jv_encoder *enc, int batch, int grid_h, int grid_w) {
+    const jv_encoder_config &c = enc->cfg;
+    if (batch <= 0 || grid_h <= 0 || grid_w <= 0)
+        return fail(JV_ERR_INVALID_ARG, "batch and grid must be positive");
+    if ((long long)grid_h * grid_w > (1 << 24)) return fail(JV_ERR_UNSUPPORTED, "more than 2^24 tokens per image");
+    if ((long long)batch * c.heads > 65535) return fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
+    const long long N = c.n_prefix + (long long)grid_h * grid_w, T = batch * N;
+    const int C = c.width;
+    jv_status st;
+    if ((st = gemm_check_shape(T, 3 * C, C)) != JV_OK) return st;
+    if ((st = gemm_check_shape(T, C, C)) != JV_OK) return st;
+    if ((st = gemm_check_shape(T, c.mlp_hidden, C)) != JV_OK) return st;
+    if ((st = gemm_check_shape(T, C, c.mlp_hidden)) != JV_OK) return st;
+    if (T > (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "more than 2^31 tokens");
+    Problem pr;
+    pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = (int)N; pr.P = c.n_prefix;
+    for (int l = 0; l < c.n_blocks; ++l)
+        if (enc->pattern[l] == 1) return window_check(pr, c.win_h, c.win_w);
+    return JV_OK;
+}
+
 }  // namespace jv
 
 extern "C" {
@@ -617,7 +654,7 @@ void jv_encoder_destroy(jv_encoder *enc) {
 size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
                                   int32_t grid_w) {
     jv::clear_error();
-    if (!enc || batch <= 0 || grid_h <= 0 || grid_w <= 0) return 0;
+    if (!enc || jv::encoder_check_shapes(enc, batch, grid_h, grid_w) != JV_OK) return 0;
     const size_t T = (size_t)batch * (enc->cfg.n_prefix + (size_t)grid_h * grid_w), C = enc->cfg.width;
     const size_t wide = 3 * C > (size_t)enc->cfg.mlp_hidden ? 3 * C : (size_t)enc->cfg.mlp_hidden;
     return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
@@ -647,8 +684,8 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
         for (int j = 0; j < i; ++j)
             if (tap_out[j] == tap_out[i]) return jv::fail(JV_ERR_INVALID_ARG, "tap_out entries must be distinct");
     }
-    if (batch <= 0 || grid_h <= 0 || grid_w <= 0)
-        return jv::fail(JV_ERR_INVALID_ARG, "batch and grid must be positive");
+    jv_status shapes = jv::encoder_check_shapes(enc, batch, grid_h, grid_w);
+    if (shapes != JV_OK) return shapes;
     if (((uintptr_t)x | (uintptr_t)y) & 15) return jv::fail(JV_ERR_INVALID_ARG, "x, y must be 16-byte aligned");
     if ((uintptr_t)workspace & 255) return jv::fail(JV_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
     const size_t need = jv_encoder_workspace_bytes(enc, batch, grid_h, grid_w);
@@ -658,7 +695,6 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
     const jv_encoder_config &c = enc->cfg;
     const int N = c.n_prefix + grid_h * grid_w, C = c.width;
     const long long T = (long long)batch * N;
-    if ((long long)batch * c.heads > 65535) return jv::fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
     hipStream_t stream = (hipStream_t)hip_stream;
     const size_t wide = 3 * (size_t)C > (size_t)c.mlp_hidden ? 3 * (size_t)C : (size_t)c.mlp_hidden;
     unsigned char *ws = (unsigned char *)workspace;

@@ -28,10 +28,11 @@ struct DwcPlan {
     size_t kappa_off = 0;   // [B][C][k*k] generated filters (dynamic mode)
     // Token-wise dynamic mode (regions of bf16 elements unless noted, offsets still in floats):
     size_t w1b_off = 0;     // [hidden][C] generator weights rounded to bf16
-    size_t w2b_off = 0;     // [C*k*k][hidden]
+    size_t w2b_off = 0;     // [k*k][C][hidden]: rows reordered tap-major
+    size_t b2p_off = 0;     // fp32 [k*k][C]: the second bias in the same order
     size_t vt_off = 0;      // [B*N][C] V as token rows, when its own layout is not such a matrix
     size_t u_off = 0;       // [B*N][hidden] hidden layer of every token
-    size_t tok_kappa_off = 0;  // [B*N][C*k*k] filters of every token
+    size_t tok_kappa_off = 0;  // fp32 [B*N][k*k][C] filters of every token, tap-major
     size_t la_off = 0;      // fp32 [B*N][C] linear-attention term before the convolution is added
     size_t total_floats = 0;
 };

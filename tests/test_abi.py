@@ -52,25 +52,35 @@ def test_argument_validation_launches_nothing():
                            binding.JvStrides(2 * 16 * 64, 16 * 64, 64),
                            binding.JvStrides(2 * 16 * 64, 16 * 64, 64))
     assert binding.jv_linear_attn_workspace_bytes(d) > 0
+    Q, K, V, O = 0x10000, 0x20000, 0x30000, 0x40000   # never dereferenced: every call below is refused
     # null tensors
     assert L.jv_full_attn_fwd(ctypes.byref(d), None, None, None, None, 0.0, None) == binding.JV_ERR_INVALID_ARG
     assert b"non-null" in L.jv_last_error()
     # head_dim other than 64
     d2 = binding.JvAttnDesc.from_buffer_copy(d)
     d2.head_dim = 128
-    assert L.jv_full_attn_fwd(ctypes.byref(d2), 16, 32, 48, 64, 0.0, None) == binding.JV_ERR_UNSUPPORTED
+    assert L.jv_full_attn_fwd(ctypes.byref(d2), Q, K, V, O, 0.0, None) == binding.JV_ERR_UNSUPPORTED
     assert binding.jv_linear_attn_workspace_bytes(d2) == 0
     # misaligned pointer, aliasing output, bad window, bad eps, small workspace
-    assert L.jv_full_attn_fwd(ctypes.byref(d), 16, 32, 48, 68, 0.0, None) == binding.JV_ERR_INVALID_ARG
-    assert L.jv_full_attn_fwd(ctypes.byref(d), 16, 32, 48, 16, 0.0, None) == binding.JV_ERR_INVALID_ARG
-    assert L.jv_window_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, 0, 4, 0.0, None) == binding.JV_ERR_INVALID_ARG
-    assert L.jv_linear_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, -1.0, 256, 1 << 30, None) == binding.JV_ERR_INVALID_ARG
-    assert L.jv_linear_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, 1e-6, 256, 16, None) == binding.JV_ERR_WORKSPACE_TOO_SMALL
-    assert L.jv_linear_attn_fwd(ctypes.byref(d), 16, 32, 48, 64, 1e-6, None, 1 << 30, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_full_attn_fwd(ctypes.byref(d), Q, K, V, O + 4, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_full_attn_fwd(ctypes.byref(d), Q, K, V, Q, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert b"overlap" in L.jv_last_error()
+    # ... also when O only overlaps the tail of an input (each tensor spans 8192 bytes here)
+    assert L.jv_full_attn_fwd(ctypes.byref(d), Q, K, V, V + 8192 - 256, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert b"overlap" in L.jv_last_error()
+    assert L.jv_full_attn_fwd(ctypes.byref(d), Q, K, V, K - 8192 + 16, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_window_attn_fwd(ctypes.byref(d), Q, K, V, O, 0, 4, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert b"window" in L.jv_last_error()
+    assert L.jv_linear_attn_fwd(ctypes.byref(d), Q, K, V, O, -1.0, 256, 1 << 30, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_linear_attn_fwd(ctypes.byref(d), Q, K, V, O, 1e-6, 256, 16, None) == binding.JV_ERR_WORKSPACE_TOO_SMALL
+    assert L.jv_linear_attn_fwd(ctypes.byref(d), Q, K, V, O, 1e-6, None, 1 << 30, None) == binding.JV_ERR_INVALID_ARG
     # stride that breaks row alignment
     d3 = binding.JvAttnDesc.from_buffer_copy(d)
     d3.q.stride_n = 66
-    assert L.jv_full_attn_fwd(ctypes.byref(d3), 16, 32, 48, 64, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_full_attn_fwd(ctypes.byref(d3), Q, K, V, O, 0.0, None) == binding.JV_ERR_INVALID_ARG
+    # a padded grid whose cell count does not fit 32 bits
+    with pytest.raises(binding.JvError):
+        binding.jv_window_geometry(1 << 24, 1, 1, 1 << 14)
     with pytest.raises(binding.JvError):
         binding.jv_window_geometry(4, 4, 0, 2)
     assert L.jv_status_string(3) == b"workspace too small"
@@ -78,7 +88,7 @@ def test_argument_validation_launches_nothing():
 
 def test_block_workspace_query_by_convolution_mode():
     """jv_linear_block_workspace_bytes (host only): grows with the mode's buffers; the token-wise
-    mode holds the bf16 filters of every token; parameter blocks the library does not support
+    mode holds the fp32 filters of every token; parameter blocks the library does not support
     answer 0."""
     B, heads, H, W, P = 2, 3, 10, 12, 4
     C, N, hidden, k = heads * 64, P + H * W, 64, 3
@@ -98,9 +108,23 @@ def test_block_workspace_query_by_convolution_mode():
     token = binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_TOKEN_DYNAMIC))
     M = B * N
     exact = (2 * hidden * C + 2 * C * k * k * hidden      # bf16 generator weights
+             + 4 * C * k * k                              # reordered second bias
              + 2 * M * C + 2 * M * hidden                 # V rows, hidden layer
-             + 2 * M * C * k * k + 4 * M * C)             # filters of every token, fp32 attention term
-    assert plain + exact <= token <= plain + exact + 6 * 256
+             + 4 * M * C * k * k + 4 * M * C)             # fp32 filters of every token, fp32 attention term
+    assert plain + exact <= token <= plain + exact + 7 * 256
     assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_TOKEN_DYNAMIC, hid=40)) == 0
     assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_STATIC, ksize=4)) == 0
     assert binding.jv_linear_block_workspace_bytes(d, params(4)) == 0
+
+
+def test_gemm_shape_limits_are_checked_on_the_host():
+    """jv_gemm_bias_act refuses on the host what its kernel cannot address; large token counts
+    (a 256 x 256 grid at batch 4 against a 4096-wide hidden layer) are inside the limits."""
+    L = binding.lib()
+    A, W, Y = 0x100000, 0x200000, 0x300000   # never dereferenced
+    call = lambda M, N, K: L.jv_gemm_bias_act(A, W, None, None, Y, M, N, K, binding.JV_EPI_NONE, binding.JV_BF16, None)
+    assert call(16, 64, 96) == binding.JV_ERR_UNSUPPORTED       # K % 64
+    assert call(16, 60, 64) == binding.JV_ERR_UNSUPPORTED       # N % 8
+    assert call(0, 64, 64) == binding.JV_ERR_INVALID_ARG
+    assert call(16, 64, 1 << 22) == binding.JV_ERR_UNSUPPORTED  # rows above 2^21 elements
+    assert call((1 << 30) + 1, 64, 64) == binding.JV_ERR_UNSUPPORTED

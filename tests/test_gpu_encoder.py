@@ -72,6 +72,32 @@ def test_gemm_epilogues(M, N, K):
     check(err_bf16(to_host(y32), plain / (1.0 + np.exp(-plain))), 1e-4)
 
 
+def test_gemm_rows_beyond_32_bit_offsets_and_rerun_bits():
+    """A above 2^30 elements (270 336 rows of 4096: the fc2 shape of a 256 x 256 grid at batch 4):
+    row tiles are addressed from 64-bit bases.  A is one 4096-row block repeated, so every block
+    of y must repeat the first one bit for bit, and the first one is checked against the oracle.
+    The same launch repeated gives the same bits (the operand ring is ordered by counted waits)."""
+    rep, M0, K, N = 66, 4096, 4096, 64
+    a = synth.round_to_bf16(synth.normal((M0, K), 640))
+    w = synth.round_to_bf16(synth.normal((N, K), 641, 1.0 / np.sqrt(K)))
+    bias = synth.normal((N,), 642)
+    da = torch.from_numpy(a).cuda().to(torch.bfloat16).repeat(rep, 1)
+    assert da.numel() > (1 << 30)
+    dw, db = torch.from_numpy(w).cuda().to(torch.bfloat16), torch.from_numpy(bias).cuda()
+    y = torch.full((rep * M0, N), float("nan"), device="cuda")
+    binding.jv_gemm_bias_act(da, dw, db, None, y, binding.JV_EPI_NONE)
+    check(err_bf16(to_host(y[:M0]), oracle.linear(a.astype(np.float64), w, bias)), 1e-4)
+    assert torch.equal(y.view(rep, M0, N), y[:M0].expand(rep, M0, N))
+    for _ in range(3):
+        y2 = torch.empty_like(y)
+        binding.jv_gemm_bias_act(da, dw, db, None, y2, binding.JV_EPI_NONE)
+        assert torch.equal(y2, y)
+    res = torch.from_numpy(synth.normal((M0, N), 643)).cuda().repeat(rep, 1)
+    z = torch.empty_like(y)
+    binding.jv_gemm_bias_act(da, dw, db, res, z, binding.JV_EPI_RESIDUAL)
+    assert torch.equal(z, y + res)
+
+
 def test_gemm_rejects_unsupported_shapes():
     a = torch.zeros(8, 96, device="cuda", dtype=torch.bfloat16)
     w = torch.zeros(16, 96, device="cuda", dtype=torch.bfloat16)
@@ -170,6 +196,57 @@ def test_config5_first_six_blocks_full_size():
     ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16))
     check(err_bf16(to_host(y), ref), BF16_TOL)
     check(err_bf16(to_host(y) - x, ref - x), BF16_TOL)   # what the six blocks added
+    enc.close()
+
+
+# Drift of the whole 24-block forward against the fp64 oracle, image 0 of the encoder workload.
+# Tensors between kernels are bf16, so every block adds roundings that the later blocks carry
+# along; the bound asserted is what the build measures plus headroom, not the per-block bar.
+FULL_DEPTH_TOL = 4e-2
+
+
+def test_config5_full_depth_against_oracle():
+    """All 24 blocks of the encoder workload (4 full / 12 window / 8 linear) on image 0 at full
+    size against the oracle's fp64 forward: the end-to-end drift, printed and bounded."""
+    H = W = 64
+    heads, hidden, C, L = 16, 4096, 1024, 24
+    pattern = synth.encoder_pattern(L)
+    x = synth.normal((4, H * W, C), 5003)[:1]
+    blocks = [synth.block_weights(C, hidden, 5000 + l) for l in range(L)]
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16))
+    dx = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    y = torch.empty_like(dx)
+    taps = {l: torch.empty_like(dx) for l in (5, 11, 17)}
+    enc.forward(dx, y, (H, W), taps=taps)
+    ref, kept = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(16, 16), taps={5, 11, 17})
+    for l in (5, 11, 17):
+        e = err_bf16(to_host(taps[l]), kept[l])
+        rms = float(np.sqrt(np.mean((to_host(taps[l]) - kept[l]) ** 2)) / np.sqrt(np.mean(kept[l] ** 2)))
+        print(f"    after block {l}: max |g - r| / RMS {e:.3e}, RMS error / RMS {rms:.3e}")
+    got = to_host(y)
+    rms = float(np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
+    print(f"    after block 23: RMS error / RMS {rms:.3e}")
+    check(err_bf16(got, ref), FULL_DEPTH_TOL)
+    enc.close()
+
+
+def test_refused_forward_touches_nothing():
+    """A (batch, grid) the pass cannot run is refused before the first launch: y keeps its
+    bytes, and the workspace query answers 0 for it."""
+    heads, hidden = 2, 256
+    C = heads * 64
+    enc = binding.Encoder(_device_blocks([synth.block_weights(C, hidden, 1100)]), [1], heads, hidden, window=(1, 1))
+    H = W = 300                       # 90 000 windows of one token: above the 65 535 the kernels index
+    assert enc.workspace_bytes(1, (H, W)) == 0
+    assert enc.workspace_bytes(1, (200, 200)) > 0
+    x = torch.zeros(1, H * W, C, device="cuda")
+    y = torch.full_like(x, 3.25)
+    ws = torch.empty(enc.workspace_bytes(1, (200, 200)) * 4, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.JvError) as e:
+        enc.forward(x, y, (H, W), ws)
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert float(y.min()) == 3.25 and float(y.max()) == 3.25
     enc.close()
 
 

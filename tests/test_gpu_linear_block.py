@@ -115,41 +115,34 @@ def test_bf16_token_wise_dynamic(B, heads, H, W, P, ksize):
     """Per-token dynamic filters (Tab. 1, "Token-wise Dynamic DWC"): generator on every token's
     V row, each token's own filters on its neighbourhood.
 
-    The generator runs as a bf16 network does: weights, hidden layer and filters are each rounded
-    to bf16 (2^-9 relative), three roundings in a chain in front of a sum of k*k products that
-    may cancel.  The bar is therefore the usual 2e-2 RMS plus the forward bound of that sum,
-    2^-7 * sum_taps |filter * v| (4 half-ulps: the three roundings and their interaction), taken
-    element-wise from the oracle; the same run is also compared with the oracle evaluated
-    with exactly these three roundings."""
+    Inputs are bf16 values, the generator's matrices included (as for every bf16 workload: rounded
+    once on the host, so the matrix cores multiply exactly what the oracle sees); the kernels
+    round the hidden layer to bf16 and keep the filters in fp32.  The bar is the plain one for
+    bf16 inputs with fp32 accumulation, 2e-2 RMS; the same run is also compared with the oracle
+    evaluated with that one rounding, which it must reproduce far more closely."""
     C, hidden = heads * 64, 64
     q, k, v = synth.qkv(33, B, heads, P + H * W, 64, 0.5, True)
-    tok = synth.squeeze_weights(C, hidden, ksize, 3500 + ksize)
+    w1, b1, w2, b2 = synth.squeeze_weights(C, hidden, ksize, 3500 + ksize)
+    tok = (synth.round_to_bf16(w1), b1, synth.round_to_bf16(w2), b2)
     ref = oracle.linear_block(q, k, v, H, W, 1e-6, ksize=ksize, token=tok)
     o32 = _block(q, k, v, H, W, True, torch.float32, ksize=ksize, token=_dev(*tok))
     o16 = _block(q, k, v, H, W, True, torch.bfloat16, ksize=ksize, token=_dev(*tok))
-    assert torch.equal(o32.to(torch.bfloat16), o16), "bf16 output is not RNE(fp32 output)"
-    vg = np.ascontiguousarray(v[:, :, P:])
-    kap = oracle.tokenwise_kernels(vg, *tok, ksize)
-    slack = np.zeros_like(ref)
-    slack[:, :, P:] = 2.0 ** -7 * oracle.dwc_tokenwise(np.abs(vg), np.abs(kap), H, W)
-    rms = np.sqrt(np.mean(ref * ref))
-    g32, g16 = to_host(o32), to_host(o16)
-    check(float(np.max(np.abs(g32 - ref) - slack) / rms), BF16_TOL)
-    check(float(np.max(np.abs(g16 - ref) - slack - np.abs(ref) * 2.0 ** -8) / rms), BF16_TOL)
-    # the same three roundings applied to the oracle's own stages
+    check_bf16_pair(o32, o16, ref)
+    # the hidden layer's rounding applied to the oracle's own stages
     rb = lambda a: synth.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
     w1, b1, w2, b2 = tok
+    vg = np.ascontiguousarray(v[:, :, P:])
     rows = vg.transpose(0, 2, 1, 3).reshape(B, H * W, C).astype(np.float64)
-    pre = rows @ rb(w1).T + b1
+    pre = rows @ w1.astype(np.float64).T + b1
     u = rb(pre / (1.0 + np.exp(-pre)))
-    kap_r = rb(u @ rb(w2).T + b2).reshape(B, H * W, C, ksize, ksize)
+    kap_r = (u @ w2.astype(np.float64).T + b2).reshape(B, H * W, C, ksize, ksize)
     la = oracle.linear_attn_quadratic(q, k, v, 1e-6)
     same = la.copy()
     same[:, :, P:] += oracle.dwc_tokenwise(vg, kap_r, H, W)
-    # fp32 against fp64 accumulation flips the bf16 rounding of a few filter entries by one
-    # ulp: isolated differences of up to ulp(filter) * |v|, none on average
+    # (fp32 against fp64 accumulation flips the bf16 rounding of a few hidden units by one ulp)
+    g32, rms = to_host(o32), np.sqrt(np.mean(ref * ref))
     check(float(np.sqrt(np.mean((g32 - same) ** 2)) / rms), 3e-4)
-    check(err_bf16(g32, same, rms), 2.0 ** -7 * np.abs(kap).max() * np.abs(vg).max() / rms + 1e-3)
+    check(err_bf16(g32, same, rms), 5e-3)
     if P:           # prefix rows are plain linear attention, bit for bit
         dq, dk, dv = (to_device(x, True) for x in (q, k, v))
         plain = torch.empty_like(o32)
@@ -158,9 +151,8 @@ def test_bf16_token_wise_dynamic(B, heads, H, W, P, ksize):
 
 
 def test_token_wise_special_filters():
-    """W2 = 0 makes every token's filters the static bank b2 (chosen bf16-representable, as the
-    generated filters are stored in bf16): the static block's result up to the order of the
-    fp32 additions."""
+    """W2 = 0 makes every token's filters the static bank b2: the static block's result up to the
+    order of the fp32 additions."""
     B, heads, H, W = 1, 2, 12, 9
     C, hidden = heads * 64, 64
     q, k, v = synth.qkv(34, B, heads, H * W, 64, 0.5, True)
