@@ -199,15 +199,11 @@ def test_config5_first_six_blocks_full_size():
     enc.close()
 
 
-# Drift of the whole 24-block forward against the fp64 oracle, image 0 of the encoder workload.
-# Tensors between kernels are bf16, so every block adds roundings that the later blocks carry
-# along; the bound asserted is what the build measures plus headroom, not the per-block bar.
-FULL_DEPTH_TOL = 4e-2
-
-
 def test_config5_full_depth_against_oracle():
     """All 24 blocks of the encoder workload (4 full / 12 window / 8 linear) on image 0 at full
-    size against the oracle's fp64 forward: the end-to-end drift, printed and bounded."""
+    size against the oracle's fp64 forward: the end-to-end drift, printed, and held to the same
+    2e-2 RMS bar as a single block (measured: 1.2e-2 at every tap and at the end; the stream's
+    own RMS grows with depth as fast as the roundings the blocks add)."""
     H = W = 64
     heads, hidden, C, L = 16, 4096, 1024, 24
     pattern = synth.encoder_pattern(L)
@@ -226,7 +222,7 @@ def test_config5_full_depth_against_oracle():
     got = to_host(y)
     rms = float(np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
     print(f"    after block 23: RMS error / RMS {rms:.3e}")
-    check(err_bf16(got, ref), FULL_DEPTH_TOL)
+    check(err_bf16(got, ref), BF16_TOL)
     enc.close()
 
 
