@@ -116,6 +116,23 @@ jv_status jv_linear_attn_fwd(const jv_attn_desc *desc, const void *q, const void
                              size_t workspace_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * jv_linear_attn_fwd_static: jv_linear_attn_fwd for callers that cannot allocate device memory
+ * or pass a workspace -- code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels and same result as jv_linear_attn_fwd; the partial states live in a
+ * fixed array of JV_STATIC_SCRATCH_BYTES of device memory that is part of the library's code
+ * object (every GPU the library runs on holds one copy until the process ends).  The call
+ * allocates and frees nothing; its first call on a device looks the array's address up.
+ * Problems whose states need more than the array holds (jv_linear_attn_workspace_bytes(desc) >
+ * JV_STATIC_SCRATCH_BYTES) are refused with JV_ERR_UNSUPPORTED before any launch.  All calls on
+ * one GPU share the array: calls that may overlap in time on the same GPU (different streams or
+ * threads) race with each other and must be serialised by the caller; calls on one stream are
+ * ordered by the stream.  Nothing in the array has to be cleared between calls.
+ * ------------------------------------------------------------------------- */
+#define JV_STATIC_SCRATCH_BYTES (32u << 20)
+jv_status jv_linear_attn_fwd_static(const jv_attn_desc *desc, const void *q, const void *k,
+                                    const void *v, void *o, float eps, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * The paper's linear-attention block (Sec. 3.2.1, Eq. 4): the normalised ReLU linear attention
  * above plus a depth-wise convolution of V on the token grid,
  *     O = LA(Q, K, V) + DWC(V).

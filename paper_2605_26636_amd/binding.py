@@ -18,7 +18,7 @@ JV_F32, JV_BF16 = 0, 1
 
 EXPORTS = [
     "jv_version", "jv_status_string", "jv_last_error",
-    "jv_linear_attn_workspace_bytes", "jv_linear_attn_fwd",
+    "jv_linear_attn_workspace_bytes", "jv_linear_attn_fwd", "jv_linear_attn_fwd_static",
     "jv_linear_block_workspace_bytes", "jv_linear_block_fwd", "jv_linear_block_focused_fwd",
     "jv_window_geometry", "jv_window_maps_host", "jv_window_maps_device",
     "jv_window_attn_fwd", "jv_full_attn_fwd",
@@ -89,6 +89,7 @@ def lib():
         vp = ctypes.c_void_p
         L.jv_linear_attn_fwd.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp,
                                          ctypes.c_float, vp, ctypes.c_size_t, vp]
+        L.jv_linear_attn_fwd_static.argtypes = [ctypes.POINTER(JvAttnDesc), vp, vp, vp, vp, ctypes.c_float, vp]
         L.jv_linear_block_workspace_bytes.restype = ctypes.c_size_t
         L.jv_linear_block_workspace_bytes.argtypes = [ctypes.POINTER(JvAttnDesc),
                                                       ctypes.POINTER(JvDwcParams)]
@@ -183,6 +184,17 @@ def jv_linear_attn_fwd(q, k, v, o, grid, eps=1e-6, workspace=None, stream=None):
                                     o.data_ptr(), eps, workspace.data_ptr(),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
     return workspace
+
+
+JV_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def jv_linear_attn_fwd_static(q, k, v, o, grid, eps=1e-6, stream=None):
+    """o <- ReLU linear attention of (q, k, v) through the entry point that takes its scratch from
+    the library's fixed device array (allocates nothing)."""
+    desc = make_desc(q, k, v, o, grid)
+    _check(lib().jv_linear_attn_fwd_static(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                           o.data_ptr(), eps, _stream(stream)))
 
 
 def make_dwc_params(static_kernel=None, squeeze=None, ksize=3, token=None):

@@ -224,6 +224,36 @@ jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStrea
 
 }  // namespace jv
 
+// ---------------------------------------------------------------------------------------
+// Scratch of the allocation-free entry point (jv_linear_attn_fwd_static): the partial and
+// combined linear-attention states live in a fixed array in device memory that belongs to the
+// library's code object -- one copy per GPU, at its own address on each, held until the
+// process ends.  In host code the array's name is only a handle for the symbol lookup below;
+// what the kernels get is the device address that lookup returns.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char jv_static_scratch[JV_STATIC_SCRATCH_BYTES];
+
+namespace jv {
+// Device address of jv_static_scratch on the current device, looked up once per device.
+static jv_status static_scratch_address(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> address[kMaxDevices];  // zero-initialised
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(JV_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(JV_ERR_UNSUPPORTED, "device ordinal %d above %d", dev, kMaxDevices - 1);
+    void *p = address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(jv_static_scratch));
+        if (e != hipSuccess || !p)
+            return fail(JV_ERR_HIP, "hipGetSymbolAddress(static scratch): %s", hipGetErrorString(e));
+        address[dev].store(p, std::memory_order_release);  // (two threads may both look it up: same value)
+    }
+    *out = p;
+    return JV_OK;
+}
+}  // namespace jv
+
 static jv_status check_linear_args(float eps, const void *workspace) {
     if (!(eps >= 0.0f)) return jv::fail(JV_ERR_INVALID_ARG, "eps must be >= 0");
     if (!workspace) return jv::fail(JV_ERR_INVALID_ARG, "workspace is null");
@@ -263,6 +293,27 @@ jv_status jv_linear_block_fwd(const jv_attn_desc *desc, const void *q, const voi
     if (st != JV_OK) return st;
     if ((st = check_linear_args(eps, workspace)) != JV_OK) return st;
     return jv::linear_block_forward(pr, eps, dwc, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+jv_status jv_linear_attn_fwd_static(const jv_attn_desc *desc, const void *q, const void *k,
+                                    const void *v, void *o, float eps, void *hip_stream) {
+    jv::clear_error();
+    jv::Problem pr;
+    jv_status st = jv::make_problem(desc, q, k, v, o, &pr);
+    if (st != JV_OK) return st;
+    if (!(eps >= 0.0f)) return jv::fail(JV_ERR_INVALID_ARG, "eps must be >= 0");
+    jv::DwcPlan plain;
+    if ((st = jv::plan_dwc(nullptr, jv::plan_linear(pr.B, pr.heads, pr.N), pr.B, pr.heads, pr.N, &plain)) != JV_OK)
+        return st;
+    const size_t need = plain.total_floats * sizeof(float);  // what jv_linear_attn_workspace_bytes answers
+    if (need > (size_t)JV_STATIC_SCRATCH_BYTES)
+        return jv::fail(JV_ERR_UNSUPPORTED, "this problem needs %zu bytes of scratch, the static scratch holds %zu",
+                        need, (size_t)JV_STATIC_SCRATCH_BYTES);
+    void *scratch = nullptr;
+    if ((st = jv::static_scratch_address(&scratch)) != JV_OK) return st;
+    // Nothing in the scratch has to start at zero: the state pass writes every partial state it
+    // later reads in full.
+    return jv::linear_block_forward(pr, eps, nullptr, scratch, need, (hipStream_t)hip_stream);
 }
 
 jv_status jv_linear_block_focused_fwd(const jv_attn_desc *desc, const void *q, const void *k,
