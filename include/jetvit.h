@@ -347,6 +347,25 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
                             jv_encoder **out);
 size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
                                   int32_t grid_w);
+/* ---------------------------------------------------------------------------
+ * jv_encoder_fold_layernorm (optional, once after jv_encoder_create): fold the block's two
+ * LayerNorms into the matrix products behind them, so that a forward pass runs no LayerNorm pass
+ * except the very first one.  The block is unchanged as a function (pre-LN block of Sec. 3.2.3's
+ * inherited MLP and projections); what changes is where the normalisation is applied:
+ *     W LN(x) + b = rstd (W diag(gamma)) x - rstd mean (W gamma) + (W beta + b),
+ * so the products multiply the bf16 stream itself with the weights scaled by gamma (rounded to
+ * bf16 once more), and mean and 1/sigma enter their epilogues; the residual products before
+ * them write the stream's bf16 rows and per-row statistics next to their result.  Rounding
+ * differs from the separate pass (the stream is rounded before the mean is removed, so the
+ * relative error grows with |mean| / sigma of a token's features), the arithmetic does not.
+ * buffer: device memory of jv_encoder_fold_bytes(enc) bytes, 256-byte aligned, owned by the
+ * caller; the call launches the folding kernels on hip_stream and the encoder keeps the pointer:
+ * the buffer must stay alive and unchanged while forward passes run.  Afterwards
+ * jv_encoder_workspace_bytes asks for one more [tokens, width] bf16 buffer and the statistics.
+ * buffer = NULL switches back to separate LayerNorm passes.
+ * ------------------------------------------------------------------------- */
+size_t jv_encoder_fold_bytes(const jv_encoder *enc);
+jv_status jv_encoder_fold_layernorm(jv_encoder *enc, void *buffer, size_t buffer_bytes, void *hip_stream);
 jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
                              int32_t grid_h, int32_t grid_w, void *workspace,
                              size_t workspace_bytes, void *hip_stream);

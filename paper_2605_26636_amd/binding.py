@@ -24,6 +24,7 @@ EXPORTS = [
     "jv_window_attn_fwd", "jv_full_attn_fwd",
     "jv_layernorm_fwd", "jv_gemm_bias_act",
     "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_forward_taps", "jv_encoder_destroy",
+    "jv_encoder_fold_bytes", "jv_encoder_fold_layernorm",
 ]
 JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL, JV_EPI_SILU = 0, 1, 2, 3
 JV_DWC_NONE, JV_DWC_STATIC, JV_DWC_SQUEEZE_DYNAMIC, JV_DWC_TOKEN_DYNAMIC = 0, 1, 2, 3
@@ -116,6 +117,9 @@ def lib():
         L.jv_encoder_workspace_bytes.argtypes = [vp, i32, i32, i32]
         L.jv_encoder_forward.argtypes = [vp, vp, vp, i32, i32, i32, vp, ctypes.c_size_t, vp]
         L.jv_encoder_forward_taps.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.jv_encoder_fold_bytes.restype = ctypes.c_size_t
+        L.jv_encoder_fold_bytes.argtypes = [vp]
+        L.jv_encoder_fold_layernorm.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.jv_encoder_destroy.restype = None
         L.jv_encoder_destroy.argtypes = [vp]
         _lib = L
@@ -332,7 +336,7 @@ class Encoder:
     weights bf16, biases and LayerNorm parameters fp32); the tensors are kept alive here."""
 
     def __init__(self, blocks, pattern, heads, mlp_hidden, window=(16, 16), ln_eps=1e-6, la_eps=1e-6,
-                 la_focus_p=1, n_prefix=0, stream_dtype=torch.float32):
+                 la_focus_p=1, n_prefix=0, stream_dtype=torch.float32, fold_layernorm=False):
         self.blocks = blocks
         self.width = blocks[0]["w_o"].shape[0]
         n = len(blocks)
@@ -357,6 +361,21 @@ class Encoder:
                 table[i].dwc = ctypes.pointer(params)
         self._handle = ctypes.c_void_p()
         _check(lib().jv_encoder_create(ctypes.byref(cfg), table, ctypes.byref(self._handle)))
+        self._folded = None
+        if fold_layernorm:
+            self.fold_layernorm()
+
+    def fold_layernorm(self, enable=True, stream=None):
+        """Fold the LayerNorms into the products behind them (jv_encoder_fold_layernorm): the
+        folded weights live in a device tensor kept alive here."""
+        if not enable:
+            _check(lib().jv_encoder_fold_layernorm(self._handle, None, 0, _stream(stream)))
+            self._folded = None
+            return
+        need = int(lib().jv_encoder_fold_bytes(self._handle))
+        buf = torch.empty(max(need, 256), dtype=torch.uint8, device=self.blocks[0]["w_o"].device)
+        _check(lib().jv_encoder_fold_layernorm(self._handle, buf.data_ptr(), buf.numel(), _stream(stream)))
+        self._folded = buf
 
     def workspace_bytes(self, batch, grid):
         return int(lib().jv_encoder_workspace_bytes(self._handle, batch, grid[0], grid[1]))

@@ -179,11 +179,44 @@ __device__ inline void wait_loads_and_barrier(int pending) {
     else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int EPI, bool OUT_BF16>
+// LayerNorm folded into the matrix product that consumes it (the block's two LayerNorms sit
+// between a residual GEMM and a GEMM):
+//   sum_k w[n][k] LN(x)[k] = rstd (sum_k (w gamma)[n][k] x[k] - mean c1[n]) + c2[n],
+//   c1[n] = sum_k (w gamma)[n][k],  c2[n] = sum_k w[n][k] beta[k] + bias[n].
+// kLnProduce (residual epilogue): besides y it writes the stream rounded to bf16 (the A operand
+// of the next product; omitted when y is bf16 itself) and, per row and group of 64 features, the
+// group's mean and its sum of squared deviations.  kLnConsume (plain and GELU epilogues): A is
+// that bf16 stream, w is (w gamma) rounded to bf16, `bias` is c2; every workgroup first merges
+// the group statistics of its 256 rows into mean and 1/sigma (pairwise update of mean and
+// squared deviations), and the epilogue applies the formula above.
+enum { kLnNone = 0, kLnConsume = 1, kLnProduce = 2 };
+struct GemmLn {
+    const float *c1;        // consume: [N]
+    const float *stats_in;  // consume: [M][groups][2] (mean, sum of squared deviations) of 64 features each
+    float *stats_out;       // produce: [M][N / 64][2]
+    void *xb_out;           // produce: [M][N] bf16 copy of y, or null
+    int groups;             // consume: K / 64
+    float eps;              // consume
+};
+
+// Sum over the 16 lanes of a DPP row (the lanes that hold one token row of the fp32 tile).
+__device__ inline float row16_sum(float x) {
+    auto dpp = [](float v, auto ctrl_tag) {
+        constexpr int ctrl = decltype(ctrl_tag)::value;
+        return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
+    };
+    x += dpp(x, std::integral_constant<int, 0xB1>());   // quad_perm [1, 0, 3, 2]
+    x += dpp(x, std::integral_constant<int, 0x4E>());   // quad_perm [2, 3, 0, 1]
+    x += dpp(x, std::integral_constant<int, 0x141>());  // row_half_mirror
+    x += dpp(x, std::integral_constant<int, 0x140>());  // row_mirror
+    return x;
+}
+
+template <int EPI, bool OUT_BF16, int LN>
 __global__ void __launch_bounds__(512, 1)
 gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                  const float *__restrict__ bias, const void *residual, void *Y, int M, int N,
-                 int K, int lda, int tiles_n, int n_tiles) {
+                 int K, int lda, int tiles_n, int n_tiles, GemmLn ln) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
     const int per_xcd = (n_tiles + 7) / 8;
@@ -343,13 +376,68 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     // GELU reads the normal distribution function from a table in the third free slot, built
     // here by all threads (two or three entries each; see gelu_from_table).
     float *phi_table = (float *)(smem + a_slot * kGemmPart);
+    // Folded LayerNorm: thread t < 256 merges the group statistics of row m0 + t into mean and
+    // 1/sigma and hands the pair to the lanes that hold the row's token through LDS.  (Done here
+    // rather than under the first operand loads: values held across the K loop cost it more
+    // than this round trip costs the epilogue.)
+    constexpr int kStatLoads = 8;  // 16-byte loads (two groups each) in flight per thread
+    f32x4 stat_part[kStatLoads];
+    const f32x4 *gs = nullptr;
+    if (LN == kLnConsume && tid < kBM) {
+        gs = (const f32x4 *)((const float2 *)ln.stats_in + (size_t)min(m0 + tid, M - 1) * ln.groups);
+        const int pairs = ln.groups >> 1;
+#pragma unroll
+        for (int i = 0; i < kStatLoads; ++i) stat_part[i] = gs[min(i, max(pairs - 1, 0))];
+    }
+    float row_mean = 0.f, row_rstd = 0.f;
+    if (LN == kLnConsume && tid < kBM) {
+        float cnt = 0.f, mean = 0.f, m2 = 0.f;
+        auto merge = [&](float gmean, float gm2) {
+            const float delta = gmean - mean, total = cnt + 64.f, share = 64.f * __builtin_amdgcn_rcpf(total);
+            mean = fmaf(delta, share, mean);
+            m2 += gm2 + delta * delta * cnt * share;
+            cnt = total;
+        };
+        const int pairs = ln.groups >> 1;  // an odd last group is handled below
+        for (int p0 = 0; p0 < pairs; p0 += kStatLoads) {
+            if (p0 > 0) {  // more than sixteen groups (width above 1024): further rounds of loads
+#pragma unroll
+                for (int i = 0; i < kStatLoads; ++i) stat_part[i] = gs[min(p0 + i, pairs - 1)];
+            }
+#pragma unroll
+            for (int i = 0; i < kStatLoads; ++i)
+                if (p0 + i < pairs) {
+                    merge(stat_part[i][0], stat_part[i][1]);
+                    merge(stat_part[i][2], stat_part[i][3]);
+                }
+        }
+        if (ln.groups & 1) {
+            const float2 last = ((const float2 *)gs)[ln.groups - 1];
+            merge(last.x, last.y);
+        }
+        row_mean = mean;
+        row_rstd = 1.0f / sqrtf(m2 / cnt + ln.eps);
+    }
+    float2 *row_stats = (float2 *)(smem + a_slot * kGemmPart + 16384);  // behind the table, [256]
+    if (LN == kLnConsume && tid < kBM) row_stats[tid] = float2{row_mean, row_rstd};
     if (EPI == JV_EPI_GELU) {
         for (int i = tid; i <= kPhiSteps; i += 512) {
             const float p0 = normal_cdf(kPhiLo + (float)i * kPhiStep);
             phi_table[2 * i] = p0;
             phi_table[2 * i + 1] = normal_cdf(kPhiLo + (float)(i + 1) * kPhiStep) - p0;
         }
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+    if (EPI == JV_EPI_GELU || LN == kLnConsume) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    f32x4 c1_reg[2][4];
+    if (LN == kLnConsume) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int col = n0 + wn * 64 + nt * 32 + 8 * q4 + 4 * g;
+                f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                c1_reg[nt][q4] = col < N ? *(const f32x4 *)(ln.c1 + col) : zero;
+            }
     }
     f32x4 bias_reg[2][4];
 #pragma unroll
@@ -396,7 +484,15 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
             for (int q4 = 0; q4 < 4; ++q4) {
                 f32x4 val = {acc[nt][mt][4 * q4], acc[nt][mt][4 * q4 + 1], acc[nt][mt][4 * q4 + 2],
                              acc[nt][mt][4 * q4 + 3]};
-                val += bias_reg[nt][q4];
+                if (LN == kLnConsume) {  // rstd (acc - mean c1) + c2 for this lane's token
+                    const float2 st = row_stats[wm * 128 + mt * 32 + li];
+                    const float rm = -st.x * st.y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        val[e] = fmaf(val[e], st.y, fmaf(rm, c1_reg[nt][q4][e], bias_reg[nt][q4][e]));
+                } else {
+                    val += bias_reg[nt][q4];
+                }
                 if (EPI == JV_EPI_GELU) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) val[e] = gelu_from_table(val[e], phi_table);
@@ -428,30 +524,52 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                 f32x4 out = *(const f32x4 *)(stage + orow * 256 + ((fchunk ^ (orow & 15)) << 4));
                 if (OUT_BF16) {  // bf16 tensors with a residual: 16 lanes x 8 bytes = one 128-byte row
                     const u32x2 rr = res16_reg[mt & 1][r];
-                    u32x2 pk = {pack_bf16x2(out[0] + bf16_lo(rr[0]), out[1] + bf16_hi(rr[0])),
-                                pack_bf16x2(out[2] + bf16_lo(rr[1]), out[3] + bf16_hi(rr[1]))};
+                    out[0] += bf16_lo(rr[0]); out[1] += bf16_hi(rr[0]);
+                    out[2] += bf16_lo(rr[1]); out[3] += bf16_hi(rr[1]);
+                    u32x2 pk = {pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3])};
                     if (row < M && fcol < N) *(u32x2 *)((__bf16 *)Y + (size_t)row * N + fcol) = pk;
+                    if (LN == kLnProduce) {  // the statistics describe the stream as stored
+                        out[0] = bf16_lo(pk[0]); out[1] = bf16_hi(pk[0]);
+                        out[2] = bf16_lo(pk[1]); out[3] = bf16_hi(pk[1]);
+                    }
                 } else {
                     if (kResidual) out += res_reg[mt & 1][r];
                     if (row < M && fcol < N) *(f32x4 *)((float *)Y + (size_t)row * N + fcol) = out;
+                    if (LN == kLnProduce && ln.xb_out) {
+                        u32x2 pk = {pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3])};
+                        if (row < M && fcol < N) *(u32x2 *)((__bf16 *)ln.xb_out + (size_t)row * N + fcol) = pk;
+                        // (the next product multiplies these rounded values)
+                        out[0] = bf16_lo(pk[0]); out[1] = bf16_hi(pk[0]);
+                        out[2] = bf16_lo(pk[1]); out[3] = bf16_hi(pk[1]);
+                    }
+                }
+                if (LN == kLnProduce) {
+                    // mean and squared deviations of this wavefront's 64 features of the row
+                    // (16 lanes x 4); N % 64 == 0 here, so a group is inside y or outside whole
+                    const float mean = row16_sum((out[0] + out[1]) + (out[2] + out[3])) * (1.0f / 64.0f);
+                    const float d0 = out[0] - mean, d1 = out[1] - mean, d2 = out[2] - mean, d3 = out[3] - mean;
+                    const float m2 = row16_sum(fmaf(d0, d0, d1 * d1) + fmaf(d2, d2, d3 * d3));
+                    if (fchunk == 0 && row < M && fcol < N)
+                        *(float2 *)(ln.stats_out + ((size_t)row * (N >> 6) + ((n0 + wn * 64) >> 6)) * 2) = float2{mean, m2};
                 }
             }
         }
     }
 }
 
-template <int EPI, bool OUT_BF16>
+template <int EPI, bool OUT_BF16, int LN = kLnNone>
 static jv_status launch_gemm(const void *a, const void *w, const float *bias, const void *residual,
-                             void *y, long long M, int N, int K, int lda, hipStream_t stream) {
+                             void *y, long long M, int N, int K, int lda, hipStream_t stream,
+                             const GemmLn &ln = GemmLn{}) {
     static LdsLimit lds_limit;
-    jv_status st = ensure_lds_limit(lds_limit, (const void *)gemm_bf16_kernel<EPI, OUT_BF16>, kGemmLds);
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)gemm_bf16_kernel<EPI, OUT_BF16, LN>, kGemmLds);
     if (st != JV_OK) return st;
     const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (N + kBN - 1) / kBN;
     const int n_tiles = tiles_m * tiles_n;
     dim3 grid(8 * ((n_tiles + 7) / 8));
-    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16>), grid, dim3(512), kGemmLds, stream,
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16, LN>), grid, dim3(512), kGemmLds, stream,
                        (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K, lda,
-                       tiles_n, n_tiles);
+                       tiles_n, n_tiles, ln);
     return launch_status("gemm_bf16_kernel");
 }
 
@@ -499,6 +617,71 @@ jv_status gemm_forward(const void *a, const void *w, const float *bias, const vo
     return fail(JV_ERR_INVALID_ARG, "unknown epilogue");
 }
 
+// The two GEMM forms of the folded LayerNorm (encoder only; shapes checked by the caller).
+// Residual product that also leaves what the next LayerNorm needs: y = a w^T + bias + residual
+// (fp32 or bf16), xb = bf16(y) when y is fp32, stats [M][N / 64][2].
+static jv_status gemm_ln_produce(const void *a, const void *w, const float *bias, const void *residual,
+                                 void *y, long long M, int N, int K, bool out_bf16, void *xb,
+                                 float *stats, hipStream_t stream) {
+    GemmLn ln{};
+    ln.stats_out = stats;
+    ln.xb_out = out_bf16 ? nullptr : xb;
+    return out_bf16 ? launch_gemm<JV_EPI_RESIDUAL, true, kLnProduce>(a, w, bias, residual, y, M, N, K, K, stream, ln)
+                    : launch_gemm<JV_EPI_RESIDUAL, false, kLnProduce>(a, w, bias, residual, y, M, N, K, K, stream, ln);
+}
+// Product that consumes a LayerNorm: y = epilogue(rstd (xb wg^T - mean c1) + c2), bf16 output.
+static jv_status gemm_ln_consume(const void *xb, const void *wg, const float *c1, const float *c2,
+                                 const float *stats, float eps, void *y, long long M, int N, int K,
+                                 bool gelu, hipStream_t stream) {
+    GemmLn ln{};
+    ln.c1 = c1;
+    ln.stats_in = stats;
+    ln.groups = K / 64;
+    ln.eps = eps;
+    return gelu ? launch_gemm<JV_EPI_GELU, true, kLnConsume>(xb, wg, c2, nullptr, y, M, N, K, K, stream, ln)
+                : launch_gemm<JV_EPI_NONE, true, kLnConsume>(xb, wg, c2, nullptr, y, M, N, K, K, stream, ln);
+}
+
+// Folding a LayerNorm's scale and shift into the weights of the product behind it, one
+// wavefront per output feature n:  wg[n][k] = bf16(w[n][k] gamma[k]),  c1[n] = sum_k wg[n][k]
+// (of the rounded values, which are what the matrix cores multiply),  c2[n] = bias[n] +
+// sum_k w[n][k] beta[k].  grid (ceil(N / 4)), 256 threads; K % 8 == 0.
+__global__ void __launch_bounds__(256)
+fold_layernorm_kernel(const __bf16 *__restrict__ w, const float *__restrict__ bias,
+                      const float *__restrict__ gamma, const float *__restrict__ beta,
+                      __bf16 *__restrict__ wg, float *__restrict__ c1, float *__restrict__ c2, int N, int K) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + wave;
+    if (n >= N) return;
+    float s1 = 0.f, s2 = 0.f;
+    for (int k = 8 * lane; k < K; k += 512) {
+        const u32x4 raw = *(const u32x4 *)(w + (size_t)n * K + k);
+        const f32x4 g0 = *(const f32x4 *)(gamma + k), g1 = *(const f32x4 *)(gamma + k + 4);
+        const f32x4 b0 = *(const f32x4 *)(beta + k), b1 = *(const f32x4 *)(beta + k + 4);
+        const float x[8] = {bf16_lo(raw[0]), bf16_hi(raw[0]), bf16_lo(raw[1]), bf16_hi(raw[1]),
+                            bf16_lo(raw[2]), bf16_hi(raw[2]), bf16_lo(raw[3]), bf16_hi(raw[3])};
+        const float gm[8] = {g0[0], g0[1], g0[2], g0[3], g1[0], g1[1], g1[2], g1[3]};
+        const float bt[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+        u32x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            out[e] = pack_bf16x2(x[2 * e] * gm[2 * e], x[2 * e + 1] * gm[2 * e + 1]);
+            s1 += bf16_lo(out[e]) + bf16_hi(out[e]);
+            s2 = fmaf(x[2 * e], bt[2 * e], fmaf(x[2 * e + 1], bt[2 * e + 1], s2));
+        }
+        *(u32x4 *)(wg + (size_t)n * K + k) = out;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        s1 += __shfl_xor(s1, off, 64);
+        s2 += __shfl_xor(s2, off, 64);
+    }
+    if (lane == 0) {
+        c1[n] = s1;
+        c2[n] = s2 + (bias ? bias[n] : 0.f);
+    }
+}
+
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace jv
@@ -514,6 +697,7 @@ struct jv_encoder {
     uint8_t *pattern;
     jv_block_weights *blocks;
     jv_dwc_params *dwc;  // per block, a copy of the caller's parameters (mode none if absent)
+    unsigned char *folded;  // caller's buffer with the LayerNorm-folded weights, or null (jv_encoder_fold_layernorm)
 };
 
 namespace jv {
@@ -637,6 +821,7 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
         e->blocks[l].dwc = &e->dwc[l];
     }
     e->cfg.pattern = e->pattern;
+    e->folded = nullptr;
     *out = e;
     return JV_OK;
 }
@@ -649,16 +834,76 @@ void jv_encoder_destroy(jv_encoder *enc) {
     delete enc;
 }
 
+// Folded LayerNorm weights in the caller's buffer, per block: (w_qkv gamma1) bf16 [3C][C], c1 and
+// c2 fp32 [3C]; (w_fc1 gamma2) bf16 [hidden][C], c1 and c2 fp32 [hidden]; each 256-byte aligned.
+namespace jv {
+struct FoldLayout {
+    size_t wqkv, c1qkv, c2qkv, wfc1, c1fc1, c2fc1, block_bytes;
+};
+static FoldLayout fold_layout(const jv_encoder_config &c) {
+    const size_t C = c.width, Hd = c.mlp_hidden;
+    FoldLayout f;
+    f.wqkv = 0;
+    f.c1qkv = f.wqkv + align256(3 * C * C * 2);
+    f.c2qkv = f.c1qkv + align256(3 * C * 4);
+    f.wfc1 = f.c2qkv + align256(3 * C * 4);
+    f.c1fc1 = f.wfc1 + align256(Hd * C * 2);
+    f.c2fc1 = f.c1fc1 + align256(Hd * 4);
+    f.block_bytes = f.c2fc1 + align256(Hd * 4);
+    return f;
+}
+}  // namespace jv
+
+size_t jv_encoder_fold_bytes(const jv_encoder *enc) {
+    jv::clear_error();
+    if (!enc) return 0;
+    return jv::fold_layout(enc->cfg).block_bytes * (size_t)enc->cfg.n_blocks;
+}
+
+jv_status jv_encoder_fold_layernorm(jv_encoder *enc, void *buffer, size_t buffer_bytes, void *hip_stream) {
+    jv::clear_error();
+    if (!enc) return jv::fail(JV_ERR_INVALID_ARG, "null encoder");
+    if (!buffer) {  // back to separate LayerNorm passes
+        enc->folded = nullptr;
+        return JV_OK;
+    }
+    if ((uintptr_t)buffer & 255) return jv::fail(JV_ERR_INVALID_ARG, "buffer must be 256-byte aligned");
+    const size_t need = jv_encoder_fold_bytes(enc);
+    if (buffer_bytes < need)
+        return jv::fail(JV_ERR_WORKSPACE_TOO_SMALL, "buffer has %zu bytes, %zu needed", buffer_bytes, need);
+    const jv_encoder_config &c = enc->cfg;
+    const jv::FoldLayout f = jv::fold_layout(c);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    enc->folded = nullptr;
+    for (int l = 0; l < c.n_blocks; ++l) {
+        const jv_block_weights &b = enc->blocks[l];
+        unsigned char *base = (unsigned char *)buffer + (size_t)l * f.block_bytes;
+        hipLaunchKernelGGL(jv::fold_layernorm_kernel, dim3((3 * c.width + 3) / 4), dim3(256), 0, stream,
+                           (const __bf16 *)b.w_qkv, b.b_qkv, b.ln1_g, b.ln1_b, (__bf16 *)(base + f.wqkv),
+                           (float *)(base + f.c1qkv), (float *)(base + f.c2qkv), 3 * c.width, c.width);
+        hipLaunchKernelGGL(jv::fold_layernorm_kernel, dim3((c.mlp_hidden + 3) / 4), dim3(256), 0, stream,
+                           (const __bf16 *)b.w_fc1, b.b_fc1, b.ln2_g, b.ln2_b, (__bf16 *)(base + f.wfc1),
+                           (float *)(base + f.c1fc1), (float *)(base + f.c2fc1), c.mlp_hidden, c.width);
+        jv_status st = jv::launch_status("fold_layernorm_kernel");
+        if (st != JV_OK) return st;
+    }
+    enc->folded = (unsigned char *)buffer;
+    return JV_OK;
+}
+
 // Workspace: [T, width] bf16 (LayerNorm output, later the mixer output), [T, max(3 width,
-// mlp_hidden)] bf16 (QKV, later the MLP hidden layer), then the linear-attention states.
+// mlp_hidden)] bf16 (QKV, later the MLP hidden layer), then the linear-attention states; with
+// folded LayerNorms also a second [T, width] bf16 buffer and the row statistics
+// [T, width / 64, 2] fp32.
 size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
                                   int32_t grid_w) {
     jv::clear_error();
     if (!enc || jv::encoder_check_shapes(enc, batch, grid_h, grid_w) != JV_OK) return 0;
     const size_t T = (size_t)batch * (enc->cfg.n_prefix + (size_t)grid_h * grid_w), C = enc->cfg.width;
     const size_t wide = 3 * C > (size_t)enc->cfg.mlp_hidden ? 3 * C : (size_t)enc->cfg.mlp_hidden;
+    const size_t fold = enc->folded ? jv::align256(T * C * 2) + jv::align256(T * (C / 64) * 8) : 0;
     return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
-           jv::align256(jv::encoder_linear_workspace(enc, batch, enc->cfg.n_prefix + grid_h * grid_w));
+           jv::align256(jv::encoder_linear_workspace(enc, batch, enc->cfg.n_prefix + grid_h * grid_w)) + fold;
 }
 
 jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
@@ -702,6 +947,15 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
     __bf16 *widebuf = (__bf16 *)(ws + jv::align256(T * C * 2));     // [T, 3C] or [T, hidden]
     void *la_ws = ws + jv::align256(T * C * 2) + jv::align256(T * wide * 2);
     const size_t la_ws_bytes = jv::align256(jv::encoder_linear_workspace(enc, batch, N));
+    // Folded LayerNorms (jv_encoder_fold_layernorm): the residual products leave the stream as
+    // bf16 rows (when it is fp32) and the row statistics, and the products behind a LayerNorm
+    // read those; only block 0's first LayerNorm, whose input no product of this pass wrote,
+    // runs as a pass of its own.
+    const bool fold = enc->folded != nullptr;
+    __bf16 *stream16 = (__bf16 *)((unsigned char *)la_ws + la_ws_bytes);  // [T, C], the stream before LayerNorm 2
+    float *row_stats = (float *)((unsigned char *)stream16 + jv::align256(T * C * 2));
+    const jv::FoldLayout fl = jv::fold_layout(c);
+    bool ln1_folded = false;  // the previous block's last product has left rows and statistics for LayerNorm 1
 
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
     jv::Problem pr;
@@ -719,8 +973,15 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
     int next_tap = 0;
     for (int l = 0; l < c.n_blocks; ++l) {
         const jv_block_weights &b = enc->blocks[l];
-        if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
-        if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
+        const unsigned char *fw = fold ? enc->folded + (size_t)l * fl.block_bytes : nullptr;
+        if (ln1_folded) {
+            st = jv::gemm_ln_consume(s16 ? resid : (const void *)narrow, fw + fl.wqkv, (const float *)(fw + fl.c1qkv),
+                                     (const float *)(fw + fl.c2qkv), row_stats, c.ln_eps, widebuf, T, 3 * C, C, false, stream);
+            if (st != JV_OK) return st;
+        } else {
+            if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
+            if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
+        }
         switch (enc->pattern[l]) {
             case 0:
                 st = jv::linear_block_forward(pr, c.la_eps, &enc->dwc[l], la_ws, la_ws_bytes, stream,
@@ -730,14 +991,26 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
             default: st = jv::full_forward(pr, 0.f, stream); break;
         }
         if (st != JV_OK) return st;
-        if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
-        if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
-        if ((st = jv::gemm_forward(narrow, b.w_fc1, b.b_fc1, nullptr, widebuf, T, c.mlp_hidden, C, JV_EPI_GELU, true, stream)) != JV_OK) return st;
+        if (fold) {
+            if ((st = jv::gemm_ln_produce(narrow, b.w_o, b.b_o, resid, y, T, C, C, s16, stream16, row_stats, stream)) != JV_OK) return st;
+            st = jv::gemm_ln_consume(s16 ? (const void *)y : (const void *)stream16, fw + fl.wfc1, (const float *)(fw + fl.c1fc1),
+                                     (const float *)(fw + fl.c2fc1), row_stats, c.ln_eps, widebuf, T, c.mlp_hidden, C, true, stream);
+            if (st != JV_OK) return st;
+        } else {
+            if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
+            if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
+            if ((st = jv::gemm_forward(narrow, b.w_fc1, b.b_fc1, nullptr, widebuf, T, c.mlp_hidden, C, JV_EPI_GELU, true, stream)) != JV_OK) return st;
+        }
         // A tapped block leaves its result in the tap buffer and the next block picks the stream
         // up from there; the last block's result has to be in y as well.
         const bool tapped = next_tap < n_taps && tap_blocks[next_tap] == l;
         void *out = tapped && l + 1 < c.n_blocks ? tap_out[next_tap] : y;
-        if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
+        ln1_folded = fold && l + 1 < c.n_blocks;
+        if (ln1_folded) {  // (the bf16 rows go where the next block's LayerNorm 1 would have written)
+            if ((st = jv::gemm_ln_produce(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, s16, narrow, row_stats, stream)) != JV_OK) return st;
+        } else {
+            if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
+        }
         if (tapped && out == y) {
             hipError_t e = hipMemcpyAsync(tap_out[next_tap], y, (size_t)T * C * (s16 ? 2 : 4), hipMemcpyDeviceToDevice, stream);
             if (e != hipSuccess) return jv::fail(JV_ERR_HIP, "hipMemcpyAsync: %s", hipGetErrorString(e));

@@ -126,7 +126,8 @@ def _device_blocks(blocks):
     return out
 
 
-def test_small_encoder_each_mixer_and_pattern():
+@pytest.mark.parametrize("fold", [False, True], ids=["layernorm passes", "layernorm folded"])
+def test_small_encoder_each_mixer_and_pattern(fold):
     B, H, W, heads, hidden = 2, 8, 8, 2, 256
     C = heads * 64
     x = synth.normal((B, H * W, C), 700)
@@ -135,10 +136,11 @@ def test_small_encoder_each_mixer_and_pattern():
         for key in ("b_qkv", "b_o", "b_fc1", "b_fc2", "ln1_b", "ln2_b"):
             b[key] = synth.normal(b[key].shape, 720 + len(key)) * 0.1
         b["ln1_g"] = 1.0 + 0.1 * synth.normal((C,), 730)
+        b["ln2_g"] = 1.0 + 0.1 * synth.normal((C,), 731)
     dev = _device_blocks(blocks)
     dx = torch.from_numpy(x).cuda()
     for pattern in ([0, 0, 0], [1, 1, 1], [2, 2, 2], [0, 1, 2]):
-        enc = binding.Encoder(dev, pattern, heads, hidden, window=(4, 4))
+        enc = binding.Encoder(dev, pattern, heads, hidden, window=(4, 4), fold_layernorm=fold)
         y = torch.empty_like(dx)
         enc.forward(dx, y, (H, W))
         ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 4))
@@ -179,7 +181,8 @@ def test_vit_l_blocks_teacher_forced():
         enc.close()
 
 
-def test_config5_first_six_blocks_full_size():
+@pytest.mark.parametrize("fold", [False, True], ids=["layernorm passes", "layernorm folded"])
+def test_config5_first_six_blocks_full_size(fold):
     """The encoder workload at its real shape (64 x 64 grid, width 1024, 16 heads, MLP 4096),
     image 0, through blocks 0..5 of the benchmark pattern (window, linear, window, linear,
     window, full): every mixer and every GEMM shape at full size against the oracle."""
@@ -189,7 +192,7 @@ def test_config5_first_six_blocks_full_size():
     assert pattern == [1, 0, 1, 0, 1, 2]
     x = synth.normal((4, H * W, C), 5003)[:1]
     blocks = [synth.block_weights(C, hidden, 5000 + l) for l in range(6)]
-    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16))
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16), fold_layernorm=fold)
     dx = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     y = torch.empty_like(dx)
     enc.forward(dx, y, (H, W))
@@ -199,7 +202,8 @@ def test_config5_first_six_blocks_full_size():
     enc.close()
 
 
-def test_config5_full_depth_against_oracle():
+@pytest.mark.parametrize("fold", [False, True], ids=["layernorm passes", "layernorm folded"])
+def test_config5_full_depth_against_oracle(fold):
     """All 24 blocks of the encoder workload (4 full / 12 window / 8 linear) on image 0 at full
     size against the oracle's fp64 forward: the end-to-end drift, printed, and held to the same
     2e-2 RMS bar as a single block (measured: 1.2e-2 at every tap and at the end; the stream's
@@ -209,7 +213,7 @@ def test_config5_full_depth_against_oracle():
     pattern = synth.encoder_pattern(L)
     x = synth.normal((4, H * W, C), 5003)[:1]
     blocks = [synth.block_weights(C, hidden, 5000 + l) for l in range(L)]
-    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16))
+    enc = binding.Encoder(_device_blocks(blocks), pattern, heads, hidden, window=(16, 16), fold_layernorm=fold)
     dx = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     y = torch.empty_like(dx)
     taps = {l: torch.empty_like(dx) for l in (5, 11, 17)}
@@ -354,6 +358,53 @@ def test_encoder_bf16_residual_stream():
         with pytest.raises(ValueError):   # an fp32 tensor for a bf16 stream
             enc.forward(dx.float(), y, (H, W))
         enc.close()
+
+
+def test_folded_layernorm_variants():
+    """LayerNorms folded into the products behind them: non-trivial gamma and beta, a stream whose
+    tokens have a mean of the size of their spread (the case the folded form is most sensitive to),
+    prefix tokens, taps, ragged token counts, fp32 and bf16 streams, in place; and switching the
+    fold off again gives back the bits of the separate passes."""
+    B, H, W, heads, hidden, P = 2, 7, 9, 3, 320, 2
+    C = heads * 64
+    x = synth.normal((B, P + H * W, C), 1200) + 0.8
+    blocks = [synth.block_weights(C, hidden, 1210 + i) for i in range(4)]
+    for i, b in enumerate(blocks):
+        for key in ("b_qkv", "b_o", "b_fc1", "b_fc2", "ln1_b", "ln2_b"):
+            b[key] = synth.normal(b[key].shape, 1220 + 7 * i + len(key)) * 0.2
+        b["ln1_g"] = 1.0 + 0.3 * synth.normal((C,), 1230 + i)
+        b["ln2_g"] = 0.7 + 0.3 * synth.normal((C,), 1240 + i)
+    pattern = [1, 0, 2, 0]
+    dev = _device_blocks(blocks)
+    ref, kept = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 3), taps=[1], n_prefix=P)
+    dx = torch.from_numpy(x).cuda()
+    enc = binding.Encoder(dev, pattern, heads, hidden, window=(4, 3), n_prefix=P)
+    plain = torch.empty_like(dx)
+    enc.forward(dx, plain, (H, W))
+    enc.fold_layernorm()
+    y, tap = torch.full_like(dx, float("nan")), torch.full_like(dx, float("nan"))
+    enc.forward(dx, y, (H, W), taps={1: tap})
+    check(err_bf16(to_host(y), ref), BF16_TOL)
+    check(err_bf16(to_host(tap), kept[1]), BF16_TOL)
+    assert not torch.equal(y, plain)                    # another rounding order: the fold really ran
+    z = dx.clone()
+    enc.forward(z, z, (H, W))                           # in place
+    assert torch.equal(z, y)
+    enc.fold_layernorm(False)
+    again = torch.empty_like(dx)
+    enc.forward(dx, again, (H, W))
+    assert torch.equal(again, plain)
+    enc.close()
+    # bf16 stream: the residual products' own output is what the folded products read
+    xb = synth.round_to_bf16(x)
+    dxb = torch.from_numpy(xb).cuda().to(torch.bfloat16)
+    refb = oracle.encoder_forward(xb, blocks[:2], pattern[:2], H, W, heads, window=(4, 3), n_prefix=P)
+    enc = binding.Encoder(dev[:2], pattern[:2], heads, hidden, window=(4, 3), n_prefix=P,
+                          stream_dtype=torch.bfloat16, fold_layernorm=True)
+    yb = torch.full_like(dxb, float("nan"))
+    enc.forward(dxb, yb, (H, W))
+    check(err_bf16_stored(to_host(yb), refb), BF16_TOL)
+    enc.close()
 
 
 def test_encoder_taps_intermediate_streams():
