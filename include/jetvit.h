@@ -153,15 +153,17 @@ jv_status jv_linear_attn_fwd_static(const jv_attn_desc *desc, const void *q, con
  *       ksize x ksize neighbourhood:
  *           u_n = silu(w1 V[b, :, n] + b1);  kernel[b, n] = reshape(w2 u_n + b2, [C, k, k]);
  *           DWC(V)[b, c, n] = sum_taps kernel[b, n][c, tap] * V[b, c, n + tap]
- *       Weights as for the squeeze-dynamic mode.  bf16 tensors only, hidden a multiple of 64
- *       (JV_ERR_UNSUPPORTED otherwise).  The generator runs as two matrix products with bf16
+ *       Weights as for the squeeze-dynamic mode; hidden a multiple of 64 (JV_ERR_UNSUPPORTED
+ *       otherwise).  bf16 tensors: the generator runs as two matrix products with bf16
  *       operands and fp32 accumulation (w1, w2 and the hidden layer are rounded to bf16: pass
  *       weights that are bf16 values already and only the hidden layer is rounded; the filters
  *       stay fp32) over V as the matrix [batch * tokens, C] -- read in place when V's strides
  *       already describe one (head stride 64, batch stride = tokens * token stride), from a
  *       packed copy otherwise; the workspace holds the filters of all tokens (batch * tokens *
- *       C * k * k fp32), the cost the paper rejects the variant for.  Prefix tokens get no
- *       convolution term.
+ *       C * k * k fp32), the cost the paper rejects the variant for.  fp32 tensors: plain fp32
+ *       arithmetic throughout, one workgroup per token, only the hidden layer is kept (the
+ *       workspace size is the same for both element types).  Prefix tokens get no convolution
+ *       term.
  * ksize is 3 or 5; C <= 8192 and hidden <= 1024 (JV_ERR_UNSUPPORTED otherwise).  Pointers the
  * mode does not use are ignored.  workspace as for jv_linear_attn_fwd, sized by
  * jv_linear_block_workspace_bytes (0 for an invalid descriptor or parameter block).

@@ -3,9 +3,10 @@
 //   squeeze_hidden / squeeze_kappa   the generator of the dynamic filters ("Squeeze Dynamic
 //                                    Convolution": token mean of V -> Linear -> SiLU -> Linear)
 //   v_sum_f32, dwc_add_f32           plain fp32 kernels for fp32 tensors
-//   cast_to_bf16, pack_v_rows,       the token-wise dynamic variant the paper rejects for its cost
-//   dwc_token_add                    (Tab. 1): the generator as two matrix products over all
+//   cast_to_bf16, reorder_w2,        the token-wise dynamic variant the paper rejects for its cost
+//   pack_v_rows, dwc_token_add       (Tab. 1): the generator as two matrix products over all
 //                                    tokens, then every token's own filters on its neighbourhood
+//   token_hidden_f32, token_dwc_f32  the same variant for fp32 tensors, plain fp32 arithmetic
 #include "jv_linear.h"
 #include "jv_mfma.h"
 
@@ -354,6 +355,87 @@ jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPla
         else launch_token_add<5, false>(stream, pr, la, kappa, total);
     }
     return launch_status("dwc_token_add");
+}
+
+// ---------------------------------------------------------------------------------------
+// Token-wise dynamic filters on fp32 tensors: plain fp32 arithmetic, nothing materialised but
+// the hidden layer.  One workgroup per grid token.
+// ---------------------------------------------------------------------------------------
+
+// u[m][j] = silu(b1[j] + sum_c w1[j][c] v[m][c]) for grid token m = b*N + n (n >= P); channel
+// c = head*64 + c'.  grid (B*N), 256 threads, C floats of dynamic LDS (the token's V row); one
+// wavefront per hidden unit at a time.
+__global__ void __launch_bounds__(256)
+token_hidden_f32(TensorArg vt, const float *__restrict__ w1, const float *__restrict__ b1,
+                 float *__restrict__ u, int heads, int N, int P, int hidden) {
+    extern __shared__ float vrow[];
+    const int m = blockIdx.x, b = m / N, n = m - b * N;
+    if (n < P) return;  // whole workgroup: prefix tokens have no filters
+    const int C = heads * kHeadDim;
+    const float *vp = (const float *)vt.ptr + b * vt.sb + (long long)n * vt.sn;
+    for (int c = threadIdx.x; c < C; c += 256) vrow[c] = vp[(c >> 6) * vt.sh + (c & 63)];
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int j = wave; j < hidden; j += 4) {
+        const float *wr = w1 + (size_t)j * C;
+        float s = 0.f;
+        for (int c = lane; c < C; c += 64) s = fmaf(wr[c], vrow[c], s);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) {
+            const float pre = s + b1[j];
+            u[(size_t)m * hidden + j] = pre / (1.0f + expf(-pre));
+        }
+    }
+}
+
+// o[m][c] += sum_taps kappa[m][c][tap] v[m + tap][c],  kappa[m][c][tap] = b2[c k^2 + tap] +
+// sum_j w2[c k^2 + tap][j] u[m][j]  (zero outside the H x W grid that follows P prefix tokens).
+// grid (B*N), 256 threads (one channel each, strided), hidden floats of dynamic LDS.
+__global__ void __launch_bounds__(256)
+token_dwc_f32(TensorArg vt, TensorArg ot, const float *__restrict__ u, const float *__restrict__ w2,
+              const float *__restrict__ b2, int heads, int N, int P, int H, int W, int hidden, int ksize) {
+    extern __shared__ float urow[];
+    const int m = blockIdx.x, b = m / N, n = m - b * N;
+    if (n < P) return;  // whole workgroup
+    for (int j = threadIdx.x; j < hidden; j += 256) urow[j] = u[(size_t)m * hidden + j];
+    __syncthreads();
+    const int C = heads * kHeadDim, kk = ksize * ksize, pad = ksize / 2;
+    const int g = n - P, r = g / W, col = g - r * W;
+    for (int c = threadIdx.x; c < C; c += 256) {
+        const int h = c >> 6, c1 = c & 63;
+        const float *vp = (const float *)vt.ptr + b * vt.sb + h * vt.sh + c1;
+        float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)n * ot.sn + c1;
+        float acc = *op;
+        for (int di = -pad; di <= pad; ++di)
+            for (int dj = -pad; dj <= pad; ++dj) {
+                const int r2 = r + di, c2 = col + dj;
+                if (r2 < 0 || r2 >= H || c2 < 0 || c2 >= W) continue;
+                const int row = c * kk + (di + pad) * ksize + dj + pad;
+                const float *wr = w2 + (size_t)row * hidden;
+                float kap = b2[row];
+                for (int j = 0; j < hidden; j += 4) {
+                    const f32x4 w4 = *(const f32x4 *)(wr + j);
+                    kap = fmaf(w4[0], urow[j], fmaf(w4[1], urow[j + 1], fmaf(w4[2], urow[j + 2], fmaf(w4[3], urow[j + 3], kap))));
+                }
+                acc = fmaf(kap, vp[(long long)(P + r2 * W + c2) * vt.sn], acc);
+            }
+        *op = acc;
+    }
+}
+
+jv_status token_dwc_forward_f32(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream) {
+    const int C = pr.heads * kHeadDim;
+    const long long M = (long long)pr.B * pr.N;
+    if (M >= (1ll << 31) - 1) return fail(JV_ERR_UNSUPPORTED, "token-wise filters: too many tokens");
+    float *u = ws + dwc.tok_kappa_off;  // [B*N][hidden]; the region sized for the bf16 path's filters
+    hipLaunchKernelGGL(token_hidden_f32, dim3((unsigned)M), dim3(256), C * sizeof(float), stream, pr.v,
+                       dwc.w1, dwc.b1, u, pr.heads, pr.N, pr.P, dwc.hidden);
+    jv_status st = launch_status("token_hidden_f32");
+    if (st != JV_OK) return st;
+    hipLaunchKernelGGL(token_dwc_f32, dim3((unsigned)M), dim3(256), dwc.hidden * sizeof(float), stream, pr.v,
+                       pr.o, u, dwc.w2, dwc.b2, pr.heads, pr.N, pr.P, pr.H, pr.W, dwc.hidden, dwc.ksize);
+    return launch_status("token_dwc_f32");
 }
 
 jv_status vsum_f32_launch(const Problem &pr, const LinearPlan &plan, float *vsum, hipStream_t stream) {

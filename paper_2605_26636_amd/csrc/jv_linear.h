@@ -67,6 +67,9 @@ jv_status dwc_add_f32_launch(const Problem &pr, const DwcArg &cv, int ksize, hip
 jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPlan &dwc, float *ws,
                             hipStream_t stream);
 
+// The same for fp32 tensors: pr.o already holds the linear-attention term; adds the convolution.
+jv_status token_dwc_forward_f32(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream);
+
 jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params *dwc,
                                void *workspace, size_t workspace_bytes, hipStream_t stream,
                                int focus_p = 1);

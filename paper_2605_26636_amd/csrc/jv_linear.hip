@@ -187,7 +187,16 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
     if (cv.mode == JV_DWC_TOKEN_DYNAMIC) {
         // Plain linear attention into an fp32 tensor (O itself when it is fp32), then one pass
         // that adds every token's own convolution term and rounds once.
-        if (!pr.bf16) return fail(JV_ERR_UNSUPPORTED, "token-wise filters are built for bf16 tensors only");
+        if (!pr.bf16) {  // fp32 tensors: the plain two-pass attention, then the convolution added in place
+            const int BH = pr.B * pr.heads;
+            hipLaunchKernelGGL(la_state_f32, dim3(plan.n_split, BH), dim3(256), 0, stream, pr.k, pr.v, ws,
+                               pr.heads, pr.N, plan.chunk, focus_p);
+            if ((st = launch_status("la_state_f32")) != JV_OK) return st;
+            hipLaunchKernelGGL(la_apply_f32, dim3((pr.N + 255) / 256, BH), dim3(256), 0, stream, pr.q, pr.o,
+                               ws, pr.heads, pr.N, plan.n_split, eps, focus_p);
+            if ((st = launch_status("la_apply_f32")) != JV_OK) return st;
+            return token_dwc_forward_f32(pr, cv, ws, stream);
+        }
         Problem la = pr;
         if (pr.o_bf16) {
             const long long C = (long long)pr.heads * kHeadDim;

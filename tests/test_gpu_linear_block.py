@@ -150,6 +150,24 @@ def test_bf16_token_wise_dynamic(B, heads, H, W, P, ksize):
         assert torch.equal(plain[:, :, :P], o32[:, :, :P])
 
 
+@pytest.mark.parametrize("ksize", [3, 5])
+@pytest.mark.parametrize("B,heads,H,W,P", [(2, 3, 13, 11, 0), (1, 2, 5, 7, 3), (1, 1, 1, 1, 0), (1, 5, 9, 40, 0)])
+def test_fp32_token_wise_dynamic(B, heads, H, W, P, ksize):
+    """The token-wise variant on fp32 tensors (plain fp32 kernels), at the fp32 bar; prefix rows
+    are plain linear attention bit for bit."""
+    C, hidden = heads * 64, 64
+    q, k, v = synth.qkv(35, B, heads, P + H * W, 64, 0.5, False)
+    tok = synth.squeeze_weights(C, hidden, ksize, 3700 + ksize)
+    ref = oracle.linear_block(q, k, v, H, W, 1e-6, ksize=ksize, token=tok)
+    got = _block(q, k, v, H, W, False, torch.float32, ksize=ksize, token=_dev(*tok))
+    check(err_fp32(to_host(got), ref), FP32_TOL)
+    if P:
+        dq, dk, dv = (to_device(x, False) for x in (q, k, v))
+        plain = torch.empty_like(got)
+        binding.jv_linear_attn_fwd(dq, dk, dv, plain, (H, W))
+        assert torch.equal(plain[:, :, :P], got[:, :, :P])
+
+
 def test_token_wise_special_filters():
     """W2 = 0 makes every token's filters the static bank b2: the static block's result up to the
     order of the fp32 additions."""
@@ -186,12 +204,7 @@ def test_token_wise_reads_v_in_place_from_fused_rows():
 
 
 def test_token_wise_rejects_unsupported():
-    q = torch.zeros(1, 1, 16, 64, device="cuda")
-    tok = _dev(*synth.squeeze_weights(64, 64, 3, 1))
-    with pytest.raises(binding.JvError) as e:     # fp32 tensors
-        binding.jv_linear_block_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (4, 4), token=tok)
-    assert e.value.status == binding.JV_ERR_UNSUPPORTED
-    qb = q.to(torch.bfloat16)
+    qb = torch.zeros(1, 1, 16, 64, device="cuda", dtype=torch.bfloat16)
     with pytest.raises(binding.JvError) as e:     # hidden not a multiple of 64
         binding.jv_linear_block_fwd(qb, qb.clone(), qb.clone(), torch.empty_like(qb), (4, 4),
                                     token=_dev(*synth.squeeze_weights(64, 8, 3, 2)))
