@@ -22,8 +22,8 @@ void clear_error() { g_err[0] = '\0'; }
 
 static bool dtype_ok(jv_dtype t) { return t == JV_F32 || t == JV_BF16; }
 
-static jv_status check_strides(const char *name, const jv_strides &s, int64_t align_elems) {
-    if (s.stride_n < kHeadDim) return fail(JV_ERR_INVALID_ARG, "%s: stride_n < head_dim", name);
+static jv_status check_strides(const char *name, const jv_strides &s, int64_t align_elems, int head_dim) {
+    if (s.stride_n < head_dim) return fail(JV_ERR_INVALID_ARG, "%s: stride_n < head_dim", name);
     if (s.stride_b < 0 || s.stride_h < 0)
         return fail(JV_ERR_INVALID_ARG, "%s: negative stride", name);
     if (s.stride_b % align_elems || s.stride_h % align_elems || s.stride_n % align_elems)
@@ -42,18 +42,21 @@ jv_status check_desc(const jv_attn_desc *d) {
     if ((int64_t)d->batch * d->heads > 65535)
         return fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
     if (d->head_dim <= 0) return fail(JV_ERR_INVALID_ARG, "head_dim must be positive");
-    if (d->head_dim != kHeadDim) return fail(JV_ERR_UNSUPPORTED, "head_dim must be 64");
+    if (d->head_dim != kHeadDim && d->head_dim != kHeadDimWide)
+        return fail(JV_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
     if (!dtype_ok(d->dtype) || !dtype_ok(d->o_dtype))
         return fail(JV_ERR_INVALID_ARG, "unknown dtype");
+    if (d->head_dim == kHeadDimWide && d->dtype != JV_BF16)
+        return fail(JV_ERR_UNSUPPORTED, "head_dim 128 is built for bf16 tensors only");
     if (d->dtype == JV_F32 && d->o_dtype != JV_F32)
         return fail(JV_ERR_UNSUPPORTED, "fp32 inputs need an fp32 output");
     const int64_t in_align = d->dtype == JV_BF16 ? 8 : 4;
     const int64_t out_align = d->o_dtype == JV_BF16 ? 8 : 4;
     jv_status st;
-    if ((st = check_strides("q", d->q, in_align)) != JV_OK) return st;
-    if ((st = check_strides("k", d->k, in_align)) != JV_OK) return st;
-    if ((st = check_strides("v", d->v, in_align)) != JV_OK) return st;
-    if ((st = check_strides("o", d->o, out_align)) != JV_OK) return st;
+    if ((st = check_strides("q", d->q, in_align, d->head_dim)) != JV_OK) return st;
+    if ((st = check_strides("k", d->k, in_align, d->head_dim)) != JV_OK) return st;
+    if ((st = check_strides("v", d->v, in_align, d->head_dim)) != JV_OK) return st;
+    if ((st = check_strides("o", d->o, out_align, d->head_dim)) != JV_OK) return st;
     return JV_OK;
 }
 
@@ -67,7 +70,7 @@ jv_status make_problem(const jv_attn_desc *d, const void *q, const void *k, cons
     // O may not overlap an input: compare the byte ranges the four tensors span.
     const int64_t N = d->n_prefix + (int64_t)d->grid_h * d->grid_w;
     auto span = [&](const jv_strides &t, int64_t esz) {
-        return ((d->batch - 1) * t.stride_b + (d->heads - 1) * t.stride_h + (N - 1) * t.stride_n + kHeadDim) * esz;
+        return ((d->batch - 1) * t.stride_b + (d->heads - 1) * t.stride_h + (N - 1) * t.stride_n + d->head_dim) * esz;
     };
     const int64_t in_esz = d->dtype == JV_BF16 ? 2 : 4, out_esz = d->o_dtype == JV_BF16 ? 2 : 4;
     const uintptr_t o0 = (uintptr_t)o, o1 = o0 + (uintptr_t)span(d->o, out_esz);
@@ -83,6 +86,7 @@ jv_status make_problem(const jv_attn_desc *d, const void *q, const void *k, cons
     p->W = d->grid_w;
     p->P = d->n_prefix;
     p->N = d->n_prefix + d->grid_h * d->grid_w;
+    p->D = d->head_dim;
     p->bf16 = d->dtype == JV_BF16;
     p->o_bf16 = d->o_dtype == JV_BF16;
     p->q = {q, d->q.stride_b, d->q.stride_h, d->q.stride_n};

@@ -125,7 +125,7 @@ jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStre
     jv_status st = window_check(pr, wh, ww);
     if (st != JV_OK) return st;
     make_window_geom(pr.H, pr.W, wh, ww, &g);
-    if (pr.P == 0) return attn_dispatch(pr, g, resolve_scale(scale), g.slots, stream);
+    if (pr.P == 0) return attn_dispatch(pr, g, resolve_scale(scale, pr.D), g.slots, stream);
     // Prefix tokens: the grid tokens run window attention among themselves; the prefix
     // tokens (the first P query slots of the whole sequence) attend to every token.
     Problem grid = pr;
@@ -135,17 +135,17 @@ jv_status window_forward(const Problem &pr, int wh, int ww, float scale, hipStre
     grid.k = from_token(pr.k, pr.P, pr.bf16);
     grid.v = from_token(pr.v, pr.P, pr.bf16);
     grid.o = from_token(pr.o, pr.P, pr.o_bf16);
-    if ((st = attn_dispatch(grid, g, resolve_scale(scale), g.slots, stream)) != JV_OK) return st;
-    return attn_dispatch(pr, sequence_geom(pr.N), resolve_scale(scale), pr.P, stream);
+    if ((st = attn_dispatch(grid, g, resolve_scale(scale, pr.D), g.slots, stream)) != JV_OK) return st;
+    return attn_dispatch(pr, sequence_geom(pr.N), resolve_scale(scale, pr.D), pr.P, stream);
 }
 
 jv_status full_forward(const Problem &pr, float scale, hipStream_t stream) {
-    if (pr.P > 0) return attn_dispatch(pr, sequence_geom(pr.N), resolve_scale(scale), pr.N, stream);
+    if (pr.P > 0) return attn_dispatch(pr, sequence_geom(pr.N), resolve_scale(scale, pr.D), pr.N, stream);
     // One window that spans the grid; the token order inside it is the raster order.
     WindowGeom g;
     g.H = pr.H; g.W = pr.W; g.wh = pr.H; g.ww = pr.W;
     g.Hp = pr.H; g.Wp = pr.W; g.wins_x = 1; g.wins_y = 1; g.n_win = 1; g.slots = pr.N;
-    return attn_dispatch(pr, g, resolve_scale(scale), g.slots, stream);
+    return attn_dispatch(pr, g, resolve_scale(scale, pr.D), g.slots, stream);
 }
 
 }  // namespace jv

@@ -1138,6 +1138,214 @@ static jv_status launch_window8(const AttnArgs &a, int BH, hipStream_t stream) {
     return launch_status("attn_window8_bf16");
 }
 
+// ---------------------------------------------------------------------------------------
+// head_dim 128 (the wide heads of the paper's largest backbones): one streaming kernel for
+// every geometry -- full attention, windows of any size, padded grids, a query-slot limit.
+// Same algorithm as above with one block of 32 query columns per wavefront (NT = 1): a
+// workgroup holds 128 consecutive query slots of one window (4 wavefronts x 32); the window's
+// keys pass through LDS in double-buffered stages of 32 (K rows, then V rows, 256 bytes each;
+// register-staged: the next stage is fetched before, and stored after, this stage's
+// arithmetic).  Per stage a wavefront issues 8 matrix instructions for the scores (K = 128
+// channels in steps of 16) and 8 for O^T += V^T P^T (four 32-channel blocks x two steps of 16
+// keys) around the same softmax arithmetic as for 64 channels on half as many columns: the
+// vector work per matrix instruction is half that of the 64-channel kernels.
+// grid (ceil(q_slots / 128), n_win, B*heads), 256 threads.
+// ---------------------------------------------------------------------------------------
+constexpr int kStageWide = 32;
+constexpr int kTileWideBytes = kStageWide * 256;    // the K rows or the V rows of a stage
+constexpr int kStageWideBytes = 2 * kTileWideBytes;
+
+// 256-byte rows in LDS.  Row-per-lane 16-byte reads (K operands, output staging): the chunk
+// index is rotated by the row, so that 16 consecutive rows land on 16 different bank groups.
+__device__ inline unsigned wide_off_row(int row, int chunk16) {
+    return (unsigned)(row * 256 + ((chunk16 ^ (row & 15)) << 4));
+}
+// Transposing reads (V operands) touch 64 bytes of each of four consecutive rows per half
+// wavefront: the 64-byte quarter of a row is rotated by the row, which spreads them over all banks.
+__device__ inline unsigned wide_off_tr(int row, int chunk16) {
+    return (unsigned)(row * 256 + ((((chunk16 >> 2) ^ (row & 3)) << 6) | ((chunk16 & 3) << 4)));
+}
+
+struct WaveStateWide {
+    f32x16 acc[4];  // channel blocks of 32
+    float m, l;     // l is this lane's half of the keys only
+};
+
+__device__ inline void raise_reference_wide(WaveStateWide &w, const f32x16 &s, float c) {
+    float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+    float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+    float t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+    float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
+    t0 = fmaxf(fmaxf(t0, t1), t2);
+    t3 = fmaxf(fmaxf(t3, t4), s[15]);
+    float a, b;
+    pair_values(fmaxf(t0, t3) * c, &a, &b);  // this lane and lane^32 share the query column
+    const float m_new = fmaxf(w.m, fmaxf(a, b));
+    const float alpha = __builtin_amdgcn_exp2f(w.m - m_new);
+    w.m = m_new;
+    w.l *= alpha;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w.acc[mi][v] *= alpha;
+}
+
+template <bool O_BF16>
+__global__ void __launch_bounds__(256, 2) attn_wide_bf16(AttnArgs a) {
+    __shared__ __align__(16) unsigned char smem[2 * kStageWideBytes];
+    __shared__ __align__(16) float bias[2][kStageWide];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+    const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
+    const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
+    const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
+    const bool wave_live = q0 < a.q_slots;
+    const float c_log2 = a.c;
+
+    // Query operands (B of S^T = K Q^T): channels 16*ks + 8g .. +7 of query li; padding slots
+    // fetch token 0 of the slice (their columns are computed and never stored).
+    u32x4 qreg[8];
+    {
+        const int tok = max(slot_token(a, wy, wx, q0 + li), 0);
+        const __bf16 *row = (const __bf16 *)a.q.ptr + qbase + (long long)tok * a.q.sn + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qreg[ks] = *(const u32x4 *)(row + 16 * ks);
+    }
+    WaveStateWide w;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w.acc[mi][v] = 0.f;
+    w.m = kMinusHuge;
+    w.l = 0.f;
+
+    const bool ragged = (wy + 1) * a.g.wh > a.g.H || (wx + 1) * a.g.ww > a.g.W;
+    const int n_stage = (a.g.slots + kStageWide - 1) / kStageWide;
+    // This thread moves chunks lchunk and lchunk + 8 of row lrow of every stage's K and V.
+    const int lrow = tid >> 3, lchunk = tid & 7;
+    const char *kbytes = (const char *)((const __bf16 *)a.k.ptr + kbase);
+    const char *vbytes = (const char *)((const __bf16 *)a.v.ptr + vbase);
+    u32x4 kreg[2], vreg[2];
+    bool live = false;
+    auto fetch = [&](int stage) {
+        const int tok = slot_token(a, wy, wx, stage * kStageWide + lrow);
+        live = tok >= 0;
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                kreg[i] = *(const u32x4 *)(kbytes + 2 * ((long long)tok * a.k.sn + (lchunk + 8 * i) * 8));
+                vreg[i] = *(const u32x4 *)(vbytes + 2 * ((long long)tok * a.v.sn + (lchunk + 8 * i) * 8));
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+        unsigned char *kt = smem + buf * kStageWideBytes, *vt = kt + kTileWideBytes;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (!live) {  // padding rows are zero in LDS and carry a -inf bias
+                u32x4 zero = {0u, 0u, 0u, 0u};
+                kreg[i] = zero;
+                vreg[i] = zero;
+            }
+            *(u32x4 *)(kt + wide_off_row(lrow, lchunk + 8 * i)) = kreg[i];
+            *(u32x4 *)(vt + wide_off_tr(lrow, lchunk + 8 * i)) = vreg[i];
+        }
+        if (lchunk == 0) bias[buf][lrow] = live ? 0.f : -INFINITY;
+    };
+    // The 32 keys of the stage in buffer `buf`.
+    auto tile = [&](int buf, bool masked) {
+        const unsigned char *kt = smem + buf * kStageWideBytes, *vt = kt + kTileWideBytes;
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 ka = *(const u32x4 *)(kt + wide_off_row(li, 2 * ks + g));
+            s = mfma32(as_bf16x8(ka), as_bf16x8(qreg[ks]), s);
+        }
+        if (masked) add_key_bias(s, &bias[buf][0], g);
+        unsigned pk[8];
+        float tile_sum = exp_block(s, pk, c_log2, -w.m);
+        if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kLazySum)) != 0) {  // also catches inf/NaN
+            raise_reference_wide(w, s, c_log2);
+            tile_sum = exp_block(s, pk, c_log2, -w.m);
+        }
+        w.l += tile_sum;
+        // A of O^T += V^T P^T: lane = channel of a 32-block, k-slot (g, 4r + e) = key 16*kk + 8r + 4g + e
+        const int blk = lane >> 4, j = lane & 15;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const u32x4 pb = {pk[4 * kk], pk[4 * kk + 1], pk[4 * kk + 2], pk[4 * kk + 3]};
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                const int chunk16 = mi * 4 + (blk & 1) * 2 + ((j & 3) >> 1);
+                const int row0 = 16 * kk + 4 * g + (j >> 2);
+                const u32x2 r0 = lds_read_tr16(vt + wide_off_tr(row0, chunk16) + (j & 1) * 8);
+                const u32x2 r1 = lds_read_tr16(vt + wide_off_tr(row0 + 8, chunk16) + (j & 1) * 8);
+                const u32x4 va = {r0[0], r0[1], r1[0], r1[1]};
+                w.acc[mi] = mfma32(as_bf16x8(va), as_bf16x8(pb), w.acc[mi]);
+            }
+        }
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int st = 0; st < n_stage; ++st) {
+        const int buf = st & 1;
+        const bool more = st + 1 < n_stage;
+        if (more) fetch(st + 1);
+        if (wave_live) tile(buf, ragged || (st + 1) * kStageWide > a.g.slots);
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    }
+    if (!wave_live) return;  // (no barrier follows)
+
+    // Normalise and store this wavefront's 32 query columns.
+    float lo, hi;
+    pair_values(w.l, &lo, &hi);
+    const float inv = __builtin_amdgcn_rcpf(lo + hi);
+    if (O_BF16) {
+        // channel-major accumulators -> token rows of 256 bytes through 8 KB of wave-private LDS
+        unsigned char *stage = smem + wave * kTileWideBytes;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x16 &x = w.acc[mi];
+                u32x2 pk = {pack_bf16x2(x[4 * q4] * inv, x[4 * q4 + 1] * inv),
+                            pack_bf16x2(x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv)};
+                *(u32x2 *)(stage + wide_off_row(li, 4 * mi + q4) + 8 * g) = pk;
+            }
+        __bf16 *op = (__bf16 *)a.o.ptr + obase;
+        const int orow = lane >> 4, ochunk = lane & 15;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int row = 4 * r + orow;
+            const int slot = q0 + row;
+            const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
+            const u32x4 val = *(const u32x4 *)(stage + wide_off_row(row, ochunk));
+            if (tok >= 0) *(u32x4 *)(op + (long long)tok * a.o.sn + ochunk * 8) = val;
+        }
+    } else {
+        float *op = (float *)a.o.ptr + obase;
+        const int slot = q0 + li;
+        const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
+        if (tok >= 0) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const f32x16 &x = w.acc[mi];
+                    f32x4 val = {x[4 * q4] * inv, x[4 * q4 + 1] * inv, x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv};
+                    *(f32x4 *)(op + (long long)tok * a.o.sn + 32 * mi + 8 * q4 + 4 * g) = val;
+                }
+        }
+    }
+}
+
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_slots, hipStream_t stream) {
     AttnArgs a;
     a.q = pr.q; a.k = pr.k; a.v = pr.v; a.o = pr.o;
@@ -1147,6 +1355,12 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     a.q_slots = q_slots < g.slots ? q_slots : g.slots;
     a.c = scale * kLog2e;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
+    if (pr.D == kHeadDimWide) {
+        dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
+        if (pr.o_bf16) hipLaunchKernelGGL((attn_wide_bf16<true>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((attn_wide_bf16<false>), grid, dim3(256), 0, stream, a);
+        return launch_status("attn_wide_bf16");
+    }
     const bool all_queries = a.q_slots == g.slots;  // the window-resident kernels compute every slot
     // Windows that fit in LDS whole take the window-resident kernel.
     if (all_queries && g.slots <= 64)

@@ -11,7 +11,8 @@
 
 namespace jv {
 
-constexpr int kHeadDim = 64;
+constexpr int kHeadDim = 64;       // the head width every kernel family is built for ...
+constexpr int kHeadDimWide = 128;  // ... and the wide heads of the paper's largest backbones (bf16 tensors only)
 
 // Thread-local description of the last failure; returns `st` for tail calls.
 jv_status fail(jv_status st, const char *fmt, ...);
@@ -27,6 +28,7 @@ struct TensorArg {
 struct Problem {
     int B, heads, H, W, N;  // N = P + H * W tokens
     int P;                  // prefix tokens in front of the grid
+    int D;                  // head_dim: kHeadDim or kHeadDimWide
     bool bf16;      // element type of Q, K, V
     bool o_bf16;    // element type of O
     TensorArg q, k, v, o;
@@ -62,8 +64,8 @@ inline jv_status ensure_lds_limit(LdsLimit &state, const void *kernel, int bytes
     return JV_OK;
 }
 
-inline float resolve_scale(float scale) {
-    return (scale > 0.0f) ? scale : 0.125f;  // 1/sqrt(64); NaN fails the comparison too
+inline float resolve_scale(float scale, int head_dim) {  // default 1/sqrt(head_dim); NaN fails the comparison too
+    return (scale > 0.0f) ? scale : (head_dim == kHeadDimWide ? 0.08838834764831845f : 0.125f);
 }
 
 // Window partition of an H x W grid (bottom/right padding, windows anchored at (0,0)).

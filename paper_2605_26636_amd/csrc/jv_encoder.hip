@@ -734,6 +734,7 @@ static jv_status encoder_check_shapes(const jv_encoder *enc, int batch, int grid
     if (T > (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "more than 2^31 tokens");
     Problem pr;
     pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = (int)N; pr.P = c.n_prefix;
+    pr.D = kHeadDim;
     for (int l = 0; l < c.n_blocks; ++l)
         if (enc->pattern[l] == 1) return window_check(pr, c.win_h, c.win_w);
     return JV_OK;
@@ -960,6 +961,7 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
     jv::Problem pr;
     pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = N; pr.P = c.n_prefix;
+    pr.D = jv::kHeadDim;
     pr.bf16 = true; pr.o_bf16 = true;
     const long long sb = (long long)N * 3 * C, sn = 3LL * C;
     pr.q = {widebuf, sb, jv::kHeadDim, sn};

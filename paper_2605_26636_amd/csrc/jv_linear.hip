@@ -176,6 +176,7 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
                                void *workspace, size_t workspace_bytes, hipStream_t stream,
                                int focus_p) {
     if (focus_p < 1 || focus_p > 16) return fail(JV_ERR_INVALID_ARG, "focusing power must be 1 .. 16");
+    if (pr.D != kHeadDim) return fail(JV_ERR_UNSUPPORTED, "linear attention: head_dim must be 64");
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;
     jv_status st = plan_dwc(dwc, plan, pr.B, pr.heads, pr.N, &cv);

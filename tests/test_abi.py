@@ -56,11 +56,21 @@ def test_argument_validation_launches_nothing():
     # null tensors
     assert L.jv_full_attn_fwd(ctypes.byref(d), None, None, None, None, 0.0, None) == binding.JV_ERR_INVALID_ARG
     assert b"non-null" in L.jv_last_error()
-    # head_dim other than 64
+    # head_dim other than 64 or 128; 128 with fp32 tensors
     d2 = binding.JvAttnDesc.from_buffer_copy(d)
+    for width in (32, 96, 256):
+        d2.head_dim = width
+        for t in (d2.q, d2.k, d2.v, d2.o):
+            t.stride_n, t.stride_h, t.stride_b = 256, 16 * 256, 2 * 16 * 256
+        assert L.jv_full_attn_fwd(ctypes.byref(d2), Q, K, V, O, 0.0, None) == binding.JV_ERR_UNSUPPORTED
+        assert b"head_dim" in L.jv_last_error()
+        assert binding.jv_linear_attn_workspace_bytes(d2) == 0
     d2.head_dim = 128
     assert L.jv_full_attn_fwd(ctypes.byref(d2), Q, K, V, O, 0.0, None) == binding.JV_ERR_UNSUPPORTED
-    assert binding.jv_linear_attn_workspace_bytes(d2) == 0
+    assert b"bf16" in L.jv_last_error()
+    d2.dtype = d2.o_dtype = binding.JV_BF16
+    d2.q.stride_n = 64                                     # a row stride below the head width
+    assert L.jv_full_attn_fwd(ctypes.byref(d2), Q, K, V, O, 0.0, None) == binding.JV_ERR_INVALID_ARG
     # misaligned pointer, aliasing output, bad window, bad eps, small workspace
     assert L.jv_full_attn_fwd(ctypes.byref(d), Q, K, V, O + 4, 0.0, None) == binding.JV_ERR_INVALID_ARG
     assert L.jv_full_attn_fwd(ctypes.byref(d), Q, K, V, Q, 0.0, None) == binding.JV_ERR_INVALID_ARG

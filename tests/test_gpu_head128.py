@@ -1,0 +1,132 @@
+"""GPU parity at head_dim 128 (the wide heads of the paper's largest backbones, Tab. 3/4): full
+and window attention (Eq. 1, Sec. 3.2.2) and linear attention (Eq. 2) on bf16 tensors against
+the CPU oracle, which is written for any head width.
+
+Tolerance as for 64 channels: max |g - r| / RMS(r) <= 2e-2 on the fp32-output run; the
+bf16-output run is its nearest-even rounding, bit for bit (parity.check_bf16_pair)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_26636_amd import binding, synth
+from parity import BF16_TOL, check, check_bf16_pair, err_bf16, rows_of, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+
+
+def _full(q, k, v, H, W, out_dtype=torch.bfloat16, scale=0.0):
+    dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+    o = torch.full(dq.shape, float("nan"), dtype=out_dtype, device="cuda")
+    binding.jv_full_attn_fwd(dq, dk, dv, o, (H, W), scale)
+    torch.cuda.synchronize()
+    return o
+
+
+def _window(q, k, v, H, W, window, out_dtype=torch.bfloat16, scale=0.0):
+    dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+    o = torch.full(dq.shape, float("nan"), dtype=out_dtype, device="cuda")
+    binding.jv_window_attn_fwd(dq, dk, dv, o, (H, W), window, scale)
+    torch.cuda.synchronize()
+    return o
+
+
+@pytest.mark.parametrize("B,heads,H,W,vscale", [
+    (2, 3, 16, 16, 1.0),    # N = 256: two query blocks of 128, eight key stages; peaked softmax
+    (1, 2, 37, 37, 0.125),  # N = 1369: ragged query block and ragged key stage
+    (1, 2, 5, 7, 1.0),      # N = 35: one stage and three keys
+    (1, 1, 1, 1, 1.0),      # a single token
+    (2, 2, 24, 40, 0.5),    # N = 960 = 30 stages
+    (1, 2, 33, 33, 1.0),    # N = 1089: a one-key tail
+])
+def test_full_attention_small_shapes(B, heads, H, W, vscale):
+    q, k, v = synth.qkv(60, B, heads, H * W, D, vscale, True)
+    ref = oracle.full_attn(q, k, v)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref)
+
+
+@pytest.mark.parametrize("B,heads,H,W,window,vscale", [
+    (2, 2, 16, 16, (8, 8), 1.0),      # 64-slot windows
+    (1, 2, 37, 37, (8, 8), 0.125),    # padded 40 x 40, windows of 64 / 40 / 25 real tokens
+    (1, 2, 32, 48, (16, 16), 0.5),    # 256-slot windows
+    (2, 1, 7, 9, (4, 4), 1.0),        # tiny ragged windows: less than one stage
+    (1, 2, 20, 20, (32, 32), 1.0),    # window larger than the grid: whole stages of padding
+    (1, 2, 18, 30, (6, 30), 1.0),     # windows spanning whole rows
+    (1, 1, 40, 24, (24, 16), 0.5),    # 384-slot rectangular windows, ragged at the bottom
+    (1, 1, 17, 40, (16, 16), 0.5),    # bottom windows hold one real row: seven stages of padding
+])
+def test_window_attention_small_shapes(B, heads, H, W, window, vscale):
+    q, k, v = synth.qkv(61, B, heads, H * W, D, vscale, True)
+    ref = oracle.window_attn(q, k, v, H, W, *window)
+    check_bf16_pair(_window(q, k, v, H, W, window, torch.float32), _window(q, k, v, H, W, window), ref)
+
+
+def test_default_scale_is_one_over_sqrt_128_and_explicit_scale():
+    B, heads, H, W = 1, 2, 10, 10
+    q, k, v = synth.qkv(62, B, heads, H * W, D, 1.0, True)
+    ref = oracle.full_attn(q, k, v)                       # the oracle's default: 1/sqrt(d)
+    check(err_bf16(to_host(_full(q, k, v, H, W, torch.float32)), ref), BF16_TOL)
+    ref = oracle.full_attn(q, k, v, scale=0.3)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32, 0.3), _full(q, k, v, H, W, scale=0.3), ref)
+
+
+def test_large_logits_need_the_running_maximum():
+    B, heads, H, W = 1, 1, 16, 32
+    q, k, v = synth.qkv(63, B, heads, H * W, D, 1.0, True)
+    ramp = np.linspace(0.2, 6.0, H * W, dtype=np.float32).reshape(1, 1, -1, 1)
+    k = synth.round_to_bf16(k * ramp)
+    ref = oracle.full_attn(q, k, v)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref)
+
+
+def test_prefix_tokens():
+    """Prefix tokens in front of the grid: window rule of the library (grid tokens attend inside
+    their window, prefix tokens to everything) and full attention over all tokens."""
+    B, heads, H, W, P = 2, 2, 12, 9, 5
+    q, k, v = synth.qkv(64, B, heads, P + H * W, D, 0.5, True)
+    ref = oracle.window_attn_prefix(q, k, v, P, H, W, 4, 4)
+    check_bf16_pair(_window(q, k, v, H, W, (4, 4), torch.float32), _window(q, k, v, H, W, (4, 4)), ref)
+    ref = oracle.full_attn(q, k, v)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref)
+
+
+def test_fused_projection_layout_and_rerun_bits():
+    """Q, K, V as strided views of one [B, N, 3, heads, 128] buffer (the layout a fused QKV
+    projection leaves), O as [B, N, heads, 128]; several launches give the same bits."""
+    B, heads, H, W = 2, 3, 20, 12
+    N = H * W
+    q, k, v = synth.qkv(65, B, heads, N, D, 0.5, True)
+    fused = torch.empty(B, N, 3, heads, D, device="cuda", dtype=torch.bfloat16)
+    for i, x in enumerate((q, k, v)):
+        fused[:, :, i] = to_device(x, True).permute(0, 2, 1, 3)
+    views = [fused[:, :, i].permute(0, 2, 1, 3) for i in range(3)]
+    out = torch.empty(B, N, heads, D, device="cuda", dtype=torch.bfloat16)
+    o = out.permute(0, 2, 1, 3)
+    binding.jv_window_attn_fwd(*views, o, (H, W), (8, 8))
+    assert torch.equal(o, _window(q, k, v, H, W, (8, 8)))
+    first = o.clone()
+    for _ in range(4):
+        binding.jv_window_attn_fwd(*views, o, (H, W), (8, 8))
+        assert torch.equal(o, first)
+    binding.jv_full_attn_fwd(*views, o, (H, W))
+    assert torch.equal(o, _full(q, k, v, H, W))
+
+
+def test_vit_layer_size_elementwise():
+    """A layer of the benchmark's size with wide heads (batch 8, 64 x 64 grid, 8 heads x 128):
+    every element of window and full attention against the oracle."""
+    B, heads, H, W = 8, 8, 64, 64
+    q, k, v = synth.qkv(66, B, heads, H * W, D, 0.125, True)
+    ref = oracle.window_attn(q, k, v, H, W, 16, 16)
+    check_bf16_pair(_window(q, k, v, H, W, (16, 16), torch.float32), _window(q, k, v, H, W, (16, 16)), ref)
+    ref = oracle.full_attn(q, k, v)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref)
+
+
+def test_fp32_tensors_are_refused():
+    q = torch.zeros(1, 1, 16, D, device="cuda")
+    with pytest.raises(binding.JvError) as e:
+        binding.jv_full_attn_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (4, 4))
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
