@@ -1155,17 +1155,6 @@ constexpr int kStageWide = 32;
 constexpr int kTileWideBytes = kStageWide * 256;    // the K rows or the V rows of a stage
 constexpr int kStageWideBytes = 2 * kTileWideBytes;
 
-// 256-byte rows in LDS.  Row-per-lane 16-byte reads (K operands, output staging): the chunk
-// index is rotated by the row, so that 16 consecutive rows land on 16 different bank groups.
-__device__ inline unsigned wide_off_row(int row, int chunk16) {
-    return (unsigned)(row * 256 + ((chunk16 ^ (row & 15)) << 4));
-}
-// Transposing reads (V operands) touch 64 bytes of each of four consecutive rows per half
-// wavefront: the 64-byte quarter of a row is rotated by the row, which spreads them over all banks.
-__device__ inline unsigned wide_off_tr(int row, int chunk16) {
-    return (unsigned)(row * 256 + ((((chunk16 >> 2) ^ (row & 3)) << 6) | ((chunk16 & 3) << 4)));
-}
-
 struct WaveStateWide {
     f32x16 acc[4];  // channel blocks of 32
     float m, l;     // l is this lane's half of the keys only

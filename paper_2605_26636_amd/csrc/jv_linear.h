@@ -53,6 +53,10 @@ struct DwcArg {
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
                       const DwcPlan &dwc, int focus_p, hipStream_t stream);
 
+// head_dim 128 (bf16 tensors, plain linear attention): workspace floats and the two passes.
+size_t linear_wide_workspace_floats(int B, int heads, int N);
+jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream);
+
 // Generator of the dynamic filters: partial token sums of V -> hidden layer -> filters.
 jv_status squeeze_generate(const DwcPlan &dwc, float *ws, int n_part, int B, int heads, int N,
                            hipStream_t stream);

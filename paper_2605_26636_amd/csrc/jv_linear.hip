@@ -176,7 +176,14 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
                                void *workspace, size_t workspace_bytes, hipStream_t stream,
                                int focus_p) {
     if (focus_p < 1 || focus_p > 16) return fail(JV_ERR_INVALID_ARG, "focusing power must be 1 .. 16");
-    if (pr.D != kHeadDim) return fail(JV_ERR_UNSUPPORTED, "linear attention: head_dim must be 64");
+    if (pr.D == kHeadDimWide) {
+        if (focus_p != 1 || (dwc && dwc->mode != JV_DWC_NONE))
+            return fail(JV_ERR_UNSUPPORTED, "head_dim 128: plain linear attention only (no convolution branch, no focused map)");
+        const size_t need = linear_wide_workspace_floats(pr.B, pr.heads, pr.N) * sizeof(float);
+        if (workspace_bytes < need)
+            return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+        return linear_wide_bf16(pr, eps, (float *)workspace, stream);
+    }
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;
     jv_status st = plan_dwc(dwc, plan, pr.B, pr.heads, pr.N, &cv);
@@ -229,7 +236,9 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
 }
 
 jv_status linear_forward(const Problem &pr, float eps, void *workspace, hipStream_t stream) {
-    return linear_block_forward(pr, eps, nullptr, workspace, linear_workspace_bytes(pr.B, pr.heads, pr.N), stream);
+    const size_t bytes = pr.D == kHeadDimWide ? linear_wide_workspace_floats(pr.B, pr.heads, pr.N) * sizeof(float)
+                                              : linear_workspace_bytes(pr.B, pr.heads, pr.N);
+    return linear_block_forward(pr, eps, nullptr, workspace, bytes, stream);
 }
 
 }  // namespace jv
@@ -283,6 +292,13 @@ size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_pa
     if (jv::check_desc(desc) != JV_OK) return 0;
     jv::DwcPlan cv;
     const int N = desc->n_prefix + desc->grid_h * desc->grid_w;
+    if (desc->head_dim == jv::kHeadDimWide) {
+        if (dwc && dwc->mode != JV_DWC_NONE) {
+            jv::fail(JV_ERR_UNSUPPORTED, "head_dim 128: plain linear attention only");
+            return 0;
+        }
+        return jv::linear_wide_workspace_floats(desc->batch, desc->heads, N) * sizeof(float);
+    }
     const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, N);
     if (jv::plan_dwc(dwc, plan, desc->batch, desc->heads, N, &cv) != JV_OK) return 0;
     return cv.total_floats * sizeof(float);
@@ -315,7 +331,9 @@ jv_status jv_linear_attn_fwd_static(const jv_attn_desc *desc, const void *q, con
     jv::DwcPlan plain;
     if ((st = jv::plan_dwc(nullptr, jv::plan_linear(pr.B, pr.heads, pr.N), pr.B, pr.heads, pr.N, &plain)) != JV_OK)
         return st;
-    const size_t need = plain.total_floats * sizeof(float);  // what jv_linear_attn_workspace_bytes answers
+    // what jv_linear_attn_workspace_bytes answers
+    const size_t need = (pr.D == jv::kHeadDimWide ? jv::linear_wide_workspace_floats(pr.B, pr.heads, pr.N)
+                                                  : plain.total_floats) * sizeof(float);
     if (need > (size_t)JV_STATIC_SCRATCH_BYTES)
         return jv::fail(JV_ERR_UNSUPPORTED, "this problem needs %zu bytes of scratch, the static scratch holds %zu",
                         need, (size_t)JV_STATIC_SCRATCH_BYTES);

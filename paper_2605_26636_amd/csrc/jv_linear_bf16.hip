@@ -82,16 +82,20 @@ constexpr int kStateLds = 4 * kWaveLds + 2 * 8 * kHeadDim * 4;
 // the block's convolution branch) to vsum[part][bh][64]; it falls out of the V operands.
 // KEEP_V: the apply pass reads V again (convolution branch), so V is loaded with the default
 // cache policy; K, and V otherwise, are read once and loaded as a stream.
+// wide: heads of 128 channels, handled as four 64 x 64 quadrants: `heads` then counts four
+// virtual heads per head, and virtual head 4h + 2i + j reduces channels 64i .. 64i+63 of K
+// against channels 64j .. 64j+63 of V of head h (S_ij = relu(K_i)^T V_j, z_i = sum relu(K_i)).
 template <bool VSUM, bool KEEP_V>
 __global__ void __launch_bounds__(256, 2)
 la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restrict__ vsum,
-              int heads, int N, int chunk, int focus_p) {
+              int heads, int N, int chunk, int focus_p, int wide) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
-    const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x;
+    const int bh = blockIdx.y, b = bh / heads, hv = bh % heads, part = blockIdx.x;
     const int BH = gridDim.y;
-    const __bf16 *kp = (const __bf16 *)kt.ptr + b * kt.sb + h * kt.sh;
-    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh;
+    const int h = wide ? hv >> 2 : hv, k_first = wide ? ((hv >> 1) & 1) * kHeadDim : 0, v_first = wide ? (hv & 1) * kHeadDim : 0;
+    const __bf16 *kp = (const __bf16 *)kt.ptr + b * kt.sb + h * kt.sh + k_first;
+    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh + v_first;
     unsigned char *ktile = smem + wave * kWaveLds;
     unsigned char *vtile = ktile + 8192;
     const int n0 = part * chunk, n1 = min(N, n0 + chunk);
@@ -512,13 +516,13 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
     const bool dynamic = dwc.mode == JV_DWC_SQUEEZE_DYNAMIC;
     if (dynamic)
         hipLaunchKernelGGL((la_state_bf16<true, true>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p);
+                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p, 0);
     else if (dwc.mode != JV_DWC_NONE)
         hipLaunchKernelGGL((la_state_bf16<false, true>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p, 0);
     else
         hipLaunchKernelGGL((la_state_bf16<false, false>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p, 0);
     if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
     const float *states = ws;
     int n_part = plan.n_split;
@@ -548,6 +552,165 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
         else launch_apply<false, 5>(stream, pr, states, n_part, part_stride, plan.apply_tokens, eps, cv, focus_p);
     }
     return launch_status("la_apply_bf16");
+}
+
+// ---------------------------------------------------------------------------------------
+// head_dim 128.  The state pass is la_state_bf16 over four quadrants per head (see there);
+// la_combine sums the partial quadrant states; this is the apply pass:
+//   o[c2] = sum_i relu(q_i) S_ij[:, c2] / (sum_i relu(q_i) . z_i + eps),   j = c2 / 64,
+// q_i the two 64-channel halves of a query row.  A workgroup streams one token chunk of one
+// (batch, head); its four wavefronts own the four 32-channel quarters of the output, each with
+// the matching rows of S_0j^T and S_1j^T as bf16 high + low operands in registers (what a
+// wavefront of the 64-channel kernel holds for its 64 output channels), and all four run over
+// the same 64-token query tile in LDS; the denominator is one more row block, as there.
+// grid (n_chunks * B*heads), 256 threads.
+// ---------------------------------------------------------------------------------------
+template <bool O_BF16>
+__global__ void __launch_bounds__(256, 2)
+la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int heads, int N,
+                   int tokens_per_wg, int n_chunks, float eps) {
+    __shared__ __align__(16) unsigned char smem[2 * 16384];  // query tile, output tile: [64 tokens][256 B]
+    unsigned char *qtile = smem, *otile = smem + 16384;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+    const int bh = blockIdx.x / n_chunks, b = bh / heads, h = bh % heads;
+    const __bf16 *qp = (const __bf16 *)qt.ptr + b * qt.sb + h * qt.sh;
+    const int n0 = (blockIdx.x % n_chunks) * tokens_per_wg, n1 = min(N, n0 + tokens_per_wg);
+    const int frow = tid >> 4, fchunk = tid & 15;  // this thread's 16 bytes of rows frow + 16 r of a tile
+
+    u32x4 qreg[4];
+    auto fetch = [&](int t0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int n = t0 + 16 * r + frow;
+            u32x4 zero = {0u, 0u, 0u, 0u};
+            qreg[r] = zero;
+            if (n < n1) qreg[r] = ld_stream((const u32x4 *)(qp + (long long)n * qt.sn + fchunk * 8));
+        }
+    };
+    fetch(n0);
+
+    // A operands: rows c2 of S_ij^T (this wavefront's quarter), k-slots c1 = 16 ks + 8 g + (0..7).
+    const int j = wave >> 1, c2 = 32 * (wave & 1) + li;
+    bf16x8 s_hi[2][4], s_lo[2][4], z_op[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const float *st = states + ((size_t)bh * 4 + 2 * i + j) * kStateFloats;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const float *row = st + c2 * kHeadDim + 16 * ks + 8 * g;
+            const float *zrow = st + kHeadDim * kHeadDim + 16 * ks + 8 * g;
+            const f32x4 x0 = *(const f32x4 *)row, x1 = *(const f32x4 *)(row + 4);
+            const f32x4 z0 = *(const f32x4 *)zrow, z1 = *(const f32x4 *)(zrow + 4);
+            const float x[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+            const float zv[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const __bf16 hi = (__bf16)x[e];
+                s_hi[i][ks][e] = hi;
+                s_lo[i][ks][e] = (__bf16)(x[e] - (float)hi);
+                // denominator block: row 0 = z high part, row 1 = z low part, other rows zero
+                const __bf16 zh = (__bf16)zv[e];
+                const __bf16 zl = (__bf16)(zv[e] - (float)zh);
+                z_op[i][ks][e] = li == 0 ? zh : (li == 1 ? zl : (__bf16)0.f);
+            }
+        }
+    }
+
+    for (int t = n0; t < n1; t += 64) {
+        __syncthreads();  // the previous tile has been read, and its output rows stored
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            *(u32x4 *)(qtile + wide_off_row(16 * r + frow, fchunk)) = relu_bf16x8(qreg[r]);
+        if (t + 64 < n1) fetch(t + 64);
+        __syncthreads();
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            if (t + 32 * nt >= n1) break;  // the same for every wavefront of the workgroup
+            f32x16 acc, accz;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { acc[v] = 0.f; accz[v] = 0.f; }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const bf16x8 qb = as_bf16x8(*(const u32x4 *)(qtile + wide_off_row(32 * nt + li, 2 * (4 * i + ks) + g)));
+                    accz = mfma32(z_op[i][ks], qb, accz);
+                    acc = mfma32(s_lo[i][ks], qb, acc);
+                    acc = mfma32(s_hi[i][ks], qb, acc);
+                }
+            // den lives in rows 0 and 1 of the denominator block: registers 0, 1 of lanes g = 0.
+            float den_lo, den_hi;
+            pair_values(accz[0] + accz[1], &den_lo, &den_hi);
+            const float inv = __builtin_amdgcn_rcpf(den_lo + eps);
+            if (O_BF16) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    u32x2 pk = {pack_bf16x2(acc[4 * q4] * inv, acc[4 * q4 + 1] * inv),
+                                pack_bf16x2(acc[4 * q4 + 2] * inv, acc[4 * q4 + 3] * inv)};
+                    *(u32x2 *)(otile + wide_off_row(32 * nt + li, 4 * wave + q4) + 8 * g) = pk;
+                }
+            } else {
+                const int n = t + 32 * nt + li;
+                float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh;
+                if (n < n1) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        f32x4 val = {acc[4 * q4] * inv, acc[4 * q4 + 1] * inv, acc[4 * q4 + 2] * inv, acc[4 * q4 + 3] * inv};
+                        *(f32x4 *)(op + (long long)n * ot.sn + 32 * wave + 8 * q4 + 4 * g) = val;
+                    }
+                }
+            }
+        }
+        if (O_BF16) {
+            __syncthreads();  // the four quarters of every row are in the output tile
+            __bf16 *op = (__bf16 *)ot.ptr + b * ot.sb + h * ot.sh;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * r + frow, n = t + row;
+                const u32x4 val = *(const u32x4 *)(otile + wide_off_row(row, fchunk));
+                if (n < n1) st_stream((u32x4 *)(op + (long long)n * ot.sn + fchunk * 8), val);
+            }
+        }
+    }
+}
+
+LinearPlan plan_linear_wide(int B, int heads, int N) {
+    LinearPlan p = plan_linear(B, 4 * heads, N);
+    p.combine = p.n_split > 1;  // the apply pass reads one state per quadrant
+    return p;
+}
+size_t linear_wide_workspace_floats(int B, int heads, int N) {
+    return linear_workspace_floats(plan_linear_wide(B, heads, N), B, 4 * heads);
+}
+
+jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream) {
+    static LdsLimit lds_limit;
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)la_state_bf16<false, false>, kStateLds);
+    if (st != JV_OK) return st;
+    const LinearPlan plan = plan_linear_wide(pr.B, pr.heads, pr.N);
+    const long long BHv = 4ll * pr.B * pr.heads;
+    if (BHv > 65535) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
+    hipLaunchKernelGGL((la_state_bf16<false, false>), dim3(plan.n_split, (unsigned)BHv), dim3(256), kStateLds, stream,
+                       pr.k, pr.v, ws, (float *)nullptr, 4 * pr.heads, pr.N, plan.chunk, 1, 1);
+    if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
+    const float *states = ws;
+    if (plan.combine) {
+        float *dst = ws + (size_t)plan.n_split * BHv * kStateFloats;
+        hipLaunchKernelGGL(la_combine, dim3((unsigned)BHv, ((kStateFloats + kHeadDim) / 4 + 255) / 256), dim3(256), 0,
+                           stream, ws, dst, (float *)nullptr, plan.n_split);
+        if ((st = launch_status("la_combine")) != JV_OK) return st;
+        states = dst;
+    }
+    const int n_chunks = (pr.N + plan.apply_tokens - 1) / plan.apply_tokens;
+    const long long n_wg = (long long)n_chunks * pr.B * pr.heads;
+    if (n_wg >= (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: too many token chunks");
+    if (pr.o_bf16)
+        hipLaunchKernelGGL((la_apply_wide_bf16<true>), dim3((unsigned)n_wg), dim3(256), 0, stream, pr.q, pr.o, states,
+                           pr.heads, pr.N, plan.apply_tokens, n_chunks, eps);
+    else
+        hipLaunchKernelGGL((la_apply_wide_bf16<false>), dim3((unsigned)n_wg), dim3(256), 0, stream, pr.q, pr.o, states,
+                           pr.heads, pr.N, plan.apply_tokens, n_chunks, eps);
+    return launch_status("la_apply_wide_bf16");
 }
 
 }  // namespace jv

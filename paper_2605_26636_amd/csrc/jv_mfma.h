@@ -179,6 +179,17 @@ __device__ inline unsigned tile_off_row(int row, int chunk16) {
     return (unsigned)(row * 128 + ((chunk16 ^ tile_row_rotation(row)) << 4));
 }
 
+// Tiles of 256-byte rows (128 channels of 16 bits).  Row-per-lane 16-byte reads: the chunk
+// index is rotated by the row, so that 16 consecutive rows land on 16 different bank groups.
+__device__ inline unsigned wide_off_row(int row, int chunk16) {
+    return (unsigned)(row * 256 + ((chunk16 ^ (row & 15)) << 4));
+}
+// Transposing reads (V operands) touch 64 bytes of each of four consecutive rows per half
+// wavefront: the 64-byte quarter of a row is rotated by the row, which spreads them over all banks.
+__device__ inline unsigned wide_off_tr(int row, int chunk16) {
+    return (unsigned)(row * 256 + ((((chunk16 >> 2) ^ (row & 3)) << 6) | ((chunk16 & 3) << 4)));
+}
+
 // Operand "lane = channel, k-slots = 8 tokens" read from a [token][channel] tile laid out
 // with tile_off_tr: channels 32*blk32 .. +31, tokens tok0 + 8g + (0..7).
 __device__ inline bf16x8 load_tr_operand(const unsigned char *tile, int tok0, int blk32,

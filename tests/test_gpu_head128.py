@@ -130,3 +130,63 @@ def test_fp32_tensors_are_refused():
     with pytest.raises(binding.JvError) as e:
         binding.jv_full_attn_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (4, 4))
     assert e.value.status == binding.JV_ERR_UNSUPPORTED
+
+
+def _linear(q, k, v, H, W, out_dtype=torch.bfloat16, eps=1e-6):
+    dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+    o = torch.full(dq.shape, float("nan"), dtype=out_dtype, device="cuda")
+    binding.jv_linear_attn_fwd(dq, dk, dv, o, (H, W), eps)
+    torch.cuda.synchronize()
+    return o
+
+
+@pytest.mark.parametrize("B,heads,H,W,vscale", [
+    (2, 3, 16, 16, 1.0),     # one chunk per head
+    (1, 2, 37, 37, 0.125),   # ragged last tile
+    (1, 2, 5, 7, 1.0),       # less than one tile
+    (1, 1, 1, 1, 1.0),       # a single token
+    (1, 1, 64, 80, 0.5),     # 5 120 tokens: several chunks per head, partial states combined
+    (2, 2, 33, 31, 0.5),     # 1 023 tokens
+])
+def test_linear_attention_small_shapes(B, heads, H, W, vscale):
+    q, k, v = synth.qkv(67, B, heads, H * W, D, vscale, True)
+    ref = oracle.linear_attn_quadratic(q, k, v, 1e-6)
+    check_bf16_pair(_linear(q, k, v, H, W, torch.float32), _linear(q, k, v, H, W), ref)
+
+
+def test_linear_attention_vit_layer_size_elementwise_and_rerun_bits():
+    B, heads, H, W = 8, 8, 64, 64
+    q, k, v = synth.qkv(68, B, heads, H * W, D, 0.125, True)
+    ref = oracle.linear_attn_state(q, k, v, 1e-6)[0]
+    o = _linear(q, k, v, H, W)
+    check_bf16_pair(_linear(q, k, v, H, W, torch.float32), o, ref)
+    for _ in range(3):
+        assert torch.equal(_linear(q, k, v, H, W), o)
+
+
+def test_linear_attention_prefix_and_fused_layout():
+    """Prefix tokens are ordinary tokens of linear attention; Q, K, V as views of a fused
+    [B, N, 3, heads, 128] buffer give the same bits as contiguous tensors."""
+    B, heads, H, W, P = 2, 3, 20, 12, 4
+    N = P + H * W
+    q, k, v = synth.qkv(69, B, heads, N, D, 0.5, True)
+    ref = oracle.linear_attn_quadratic(q, k, v, 1e-6)
+    o = _linear(q, k, v, H, W)
+    check_bf16_pair(_linear(q, k, v, H, W, torch.float32), o, ref)
+    fused = torch.empty(B, N, 3, heads, D, device="cuda", dtype=torch.bfloat16)
+    for i, x in enumerate((q, k, v)):
+        fused[:, :, i] = to_device(x, True).permute(0, 2, 1, 3)
+    views = [fused[:, :, i].permute(0, 2, 1, 3) for i in range(3)]
+    out = torch.empty(B, N, heads, D, device="cuda", dtype=torch.bfloat16).permute(0, 2, 1, 3)
+    binding.jv_linear_attn_fwd(*views, out, (H, W))
+    assert torch.equal(out, o)
+
+
+def test_linear_block_variants_are_refused():
+    """The convolution branch and the focused map are built for 64-channel heads."""
+    B, heads, H, W = 1, 1, 4, 4
+    q = torch.zeros(B, heads, H * W, D, device="cuda", dtype=torch.bfloat16)
+    kern = torch.zeros(heads * D, 3, 3, device="cuda")
+    with pytest.raises(binding.JvError) as e:
+        binding.jv_linear_block_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (H, W), static_kernel=kern)
+    assert e.value.status in (binding.JV_ERR_UNSUPPORTED, binding.JV_ERR_WORKSPACE_TOO_SMALL)
