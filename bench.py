@@ -100,6 +100,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time linear, window 16x16 (and full, up to 16 384 tokens) attention over the "
                          "token-count sweep at 32 768 tokens per call: 1 024 ... 65 536 tokens per image")
+    ap.add_argument("--head-dim", type=int, choices=[64, 128], default=64,
+                    help="--sweep: channels per head (1024 channels per token either way: 16 x 64 or 8 x 128)")
     ap.add_argument("--only", choices=["linear", "window", "full", "block"], default=None,
                     help="run only this mixer's launches (for counter collection)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -126,7 +128,7 @@ def main():
         print(json.dumps(bench_la_ablation(args.steps, args.warmup)))
         return
     if args.sweep:
-        print(json.dumps(bench_sweep(args.steps, args.warmup, args.buffers)))
+        print(json.dumps(bench_sweep(args.steps, args.warmup, args.buffers, args.head_dim)))
         return
     if args.gemm:
         print(json.dumps(bench_gemm(args.steps, args.warmup)))
@@ -448,15 +450,16 @@ def bench_gemm(steps, warmup):
             "steps": steps, "warmup": warmup, "dtype": "bf16", "data": "synthetic", "gemm": out}
 
 
-def bench_sweep(steps, warmup, buffers):
-    """Token-count sweep of the crossover experiment (bf16, 16 heads x 64): 32 768 tokens per call
+def bench_sweep(steps, warmup, buffers, head_dim=64):
+    """Token-count sweep of the crossover experiment (bf16, 16 heads x 64, or 8 heads x 128 with
+    --head-dim 128: the same bytes and flops per token): 32 768 tokens per call
     as 32 images of 1 024 tokens ... 2 images of 16 384, and one image of 65 536 tokens.  Linear and
     16x16 window attention move the same bytes per token at every size; full attention (timed up
     to 16 384 tokens per image) grows with the image.  Events on the launch stream, rotating
     buffer sets."""
     import torch
     from paper_2605_26636_amd import binding, synth
-    heads, d = 16, 64
+    heads, d = 1024 // head_dim, head_dim
     stream = torch.cuda.current_stream()
     rows = []
     for B, H, W in synth.SWEEP:
@@ -498,7 +501,7 @@ def bench_sweep(steps, warmup, buffers):
         rows.append(row)
         del sets, base, ws
         torch.cuda.empty_cache()
-    return {"metric": "mixer time over the token-count sweep (bf16, 16 heads x 64, 16x16 windows)",
+    return {"metric": f"mixer time over the token-count sweep (bf16, {heads} heads x {d}, 16x16 windows)",
             "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16",
             "data": "synthetic", "sweep": rows}
 

@@ -24,7 +24,10 @@
  *    strides given in jv_strides, so a fused QKV projection output laid out
  *    [batch, N, 3, heads, head_dim] can be consumed without a transpose.
  *    Base pointers and all strides must keep every (b, h, n) row 16-byte aligned.
- *  - head_dim must be 64.
+ *  - head_dim is 64, or 128 (the wide heads of the paper's largest backbones, Tab. 3/4) with
+ *    JV_BF16 tensors: full, window and linear attention (prefix tokens included) are built for
+ *    both; the convolution branch and the focused map of the linear-attention block, and
+ *    JV_F32 tensors, for 64 only (JV_ERR_UNSUPPORTED otherwise).
  *  - Inputs are never written.  O must not overlap Q, K or V: the byte range that O's
  *    strides span may not intersect the range of any input (JV_ERR_INVALID_ARG).
  *  - Arithmetic: JV_F32 tensors are processed in fp32 throughout.  JV_BF16
@@ -71,7 +74,7 @@ typedef struct {
 typedef struct {
     int32_t batch, heads;
     int32_t grid_h, grid_w; /* token grid */
-    int32_t head_dim;       /* 64 */
+    int32_t head_dim;       /* 64 or 128 (128: bf16 tensors) */
     jv_dtype dtype;         /* element type of Q, K, V */
     jv_dtype o_dtype;       /* element type of O: equal to dtype, or JV_F32 with JV_BF16 inputs */
     jv_strides q, k, v, o;
@@ -279,7 +282,7 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
 /* ---------------------------------------------------------------------------
  * Hybrid encoder forward (Fig. 2 of the paper: per layer, one of the three token mixers;
  * Sec. 4.4 works with a 24-layer ViT-Large).  For every block l:
- *     a = LN(x; ln1);  [Q K V] = a W_qkv^T + b_qkv, split into heads of 64;
+ *     a = LN(x; ln1);  [Q K V] = a W_qkv^T + b_qkv, split into heads of width / heads channels;
  *     x += mix_{pattern[l]}(Q, K, V) W_o^T + b_o;
  *     x += gelu(LN(x; ln2) W_fc1^T + b_fc1) W_fc2^T + b_fc2.
  * The residual stream x is fp32 (stream_dtype JV_F32, the default) or bf16 (JV_BF16: what a
@@ -294,8 +297,9 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * (0 linear, 1 window, 2 full).  Weights per block: LayerNorm gamma/beta fp32 [width];
  * w_qkv bf16 [3*width, width] (rows: Q features, then K, then V), b_qkv fp32 [3*width];
  * w_o bf16 [width, width], b_o fp32; w_fc1 bf16 [mlp_hidden, width], b_fc1 fp32;
- * w_fc2 bf16 [width, mlp_hidden], b_fc2 fp32.  width = heads * 64, width and mlp_hidden
- * multiples of 64.
+ * w_fc2 bf16 [width, mlp_hidden], b_fc2 fp32.  width = heads * 64 or heads * 128 (wide heads:
+ * linear-attention blocks without the convolution branch and with the ReLU map only), width
+ * and mlp_hidden multiples of 64.
  *
  * jv_encoder_forward: x and y are device [batch, n_prefix + grid_h*grid_w, width] of stream_dtype
  * (y may be x);

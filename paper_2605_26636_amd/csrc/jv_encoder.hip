@@ -703,7 +703,10 @@ struct jv_encoder {
 namespace jv {
 // Largest linear-attention workspace any block needs (the blocks with a convolution branch
 // also keep their generated filters there).
+static int encoder_head_dim(const jv_encoder_config &c) { return c.width / c.heads; }  // 64 or 128 (jv_encoder_create)
 static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N) {
+    if (encoder_head_dim(enc->cfg) == kHeadDimWide)
+        return linear_wide_workspace_floats(batch, enc->cfg.heads, N) * sizeof(float);
     const LinearPlan lp = plan_linear(batch, enc->cfg.heads, N);
     size_t need = linear_workspace_bytes(batch, enc->cfg.heads, N);
     for (int l = 0; l < enc->cfg.n_blocks; ++l) {
@@ -724,6 +727,9 @@ static jv_status encoder_check_shapes(const jv_encoder *enc, int batch, int grid
         return fail(JV_ERR_INVALID_ARG, "batch and grid must be positive");
     if ((long long)grid_h * grid_w > (1 << 24)) return fail(JV_ERR_UNSUPPORTED, "more than 2^24 tokens per image");
     if ((long long)batch * c.heads > 65535) return fail(JV_ERR_UNSUPPORTED, "batch * heads above 65535");
+    if (encoder_head_dim(c) == kHeadDimWide && (long long)batch * c.heads > 16383)
+        for (int l = 0; l < c.n_blocks; ++l)
+            if (enc->pattern[l] == 0) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
     const long long N = c.n_prefix + (long long)grid_h * grid_w, T = batch * N;
     const int C = c.width;
     jv_status st;
@@ -734,7 +740,7 @@ static jv_status encoder_check_shapes(const jv_encoder *enc, int batch, int grid
     if (T > (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "more than 2^31 tokens");
     Problem pr;
     pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = (int)N; pr.P = c.n_prefix;
-    pr.D = kHeadDim;
+    pr.D = encoder_head_dim(c);
     for (int l = 0; l < c.n_blocks; ++l)
         if (enc->pattern[l] == 1) return window_check(pr, c.win_h, c.win_w);
     return JV_OK;
@@ -778,8 +784,11 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
         return jv::fail(JV_ERR_INVALID_ARG, "null argument");
     const jv_encoder_config &c = *config;
     if (c.n_blocks <= 0 || c.n_blocks > 4096) return jv::fail(JV_ERR_INVALID_ARG, "bad n_blocks");
-    if (c.heads <= 0 || c.width != c.heads * jv::kHeadDim)
-        return jv::fail(JV_ERR_UNSUPPORTED, "width must be heads * 64");
+    if (c.heads <= 0 || (c.width != c.heads * jv::kHeadDim && c.width != c.heads * jv::kHeadDimWide))
+        return jv::fail(JV_ERR_UNSUPPORTED, "width must be heads * 64 or heads * 128");
+    const bool wide = c.width == c.heads * jv::kHeadDimWide;
+    if (wide && c.la_focus_p > 1)
+        return jv::fail(JV_ERR_UNSUPPORTED, "head_dim 128: the focused map is built for 64-channel heads");
     if (c.mlp_hidden <= 0 || c.mlp_hidden % 64)
         return jv::fail(JV_ERR_UNSUPPORTED, "mlp_hidden must be a positive multiple of 64");
     if (c.win_h <= 0 || c.win_w <= 0) return jv::fail(JV_ERR_INVALID_ARG, "window must be positive");
@@ -795,6 +804,8 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
         for (const void *p : ptrs)
             if (!p || ((uintptr_t)p & 15))
                 return jv::fail(JV_ERR_INVALID_ARG, "block %d: null or misaligned weight pointer", l);
+        if (c.pattern[l] == 0 && b.dwc && b.dwc->mode != JV_DWC_NONE && wide)
+            return jv::fail(JV_ERR_UNSUPPORTED, "block %d: head_dim 128: the convolution branch is built for 64-channel heads", l);
         if (c.pattern[l] == 0 && b.dwc) {  // validate the convolution parameters now
             jv::DwcPlan plan;
             jv_status st = jv::plan_dwc(b.dwc, jv::plan_linear(1, c.heads, 256), 1, c.heads, 256, &plan);
@@ -961,13 +972,13 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
     jv::Problem pr;
     pr.B = batch; pr.heads = c.heads; pr.H = grid_h; pr.W = grid_w; pr.N = N; pr.P = c.n_prefix;
-    pr.D = jv::kHeadDim;
+    pr.D = jv::encoder_head_dim(c);
     pr.bf16 = true; pr.o_bf16 = true;
     const long long sb = (long long)N * 3 * C, sn = 3LL * C;
-    pr.q = {widebuf, sb, jv::kHeadDim, sn};
-    pr.k = {widebuf + C, sb, jv::kHeadDim, sn};
-    pr.v = {widebuf + 2 * C, sb, jv::kHeadDim, sn};
-    pr.o = {narrow, (long long)N * C, jv::kHeadDim, C};
+    pr.q = {widebuf, sb, pr.D, sn};
+    pr.k = {widebuf + C, sb, pr.D, sn};
+    pr.v = {widebuf + 2 * C, sb, pr.D, sn};
+    pr.o = {narrow, (long long)N * C, pr.D, C};
 
     jv_status st;
     const bool s16 = c.stream_dtype == JV_BF16;  // element type of the residual stream

@@ -190,3 +190,44 @@ def test_linear_block_variants_are_refused():
     with pytest.raises(binding.JvError) as e:
         binding.jv_linear_block_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (H, W), static_kernel=kern)
     assert e.value.status in (binding.JV_ERR_UNSUPPORTED, binding.JV_ERR_WORKSPACE_TOO_SMALL)
+
+
+def _device_blocks(blocks):
+    return [{k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_") else torch.from_numpy(v).cuda())
+             for k, v in b.items()} for b in blocks]
+
+
+@pytest.mark.parametrize("fold", [False, True], ids=["layernorm passes", "layernorm folded"])
+def test_encoder_with_wide_heads(fold):
+    """A small hybrid encoder whose width is heads x 128 (the head width follows from width and
+    heads): every mixer type, a mixed pattern, prefix tokens, against the oracle's encoder."""
+    B, H, W, heads, hidden = 2, 8, 8, 2, 512
+    C = heads * D
+    blocks = [synth.block_weights(C, hidden, 7100 + i) for i in range(3)]
+    for b in blocks:
+        for key in ("b_qkv", "b_o", "b_fc1", "b_fc2", "ln1_b", "ln2_b"):
+            b[key] = synth.normal(b[key].shape, 7200 + len(key)) * 0.1
+    dev = _device_blocks(blocks)
+    for pattern, P in (([0, 0, 0], 0), ([1, 1, 1], 0), ([2, 2, 2], 0), ([0, 1, 2], 0), ([1, 0, 2], 3)):
+        x = synth.normal((B, P + H * W, C), 7000 + P)
+        dx = torch.from_numpy(x).cuda()
+        enc = binding.Encoder(dev, pattern, heads, hidden, window=(4, 4), n_prefix=P, fold_layernorm=fold)
+        y = torch.empty_like(dx)
+        enc.forward(dx, y, (H, W))
+        ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 4), n_prefix=P)
+        check(err_bf16(to_host(y), ref), BF16_TOL)
+        enc.close()
+
+
+def test_encoder_wide_heads_refuses_block_variants():
+    heads, hidden = 2, 256
+    C = heads * D
+    blocks = [synth.block_weights(C, hidden, 7300)]
+    dev = _device_blocks(blocks)
+    with pytest.raises(binding.JvError) as e:
+        binding.Encoder(dev, [0], heads, hidden, window=(4, 4), la_focus_p=3)
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
+    dev[0]["dwc"] = {"static_kernel": torch.zeros(C, 3, 3, device="cuda"), "ksize": 3}
+    with pytest.raises(binding.JvError) as e:
+        binding.Encoder(dev, [0], heads, hidden, window=(4, 4))
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
