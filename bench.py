@@ -83,7 +83,8 @@ def main():
     ap.add_argument("--paper-ratio", action="store_true",
                     help="encoder latency of all-full-attention vs hybrid patterns on a 64x128 grid "
                          "(the resolution of the paper's speed tables), as ratios")
-    ap.add_argument("--model", choices=["L", "B", "H", "G"], default="L", help="ViT size for --paper-ratio")
+    ap.add_argument("--model", choices=["L", "B", "H", "G", "7B"], default="L",
+                    help="ViT size for --paper-ratio (7B: 40 blocks, width 4096, 32 heads x 128, MLP 8192)")
     ap.add_argument("--graph", action="store_true",
                     help="--paper-ratio: replay each forward pass as one captured HIP graph")
     ap.add_argument("--la-ablation", action="store_true",
@@ -343,15 +344,31 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
     same with ViT-B (12 blocks, width 768, 12 heads), full attention kept at blocks 7 and 11, or
     "H" (32 blocks, width 1280, 20 heads, MLP 5120), blocks 19 and 29, or "G" (40 blocks, width
     1536, 24 heads, MLP 6144), blocks 24 and 37 (the paper prints positions for ViT-L only: scaled
-    to the other depths)."""
+    to the other depths).  "7B": the shape of the paper's largest teacher (Tab. 3: 40 blocks, width
+    4096, 32 heads of 128 channels, MLP 8192), full attention kept at blocks 24 and 37; its weights
+    (10.7 GB) are drawn on the device, and its linear-attention blocks run without the convolution
+    branch (built for 64-channel heads)."""
     import torch
     from paper_2605_26636_amd import binding, synth
     B, H, W = 1, 64, 128
     heads, hidden, L, full_at_two = {"L": (16, 4096, 24, (14, 22)), "B": (12, 3072, 12, (7, 11)),
-                                     "H": (20, 5120, 32, (19, 29)), "G": (24, 6144, 40, (24, 37))}[model]
-    C, N = heads * 64, H * W
+                                     "H": (20, 5120, 32, (19, 29)), "G": (24, 6144, 40, (24, 37)),
+                                     "7B": (32, 8192, 40, (24, 37))}[model]
+    wide = model == "7B"
+    C, N = heads * (128 if wide else 64), H * W
     dev = []
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5000)
     for l in range(L):
+        if wide:  # Xavier-normal weights drawn on the device, zero biases, unit LayerNorm scale
+            def w(rows, cols, fan):
+                return (torch.randn(rows, cols, generator=gen, device="cuda") * (2.0 / fan) ** 0.5).to(torch.bfloat16)
+            zeros = lambda n: torch.zeros(n, device="cuda")
+            dev.append({"ln1_g": torch.ones(C, device="cuda"), "ln1_b": zeros(C), "w_qkv": w(3 * C, C, 2 * C),
+                        "b_qkv": zeros(3 * C), "w_o": w(C, C, 2 * C), "b_o": zeros(C),
+                        "ln2_g": torch.ones(C, device="cuda"), "ln2_b": zeros(C), "w_fc1": w(hidden, C, C + hidden),
+                        "b_fc1": zeros(hidden), "w_fc2": w(C, hidden, C + hidden), "b_fc2": zeros(C)})
+            continue
         wts = synth.block_weights(C, hidden, 5000 + l)
         d = {k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_")
                  else torch.from_numpy(v).cuda()) for k, v in wts.items()}
