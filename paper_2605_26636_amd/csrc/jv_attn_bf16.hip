@@ -755,17 +755,18 @@ __global__ void __launch_bounds__(256, 2) attn_window8_bf16(AttnArgs a, int n_it
 // Same tiling as attn_stream_bf16 (a workgroup holds 256 query slots, keys pass through LDS
 // in stages of 64), but built so that the inner loop is nothing but matrix instructions,
 // exponentials and LDS operand reads:
-//   * K/V stages go from global memory straight into a ring of four LDS stages (no register
+//   * K/V stages go from global memory straight into a ring of three LDS stages (no register
 //     staging, no LDS stores, no per-row selects), two stages ahead of the arithmetic; a
-//     stage costs each wavefront four load instructions, one counted wait and one barrier,
-//     which sits between the stage's two tiles so that the K operands of the next stage's
-//     first tile are read under this stage's second tile;
+//     stage costs each wavefront four load instructions, one wait and one barrier, which sit
+//     between the stage's two tiles so that the K operands of the next stage's first tile are
+//     read under this stage's second tile (a ring of four stages, three in flight and a
+//     counted wait, measured 2 % slower);
 //   * every full stage runs the unmasked tile code, which is one basic block per tile apart
 //     from the (rarely taken) branch that raises the softmax reference; only the last,
 //     partial stage of a window masks keys, and it does so by key index, not through LDS.
 // grid (ceil(slots/256), n_win, B*heads), 256 threads.
 // ---------------------------------------------------------------------------------------
-constexpr int kRing = 4;
+constexpr int kRing = 3;
 
 // One tile of 32 keys of the ring kernel, as attn_tile32: `ka` holds its K operands, its V rows
 // are at vaddr + VOFF, and if KNEXT >= 0 the K operands at kaddr + KNEXT are read into `ka`
@@ -897,17 +898,17 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
             vcur[i] += vstep;
         }
     };
-    static_assert(kLoads == 2 && kRing == 4, "the waits below count 2 * kLoads loads per stage in flight");
-    // Between the two tiles of stage st: stage st + 1 has landed for every wavefront (one more
-    // stage may be in flight), and every wavefront has left stage st - 1, whose ring slot takes
-    // stage st + 3.  The second tile of stage st may then read the first K operands of stage
-    // st + 1, so no tile waits for its operands at a stage boundary.
+    static_assert(kLoads == 2 && (kRing == 3 || kRing == 4), "the waits below count 2 * kLoads loads per stage in flight");
+    // Between the two tiles of stage st: stage st + 1 has landed for every wavefront (with a
+    // ring of four, one more stage may be in flight), and every wavefront has left stage st - 1,
+    // whose ring slot takes stage st + kRing - 1.  The second tile of stage st may then read the
+    // first K operands of stage st + 1, so no tile waits for its operands at a stage boundary.
     auto next_stage_ready = [&](int st) {
         if (st + 1 >= n_stage) return;  // uniform
-        if (st + 2 < n_stage) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (kRing == 4 && st + 2 < n_stage) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         lds_barrier();
-        if (st + 3 < n_stage) issue(st + 3);
+        if (st + kRing - 1 < n_stage) issue(st + kRing - 1);
     };
     const unsigned vaddr[2] = {vt_lane_address(smem + kStage * 128, 0, lane),
                                vt_lane_address(smem + kStage * 128, 1, lane)};  // V rows of ring slot 0
@@ -927,8 +928,8 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
 
     if (n_stage > 0) issue(0);
     if (n_stage > 1) issue(1);
-    if (n_stage > 2) issue(2);
-    if (n_stage > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    if (kRing == 4 && n_stage > 2) issue(2);
+    if (kRing == 4 && n_stage > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else if (n_stage > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();  // stage 0 has landed
@@ -936,11 +937,11 @@ __global__ void __launch_bounds__(256, 2) attn_ring_bf16(AttnArgs a) {
     load_k_operands<0>(ka, kaddr);
     k_operands_landed(ka);
     int st = 0;
-    for (; st + 3 < n_full; st += 4) {
+    for (; st + kRing - 1 < n_full; st += kRing) {
         full_stage(st, std::integral_constant<int, 0>());
         full_stage(st + 1, std::integral_constant<int, 1>());
         full_stage(st + 2, std::integral_constant<int, 2>());
-        full_stage(st + 3, std::integral_constant<int, 3>());
+        if (kRing == 4) full_stage(st + 3, std::integral_constant<int, 3 % kRing>());
     }
     if (st < n_full) {
         full_stage(st, std::integral_constant<int, 0>());
