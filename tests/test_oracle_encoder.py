@@ -208,3 +208,31 @@ def test_tokenwise_dynamic_filters():
     vg = np.ascontiguousarray(vv[:, :, 2:])
     conv = oracle.dwc_tokenwise(vg, oracle.tokenwise_kernels(vg, *tok, k), H, W)
     assert np.abs(out[:, :, 2:] - la[:, :, 2:] - conv).max() < 1e-13
+
+
+def test_layernorm_folded_into_the_next_product_is_the_same_function():
+    """The identity the encoder's folded LayerNorm rests on (Sec. 3.2.3's inherited pre-LN block):
+    W LN(x) + b = (1/sigma) ((W gamma) x - mean (W gamma) 1) + (W beta + b), with the row
+    statistics merged from groups of 64 features by the pairwise update of mean and squared
+    deviations -- checked against the oracle's LayerNorm followed by its linear layer."""
+    T, C, N, eps = 9, 192, 40, 1e-6
+    x = synth.normal((T, C), 41).astype(np.float64) * 2.0 + 0.7
+    gamma, beta = 1.0 + 0.2 * synth.normal((C,), 42), 0.3 * synth.normal((C,), 43)
+    w, b = synth.normal((N, C), 44) / 8, synth.normal((N,), 45)
+    want = oracle.linear(oracle.layernorm(x, gamma, beta, eps), w, b)
+    # statistics per group of 64 features, then merged group by group
+    cnt, mean, m2 = 0.0, np.zeros(T), np.zeros(T)
+    for g0 in range(0, C, 64):
+        part = x[:, g0:g0 + 64]
+        gmean = part.mean(-1)
+        gm2 = ((part - gmean[:, None]) ** 2).sum(-1)
+        delta, total = gmean - mean, cnt + 64.0
+        mean = mean + delta * 64.0 / total
+        m2 = m2 + gm2 + delta * delta * cnt * 64.0 / total
+        cnt = total
+    assert np.abs(mean - x.mean(-1)).max() < 1e-13 and np.abs(m2 / cnt - x.var(-1)).max() < 1e-12
+    rstd = 1.0 / np.sqrt(m2 / cnt + eps)
+    wg = w.astype(np.float64) * gamma.astype(np.float64)[None, :]
+    c1, c2 = wg.sum(-1), w.astype(np.float64) @ beta.astype(np.float64) + b
+    got = rstd[:, None] * (x @ wg.T - mean[:, None] * c1[None, :]) + c2[None, :]
+    assert np.abs(got - want).max() < 1e-11

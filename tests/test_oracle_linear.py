@@ -148,3 +148,26 @@ def test_focused_linear_attention_reduces_and_is_scale_free():
     H, W = 9, 5
     blk = oracle.linear_block(q, k, v, H, W, static_kernel=kern, focus_p=3)
     assert np.abs(blk - (oracle.focused_linear_attn(q, k, v, 3) + oracle.dwc(v, kern[None], H, W))).max() < 1e-12
+
+
+def test_wide_head_state_is_four_quadrants():
+    """What the 128-channel kernels compute: with q, k, v split into two 64-channel halves,
+    o[.., 64 j + c] = sum_i relu(q_i) S_ij[:, c] / (sum_i relu(q_i) . z_i + eps), where S_ij and
+    z_i are the states of the half-width problems (k_i, v_j) -- against the oracle's plain
+    definition at full width."""
+    B, h, N, d = 1, 2, 37, 128
+    q, k, v = synth.qkv(330, B, h, N, d, 1.0, False)
+    want = oracle.linear_attn_quadratic(q, k, v, 1e-6)
+    rq = np.maximum(q.astype(np.float64), 0.0)
+    num = np.zeros((B, h, N, d))
+    den = np.zeros((B, h, N))
+    for i in range(2):
+        ki, qi = np.ascontiguousarray(k[..., 64 * i:64 * i + 64]), rq[..., 64 * i:64 * i + 64]
+        for j in range(2):
+            vj = np.ascontiguousarray(v[..., 64 * j:64 * j + 64])
+            _, S, z = oracle.linear_attn_state(ki, ki, vj, 1e-6)     # S = relu(k_i)^T v_j, z = sum relu(k_i)
+            num[..., 64 * j:64 * j + 64] += np.einsum("bhnc,bhcd->bhnd", qi, S)
+            if j == 0:
+                den += np.einsum("bhnc,bhc->bhn", qi, z)
+    got = num / (den[..., None] + 1e-6)
+    assert np.abs(got - want).max() < 1e-12
