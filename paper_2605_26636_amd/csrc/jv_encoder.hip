@@ -347,39 +347,11 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         }
     };
     static_assert(kPartLoads == 4, "the block spreads four loads per part over its steps");
-    const int n_first = min(n_parts, kGemmSlots - 1);  // parts 0..3 go out at once, part 4 with block 0
-    for (int part = 0; part < n_first; ++part) issue_part(part, part);
-    wait_loads_and_barrier(kPartLoads * (n_first - 2));  // block 0 has landed
-    load_ops(0, 1, 0, 0);
-    int p = 0, a_slot = 0, w_slot = 1;
-    for (; 2 * p + 5 < n_parts; ++p) {  // steady state
-        block(p, a_slot, w_slot, true, true);
-        a_slot = next_slot(a_slot, 2);
-        w_slot = next_slot(w_slot, 2);
-    }
-    for (; p < n_b; ++p) {  // the last two blocks: everything has been issued
-        block(p, a_slot, w_slot, false, p + 1 < n_b);
-        a_slot = next_slot(a_slot, 2);
-        w_slot = next_slot(w_slot, 2);
-    }
-
-    // Epilogue: accumulator register v of block (nt, mt) is output feature
-    // n0 + 64 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li: a lane holds
-    // 4 consecutive features of one token.  Stored from there, an instruction would touch 32
-    // token rows with 16 or 32 bytes each, and every 128-byte line of y would be written by 4 to
-    // 8 different instructions.  Instead each wavefront turns its 32 x 64 blocks into token rows
-    // in 8 KB of LDS of its own and stores whole rows (128 or 256 contiguous bytes per token);
-    // the residual is read in the same row layout.  The LDS comes from the operand ring: the
-    // last block occupies two of the five slots, and every wavefront has passed the barrier
-    // after which nobody reads the other three (a_slot points at the first of them here).
-    unsigned char *stage = smem + next_slot(a_slot, 1 + (wave >> 2)) * kGemmPart + (wave & 3) * 8192;
-    // GELU reads the normal distribution function from a table in the third free slot, built
-    // here by all threads (two or three entries each; see gelu_from_table).
-    float *phi_table = (float *)(smem + a_slot * kGemmPart);
     // Folded LayerNorm: thread t < 256 merges the group statistics of row m0 + t into mean and
-    // 1/sigma and hands the pair to the lanes that hold the row's token through LDS.  (Done here
-    // rather than under the first operand loads: values held across the K loop cost it more
-    // than this round trip costs the epilogue.)
+    // 1/sigma.  The statistics are fetched before the first operand parts are issued and merged
+    // while those are in flight, so that the epilogue finds the two values in registers (done
+    // in the epilogue, the fetch and the chain of sixteen dependent updates cost every tile 3.4 us
+    // with all eight wavefronts waiting at its barrier).
     constexpr int kStatLoads = 8;  // 16-byte loads (two groups each) in flight per thread
     f32x4 stat_part[kStatLoads];
     const f32x4 *gs = nullptr;
@@ -389,6 +361,8 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
 #pragma unroll
         for (int i = 0; i < kStatLoads; ++i) stat_part[i] = gs[min(i, max(pairs - 1, 0))];
     }
+    const int n_first = min(n_parts, kGemmSlots - 1);  // parts 0..3 go out at once, part 4 with block 0
+    for (int part = 0; part < n_first; ++part) issue_part(part, part);
     float row_mean = 0.f, row_rstd = 0.f;
     if (LN == kLnConsume && tid < kBM) {
         float cnt = 0.f, mean = 0.f, m2 = 0.f;
@@ -418,6 +392,35 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         row_mean = mean;
         row_rstd = 1.0f / sqrtf(m2 / cnt + ln.eps);
     }
+    wait_loads_and_barrier(kPartLoads * (n_first - 2));  // block 0 has landed
+    load_ops(0, 1, 0, 0);
+    int p = 0, a_slot = 0, w_slot = 1;
+    for (; 2 * p + 5 < n_parts; ++p) {  // steady state
+        block(p, a_slot, w_slot, true, true);
+        a_slot = next_slot(a_slot, 2);
+        w_slot = next_slot(w_slot, 2);
+    }
+    for (; p < n_b; ++p) {  // the last two blocks: everything has been issued
+        block(p, a_slot, w_slot, false, p + 1 < n_b);
+        a_slot = next_slot(a_slot, 2);
+        w_slot = next_slot(w_slot, 2);
+    }
+
+    // Epilogue: accumulator register v of block (nt, mt) is output feature
+    // n0 + 64 wn + 32 nt + 8 (v/4) + 4 g + v%4 of token m0 + 128 wm + 32 mt + li: a lane holds
+    // 4 consecutive features of one token.  Stored from there, an instruction would touch 32
+    // token rows with 16 or 32 bytes each, and every 128-byte line of y would be written by 4 to
+    // 8 different instructions.  Instead each wavefront turns its 32 x 64 blocks into token rows
+    // in 8 KB of LDS of its own and stores whole rows (128 or 256 contiguous bytes per token);
+    // the residual is read in the same row layout.  The LDS comes from the operand ring: the
+    // last block occupies two of the five slots, and every wavefront has passed the barrier
+    // after which nobody reads the other three (a_slot points at the first of them here).
+    unsigned char *stage = smem + next_slot(a_slot, 1 + (wave >> 2)) * kGemmPart + (wave & 3) * 8192;
+    // GELU reads the normal distribution function from a table in the third free slot, built
+    // here by all threads (two or three entries each; see gelu_from_table).
+    float *phi_table = (float *)(smem + a_slot * kGemmPart);
+    // Folded LayerNorm: the rows' mean and 1/sigma (merged under the first operand loads, above)
+    // go to the lanes that hold the rows' tokens through LDS.
     float2 *row_stats = (float2 *)(smem + a_slot * kGemmPart + 16384);  // behind the table, [256]
     if (LN == kLnConsume && tid < kBM) row_stats[tid] = float2{row_mean, row_rstd};
     if (EPI == JV_EPI_GELU) {
