@@ -192,8 +192,8 @@ __device__ inline void wait_loads_and_barrier(int pending) {
 enum { kLnNone = 0, kLnConsume = 1, kLnProduce = 2 };
 struct GemmLn {
     const float *c1;        // consume: [N]
-    const float *stats_in;  // consume: [M][groups][2] (mean, sum of squared deviations) of 64 features each
-    float *stats_out;       // produce: [M][N / 64][2]
+    const float *stats_in;  // consume: [groups][M][2] (mean, sum of squared deviations) of 64 features each
+    float *stats_out;       // produce: [N / 64][M][2]
     void *xb_out;           // produce: [M][N] bf16 copy of y, or null
     int groups;             // consume: K / 64
     float eps;              // consume
@@ -347,50 +347,43 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         }
     };
     static_assert(kPartLoads == 4, "the block spreads four loads per part over its steps");
-    // Folded LayerNorm: thread t < 256 merges the group statistics of row m0 + t into mean and
-    // 1/sigma.  The statistics are fetched before the first operand parts are issued and merged
-    // while those are in flight, so that the epilogue finds the two values in registers (done
-    // in the epilogue, the fetch and the chain of sixteen dependent updates cost every tile 3.4 us
-    // with all eight wavefronts waiting at its barrier).
-    constexpr int kStatLoads = 8;  // 16-byte loads (two groups each) in flight per thread
-    f32x4 stat_part[kStatLoads];
-    const f32x4 *gs = nullptr;
-    if (LN == kLnConsume && tid < kBM) {
-        gs = (const f32x4 *)((const float2 *)ln.stats_in + (size_t)min(m0 + tid, M - 1) * ln.groups);
-        const int pairs = ln.groups >> 1;
+    // Folded LayerNorm: thread t < 256 turns the group statistics of row m0 + t into the row's mean
+    // and 1/sigma.  The groups all hold 64 features, so the mean is the plain average of the group
+    // means and the squared deviations add up as sum_g (m2_g + 64 (mean_g - mean)^2): two short
+    // passes over values in registers, no chain of dependent updates.  The statistics are stored
+    // group-major ([group][row]), so that the 64 rows of a wavefront are one contiguous 512-byte
+    // piece per group; they are fetched before the first operand parts are issued and combined
+    // while those are in flight, so that the epilogue finds the two values in registers.
+    constexpr int kStatChunk = 16;  // groups held in registers at a time (width 1024: all of them)
+    float2 stat_part[kStatChunk];
+    const float2 *gs = (const float2 *)ln.stats_in + min(m0 + tid, M - 1);
+    auto fetch_stats = [&](int g0) {
 #pragma unroll
-        for (int i = 0; i < kStatLoads; ++i) stat_part[i] = gs[min(i, max(pairs - 1, 0))];
-    }
+        for (int i = 0; i < kStatChunk; ++i) stat_part[i] = gs[(size_t)min(g0 + i, ln.groups - 1) * M];
+    };
+    if (LN == kLnConsume && tid < kBM) fetch_stats(0);
     const int n_first = min(n_parts, kGemmSlots - 1);  // parts 0..3 go out at once, part 4 with block 0
     for (int part = 0; part < n_first; ++part) issue_part(part, part);
-    float row_mean = 0.f, row_rstd = 0.f;
+    float row_mean = 0.f, row_rstd = 1.f;
     if (LN == kLnConsume && tid < kBM) {
-        float cnt = 0.f, mean = 0.f, m2 = 0.f;
-        auto merge = [&](float gmean, float gm2) {
-            const float delta = gmean - mean, total = cnt + 64.f, share = 64.f * __builtin_amdgcn_rcpf(total);
-            mean = fmaf(delta, share, mean);
-            m2 += gm2 + delta * delta * cnt * share;
-            cnt = total;
-        };
-        const int pairs = ln.groups >> 1;  // an odd last group is handled below
-        for (int p0 = 0; p0 < pairs; p0 += kStatLoads) {
-            if (p0 > 0) {  // more than sixteen groups (width above 1024): further rounds of loads
+        float sum = 0.f;
+        for (int g0 = 0; g0 < ln.groups; g0 += kStatChunk) {
+            if (g0 > 0) fetch_stats(g0);  // more than sixteen groups (width above 1024)
 #pragma unroll
-                for (int i = 0; i < kStatLoads; ++i) stat_part[i] = gs[min(p0 + i, pairs - 1)];
-            }
-#pragma unroll
-            for (int i = 0; i < kStatLoads; ++i)
-                if (p0 + i < pairs) {
-                    merge(stat_part[i][0], stat_part[i][1]);
-                    merge(stat_part[i][2], stat_part[i][3]);
-                }
+            for (int i = 0; i < kStatChunk; ++i) sum += g0 + i < ln.groups ? stat_part[i].x : 0.f;
         }
-        if (ln.groups & 1) {
-            const float2 last = ((const float2 *)gs)[ln.groups - 1];
-            merge(last.x, last.y);
+        const float mean = sum / (float)ln.groups;
+        float m2 = 0.f;
+        for (int g0 = 0; g0 < ln.groups; g0 += kStatChunk) {
+            if (ln.groups > kStatChunk) fetch_stats(g0);
+#pragma unroll
+            for (int i = 0; i < kStatChunk; ++i) {
+                const float d = stat_part[i].x - mean;
+                m2 += g0 + i < ln.groups ? fmaf(64.f * d, d, stat_part[i].y) : 0.f;
+            }
         }
         row_mean = mean;
-        row_rstd = 1.0f / sqrtf(m2 / cnt + ln.eps);
+        row_rstd = 1.0f / sqrtf(m2 / (64.f * (float)ln.groups) + ln.eps);
     }
     wait_loads_and_barrier(kPartLoads * (n_first - 2));  // block 0 has landed
     load_ops(0, 1, 0, 0);
@@ -553,7 +546,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                     const float d0 = out[0] - mean, d1 = out[1] - mean, d2 = out[2] - mean, d3 = out[3] - mean;
                     const float m2 = row16_sum(fmaf(d0, d0, d1 * d1) + fmaf(d2, d2, d3 * d3));
                     if (fchunk == 0 && row < M && fcol < N)
-                        *(float2 *)(ln.stats_out + ((size_t)row * (N >> 6) + ((n0 + wn * 64) >> 6)) * 2) = float2{mean, m2};
+                        *(float2 *)(ln.stats_out + ((size_t)((n0 + wn * 64) >> 6) * M + row) * 2) = float2{mean, m2};
                 }
             }
         }

@@ -231,6 +231,12 @@ def test_layernorm_folded_into_the_next_product_is_the_same_function():
         m2 = m2 + gm2 + delta * delta * cnt * 64.0 / total
         cnt = total
     assert np.abs(mean - x.mean(-1)).max() < 1e-13 and np.abs(m2 / cnt - x.var(-1)).max() < 1e-12
+    # equal group sizes: the same statistics without a running merge (what the kernel does)
+    gmeans = np.stack([x[:, g0:g0 + 64].mean(-1) for g0 in range(0, C, 64)], -1)
+    gm2s = np.stack([((x[:, g0:g0 + 64] - x[:, g0:g0 + 64].mean(-1, keepdims=True)) ** 2).sum(-1) for g0 in range(0, C, 64)], -1)
+    mean2 = gmeans.mean(-1)
+    m2b = (gm2s + 64.0 * (gmeans - mean2[:, None]) ** 2).sum(-1)
+    assert np.abs(mean2 - mean).max() < 1e-13 and np.abs(m2b - m2).max() < 1e-10
     rstd = 1.0 / np.sqrt(m2 / cnt + eps)
     wg = w.astype(np.float64) * gamma.astype(np.float64)[None, :]
     c1, c2 = wg.sum(-1), w.astype(np.float64) @ beta.astype(np.float64) + b
