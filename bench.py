@@ -346,8 +346,7 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
     1536, 24 heads, MLP 6144), blocks 24 and 37 (the paper prints positions for ViT-L only: scaled
     to the other depths).  "7B": the shape of the paper's largest teacher (Tab. 3: 40 blocks, width
     4096, 32 heads of 128 channels, MLP 8192), full attention kept at blocks 24 and 37; its weights
-    (10.7 GB) are drawn on the device, and its linear-attention blocks run without the convolution
-    branch (built for 64-channel heads)."""
+    (10.7 GB) are drawn on the device."""
     import torch
     from paper_2605_26636_amd import binding, synth
     B, H, W = 1, 64, 128
@@ -368,6 +367,10 @@ def bench_paper_ratio(steps, warmup, model="L", graph=False):
                         "b_qkv": zeros(3 * C), "w_o": w(C, C, 2 * C), "b_o": zeros(C),
                         "ln2_g": torch.ones(C, device="cuda"), "ln2_b": zeros(C), "w_fc1": w(hidden, C, C + hidden),
                         "b_fc1": zeros(hidden), "w_fc2": w(C, hidden, C + hidden), "b_fc2": zeros(C)})
+            hid = C // 16  # the squeeze-dynamic 3x3 branch, weights scaled as synth.squeeze_weights does
+            rnd = lambda shape, scale: torch.randn(*shape, generator=gen, device="cuda") * scale
+            dev[-1]["dwc"] = {"squeeze": (rnd((hid, C), 4.0 / C ** 0.5), rnd((hid,), 0.5),
+                                          rnd((C * 9, hid), 1.0 / (3 * hid ** 0.5)), rnd((C * 9,), 0.5 / 3)), "ksize": 3}
             continue
         wts = synth.block_weights(C, hidden, 5000 + l)
         d = {k: (torch.from_numpy(v).cuda().to(torch.bfloat16) if k.startswith("w_")

@@ -25,9 +25,10 @@
  *    [batch, N, 3, heads, head_dim] can be consumed without a transpose.
  *    Base pointers and all strides must keep every (b, h, n) row 16-byte aligned.
  *  - head_dim is 64, or 128 (the wide heads of the paper's largest backbones, Tab. 3/4) with
- *    JV_BF16 tensors: full, window and linear attention (prefix tokens included) are built for
- *    both; the convolution branch and the focused map of the linear-attention block, and
- *    JV_F32 tensors, for 64 only (JV_ERR_UNSUPPORTED otherwise).
+ *    JV_BF16 tensors: full, window and linear attention (prefix tokens included) and the
+ *    linear-attention block with static or squeeze-dynamic filters are built for both; the
+ *    focused map, token-wise filters and JV_F32 tensors for 64 only (JV_ERR_UNSUPPORTED
+ *    otherwise).
  *  - Inputs are never written.  O must not overlap Q, K or V: the byte range that O's
  *    strides span may not intersect the range of any input (JV_ERR_INVALID_ARG).
  *  - Arithmetic: JV_F32 tensors are processed in fp32 throughout.  JV_BF16
@@ -298,7 +299,7 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * w_qkv bf16 [3*width, width] (rows: Q features, then K, then V), b_qkv fp32 [3*width];
  * w_o bf16 [width, width], b_o fp32; w_fc1 bf16 [mlp_hidden, width], b_fc1 fp32;
  * w_fc2 bf16 [width, mlp_hidden], b_fc2 fp32.  width = heads * 64 or heads * 128 (wide heads:
- * linear-attention blocks without the convolution branch and with the ReLU map only), width
+ * linear-attention blocks with the ReLU map only, static or squeeze-dynamic filters), width
  * and mlp_hidden multiples of 64.
  *
  * jv_encoder_forward: x and y are device [batch, n_prefix + grid_h*grid_w, width] of stream_dtype

@@ -701,8 +701,16 @@ namespace jv {
 // also keep their generated filters there).
 static int encoder_head_dim(const jv_encoder_config &c) { return c.width / c.heads; }  // 64 or 128 (jv_encoder_create)
 static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N) {
-    if (encoder_head_dim(enc->cfg) == kHeadDimWide)
-        return linear_wide_workspace_floats(batch, enc->cfg.heads, N) * sizeof(float);
+    if (encoder_head_dim(enc->cfg) == kHeadDimWide) {
+        const size_t base = linear_wide_workspace_floats(batch, enc->cfg.heads, N);
+        size_t need = base;
+        for (int l = 0; l < enc->cfg.n_blocks; ++l) {
+            DwcPlan plan;
+            if (plan_dwc_wide(&enc->dwc[l], base, batch, enc->cfg.heads, N, &plan) == JV_OK)
+                need = plan.total_floats > need ? plan.total_floats : need;
+        }
+        return need * sizeof(float);
+    }
     const LinearPlan lp = plan_linear(batch, enc->cfg.heads, N);
     size_t need = linear_workspace_bytes(batch, enc->cfg.heads, N);
     for (int l = 0; l < enc->cfg.n_blocks; ++l) {
@@ -800,11 +808,10 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
         for (const void *p : ptrs)
             if (!p || ((uintptr_t)p & 15))
                 return jv::fail(JV_ERR_INVALID_ARG, "block %d: null or misaligned weight pointer", l);
-        if (c.pattern[l] == 0 && b.dwc && b.dwc->mode != JV_DWC_NONE && wide)
-            return jv::fail(JV_ERR_UNSUPPORTED, "block %d: head_dim 128: the convolution branch is built for 64-channel heads", l);
         if (c.pattern[l] == 0 && b.dwc) {  // validate the convolution parameters now
             jv::DwcPlan plan;
-            jv_status st = jv::plan_dwc(b.dwc, jv::plan_linear(1, c.heads, 256), 1, c.heads, 256, &plan);
+            jv_status st = wide ? jv::plan_dwc_wide(b.dwc, 0, 1, c.heads, 256, &plan)
+                                : jv::plan_dwc(b.dwc, jv::plan_linear(1, c.heads, 256), 1, c.heads, 256, &plan);
             if (st != JV_OK) return st;
         }
     }

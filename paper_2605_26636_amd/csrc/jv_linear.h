@@ -57,6 +57,11 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
 size_t linear_wide_workspace_floats(int B, int heads, int N);
 jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream);
 
+// head_dim 128: the block's convolution branch (static or squeeze-dynamic filters) as passes of
+// their own; `base` = floats the linear-attention states take (linear_wide_workspace_floats).
+jv_status plan_dwc_wide(const jv_dwc_params *dwc, size_t base, int B, int heads, int N, DwcPlan *out);
+jv_status dwc_wide_forward(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream);
+
 // Generator of the dynamic filters: partial token sums of V -> hidden layer -> filters.
 jv_status squeeze_generate(const DwcPlan &dwc, float *ws, int n_part, int B, int heads, int N,
                            hipStream_t stream);

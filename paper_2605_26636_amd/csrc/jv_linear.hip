@@ -177,12 +177,22 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
                                int focus_p) {
     if (focus_p < 1 || focus_p > 16) return fail(JV_ERR_INVALID_ARG, "focusing power must be 1 .. 16");
     if (pr.D == kHeadDimWide) {
-        if (focus_p != 1 || (dwc && dwc->mode != JV_DWC_NONE))
-            return fail(JV_ERR_UNSUPPORTED, "head_dim 128: plain linear attention only (no convolution branch, no focused map)");
-        const size_t need = linear_wide_workspace_floats(pr.B, pr.heads, pr.N) * sizeof(float);
+        if (focus_p != 1) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: the focused map is built for 64-channel heads");
+        DwcPlan cv;
+        jv_status st = plan_dwc_wide(dwc, linear_wide_workspace_floats(pr.B, pr.heads, pr.N), pr.B, pr.heads, pr.N, &cv);
+        if (st != JV_OK) return st;
+        const size_t need = cv.total_floats * sizeof(float);
         if (workspace_bytes < need)
             return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
-        return linear_wide_bf16(pr, eps, (float *)workspace, stream);
+        float *ws = (float *)workspace;
+        if (cv.mode == JV_DWC_NONE) return linear_wide_bf16(pr, eps, ws, stream);
+        // the attention term in fp32, then the convolution added and the sum rounded once
+        Problem la = pr;
+        const long long C = (long long)pr.heads * kHeadDimWide;
+        la.o = {ws + cv.la_off, (long long)pr.N * C, kHeadDimWide, C};
+        la.o_bf16 = false;
+        if ((st = linear_wide_bf16(la, eps, ws, stream)) != JV_OK) return st;
+        return dwc_wide_forward(pr, cv, ws, stream);
     }
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;
@@ -293,11 +303,10 @@ size_t jv_linear_block_workspace_bytes(const jv_attn_desc *desc, const jv_dwc_pa
     jv::DwcPlan cv;
     const int N = desc->n_prefix + desc->grid_h * desc->grid_w;
     if (desc->head_dim == jv::kHeadDimWide) {
-        if (dwc && dwc->mode != JV_DWC_NONE) {
-            jv::fail(JV_ERR_UNSUPPORTED, "head_dim 128: plain linear attention only");
+        if (jv::plan_dwc_wide(dwc, jv::linear_wide_workspace_floats(desc->batch, desc->heads, N), desc->batch,
+                              desc->heads, N, &cv) != JV_OK)
             return 0;
-        }
-        return jv::linear_wide_workspace_floats(desc->batch, desc->heads, N) * sizeof(float);
+        return cv.total_floats * sizeof(float);
     }
     const jv::LinearPlan plan = jv::plan_linear(desc->batch, desc->heads, N);
     if (jv::plan_dwc(dwc, plan, desc->batch, desc->heads, N, &cv) != JV_OK) return 0;

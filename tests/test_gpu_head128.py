@@ -182,13 +182,40 @@ def test_linear_attention_prefix_and_fused_layout():
     assert torch.equal(out, o)
 
 
-def test_linear_block_variants_are_refused():
-    """The convolution branch and the focused map are built for 64-channel heads."""
+@pytest.mark.parametrize("ksize", [3, 5])
+@pytest.mark.parametrize("B,heads,H,W,P", [(2, 2, 13, 11, 0), (1, 3, 37, 37, 0), (1, 1, 1, 1, 0), (2, 2, 12, 9, 5)])
+def test_linear_block_static_and_squeeze_dynamic(B, heads, H, W, P, ksize):
+    """The paper's linear-attention block (Eq. 4) on 128-channel heads: static filters and the
+    squeeze-dynamic generator, against the oracle; prefix tokens get no convolution term."""
+    C, hidden = heads * D, 8
+    q, k, v = synth.qkv(70, B, heads, P + H * W, D, 0.5, True)
+    kern = synth.dwc_static_kernel(C, ksize, 7400 + ksize)
+    sq = synth.squeeze_weights(C, hidden, ksize, 7500 + ksize)
+    dev = lambda *a: tuple(torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in a)
+
+    def block(out_dtype, **kw):
+        dq, dk, dv = (to_device(x, True) for x in (q, k, v))
+        o = torch.full(dq.shape, float("nan"), dtype=out_dtype, device="cuda")
+        binding.jv_linear_block_fwd(dq, dk, dv, o, (H, W), 1e-6, ksize=ksize, **kw)
+        torch.cuda.synchronize()
+        return o
+
+    ref = oracle.linear_block(q, k, v, H, W, 1e-6, static_kernel=kern, ksize=ksize)
+    check_bf16_pair(block(torch.float32, static_kernel=dev(kern)[0]), block(torch.bfloat16, static_kernel=dev(kern)[0]), ref)
+    ref = oracle.linear_block(q, k, v, H, W, 1e-6, squeeze=sq, ksize=ksize)
+    check_bf16_pair(block(torch.float32, squeeze=dev(*sq)), block(torch.bfloat16, squeeze=dev(*sq)), ref)
+
+
+def test_linear_block_variants_refused_for_wide_heads():
+    """The focused map and token-wise filters are built for 64-channel heads."""
     B, heads, H, W = 1, 1, 4, 4
     q = torch.zeros(B, heads, H * W, D, device="cuda", dtype=torch.bfloat16)
-    kern = torch.zeros(heads * D, 3, 3, device="cuda")
     with pytest.raises(binding.JvError) as e:
-        binding.jv_linear_block_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (H, W), static_kernel=kern)
+        binding.jv_linear_block_focused_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (H, W), 3)
+    assert e.value.status == binding.JV_ERR_UNSUPPORTED
+    tok = tuple(torch.from_numpy(a).cuda() for a in synth.squeeze_weights(heads * D, 64, 3, 7600))
+    with pytest.raises(binding.JvError) as e:
+        binding.jv_linear_block_fwd(q, q.clone(), q.clone(), torch.empty_like(q), (H, W), token=tok)
     assert e.value.status in (binding.JV_ERR_UNSUPPORTED, binding.JV_ERR_WORKSPACE_TOO_SMALL)
 
 
@@ -219,15 +246,26 @@ def test_encoder_with_wide_heads(fold):
         enc.close()
 
 
-def test_encoder_wide_heads_refuses_block_variants():
-    heads, hidden = 2, 256
+def test_encoder_wide_heads_block_variants():
+    """Linear-attention blocks of a wide-head encoder carry the convolution branch (squeeze-dynamic
+    and static filters) like 64-channel ones; the focused map is refused."""
+    B, H, W, heads, hidden = 2, 12, 10, 2, 256
     C = heads * D
-    blocks = [synth.block_weights(C, hidden, 7300)]
-    dev = _device_blocks(blocks)
+    x = synth.normal((B, H * W, C), 7700)
+    blocks = [synth.block_weights(C, hidden, 7710 + i) for i in range(3)]
+    blocks[0]["dwc"] = {"squeeze": synth.squeeze_weights(C, 8, 3, 7720), "ksize": 3}
+    blocks[2]["dwc"] = {"static_kernel": synth.dwc_static_kernel(C, 5, 7721), "ksize": 5}
+    dev = _device_blocks([{k: v for k, v in b.items() if k != "dwc"} for b in blocks])
+    dev[0]["dwc"] = {"squeeze": tuple(torch.from_numpy(a).cuda() for a in blocks[0]["dwc"]["squeeze"]), "ksize": 3}
+    dev[2]["dwc"] = {"static_kernel": torch.from_numpy(blocks[2]["dwc"]["static_kernel"]).cuda(), "ksize": 5}
+    pattern = [0, 1, 0]
+    enc = binding.Encoder(dev, pattern, heads, hidden, window=(4, 5))
+    dx = torch.from_numpy(x).cuda()
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W))
+    ref = oracle.encoder_forward(x, blocks, pattern, H, W, heads, window=(4, 5))
+    check(err_bf16(to_host(y), ref), BF16_TOL)
+    enc.close()
     with pytest.raises(binding.JvError) as e:
-        binding.Encoder(dev, [0], heads, hidden, window=(4, 4), la_focus_p=3)
-    assert e.value.status == binding.JV_ERR_UNSUPPORTED
-    dev[0]["dwc"] = {"static_kernel": torch.zeros(C, 3, 3, device="cuda"), "ksize": 3}
-    with pytest.raises(binding.JvError) as e:
-        binding.Encoder(dev, [0], heads, hidden, window=(4, 4))
+        binding.Encoder(_device_blocks([synth.block_weights(C, hidden, 7730)]), [0], heads, hidden, window=(4, 4), la_focus_p=3)
     assert e.value.status == binding.JV_ERR_UNSUPPORTED
