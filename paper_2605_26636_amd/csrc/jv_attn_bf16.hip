@@ -1336,6 +1336,259 @@ __global__ void __launch_bounds__(256, 2) attn_wide_bf16(AttnArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// head_dim 128, windows that span whole grid rows (full attention above all): the ring design
+// of attn_ring_bf16 on 256-byte rows.  A workgroup holds 128 query slots (4 wavefronts x 32);
+// the keys pass through a ring of three LDS stages of one tile each (32 keys: 8 KB of K rows,
+// 8 KB of V rows), filled from global memory straight into LDS two stages ahead (four load
+// instructions per stage and wavefront, one wait, one barrier).  Inside a tile: the eight
+// score products; then -- behind them -- the wait for the next stage, the barrier and the loads
+// of the stage after it; the LDS reads of this tile's V operands and of the next tile's K
+// operands (in assembly, see lds_read_tr16_at); the softmax arithmetic, which hides their
+// latency; one wait; the eight P.V products.  Byte offsets inside one (batch, head) slice
+// below 2^31 (checked by the launcher).
+// grid (ceil(q_slots / 128), n_win, B*heads), 256 threads.
+// ---------------------------------------------------------------------------------------
+constexpr int kWideRing = 3;
+
+// The wavefront's LDS operand addresses for ring slot 0: K pieces (channels 16 ks + 8 g .. +7 of
+// key row li) and the first transposing V read of each 32-channel block.
+__device__ inline void wide_lane_addresses(unsigned (&kaddr)[8], unsigned (&vaddr)[4], const unsigned char *ring, int lane) {
+    const int g = lane >> 5, li = lane & 31, blk = lane >> 4, j = lane & 15;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lds_address(ring) + wide_off_row(li, 2 * ks + g);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+        vaddr[mi] = lds_address(ring + kTileWideBytes) + wide_off_tr(4 * g + (j >> 2), mi * 4 + (blk & 1) * 2 + ((j & 3) >> 1)) + (j & 1) * 8;
+}
+
+template <int OFF>
+__device__ inline void wide_load_k(u32x4 (&ka)[8], const unsigned (&kaddr)[8]) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) ka[ks] = lds_read_b128_at<OFF>(kaddr[ks]);
+}
+// va[kk][mi]: keys 16 kk + 8 r + 4 g + e in k-slot (g, 4 r + e); rows 8 apart keep their rotation,
+// so the four reads of a block are constant offsets from one address.
+template <int OFF>
+__device__ inline void wide_load_v(u32x4 (&va)[2][4], const unsigned (&vaddr)[4]) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            u32x2 r0, r1;
+            if (kk == 0) {
+                r0 = lds_read_tr16_at<OFF>(vaddr[mi]);
+                r1 = lds_read_tr16_at<OFF + 2048>(vaddr[mi]);
+            } else {
+                r0 = lds_read_tr16_at<OFF + 4096>(vaddr[mi]);
+                r1 = lds_read_tr16_at<OFF + 6144>(vaddr[mi]);
+            }
+            const u32x4 r = {r0[0], r0[1], r1[0], r1[1]};
+            va[kk][mi] = r;
+        }
+}
+__device__ inline void wide_reads_landed(u32x4 (&va)[2][4], u32x4 (&ka)[8]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[0][2]), "+v"(va[0][3]), "+v"(va[1][0]), "+v"(va[1][1]),
+                   "+v"(va[1][2]), "+v"(va[1][3]), "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(ka[4]),
+                   "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7]));
+}
+
+// One tile of 32 keys: `ka` holds its K operands; V rows at vaddr + VOFF; KNEXT >= 0: the K
+// operands at kaddr + KNEXT are read into `ka` under the exponentials; `mid` is the stage
+// hand-over; MASKED: keys with index >= key_limit are padding.
+template <int KNEXT, bool MASKED, int VOFF, class Mid>
+__device__ __forceinline__ void wide_ring_tile(WaveStateWide &w, const u32x4 (&qreg)[8], u32x4 (&ka)[8],
+                                      const unsigned (&kaddr)[8], const unsigned (&vaddr)[4], int key_limit,
+                                      float c, int lane, Mid &&mid) {
+    const int g = lane >> 5;
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = mfma32(as_bf16x8(ka[ks]), as_bf16x8(qreg[ks]), s);
+    __builtin_amdgcn_sched_barrier(0);  // the score products are issued before the hand-over and the reads
+    mid();
+    u32x4 va[2][4];
+    wide_load_v<VOFF>(va, vaddr);
+    if (KNEXT >= 0) wide_load_k<KNEXT >= 0 ? KNEXT : 0>(ka, kaddr);
+    __builtin_amdgcn_sched_barrier(0);  // ... and the reads before the softmax arithmetic
+    if (MASKED) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 8 * (v / 4) + 4 * g + (v % 4) >= key_limit ? -INFINITY : s[v];
+    }
+    unsigned pk[8];
+    float tile_sum = exp_block(s, pk, c, -w.m);
+    if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kLazySum)) != 0) {  // also catches inf/NaN
+        raise_reference_wide(w, s, c);
+        tile_sum = exp_block(s, pk, c, -w.m);
+    }
+    w.l += tile_sum;
+    wide_reads_landed(va, ka);
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const u32x4 pb = {pk[4 * kk], pk[4 * kk + 1], pk[4 * kk + 2], pk[4 * kk + 3]};
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) w.acc[mi] = mfma32(as_bf16x8(va[kk][mi]), as_bf16x8(pb), w.acc[mi]);
+    }
+}
+
+template <bool O_BF16>
+__global__ void __launch_bounds__(256, 2) attn_ring_wide_bf16(AttnArgs a) {
+    float c_log2 = a.c;
+    asm volatile("" : "+s"(c_log2));  // fetched and waited for here, not inside the key loop
+    __shared__ __align__(16) unsigned char smem[kWideRing * kStageWideBytes];
+    static_assert(kWideRing * kStageWideBytes >= 4 * kTileWideBytes, "the ring doubles as output staging");
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, li = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
+    const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    const long long qbase = b * a.q.sb + h * a.q.sh, obase = b * a.o.sb + h * a.o.sh;
+    const bool wave_live = q0 < a.q_slots;
+
+    // Query operands, in assembly (they are the wavefront's oldest loads; see load_queries).
+    u32x4 qreg[8];
+    {
+        const int tok = max(slot_token(a, wy, wx, q0 + li), 0);
+        const __bf16 *row = (const __bf16 *)a.q.ptr + qbase + (long long)tok * a.q.sn + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qreg[ks]) : "v"(row), "n"(32 * ks));
+    }
+    WaveStateWide w;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w.acc[mi][v] = 0.f;
+    w.m = kMinusHuge;
+    w.l = 0.f;
+
+    const int tok_first = wy * a.g.wh * a.g.W;
+    const int tok_limit = min(a.g.slots, a.g.H * a.g.W - tok_first);
+    const int n_full = tok_limit / kStageWide, n_stage = (tok_limit + kStageWide - 1) / kStageWide;
+
+    // Loads.  A wavefront moves rows 8 * wave .. + 7 of every stage's K and V, four rows (1 KB of
+    // LDS) per instruction: lane = 16 * (row in the group of four) + 16-byte slot of the LDS row,
+    // and it fetches the chunk of the token's row that belongs in that slot under the tile
+    // layouts.  Rows past the last token fetch the window's first token instead.
+    auto uniform = [](const char *ptr) {
+        const unsigned long long u = (unsigned long long)ptr;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+        return (const char *)(((unsigned long long)hi << 32) | lo);
+    };
+    const char *kbytes = uniform((const char *)((const __bf16 *)a.k.ptr + b * a.k.sb + h * a.k.sh + (long long)tok_first * a.k.sn));
+    const char *vbytes = uniform((const char *)((const __bf16 *)a.v.ptr + b * a.v.sb + h * a.v.sh + (long long)tok_first * a.v.sn));
+    const int lrow = lane >> 4, lslot = lane & 15;
+    unsigned kcur[2], vcur[2], kpad[2], vpad[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 8 * wave + 4 * i + lrow;
+        kpad[i] = 16u * (unsigned)(lslot ^ (row & 15));
+        vpad[i] = 16u * (unsigned)((((lslot >> 2) ^ (row & 3)) << 2) | (lslot & 3));
+        kcur[i] = 2u * (unsigned)row * (unsigned)a.k.sn + kpad[i];
+        vcur[i] = 2u * (unsigned)row * (unsigned)a.v.sn + vpad[i];
+    }
+    const unsigned kstep = 2u * kStageWide * (unsigned)a.k.sn, vstep = 2u * kStageWide * (unsigned)a.v.sn;
+    auto issue = [&](int stage) {
+        unsigned char *kt = smem + (stage % kWideRing) * kStageWideBytes, *vt = kt + kTileWideBytes;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row0 = 8 * wave + 4 * i;
+            const bool past = stage * kStageWide + row0 + lrow >= tok_limit;  // only in the window's last stage
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(kbytes + (past ? kpad[i] : kcur[i])),
+                                             (attn_lds_void *)(kt + row0 * 256), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((attn_global_cvoid *)(vbytes + (past ? vpad[i] : vcur[i])),
+                                             (attn_lds_void *)(vt + row0 * 256), 16, 0, 0);
+            kcur[i] += kstep;
+            vcur[i] += vstep;
+        }
+    };
+    // Inside the tile of stage st: stage st + 1 has landed for every wavefront, and every
+    // wavefront has left stage st - 1, whose ring slot takes stage st + 2.
+    auto hand_over = [&](int st) {
+        if (st + 1 >= n_stage) return;  // uniform
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        if (st + kWideRing - 1 < n_stage) issue(st + kWideRing - 1);
+    };
+    unsigned kaddr[8], vaddr[4];
+    wide_lane_addresses(kaddr, vaddr, smem, lane);
+    u32x4 ka[8];
+    auto full_stage = [&](int st, auto slot_tag) {
+        constexpr int slot = decltype(slot_tag)::value, after = (slot + 1) % kWideRing;
+        auto mid = [&]() { hand_over(st); };
+        if (wave_live) wide_ring_tile<after * kStageWideBytes, false, slot * kStageWideBytes>(w, qreg, ka, kaddr, vaddr, 0, c_log2, lane, mid);
+        else mid();
+    };
+
+    if (n_stage > 0) issue(0);
+    if (n_stage > 1) issue(1);
+    if (n_stage > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();  // stage 0 has landed
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[ks]));  // the queries, older than stage 0, too
+    wide_load_k<0>(ka, kaddr);
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(ka[4]), "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7]));
+    int st = 0;
+    for (; st + kWideRing - 1 < n_full; st += kWideRing) {
+        full_stage(st, std::integral_constant<int, 0>());
+        full_stage(st + 1, std::integral_constant<int, 1>());
+        full_stage(st + 2, std::integral_constant<int, 2>());
+    }
+    if (st < n_full) { full_stage(st, std::integral_constant<int, 0>()); ++st; }
+    if (st < n_full) { full_stage(st, std::integral_constant<int, 1>()); ++st; }
+    if (st < n_stage && wave_live) {  // the partial stage that ends the window (its K operands are in ka)
+        const unsigned at = (st % kWideRing) * kStageWideBytes;
+        const unsigned vlast[4] = {vaddr[0] + at, vaddr[1] + at, vaddr[2] + at, vaddr[3] + at};
+        wide_ring_tile<-1, true, 0>(w, qreg, ka, kaddr, vlast, tok_limit - st * kStageWide, c_log2, lane, [] {});
+    }
+    __syncthreads();  // every wavefront is done with the ring: reuse it as staging
+    if (!wave_live) return;
+
+    float lo, hi;
+    pair_values(w.l, &lo, &hi);
+    const float inv = __builtin_amdgcn_rcpf(lo + hi);
+    if (O_BF16) {
+        unsigned char *stage = smem + wave * kTileWideBytes;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x16 &x = w.acc[mi];
+                u32x2 pk = {pack_bf16x2(x[4 * q4] * inv, x[4 * q4 + 1] * inv),
+                            pack_bf16x2(x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv)};
+                *(u32x2 *)(stage + wide_off_row(li, 4 * mi + q4) + 8 * g) = pk;
+            }
+        __bf16 *op = (__bf16 *)a.o.ptr + obase;
+        const int orow = lane >> 4, ochunk = lane & 15;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int row = 4 * r + orow, slot = q0 + row;
+            const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
+            const u32x4 val = *(const u32x4 *)(stage + wide_off_row(row, ochunk));
+            if (tok >= 0) *(u32x4 *)(op + (long long)tok * a.o.sn + ochunk * 8) = val;
+        }
+    } else {
+        float *op = (float *)a.o.ptr + obase;
+        const int slot = q0 + li;
+        const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
+        if (tok >= 0) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const f32x16 &x = w.acc[mi];
+                    f32x4 val = {x[4 * q4] * inv, x[4 * q4 + 1] * inv, x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv};
+                    *(f32x4 *)(op + (long long)tok * a.o.sn + 32 * mi + 8 * q4 + 4 * g) = val;
+                }
+        }
+    }
+}
+
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_slots, hipStream_t stream) {
     AttnArgs a;
     a.q = pr.q; a.k = pr.k; a.v = pr.v; a.o = pr.o;
@@ -1347,6 +1600,13 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
     if (pr.D == kHeadDimWide) {
         dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
+        // windows of whole grid rows with 32-bit byte offsets inside a (batch, head) slice: the ring kernel
+        const long long wide_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
+        if (a.contig && ((long long)pr.N + 2 * kStageWide) * wide_sn * 2 + 512 < (1ll << 31)) {
+            if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true>), grid, dim3(256), 0, stream, a);
+            else hipLaunchKernelGGL((attn_ring_wide_bf16<false>), grid, dim3(256), 0, stream, a);
+            return launch_status("attn_ring_wide_bf16");
+        }
         if (pr.o_bf16) hipLaunchKernelGGL((attn_wide_bf16<true>), grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((attn_wide_bf16<false>), grid, dim3(256), 0, stream, a);
         return launch_status("attn_wide_bf16");

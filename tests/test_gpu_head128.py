@@ -40,6 +40,12 @@ def _window(q, k, v, H, W, window, out_dtype=torch.bfloat16, scale=0.0):
     (1, 1, 1, 1, 1.0),      # a single token
     (2, 2, 24, 40, 0.5),    # N = 960 = 30 stages
     (1, 2, 33, 33, 1.0),    # N = 1089: a one-key tail
+    (1, 1, 1, 31, 1.0),     # less than one stage
+    (1, 2, 8, 8, 1.0),      # exactly two stages
+    (1, 1, 8, 12, 0.5),     # exactly three: once round the ring
+    (2, 1, 8, 16, 1.0),     # four
+    (1, 1, 10, 16, 1.0),    # five
+    (1, 1, 3, 43, 1.0),     # N = 129: four stages and one key
 ])
 def test_full_attention_small_shapes(B, heads, H, W, vscale):
     q, k, v = synth.qkv(60, B, heads, H * W, D, vscale, True)
