@@ -1349,7 +1349,11 @@ __global__ void __launch_bounds__(256, 2) attn_wide_bf16(AttnArgs a) {
 // below 2^31 (checked by the launcher).
 // grid (ceil(q_slots / 128), n_win, B*heads), 256 threads.
 // ---------------------------------------------------------------------------------------
-constexpr int kWideRing = 3;
+#ifndef JV_WIDE_RING
+#define JV_WIDE_RING 3  // stages in the ring: 3, or 4 (one more stage in flight; measured the same time)
+#endif
+constexpr int kWideRing = JV_WIDE_RING;
+static_assert(kWideRing == 3 || kWideRing == 4, "the waits of attn_ring_wide_bf16 count the loads of 3 or 4 stages");
 
 // The wavefront's LDS operand addresses for ring slot 0: K pieces (channels 16 ks + 8 g .. +7 of
 // key row li) and the first transposing V read of each 32-channel block.
@@ -1394,47 +1398,98 @@ __device__ inline void wide_reads_landed(u32x4 (&va)[2][4], u32x4 (&ka)[8]) {
                    "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7]));
 }
 
+// Running softmax of NT blocks of 32 query columns over 128 channels.
+template <int NT>
+struct WideState {
+    f32x16 acc[4][NT];  // channel blocks of 32
+    float m[NT], l[NT]; // l is this lane's half of the keys only
+};
+template <int NT>
+__device__ inline void raise_reference_wide(WideState<NT> &w, int nt, const f32x16 &s, float c) {
+    float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+    float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+    float t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+    float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
+    t0 = fmaxf(fmaxf(t0, t1), t2);
+    t3 = fmaxf(fmaxf(t3, t4), s[15]);
+    float a, b;
+    pair_values(fmaxf(t0, t3) * c, &a, &b);  // this lane and lane^32 share the query column
+    const float m_new = fmaxf(w.m[nt], fmaxf(a, b));
+    const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
+    w.m[nt] = m_new;
+    w.l[nt] *= alpha;
+    // One 32-channel block at a time: with NT = 2 the accumulators live in the accumulation
+    // registers, which the vector unit cannot scale in place, and the vector registers this rare
+    // path holds at once are taken from every tile's budget.
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // One tile of 32 keys: `ka` holds its K operands; V rows at vaddr + VOFF; KNEXT >= 0: the K
 // operands at kaddr + KNEXT are read into `ka` under the exponentials; `mid` is the stage
-// hand-over; MASKED: keys with index >= key_limit are padding.
-template <int KNEXT, bool MASKED, int VOFF, class Mid>
-__device__ __forceinline__ void wide_ring_tile(WaveStateWide &w, const u32x4 (&qreg)[8], u32x4 (&ka)[8],
+// hand-over; MASKED: keys with index >= key_limit are padding.  Every operand read from LDS
+// feeds NT matrix instructions.
+template <int NT, int KNEXT, bool MASKED, int VOFF, class Mid>
+__device__ __forceinline__ void wide_ring_tile(WideState<NT> &w, const u32x4 (&qreg)[NT][8], u32x4 (&ka)[8],
                                       const unsigned (&kaddr)[8], const unsigned (&vaddr)[4], int key_limit,
                                       float c, int lane, Mid &&mid) {
     const int g = lane >> 5;
-    f32x16 s;
+    f32x16 s[NT];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = mfma32(as_bf16x8(ka[ks]), as_bf16x8(qreg[ks]), s);
+        for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) s[nt] = mfma32(as_bf16x8(ka[ks]), as_bf16x8(qreg[nt][ks]), s[nt]);
     __builtin_amdgcn_sched_barrier(0);  // the score products are issued before the hand-over and the reads
     mid();
     u32x4 va[2][4];
     wide_load_v<VOFF>(va, vaddr);
     if (KNEXT >= 0) wide_load_k<KNEXT >= 0 ? KNEXT : 0>(ka, kaddr);
     __builtin_amdgcn_sched_barrier(0);  // ... and the reads before the softmax arithmetic
-    if (MASKED) {
+    unsigned pk[NT][8];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 8 * (v / 4) + 4 * g + (v % 4) >= key_limit ? -INFINITY : s[v];
+    for (int nt = 0; nt < NT; ++nt) {
+        if (MASKED) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[nt][v] = 8 * (v / 4) + 4 * g + (v % 4) >= key_limit ? -INFINITY : s[nt][v];
+        }
+        float tile_sum = exp_block(s[nt], pk[nt], c, -w.m[nt]);
+        if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kLazySum)) != 0) {  // also catches inf/NaN
+            raise_reference_wide<NT>(w, nt, s[nt], c);
+            tile_sum = exp_block(s[nt], pk[nt], c, -w.m[nt]);
+        }
+        w.l[nt] += tile_sum;
     }
-    unsigned pk[8];
-    float tile_sum = exp_block(s, pk, c, -w.m);
-    if (__builtin_amdgcn_ballot_w64(!(tile_sum <= kLazySum)) != 0) {  // also catches inf/NaN
-        raise_reference_wide(w, s, c);
-        tile_sum = exp_block(s, pk, c, -w.m);
-    }
-    w.l += tile_sum;
     wide_reads_landed(va, ka);
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        const u32x4 pb = {pk[4 * kk], pk[4 * kk + 1], pk[4 * kk + 2], pk[4 * kk + 3]};
+    for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) w.acc[mi] = mfma32(as_bf16x8(va[kk][mi]), as_bf16x8(pb), w.acc[mi]);
-    }
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const u32x4 pb = {pk[nt][4 * kk], pk[nt][4 * kk + 1], pk[nt][4 * kk + 2], pk[nt][4 * kk + 3]};
+                w.acc[mi][nt] = mfma32(as_bf16x8(va[kk][mi]), as_bf16x8(pb), w.acc[mi][nt]);
+            }
 }
 
-template <bool O_BF16>
-__global__ void __launch_bounds__(256, 2) attn_ring_wide_bf16(AttnArgs a) {
+// NT = 1 (the build's choice): 128 query slots per workgroup, two workgroups per compute unit.
+// NT = 2: 256 query slots, one workgroup per compute unit with the whole register file
+// (accumulators and queries in the accumulation registers); every operand read from LDS feeds
+// two matrix instructions, but with one wavefront per SIMD nothing runs under its softmax
+// arithmetic: measured 27 % slower (4096 tokens x 64 heads: 687 us against 541 us).  The NT = 2
+// build is only correct while the compiler leaves the registers the assembly LDS reads write
+// alone until wide_reads_landed -- under register pressure it has copied them to accumulation
+// registers first, before the data had arrived; check the generated code when building it.
+template <bool O_BF16, int NT>
+__global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
     float c_log2 = a.c;
     asm volatile("" : "+s"(c_log2));  // fetched and waited for here, not inside the key loop
     __shared__ __align__(16) unsigned char smem[kWideRing * kStageWideBytes];
@@ -1443,26 +1498,34 @@ __global__ void __launch_bounds__(256, 2) attn_ring_wide_bf16(AttnArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
     const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
-    const int q0 = blockIdx.x * 128 + wave * 32;
+    const int q0 = (blockIdx.x * 4 + wave) * (32 * NT);
     const long long qbase = b * a.q.sb + h * a.q.sh, obase = b * a.o.sb + h * a.o.sh;
     const bool wave_live = q0 < a.q_slots;
 
     // Query operands, in assembly (they are the wavefront's oldest loads; see load_queries).
-    u32x4 qreg[8];
-    {
-        const int tok = max(slot_token(a, wy, wx, q0 + li), 0);
+    u32x4 qreg[NT][8];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int tok = max(slot_token(a, wy, wx, q0 + 32 * nt + li), 0);
         const __bf16 *row = (const __bf16 *)a.q.ptr + qbase + (long long)tok * a.q.sn + g * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qreg[ks]) : "v"(row), "n"(32 * ks));
+        for (int ks = 0; ks < 8; ++ks) {
+            // (NT = 2: straight into the accumulation registers, where the matrix instructions read them:
+            // the vector registers are left to the operands that change from tile to tile)
+            if (NT == 2) asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][ks]) : "v"(row), "n"(32 * ks));
+            else asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qreg[nt][ks]) : "v"(row), "n"(32 * ks));
+        }
     }
-    WaveStateWide w;
+    WideState<NT> w;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) w.acc[mi][v] = 0.f;
-    w.m = kMinusHuge;
-    w.l = 0.f;
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] = 0.f;
+        w.m[nt] = kMinusHuge;
+        w.l[nt] = 0.f;
+    }
 
     const int tok_first = wy * a.g.wh * a.g.W;
     const int tok_limit = min(a.g.slots, a.g.H * a.g.W - tok_first);
@@ -1509,7 +1572,8 @@ __global__ void __launch_bounds__(256, 2) attn_ring_wide_bf16(AttnArgs a) {
     // wavefront has left stage st - 1, whose ring slot takes stage st + 2.
     auto hand_over = [&](int st) {
         if (st + 1 >= n_stage) return;  // uniform
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (kWideRing == 4 && st + 2 < n_stage) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // (stage st + 2 stays in flight)
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         lds_barrier();
         if (st + kWideRing - 1 < n_stage) issue(st + kWideRing - 1);
     };
@@ -1518,76 +1582,98 @@ __global__ void __launch_bounds__(256, 2) attn_ring_wide_bf16(AttnArgs a) {
     u32x4 ka[8];
     auto full_stage = [&](int st, auto slot_tag) {
         constexpr int slot = decltype(slot_tag)::value, after = (slot + 1) % kWideRing;
-        auto mid = [&]() { hand_over(st); };
-        if (wave_live) wide_ring_tile<after * kStageWideBytes, false, slot * kStageWideBytes>(w, qreg, ka, kaddr, vaddr, 0, c_log2, lane, mid);
-        else mid();
+        // (a wavefront whose query slots all lie past the limit computes like the others, on the
+        // queries of token 0, and stores nothing: no branch around the tile, whose two sides the
+        // compiler would reconcile by moving the accumulators between register files every tile)
+        wide_ring_tile<NT, after * kStageWideBytes, false, slot * kStageWideBytes>(w, qreg, ka, kaddr, vaddr, 0, c_log2, lane, [&]() { hand_over(st); });
     };
 
     if (n_stage > 0) issue(0);
     if (n_stage > 1) issue(1);
-    if (n_stage > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    if (kWideRing == 4 && n_stage > 2) issue(2);
+    if (kWideRing == 4 && n_stage > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (n_stage > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();  // stage 0 has landed
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[ks]));  // the queries, older than stage 0, too
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {  // the queries, older than stage 0, have landed too
+            if (NT == 2) asm volatile("" : "+a"(qreg[nt][ks]));
+            else asm volatile("" : "+v"(qreg[nt][ks]));
+        }
     wide_load_k<0>(ka, kaddr);
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(ka[4]), "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7]));
     int st = 0;
-    for (; st + kWideRing - 1 < n_full; st += kWideRing) {
+    while (st < n_full) {  // (one copy of each ring slot's tile: the loop is left from wherever the full stages end)
         full_stage(st, std::integral_constant<int, 0>());
-        full_stage(st + 1, std::integral_constant<int, 1>());
-        full_stage(st + 2, std::integral_constant<int, 2>());
+        if (++st >= n_full) break;
+        full_stage(st, std::integral_constant<int, 1>());
+        if (++st >= n_full) break;
+        full_stage(st, std::integral_constant<int, 2>());
+        if (kWideRing == 4) {
+            if (++st >= n_full) break;
+            full_stage(st, std::integral_constant<int, 3 % kWideRing>());
+        }
+        ++st;
     }
-    if (st < n_full) { full_stage(st, std::integral_constant<int, 0>()); ++st; }
-    if (st < n_full) { full_stage(st, std::integral_constant<int, 1>()); ++st; }
-    if (st < n_stage && wave_live) {  // the partial stage that ends the window (its K operands are in ka)
+    if (st < n_stage) {  // the partial stage that ends the window (its K operands are in ka)
         const unsigned at = (st % kWideRing) * kStageWideBytes;
         const unsigned vlast[4] = {vaddr[0] + at, vaddr[1] + at, vaddr[2] + at, vaddr[3] + at};
-        wide_ring_tile<-1, true, 0>(w, qreg, ka, kaddr, vlast, tok_limit - st * kStageWide, c_log2, lane, [] {});
+        wide_ring_tile<NT, -1, true, 0>(w, qreg, ka, kaddr, vlast, tok_limit - st * kStageWide, c_log2, lane, [] {});
     }
     __syncthreads();  // every wavefront is done with the ring: reuse it as staging
     if (!wave_live) return;
 
-    float lo, hi;
-    pair_values(w.l, &lo, &hi);
-    const float inv = __builtin_amdgcn_rcpf(lo + hi);
-    if (O_BF16) {
-        unsigned char *stage = smem + wave * kTileWideBytes;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x16 &x = w.acc[mi];
-                u32x2 pk = {pack_bf16x2(x[4 * q4] * inv, x[4 * q4 + 1] * inv),
-                            pack_bf16x2(x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv)};
-                *(u32x2 *)(stage + wide_off_row(li, 4 * mi + q4) + 8 * g) = pk;
-            }
-        __bf16 *op = (__bf16 *)a.o.ptr + obase;
-        const int orow = lane >> 4, ochunk = lane & 15;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int row = 4 * r + orow, slot = q0 + row;
-            const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
-            const u32x4 val = *(const u32x4 *)(stage + wide_off_row(row, ochunk));
-            if (tok >= 0) *(u32x4 *)(op + (long long)tok * a.o.sn + ochunk * 8) = val;
-        }
-    } else {
-        float *op = (float *)a.o.ptr + obase;
-        const int slot = q0 + li;
-        const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
-        if (tok >= 0) {
+    for (int nt = 0; nt < NT; ++nt) {
+        float lo, hi;
+        pair_values(w.l[nt], &lo, &hi);
+        const float inv = __builtin_amdgcn_rcpf(lo + hi);
+        const int qb = q0 + 32 * nt;
+        if (O_BF16) {
+            // channel-major accumulators -> token rows of 256 bytes through 8 KB of wave-private LDS
+            unsigned char *stage = smem + wave * kTileWideBytes;
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    const f32x16 &x = w.acc[mi];
-                    f32x4 val = {x[4 * q4] * inv, x[4 * q4 + 1] * inv, x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv};
-                    *(f32x4 *)(op + (long long)tok * a.o.sn + 32 * mi + 8 * q4 + 4 * g) = val;
+                    const f32x16 &x = w.acc[mi][nt];
+                    u32x2 pk = {pack_bf16x2(x[4 * q4] * inv, x[4 * q4 + 1] * inv),
+                                pack_bf16x2(x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv)};
+                    *(u32x2 *)(stage + wide_off_row(li, 4 * mi + q4) + 8 * g) = pk;
                 }
+            __bf16 *op = (__bf16 *)a.o.ptr + obase;
+            const int orow = lane >> 4, ochunk = lane & 15;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int row = 4 * r + orow, slot = qb + row;
+                const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
+                const u32x4 val = *(const u32x4 *)(stage + wide_off_row(row, ochunk));
+                if (tok >= 0) *(u32x4 *)(op + (long long)tok * a.o.sn + ochunk * 8) = val;
+            }
+        } else {
+            float *op = (float *)a.o.ptr + obase;
+            const int slot = qb + li;
+            const int tok = slot < a.q_slots ? slot_token(a, wy, wx, slot) : -1;
+            if (tok >= 0) {
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x16 &x = w.acc[mi][nt];
+                        f32x4 val = {x[4 * q4] * inv, x[4 * q4 + 1] * inv, x[4 * q4 + 2] * inv, x[4 * q4 + 3] * inv};
+                        *(f32x4 *)(op + (long long)tok * a.o.sn + 32 * mi + 8 * q4 + 4 * g) = val;
+                    }
+            }
         }
     }
 }
+
+#ifndef JV_WIDE_NT
+#define JV_WIDE_NT 1  // blocks of 32 query columns per wavefront of the wide ring kernel
+#endif
 
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_slots, hipStream_t stream) {
     AttnArgs a;
@@ -1599,14 +1685,16 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     a.c = scale * kLog2e;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
     if (pr.D == kHeadDimWide) {
-        dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
         // windows of whole grid rows with 32-bit byte offsets inside a (batch, head) slice: the ring kernel
         const long long wide_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
         if (a.contig && ((long long)pr.N + 2 * kStageWide) * wide_sn * 2 + 512 < (1ll << 31)) {
-            if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true>), grid, dim3(256), 0, stream, a);
-            else hipLaunchKernelGGL((attn_ring_wide_bf16<false>), grid, dim3(256), 0, stream, a);
+            constexpr int NT = JV_WIDE_NT;
+            dim3 ring_grid((a.q_slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
+            if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true, NT>), ring_grid, dim3(256), 0, stream, a);
+            else hipLaunchKernelGGL((attn_ring_wide_bf16<false, NT>), ring_grid, dim3(256), 0, stream, a);
             return launch_status("attn_ring_wide_bf16");
         }
+        dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
         if (pr.o_bf16) hipLaunchKernelGGL((attn_wide_bf16<true>), grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((attn_wide_bf16<false>), grid, dim3(256), 0, stream, a);
         return launch_status("attn_wide_bf16");
