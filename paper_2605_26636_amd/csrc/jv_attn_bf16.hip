@@ -1527,9 +1527,13 @@ __global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
         w.l[nt] = 0.f;
     }
 
-    const int tok_first = wy * a.g.wh * a.g.W;
-    const int tok_limit = min(a.g.slots, a.g.H * a.g.W - tok_first);
+    // Key slots that hold tokens.  Windows of whole grid rows: slot s is token tok_first + s.
+    // Unpadded windows whose width divides the stage: a stage is 32 / ww whole window rows, so
+    // slot s is token tok_first + (s / ww) W + s % ww and a stage is still a fixed step on.
+    const int tok_first = wy * a.g.wh * a.g.W + (a.contig ? 0 : wx * a.g.ww);
+    const int tok_limit = a.contig ? min(a.g.slots, a.g.H * a.g.W - tok_first) : a.g.slots;
     const int n_full = tok_limit / kStageWide, n_stage = (tok_limit + kStageWide - 1) / kStageWide;
+    const int stage_tokens = a.contig ? kStageWide : (kStageWide / a.g.ww) * a.g.W;
 
     // Loads.  A wavefront moves rows 8 * wave .. + 7 of every stage's K and V, four rows (1 KB of
     // LDS) per instruction: lane = 16 * (row in the group of four) + 16-byte slot of the LDS row,
@@ -1548,12 +1552,13 @@ __global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = 8 * wave + 4 * i + lrow;
+        const int row_tok = a.contig ? row : (row / a.g.ww) * a.g.W + row % a.g.ww;
         kpad[i] = 16u * (unsigned)(lslot ^ (row & 15));
         vpad[i] = 16u * (unsigned)((((lslot >> 2) ^ (row & 3)) << 2) | (lslot & 3));
-        kcur[i] = 2u * (unsigned)row * (unsigned)a.k.sn + kpad[i];
-        vcur[i] = 2u * (unsigned)row * (unsigned)a.v.sn + vpad[i];
+        kcur[i] = 2u * (unsigned)row_tok * (unsigned)a.k.sn + kpad[i];
+        vcur[i] = 2u * (unsigned)row_tok * (unsigned)a.v.sn + vpad[i];
     }
-    const unsigned kstep = 2u * kStageWide * (unsigned)a.k.sn, vstep = 2u * kStageWide * (unsigned)a.v.sn;
+    const unsigned kstep = 2u * (unsigned)stage_tokens * (unsigned)a.k.sn, vstep = 2u * (unsigned)stage_tokens * (unsigned)a.v.sn;
     auto issue = [&](int stage) {
         unsigned char *kt = smem + (stage % kWideRing) * kStageWideBytes, *vt = kt + kTileWideBytes;
 #pragma unroll
@@ -1671,6 +1676,9 @@ __global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
     }
 }
 
+#ifndef JV_WIDE_WINDOWS
+#define JV_WIDE_WINDOWS 1  // unpadded windows whose width divides 32 take the ring kernel too
+#endif
 #ifndef JV_WIDE_NT
 #define JV_WIDE_NT 1  // blocks of 32 query columns per wavefront of the wide ring kernel
 #endif
@@ -1687,7 +1695,9 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     if (pr.D == kHeadDimWide) {
         // windows of whole grid rows with 32-bit byte offsets inside a (batch, head) slice: the ring kernel
         const long long wide_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
-        if (a.contig && ((long long)pr.N + 2 * kStageWide) * wide_sn * 2 + 512 < (1ll << 31)) {
+        const bool whole_windows = g.H % g.wh == 0 && g.W % g.ww == 0 && kStageWide % g.ww == 0;
+        if ((a.contig || (JV_WIDE_WINDOWS && whole_windows)) &&
+            ((long long)pr.N + 2ll * kStageWide * g.W) * wide_sn * 2 + 512 < (1ll << 31)) {
             constexpr int NT = JV_WIDE_NT;
             dim3 ring_grid((a.q_slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
             if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true, NT>), ring_grid, dim3(256), 0, stream, a);
