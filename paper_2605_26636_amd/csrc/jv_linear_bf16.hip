@@ -82,20 +82,16 @@ constexpr int kStateLds = 4 * kWaveLds + 2 * 8 * kHeadDim * 4;
 // the block's convolution branch) to vsum[part][bh][64]; it falls out of the V operands.
 // KEEP_V: the apply pass reads V again (convolution branch), so V is loaded with the default
 // cache policy; K, and V otherwise, are read once and loaded as a stream.
-// wide: heads of 128 channels, handled as four 64 x 64 quadrants: `heads` then counts four
-// virtual heads per head, and virtual head 4h + 2i + j reduces channels 64i .. 64i+63 of K
-// against channels 64j .. 64j+63 of V of head h (S_ij = relu(K_i)^T V_j, z_i = sum relu(K_i)).
 template <bool VSUM, bool KEEP_V>
 __global__ void __launch_bounds__(256, 2)
 la_state_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restrict__ vsum,
-              int heads, int N, int chunk, int focus_p, int wide) {
+              int heads, int N, int chunk, int focus_p) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
-    const int bh = blockIdx.y, b = bh / heads, hv = bh % heads, part = blockIdx.x;
+    const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x;
     const int BH = gridDim.y;
-    const int h = wide ? hv >> 2 : hv, k_first = wide ? ((hv >> 1) & 1) * kHeadDim : 0, v_first = wide ? (hv & 1) * kHeadDim : 0;
-    const __bf16 *kp = (const __bf16 *)kt.ptr + b * kt.sb + h * kt.sh + k_first;
-    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh + v_first;
+    const __bf16 *kp = (const __bf16 *)kt.ptr + b * kt.sb + h * kt.sh;
+    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh;
     unsigned char *ktile = smem + wave * kWaveLds;
     unsigned char *vtile = ktile + 8192;
     const int n0 = part * chunk, n1 = min(N, n0 + chunk);
@@ -516,13 +512,13 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
     const bool dynamic = dwc.mode == JV_DWC_SQUEEZE_DYNAMIC;
     if (dynamic)
         hipLaunchKernelGGL((la_state_bf16<true, true>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p, 0);
+                           pr.k, pr.v, ws, ws + dwc.vsum_off, pr.heads, pr.N, plan.chunk, focus_p);
     else if (dwc.mode != JV_DWC_NONE)
         hipLaunchKernelGGL((la_state_bf16<false, true>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p, 0);
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
     else
         hipLaunchKernelGGL((la_state_bf16<false, false>), dim3(plan.n_split, BH), dim3(256), kStateLds, stream,
-                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p, 0);
+                           pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, focus_p);
     if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
     const float *states = ws;
     int n_part = plan.n_split;
@@ -674,8 +670,116 @@ la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states,
     }
 }
 
+// State pass for heads of 128 channels: S = relu(K)^T V (128 x 128) and z = sum relu(K) of one
+// token chunk, K and V read once.  The workgroup's four wavefronts share tiles of 64 tokens in
+// LDS -- K (rectified) and V, each as two half tiles of 64 channels in the tile_off_tr layout --
+// and wavefront 2i + j accumulates the quadrant S_ij = relu(K_i)^T V_j (channels 64i .. 64i+63
+// of K against 64j .. 64j+63 of V) exactly as la_state_bf16 accumulates its one state, and z_i.
+// Two tile buffers: the next tile is fetched into registers while this one is reduced, and
+// stored after it; one barrier per tile.  The quadrants are written as four states of
+// kStateFloats floats, quadrant 2i + j of (batch, head) bh at index 4 bh + 2i + j of `part`.
+// grid (n_split, B*heads), 256 threads, kStateWideLds bytes of dynamic LDS.
+constexpr int kStateWideLds = 2 * 4 * 8192;
+
+__global__ void __launch_bounds__(256, 2)
+la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int N, int chunk) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x;
+    const int BH = gridDim.y;
+    const __bf16 *kp = (const __bf16 *)kt.ptr + b * kt.sb + h * kt.sh;
+    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh;
+    const int n0 = part * chunk, n1 = min(N, n0 + chunk);
+    // loads: 16 threads per token row (one 16-byte chunk each), 16 rows per pass, 4 passes per tile
+    const int lrow = tid >> 4, lchunk = tid & 15;
+    const int qi = wave >> 1, qj = wave & 1;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    float zacc[2] = {0.f, 0.f};
+
+    u32x4 kreg[4], vreg[4];
+    auto fetch = [&](int t0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int n = t0 + r * 16 + lrow;
+            u32x4 zero = {0u, 0u, 0u, 0u};
+            kreg[r] = zero;
+            vreg[r] = zero;
+            if (n < n1) {
+                kreg[r] = ld_stream((const u32x4 *)(kp + (long long)n * kt.sn + lchunk * 8));
+                vreg[r] = ld_stream((const u32x4 *)(vp + (long long)n * vt.sn + lchunk * 8));
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+        unsigned char *kt0 = smem + buf * 32768 + (lchunk >> 3) * 8192, *vt0 = kt0 + 16384;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const unsigned off = tile_off_tr(r * 16 + lrow, lchunk & 7);
+            *(u32x4 *)(kt0 + off) = relu_bf16x8(kreg[r]);
+            *(u32x4 *)(vt0 + off) = vreg[r];
+        }
+    };
+
+    int buf = 0;
+    if (n0 < n1) fetch(n0);
+    for (int t = n0; t < n1; t += 64) {
+        stash(buf);
+        __syncthreads();
+        if (t + 64 < n1) fetch(t + 64);
+        const unsigned char *ktile = smem + buf * 32768 + qi * 8192;
+        const unsigned char *vtile = smem + buf * 32768 + 16384 + qj * 8192;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 a[2], bv[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[i] = load_tr_operand(ktile, 16 * ks, i, lane);
+                bv[i] = load_tr_operand(vtile, 16 * ks, i, lane);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                u32x4 au = as_u32x4(a[mi]);
+#pragma unroll
+                for (int w = 0; w < 4; ++w) zacc[mi] = add_bf16x2(au[w], zacc[mi]);
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = mfma32(a[mi], bv[ni], acc[mi][ni]);
+            }
+        }
+        buf ^= 1;
+    }
+
+    // St[c2][c1] (c2: channel of V_j, c1: channel of K_i), then z_i[c1]: straight from the registers
+    // (16 KB per wavefront, once per chunk).
+    float *out = ws + ((size_t)part * BH * 4 + (size_t)bh * 4 + wave) * kStateFloats;
+    const int g = lane >> 5, li = lane & 31;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int c2 = 32 * ni + li, c1 = 32 * mi + 8 * q4 + 4 * g;
+                f32x4 val = {acc[mi][ni][4 * q4], acc[mi][ni][4 * q4 + 1], acc[mi][ni][4 * q4 + 2],
+                             acc[mi][ni][4 * q4 + 3]};
+                *(f32x4 *)(out + c2 * kHeadDim + c1) = val;
+            }
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+        float lo, hi;
+        pair_values(zacc[mi], &lo, &hi);  // the two halves of the tokens
+        if (g == 0) out[kHeadDim * kHeadDim + 32 * mi + li] = lo + hi;
+    }
+}
+
 LinearPlan plan_linear_wide(int B, int heads, int N) {
-    LinearPlan p = plan_linear(B, 4 * heads, N);
+    LinearPlan p = plan_linear(B, heads, N);
     p.combine = p.n_split > 1;  // the apply pass reads one state per quadrant
     return p;
 }
@@ -685,14 +789,14 @@ size_t linear_wide_workspace_floats(int B, int heads, int N) {
 
 jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream) {
     static LdsLimit lds_limit;
-    jv_status st = ensure_lds_limit(lds_limit, (const void *)la_state_bf16<false, false>, kStateLds);
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)la_state_wide_bf16, kStateWideLds);
     if (st != JV_OK) return st;
     const LinearPlan plan = plan_linear_wide(pr.B, pr.heads, pr.N);
-    const long long BHv = 4ll * pr.B * pr.heads;
+    const long long BHv = 4ll * pr.B * pr.heads;  // quadrant states
     if (BHv > 65535) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
-    hipLaunchKernelGGL((la_state_bf16<false, false>), dim3(plan.n_split, (unsigned)BHv), dim3(256), kStateLds, stream,
-                       pr.k, pr.v, ws, (float *)nullptr, 4 * pr.heads, pr.N, plan.chunk, 1, 1);
-    if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
+    hipLaunchKernelGGL(la_state_wide_bf16, dim3(plan.n_split, (unsigned)(pr.B * pr.heads)), dim3(256), kStateWideLds, stream,
+                       pr.k, pr.v, ws, pr.heads, pr.N, plan.chunk);
+    if ((st = launch_status("la_state_wide_bf16")) != JV_OK) return st;
     const float *states = ws;
     if (plan.combine) {
         float *dst = ws + (size_t)plan.n_split * BHv * kStateFloats;
