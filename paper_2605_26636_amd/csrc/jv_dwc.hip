@@ -257,21 +257,18 @@ __device__ inline float bf16_elem(const u32x4 &x, int e) {  // e = 0..7, compile
     return (e & 1) ? bf16_hi(x[e >> 1]) : bf16_lo(x[e >> 1]);
 }
 
-// o[b, n, c] = la[b, n, c] + sum_taps kappa[f][tap][c] * v[b, n + tap, c] on the H x W grid
-// behind P prefix tokens (prefix rows: o = la); kappa fp32, tap-major, one filter bank per
-// token (f = b*N + n: the token-wise variant) or per image (f = b, or 0 for one static bank:
-// filter_stride = C*k*k or 0).  Heads of 8 << dshift channels (dshift = 3: 64, 4: 128).  One
-// thread per token and 8 channels; total = B*N*C/8 threads.  la and o may be the same fp32
-// tensor (each element is read and written by one thread).
+// o[b, n, c] = la[b, n, c] + sum_taps kappa[b*N + n][tap][c] * v[b, n + tap, c] on the H x W
+// grid behind P prefix tokens (prefix rows: o = la); kappa fp32, tap-major.  One thread per
+// token and 8 channels; total = B*N*C/8 threads.  la and o may be the same fp32 tensor (each
+// element is read and written by one thread).
 template <int KS, bool O_BF16>
 __global__ void __launch_bounds__(256)
 dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const float *__restrict__ kappa,
-              int heads, int N, int P, int H, int W, long long total, int dshift, int per_token,
-              long long filter_stride) {
+              int heads, int N, int P, int H, int W, long long total) {
     constexpr int KK = KS * KS, PAD = KS / 2;
     const long long idx = blockIdx.x * 256ll + threadIdx.x;
     if (idx >= total) return;
-    const int groups = heads << dshift, cg = (int)(idx % groups), h = cg >> dshift, c8 = (cg & ((1 << dshift) - 1)) * 8;
+    const int groups = heads * 8, cg = (int)(idx % groups), h = cg >> 3, c8 = (cg & 7) * 8;
     const long long m = idx / groups;
     const int b = (int)(m / N), n = (int)(m % N);
     const float *lp = (const float *)la.ptr + b * la.sb + h * la.sh + (long long)n * la.sn + c8;
@@ -279,8 +276,8 @@ dwc_token_add(TensorArg vt, TensorArg la, TensorArg ot, const float *__restrict_
     float acc[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
     if (n >= P) {
         const int g = n - P, r = g / W, col = g - r * W;
-        const int C = heads << (dshift + 3);
-        const float *kp = kappa + (per_token ? (size_t)m * C * KK : (size_t)b * filter_stride) + cg * 8;  // 8 channels, tap 0
+        const int C = heads * kHeadDim;
+        const float *kp = kappa + (size_t)m * C * KK + cg * 8;  // this thread's 8 channels, tap 0
         const unsigned short *vp = (const unsigned short *)vt.ptr + b * vt.sb + h * vt.sh + c8;
 #pragma unroll
         for (int di = -PAD; di <= PAD; ++di)
@@ -316,7 +313,7 @@ template <int KS, bool O_BF16>
 static void launch_token_add(hipStream_t stream, const Problem &pr, const TensorArg &la,
                              const float *kappa, long long total) {
     hipLaunchKernelGGL((dwc_token_add<KS, O_BF16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                       stream, pr.v, la, pr.o, kappa, pr.heads, pr.N, pr.P, pr.H, pr.W, total, 3, 1, 0ll);
+                       stream, pr.v, la, pr.o, kappa, pr.heads, pr.N, pr.P, pr.H, pr.W, total);
 }
 
 jv_status token_dwc_forward(const Problem &pr, const TensorArg &la, const DwcPlan &dwc, float *ws,
@@ -444,24 +441,23 @@ jv_status token_dwc_forward_f32(const Problem &pr, const DwcPlan &dwc, float *ws
 }
 
 // ---------------------------------------------------------------------------------------
-// The convolution branch for heads of 128 channels (bf16 tensors): the generic route -- linear
-// attention into an fp32 tensor, the token sums of V by a pass of their own, the generator's
-// two small kernels, the filters turned tap-major, then dwc_token_add with one filter bank per
-// image.  (The 64-channel kernels fuse all of this into the two streaming passes.)
+// The convolution branch for heads of 128 channels (bf16 tensors).  The apply pass of linear
+// attention adds the convolution itself (la_apply_wide_bf16); what is left here are the filters
+// of the squeeze-dynamic mode: the token sums of V by a pass of their own, then the
+// generator's two small kernels.
 // ---------------------------------------------------------------------------------------
 
-// vsum[part][b][head*D + c] = sum of v over the tokens of chunk `part`; D = 8 << dshift channels
-// per head.  grid (n_part, B*heads), 256 threads: a row is 1 << dshift lanes of 8 channels.
+// vsum[part][b][head*128 + c] = sum of v over the tokens of chunk `part` (heads of 128 channels).
+// grid (n_part, B*heads), 256 threads: a row is 16 threads of 8 channels, 16 rows per pass.
 __global__ void __launch_bounds__(256)
-v_sum_bf16(TensorArg vt, float *__restrict__ vsum, int heads, int N, int chunk, int dshift) {
+v_sum_bf16(TensorArg vt, float *__restrict__ vsum, int heads, int N, int chunk) {
     __shared__ float red[256][8];
     const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x, BH = gridDim.y;
     const unsigned short *vp = (const unsigned short *)vt.ptr + b * vt.sb + h * vt.sh;
-    const int per_row = 1 << dshift, piece = threadIdx.x & (per_row - 1), rg = threadIdx.x >> dshift;
-    const int rows_per_pass = 256 >> dshift;
+    const int piece = threadIdx.x & 15, rg = threadIdx.x >> 4;
     const int n0 = part * chunk, n1 = min(N, n0 + chunk);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int n = n0 + rg; n < n1; n += rows_per_pass) {
+    for (int n = n0 + rg; n < n1; n += 16) {
         const u32x4 x = *(const u32x4 *)(vp + (long long)n * vt.sn + piece * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] += bf16_elem(x, e);
@@ -469,31 +465,18 @@ v_sum_bf16(TensorArg vt, float *__restrict__ vsum, int heads, int N, int chunk, 
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[threadIdx.x][e] = acc[e];
     __syncthreads();
-    const int D = 8 << dshift;
-    if (threadIdx.x < D) {  // channel c: element c % 8 of piece c / 8, summed over the row groups in order
+    if (threadIdx.x < kHeadDimWide) {  // channel c: element c % 8 of piece c / 8, summed over the row groups in order
         const int c = threadIdx.x;
         float s = 0.f;
-        for (int r = 0; r < rows_per_pass; ++r) s += red[r * per_row + (c >> 3)][c & 7];
-        vsum[((size_t)part * BH + bh) * D + c] = s;
+        for (int r = 0; r < 16; ++r) s += red[r * 16 + (c >> 3)][c & 7];
+        vsum[((size_t)part * BH + bh) * kHeadDimWide + c] = s;
     }
-}
-
-// dst[f][tap][c] = src[f][c][tap]: filter banks from the generator's (and the caller's) channel-major
-// order to tap-major.  One thread per element; total = banks * C * kk.
-__global__ void __launch_bounds__(256)
-filters_tap_major(const float *__restrict__ src, float *__restrict__ dst, int C, int kk, long long total) {
-    const long long i = blockIdx.x * 256ll + threadIdx.x;
-    if (i >= total) return;
-    const long long f = i / ((long long)C * kk);
-    const int r = (int)(i - f * C * kk), tap = r / C, c = r - tap * C;
-    dst[i] = src[f * C * kk + (long long)c * kk + tap];
 }
 
 static size_t wide_vsum_parts(int N) { return (size_t)(N + 2047) / 2048; }
 
 // Workspace of the wide-head block beyond the linear-attention states (float offsets from
-// `base`): the fp32 attention term, the partial token sums of V, the generator's hidden layer,
-// the filters as generated and tap-major.
+// `base`): the partial token sums of V, the generator's hidden layer, the generated filters.
 jv_status plan_dwc_wide(const jv_dwc_params *dwc, size_t base, int B, int heads, int N, DwcPlan *out) {
     DwcPlan p;
     // parameter validation as for 64-channel heads (C = 2 * heads * 64 channels)
@@ -503,59 +486,33 @@ jv_status plan_dwc_wide(const jv_dwc_params *dwc, size_t base, int B, int heads,
         return fail(JV_ERR_UNSUPPORTED, "head_dim 128: token-wise filters are built for 64-channel heads");
     base = align64f(base);
     p.total_floats = base;
-    if (p.mode == JV_DWC_NONE) {
-        *out = p;
-        return JV_OK;
+    if (p.mode == JV_DWC_SQUEEZE_DYNAMIC) {
+        const size_t C = (size_t)heads * kHeadDimWide, kk = (size_t)p.ksize * p.ksize;
+        p.vsum_off = base;
+        p.hidden_off = p.vsum_off + align64f(wide_vsum_parts(N) * B * C);
+        p.kappa_off = p.hidden_off + align64f((size_t)B * (p.hidden > 0 ? p.hidden : 1));
+        p.total_floats = p.kappa_off + align64f((size_t)B * C * kk);
     }
-    const size_t C = (size_t)heads * kHeadDimWide, kk = (size_t)p.ksize * p.ksize, M = (size_t)B * N;
-    p.la_off = base;
-    p.vsum_off = p.la_off + align64f(M * C);
-    p.hidden_off = p.vsum_off + align64f(wide_vsum_parts(N) * B * C);
-    p.kappa_off = p.hidden_off + align64f((size_t)B * (p.hidden > 0 ? p.hidden : 1));
-    p.tok_kappa_off = p.kappa_off + align64f((size_t)B * C * kk);   // the tap-major copy
-    p.total_floats = p.tok_kappa_off + align64f((size_t)B * C * kk);
     *out = p;
     return JV_OK;
 }
 
-// o = la + DWC(v) for heads of 128 channels; la = the fp32 attention term at ws + dwc.la_off.
-jv_status dwc_wide_forward(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream) {
-    const int C = pr.heads * kHeadDimWide, kk = dwc.ksize * dwc.ksize;
-    const long long M = (long long)pr.B * pr.N, total = M * (C / 8);
-    if (total / 256 >= (1ll << 31) - 1) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: too many tokens");
-    jv_status st;
-    const float *filters = dwc.static_kernel;
-    long long banks = 1, filter_stride = 0;
+// The filters the apply pass adds for heads of 128 channels: the static bank as it is, or the
+// bank generated per image from the token mean of V.
+jv_status dwc_wide_filters(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream, DwcArg *out) {
+    DwcArg arg = {dwc.static_kernel, 0, pr.H, pr.W, pr.P};
     if (dwc.mode == JV_DWC_SQUEEZE_DYNAMIC) {
         const int n_part = (int)wide_vsum_parts(pr.N);
         hipLaunchKernelGGL(v_sum_bf16, dim3(n_part, pr.B * pr.heads), dim3(256), 0, stream, pr.v,
-                           ws + dwc.vsum_off, pr.heads, pr.N, 2048, 4);
-        if ((st = launch_status("v_sum_bf16")) != JV_OK) return st;
+                           ws + dwc.vsum_off, pr.heads, pr.N, 2048);
+        jv_status st = launch_status("v_sum_bf16");
+        if (st != JV_OK) return st;
         if ((st = squeeze_generate(dwc, ws, n_part, pr.B, 2 * pr.heads, pr.N, stream)) != JV_OK) return st;
-        filters = ws + dwc.kappa_off;
-        banks = pr.B;
-        filter_stride = (long long)C * kk;
+        arg.kappa = ws + dwc.kappa_off;
+        arg.kappa_sb = (long long)pr.heads * kHeadDimWide * dwc.ksize * dwc.ksize;
     }
-    float *tap_major = ws + dwc.tok_kappa_off;
-    const long long n_filter = banks * C * kk;
-    hipLaunchKernelGGL(filters_tap_major, dim3((unsigned)((n_filter + 255) / 256)), dim3(256), 0, stream, filters,
-                       tap_major, C, kk, n_filter);
-    if ((st = launch_status("filters_tap_major")) != JV_OK) return st;
-    const TensorArg la = {ws + dwc.la_off, (long long)pr.N * C, kHeadDimWide, C};
-    auto launch = [&](auto ks_tag, auto bf_tag) {
-        constexpr int KS = decltype(ks_tag)::value;
-        constexpr bool O_BF16 = decltype(bf_tag)::value;
-        hipLaunchKernelGGL((dwc_token_add<KS, O_BF16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                           pr.v, la, pr.o, tap_major, pr.heads, pr.N, pr.P, pr.H, pr.W, total, 4, 0, filter_stride);
-    };
-    if (dwc.ksize == 3) {
-        if (pr.o_bf16) launch(std::integral_constant<int, 3>(), std::true_type());
-        else launch(std::integral_constant<int, 3>(), std::false_type());
-    } else {
-        if (pr.o_bf16) launch(std::integral_constant<int, 5>(), std::true_type());
-        else launch(std::integral_constant<int, 5>(), std::false_type());
-    }
-    return launch_status("dwc_token_add");
+    *out = arg;
+    return JV_OK;
 }
 
 jv_status vsum_f32_launch(const Problem &pr, const LinearPlan &plan, float *vsum, hipStream_t stream) {

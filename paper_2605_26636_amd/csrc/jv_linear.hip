@@ -186,13 +186,9 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
             return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
         float *ws = (float *)workspace;
         if (cv.mode == JV_DWC_NONE) return linear_wide_bf16(pr, eps, ws, stream);
-        // the attention term in fp32, then the convolution added and the sum rounded once
-        Problem la = pr;
-        const long long C = (long long)pr.heads * kHeadDimWide;
-        la.o = {ws + cv.la_off, (long long)pr.N * C, kHeadDimWide, C};
-        la.o_bf16 = false;
-        if ((st = linear_wide_bf16(la, eps, ws, stream)) != JV_OK) return st;
-        return dwc_wide_forward(pr, cv, ws, stream);
+        DwcArg arg;
+        if ((st = dwc_wide_filters(pr, cv, ws, stream, &arg)) != JV_OK) return st;
+        return linear_wide_bf16(pr, eps, ws, stream, cv.ksize, &arg);
     }
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;

@@ -551,22 +551,30 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
 }
 
 // ---------------------------------------------------------------------------------------
-// head_dim 128.  The state pass is la_state_bf16 over four quadrants per head (see there);
-// la_combine sums the partial quadrant states; this is the apply pass:
+// head_dim 128.  la_state_wide_bf16 (below) leaves four 64 x 64 quadrant states per head,
+// la_combine sums the partial ones; this is the apply pass:
 //   o[c2] = sum_i relu(q_i) S_ij[:, c2] / (sum_i relu(q_i) . z_i + eps),   j = c2 / 64,
 // q_i the two 64-channel halves of a query row.  A workgroup streams one token chunk of one
 // (batch, head); its four wavefronts own the four 32-channel quarters of the output, each with
 // the matching rows of S_0j^T and S_1j^T as bf16 high + low operands in registers (what a
 // wavefront of the 64-channel kernel holds for its 64 output channels), and all four run over
 // the same 64-token query tile in LDS; the denominator is one more row block, as there.
+// KS = 3 or 5: the block's convolution branch is added before the store, as in la_apply_bf16:
+// the normalised tile is staged as fp32 (512-byte token rows, the 16-byte chunk index rotated
+// by the row), and the thread that stores 8 channels of 4 consecutive tokens first adds
+// sum_taps kappa[c][tap] * V[token + tap][c] for them; the sum is rounded once.
 // grid (n_chunks * B*heads), 256 threads.
 // ---------------------------------------------------------------------------------------
-template <bool O_BF16>
+template <bool O_BF16, int KS>
 __global__ void __launch_bounds__(256, 2)
 la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states, int heads, int N,
-                   int tokens_per_wg, int n_chunks, float eps) {
-    __shared__ __align__(16) unsigned char smem[2 * 16384];  // query tile, output tile: [64 tokens][256 B]
+                   int tokens_per_wg, int n_chunks, float eps, TensorArg vt, DwcArg cv) {
+    // query tile [64 tokens][256 B]; output tile (bf16 rows of 256 B, or fp32 rows of 512 B with
+    // the convolution); the filters as [tap][channel]
+    constexpr int kOutBytes = KS ? 32768 : 16384;
+    __shared__ __align__(16) unsigned char smem[16384 + kOutBytes + KS * KS * kHeadDimWide * 4];
     unsigned char *qtile = smem, *otile = smem + 16384;
+    float *kap = (float *)(smem + 16384 + kOutBytes);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
     const int bh = blockIdx.x / n_chunks, b = bh / heads, h = bh % heads;
     const __bf16 *qp = (const __bf16 *)qt.ptr + b * qt.sb + h * qt.sh;
@@ -584,6 +592,10 @@ la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states,
         }
     };
     fetch(n0);
+    if (KS) {  // (read after the first barrier of the token loop)
+        const float *kbase = cv.kappa + b * cv.kappa_sb + (size_t)h * kHeadDimWide * KS * KS;
+        for (int e = tid; e < kHeadDimWide * KS * KS; e += 256) kap[(e % (KS * KS)) * kHeadDimWide + e / (KS * KS)] = kbase[e];
+    }
 
     // A operands: rows c2 of S_ij^T (this wavefront's quarter), k-slots c1 = 16 ks + 8 g + (0..7).
     const int j = wave >> 1, c2 = 32 * (wave & 1) + li;
@@ -612,6 +624,7 @@ la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states,
         }
     }
 
+    const __bf16 *vp = (const __bf16 *)vt.ptr + b * vt.sb + h * vt.sh;
     for (int t = n0; t < n1; t += 64) {
         __syncthreads();  // the previous tile has been read, and its output rows stored
 #pragma unroll
@@ -638,7 +651,14 @@ la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states,
             float den_lo, den_hi;
             pair_values(accz[0] + accz[1], &den_lo, &den_hi);
             const float inv = __builtin_amdgcn_rcpf(den_lo + eps);
-            if (O_BF16) {
+            if (KS) {
+                const int row = 32 * nt + li;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 val = {acc[4 * q4] * inv, acc[4 * q4 + 1] * inv, acc[4 * q4 + 2] * inv, acc[4 * q4 + 3] * inv};
+                    *(f32x4 *)(otile + row * 512 + (((8 * wave + 2 * q4 + g) ^ (row & 15)) << 4)) = val;
+                }
+            } else if (O_BF16) {
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     u32x2 pk = {pack_bf16x2(acc[4 * q4] * inv, acc[4 * q4 + 1] * inv),
@@ -657,7 +677,84 @@ la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states,
                 }
             }
         }
-        if (O_BF16) {
+        if (KS) {
+            __syncthreads();  // the four quarters of every row are in the output tile
+            // This thread finishes channels 8 fchunk .. + 7 of tokens tok0 .. tok0 + 3: the taps of
+            // neighbouring tokens overlap, so one tap row needs 4 + KS - 1 loads instead of 4 * KS.
+            // Out-of-grid taps (and tokens past the end of the range) read a valid row with
+            // weight zero, so the loads of a tap row are all in flight at once.
+            constexpr int kPad = KS / 2, kSpan = 4 + KS - 1;
+            const int tok0 = t + 4 * frow, last = n1 - 1;
+            float sum[4][8];
+            int gr[4], gc[4];
+            bool on_grid[4];  // prefix tokens (grid index below zero) get no convolution term
+            {
+                const int g0 = min(tok0, last) - cv.P;  // grid index of the thread's first token
+                const int base = max(g0, 0);
+                int r0 = base / cv.W, c0 = base - r0 * cv.W;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int orow = 4 * frow + r;
+                    const f32x4 o0 = *(const f32x4 *)(otile + orow * 512 + (((2 * fchunk) ^ (orow & 15)) << 4));
+                    const f32x4 o1 = *(const f32x4 *)(otile + orow * 512 + (((2 * fchunk + 1) ^ (orow & 15)) << 4));
+                    sum[r][0] = o0[0]; sum[r][1] = o0[1]; sum[r][2] = o0[2]; sum[r][3] = o0[3];
+                    sum[r][4] = o1[0]; sum[r][5] = o1[1]; sum[r][6] = o1[2]; sum[r][7] = o1[3];
+                    gr[r] = r0;
+                    gc[r] = c0;
+                    on_grid[r] = g0 + r >= 0;
+                    if (on_grid[r] && ++c0 == cv.W) { c0 = 0; ++r0; }
+                }
+            }
+#pragma unroll 1
+            for (int di = -kPad; di <= kPad; ++di) {
+                u32x4 vv[kSpan];
+#pragma unroll
+                for (int jj = 0; jj < kSpan; ++jj) {
+                    const int src = tok0 + jj - kPad + di * cv.W;  // token of column jj in this tap row
+                    const int safe = min(max(src, 0), N - 1);
+                    vv[jj] = *(const u32x4 *)(vp + (long long)safe * vt.sn + fchunk * 8);
+                }
+                const float *krow = kap + (di + kPad) * KS * kHeadDimWide + 8 * fchunk;
+#pragma unroll
+                for (int dj = -kPad; dj <= kPad; ++dj) {
+                    const f32x4 k0 = *(const f32x4 *)(krow + (dj + kPad) * kHeadDimWide);
+                    const f32x4 k1 = *(const f32x4 *)(krow + (dj + kPad) * kHeadDimWide + 4);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const bool ok = tok0 + r <= last && on_grid[r] && (unsigned)(gr[r] + di) < (unsigned)cv.H &&
+                                        (unsigned)(gc[r] + dj) < (unsigned)cv.W;
+                        const float m = ok ? 1.0f : 0.0f;
+                        const u32x4 x = vv[r + dj + kPad];
+                        sum[r][0] = fmaf(k0[0] * m, bf16_lo(x[0]), sum[r][0]);
+                        sum[r][1] = fmaf(k0[1] * m, bf16_hi(x[0]), sum[r][1]);
+                        sum[r][2] = fmaf(k0[2] * m, bf16_lo(x[1]), sum[r][2]);
+                        sum[r][3] = fmaf(k0[3] * m, bf16_hi(x[1]), sum[r][3]);
+                        sum[r][4] = fmaf(k1[0] * m, bf16_lo(x[2]), sum[r][4]);
+                        sum[r][5] = fmaf(k1[1] * m, bf16_hi(x[2]), sum[r][5]);
+                        sum[r][6] = fmaf(k1[2] * m, bf16_lo(x[3]), sum[r][6]);
+                        sum[r][7] = fmaf(k1[3] * m, bf16_hi(x[3]), sum[r][7]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int on = tok0 + r;
+                if (on <= last) {
+                    if (O_BF16) {
+                        __bf16 *op = (__bf16 *)ot.ptr + b * ot.sb + h * ot.sh;
+                        u32x4 pk = {pack_bf16x2(sum[r][0], sum[r][1]), pack_bf16x2(sum[r][2], sum[r][3]),
+                                    pack_bf16x2(sum[r][4], sum[r][5]), pack_bf16x2(sum[r][6], sum[r][7])};
+                        st_stream((u32x4 *)(op + (long long)on * ot.sn + fchunk * 8), pk);
+                    } else {
+                        float *op = (float *)ot.ptr + b * ot.sb + h * ot.sh + (long long)on * ot.sn + fchunk * 8;
+                        f32x4 s0 = {sum[r][0], sum[r][1], sum[r][2], sum[r][3]};
+                        f32x4 s1 = {sum[r][4], sum[r][5], sum[r][6], sum[r][7]};
+                        *(f32x4 *)op = s0;
+                        *(f32x4 *)(op + 4) = s1;
+                    }
+                }
+            }
+        } else if (O_BF16) {
             __syncthreads();  // the four quarters of every row are in the output tile
             __bf16 *op = (__bf16 *)ot.ptr + b * ot.sb + h * ot.sh;
 #pragma unroll
@@ -787,7 +884,8 @@ size_t linear_wide_workspace_floats(int B, int heads, int N) {
     return linear_workspace_floats(plan_linear_wide(B, heads, N), B, 4 * heads);
 }
 
-jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream) {
+jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream, int ksize,
+                           const DwcArg *cv) {
     static LdsLimit lds_limit;
     jv_status st = ensure_lds_limit(lds_limit, (const void *)la_state_wide_bf16, kStateWideLds);
     if (st != JV_OK) return st;
@@ -808,12 +906,23 @@ jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t 
     const int n_chunks = (pr.N + plan.apply_tokens - 1) / plan.apply_tokens;
     const long long n_wg = (long long)n_chunks * pr.B * pr.heads;
     if (n_wg >= (1ll << 31)) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: too many token chunks");
-    if (pr.o_bf16)
-        hipLaunchKernelGGL((la_apply_wide_bf16<true>), dim3((unsigned)n_wg), dim3(256), 0, stream, pr.q, pr.o, states,
-                           pr.heads, pr.N, plan.apply_tokens, n_chunks, eps);
-    else
-        hipLaunchKernelGGL((la_apply_wide_bf16<false>), dim3((unsigned)n_wg), dim3(256), 0, stream, pr.q, pr.o, states,
-                           pr.heads, pr.N, plan.apply_tokens, n_chunks, eps);
+    const DwcArg none = {nullptr, 0, pr.H, pr.W, pr.P};
+    auto launch = [&](auto bf_tag, auto ks_tag) {
+        constexpr bool O_BF16 = decltype(bf_tag)::value;
+        constexpr int KS = decltype(ks_tag)::value;
+        hipLaunchKernelGGL((la_apply_wide_bf16<O_BF16, KS>), dim3((unsigned)n_wg), dim3(256), 0, stream, pr.q, pr.o, states,
+                           pr.heads, pr.N, plan.apply_tokens, n_chunks, eps, pr.v, KS ? *cv : none);
+    };
+    const int ks = cv ? ksize : 0;
+    if (pr.o_bf16) {
+        if (ks == 0) launch(std::true_type(), std::integral_constant<int, 0>());
+        else if (ks == 3) launch(std::true_type(), std::integral_constant<int, 3>());
+        else launch(std::true_type(), std::integral_constant<int, 5>());
+    } else {
+        if (ks == 0) launch(std::false_type(), std::integral_constant<int, 0>());
+        else if (ks == 3) launch(std::false_type(), std::integral_constant<int, 3>());
+        else launch(std::false_type(), std::integral_constant<int, 5>());
+    }
     return launch_status("la_apply_wide_bf16");
 }
 
