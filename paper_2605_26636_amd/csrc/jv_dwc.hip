@@ -442,38 +442,9 @@ jv_status token_dwc_forward_f32(const Problem &pr, const DwcPlan &dwc, float *ws
 
 // ---------------------------------------------------------------------------------------
 // The convolution branch for heads of 128 channels (bf16 tensors).  The apply pass of linear
-// attention adds the convolution itself (la_apply_wide_bf16); what is left here are the filters
-// of the squeeze-dynamic mode: the token sums of V by a pass of their own, then the
-// generator's two small kernels.
+// attention adds the convolution itself (la_apply_wide_bf16) and the state pass leaves the
+// token sums of V; what is left here is the workspace plan and the generator's launch.
 // ---------------------------------------------------------------------------------------
-
-// vsum[part][b][head*128 + c] = sum of v over the tokens of chunk `part` (heads of 128 channels).
-// grid (n_part, B*heads), 256 threads: a row is 16 threads of 8 channels, 16 rows per pass.
-__global__ void __launch_bounds__(256)
-v_sum_bf16(TensorArg vt, float *__restrict__ vsum, int heads, int N, int chunk) {
-    __shared__ float red[256][8];
-    const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x, BH = gridDim.y;
-    const unsigned short *vp = (const unsigned short *)vt.ptr + b * vt.sb + h * vt.sh;
-    const int piece = threadIdx.x & 15, rg = threadIdx.x >> 4;
-    const int n0 = part * chunk, n1 = min(N, n0 + chunk);
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int n = n0 + rg; n < n1; n += 16) {
-        const u32x4 x = *(const u32x4 *)(vp + (long long)n * vt.sn + piece * 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += bf16_elem(x, e);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) red[threadIdx.x][e] = acc[e];
-    __syncthreads();
-    if (threadIdx.x < kHeadDimWide) {  // channel c: element c % 8 of piece c / 8, summed over the row groups in order
-        const int c = threadIdx.x;
-        float s = 0.f;
-        for (int r = 0; r < 16; ++r) s += red[r * 16 + (c >> 3)][c & 7];
-        vsum[((size_t)part * BH + bh) * kHeadDimWide + c] = s;
-    }
-}
-
-static size_t wide_vsum_parts(int N) { return (size_t)(N + 2047) / 2048; }
 
 // Workspace of the wide-head block beyond the linear-attention states (float offsets from
 // `base`): the partial token sums of V, the generator's hidden layer, the generated filters.
@@ -489,7 +460,7 @@ jv_status plan_dwc_wide(const jv_dwc_params *dwc, size_t base, int B, int heads,
     if (p.mode == JV_DWC_SQUEEZE_DYNAMIC) {
         const size_t C = (size_t)heads * kHeadDimWide, kk = (size_t)p.ksize * p.ksize;
         p.vsum_off = base;
-        p.hidden_off = p.vsum_off + align64f(wide_vsum_parts(N) * B * C);
+        p.hidden_off = p.vsum_off + align64f((size_t)plan_linear_wide(B, heads, N).n_split * B * C);
         p.kappa_off = p.hidden_off + align64f((size_t)B * (p.hidden > 0 ? p.hidden : 1));
         p.total_floats = p.kappa_off + align64f((size_t)B * C * kk);
     }
@@ -502,11 +473,8 @@ jv_status plan_dwc_wide(const jv_dwc_params *dwc, size_t base, int B, int heads,
 jv_status dwc_wide_filters(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream, DwcArg *out) {
     DwcArg arg = {dwc.static_kernel, 0, pr.H, pr.W, pr.P};
     if (dwc.mode == JV_DWC_SQUEEZE_DYNAMIC) {
-        const int n_part = (int)wide_vsum_parts(pr.N);
-        hipLaunchKernelGGL(v_sum_bf16, dim3(n_part, pr.B * pr.heads), dim3(256), 0, stream, pr.v,
-                           ws + dwc.vsum_off, pr.heads, pr.N, 2048);
-        jv_status st = launch_status("v_sum_bf16");
-        if (st != JV_OK) return st;
+        const int n_part = plan_linear_wide(pr.B, pr.heads, pr.N).n_split;  // the state pass's chunks
+        jv_status st;
         if ((st = squeeze_generate(dwc, ws, n_part, pr.B, 2 * pr.heads, pr.N, stream)) != JV_OK) return st;
         arg.kappa = ws + dwc.kappa_off;
         arg.kappa_sb = (long long)pr.heads * kHeadDimWide * dwc.ksize * dwc.ksize;

@@ -53,15 +53,19 @@ struct DwcArg {
 jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, float *ws,
                       const DwcPlan &dwc, int focus_p, hipStream_t stream);
 
-// head_dim 128 (bf16 tensors): workspace floats of the states, and the passes; with `cv` the apply
-// pass adds the block's convolution (filters of ksize x ksize taps).
+// head_dim 128 (bf16 tensors): launch plan and workspace floats of the states; the state pass
+// (with `vsum`, [n_split][B][C] floats, it also leaves the partial token sums of V), the apply
+// pass (with `cv` it adds the block's convolution, filters of ksize x ksize taps), and both.
+LinearPlan plan_linear_wide(int B, int heads, int N);
 size_t linear_wide_workspace_floats(int B, int heads, int N);
-jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream, int ksize = 0,
-                           const DwcArg *cv = nullptr);
+jv_status linear_wide_state(const Problem &pr, float *ws, float *vsum, hipStream_t stream);
+jv_status linear_wide_apply(const Problem &pr, float eps, float *ws, hipStream_t stream, int ksize, const DwcArg *cv);
+jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream);
 
 // head_dim 128: the block's convolution branch (static or squeeze-dynamic filters); `base` =
 // floats the linear-attention states take (linear_wide_workspace_floats).  dwc_wide_filters
-// launches what produces the filters and fills the argument of the apply pass.
+// runs the generator on the token sums the state pass left (squeeze-dynamic mode) and fills the
+// argument of the apply pass.
 jv_status plan_dwc_wide(const jv_dwc_params *dwc, size_t base, int B, int heads, int N, DwcPlan *out);
 jv_status dwc_wide_filters(const Problem &pr, const DwcPlan &dwc, float *ws, hipStream_t stream, DwcArg *out);
 

@@ -186,9 +186,11 @@ jv_status linear_block_forward(const Problem &pr, float eps, const jv_dwc_params
             return fail(JV_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
         float *ws = (float *)workspace;
         if (cv.mode == JV_DWC_NONE) return linear_wide_bf16(pr, eps, ws, stream);
+        float *vsum = cv.mode == JV_DWC_SQUEEZE_DYNAMIC ? ws + cv.vsum_off : nullptr;
+        if ((st = linear_wide_state(pr, ws, vsum, stream)) != JV_OK) return st;
         DwcArg arg;
         if ((st = dwc_wide_filters(pr, cv, ws, stream, &arg)) != JV_OK) return st;
-        return linear_wide_bf16(pr, eps, ws, stream, cv.ksize, &arg);
+        return linear_wide_apply(pr, eps, ws, stream, cv.ksize, &arg);
     }
     const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
     DwcPlan cv;

@@ -775,11 +775,16 @@ la_apply_wide_bf16(TensorArg qt, TensorArg ot, const float *__restrict__ states,
 // Two tile buffers: the next tile is fetched into registers while this one is reduced, and
 // stored after it; one barrier per tile.  The quadrants are written as four states of
 // kStateFloats floats, quadrant 2i + j of (batch, head) bh at index 4 bh + 2i + j of `part`.
+// VSUM: also write the chunk's token sum of V (the input of the dynamic-filter generator of the
+// block's convolution branch) to vsum[part][bh][128]; it falls out of the V operands of the
+// wavefronts with i = 0.
 // grid (n_split, B*heads), 256 threads, kStateWideLds bytes of dynamic LDS.
 constexpr int kStateWideLds = 2 * 4 * 8192;
 
+template <bool VSUM>
 __global__ void __launch_bounds__(256, 2)
-la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads, int N, int chunk) {
+la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__restrict__ vsum, int heads, int N,
+                   int chunk) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int bh = blockIdx.y, b = bh / heads, h = bh % heads, part = blockIdx.x;
@@ -798,7 +803,7 @@ la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    float zacc[2] = {0.f, 0.f};
+    float zacc[2] = {0.f, 0.f}, vacc[2] = {0.f, 0.f};
 
     u32x4 kreg[4], vreg[4];
     auto fetch = [&](int t0) {
@@ -848,6 +853,14 @@ la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = mfma32(a[mi], bv[ni], acc[mi][ni]);
             }
+            if (VSUM && qi == 0) {  // wave-uniform
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    u32x4 bu = as_u32x4(bv[ni]);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) vacc[ni] = add_bf16x2(bu[w], vacc[ni]);
+                }
+            }
         }
         buf ^= 1;
     }
@@ -873,6 +886,14 @@ la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, int heads
         pair_values(zacc[mi], &lo, &hi);  // the two halves of the tokens
         if (g == 0) out[kHeadDim * kHeadDim + 32 * mi + li] = lo + hi;
     }
+    if (VSUM && qi == 0) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            float lo, hi;
+            pair_values(vacc[ni], &lo, &hi);
+            if (g == 0) vsum[((size_t)part * BH + bh) * kHeadDimWide + kHeadDim * qj + 32 * ni + li] = lo + hi;
+        }
+    }
 }
 
 LinearPlan plan_linear_wide(int B, int heads, int N) {
@@ -884,17 +905,27 @@ size_t linear_wide_workspace_floats(int B, int heads, int N) {
     return linear_workspace_floats(plan_linear_wide(B, heads, N), B, 4 * heads);
 }
 
-jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream, int ksize,
-                           const DwcArg *cv) {
-    static LdsLimit lds_limit;
-    jv_status st = ensure_lds_limit(lds_limit, (const void *)la_state_wide_bf16, kStateWideLds);
+jv_status linear_wide_state(const Problem &pr, float *ws, float *vsum, hipStream_t stream) {
+    static LdsLimit lds_limit[2];
+    jv_status st = ensure_lds_limit(lds_limit[0], (const void *)la_state_wide_bf16<false>, kStateWideLds);
+    if (st == JV_OK) st = ensure_lds_limit(lds_limit[1], (const void *)la_state_wide_bf16<true>, kStateWideLds);
     if (st != JV_OK) return st;
     const LinearPlan plan = plan_linear_wide(pr.B, pr.heads, pr.N);
+    if (4ll * pr.B * pr.heads > 65535) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
+    const dim3 grid(plan.n_split, (unsigned)(pr.B * pr.heads));
+    if (vsum)
+        hipLaunchKernelGGL(la_state_wide_bf16<true>, grid, dim3(256), kStateWideLds, stream, pr.k, pr.v, ws, vsum,
+                           pr.heads, pr.N, plan.chunk);
+    else
+        hipLaunchKernelGGL(la_state_wide_bf16<false>, grid, dim3(256), kStateWideLds, stream, pr.k, pr.v, ws,
+                           (float *)nullptr, pr.heads, pr.N, plan.chunk);
+    return launch_status("la_state_wide_bf16");
+}
+
+jv_status linear_wide_apply(const Problem &pr, float eps, float *ws, hipStream_t stream, int ksize, const DwcArg *cv) {
+    jv_status st;
+    const LinearPlan plan = plan_linear_wide(pr.B, pr.heads, pr.N);
     const long long BHv = 4ll * pr.B * pr.heads;  // quadrant states
-    if (BHv > 65535) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
-    hipLaunchKernelGGL(la_state_wide_bf16, dim3(plan.n_split, (unsigned)(pr.B * pr.heads)), dim3(256), kStateWideLds, stream,
-                       pr.k, pr.v, ws, pr.heads, pr.N, plan.chunk);
-    if ((st = launch_status("la_state_wide_bf16")) != JV_OK) return st;
     const float *states = ws;
     if (plan.combine) {
         float *dst = ws + (size_t)plan.n_split * BHv * kStateFloats;
@@ -924,6 +955,11 @@ jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t 
         else launch(std::false_type(), std::integral_constant<int, 5>());
     }
     return launch_status("la_apply_wide_bf16");
+}
+
+jv_status linear_wide_bf16(const Problem &pr, float eps, float *ws, hipStream_t stream) {
+    jv_status st = linear_wide_state(pr, ws, nullptr, stream);
+    return st == JV_OK ? linear_wide_apply(pr, eps, ws, stream, 0, nullptr) : st;
 }
 
 }  // namespace jv
