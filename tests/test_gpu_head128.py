@@ -98,6 +98,16 @@ def test_prefix_tokens():
     check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref)
 
 
+def test_prefix_tokens_with_unpadded_windows():
+    """The same rule where the grid part runs on the ring kernel (windows that tile the grid, their
+    width a divisor of the 32-key stage) and the prefix queries on the query-slot limit."""
+    B, heads, P = 2, 2, 5
+    for H, W, window in [(8, 8, (4, 4)), (16, 32, (16, 16)), (6, 16, (3, 8))]:
+        q, k, v = synth.qkv(67, B, heads, P + H * W, D, 0.5, True)
+        ref = oracle.window_attn_prefix(q, k, v, P, H, W, *window)
+        check_bf16_pair(_window(q, k, v, H, W, window, torch.float32), _window(q, k, v, H, W, window), ref)
+
+
 def test_fused_projection_layout_and_rerun_bits():
     """Q, K, V as strided views of one [B, N, 3, heads, 128] buffer (the layout a fused QKV
     projection leaves), O as [B, N, heads, 128]; several launches give the same bits."""
@@ -118,6 +128,12 @@ def test_fused_projection_layout_and_rerun_bits():
         assert torch.equal(o, first)
     binding.jv_full_attn_fwd(*views, o, (H, W))
     assert torch.equal(o, _full(q, k, v, H, W))
+    binding.jv_window_attn_fwd(*views, o, (H, W), (4, 4))   # windows that tile the grid: the ring kernel
+    assert torch.equal(o, _window(q, k, v, H, W, (4, 4)))
+    first = o.clone()
+    for _ in range(4):
+        binding.jv_window_attn_fwd(*views, o, (H, W), (4, 4))
+        assert torch.equal(o, first)
 
 
 def test_vit_layer_size_elementwise():
