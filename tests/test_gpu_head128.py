@@ -62,6 +62,11 @@ def test_full_attention_small_shapes(B, heads, H, W, vscale):
     (1, 2, 18, 30, (6, 30), 1.0),     # windows spanning whole rows
     (1, 1, 40, 24, (24, 16), 0.5),    # 384-slot rectangular windows, ragged at the bottom
     (1, 1, 17, 40, (16, 16), 0.5),    # bottom windows hold one real row: seven stages of padding
+    (1, 2, 16, 64, (8, 32), 0.5),     # windows as wide as a key stage (one window row per stage)
+    (1, 1, 8, 8, (8, 2), 1.0),        # narrow windows: sixteen window rows per stage
+    (2, 1, 6, 5, (3, 1), 1.0),        # one-column windows of three tokens: less than a stage
+    (1, 1, 48, 4, (24, 4), 0.5),      # 96-slot windows: three stages exactly
+    (1, 1, 10, 8, (5, 8), 1.0),       # whole-row windows of 40 tokens: a stage and a quarter
 ])
 def test_window_attention_small_shapes(B, heads, H, W, window, vscale):
     q, k, v = synth.qkv(61, B, heads, H * W, D, vscale, True)
