@@ -1140,8 +1140,9 @@ static jv_status launch_window8(const AttnArgs &a, int BH, hipStream_t stream) {
 }
 
 // ---------------------------------------------------------------------------------------
-// head_dim 128 (the wide heads of the paper's largest backbones): one streaming kernel for
-// every geometry -- full attention, windows of any size, padded grids, a query-slot limit.
+// head_dim 128 (the wide heads of the paper's largest backbones): the streaming kernel that
+// handles every geometry -- windows of any size, padded grids, a query-slot limit (and full
+// attention; the launcher gives the geometries it can to attn_ring_wide_bf16, further down).
 // Same algorithm as above with one block of 32 query columns per wavefront (NT = 1): a
 // workgroup holds 128 consecutive query slots of one window (4 wavefronts x 32); the window's
 // keys pass through LDS in double-buffered stages of 32 (K rows, then V rows, 256 bytes each;
@@ -1337,8 +1338,10 @@ __global__ void __launch_bounds__(256, 2) attn_wide_bf16(AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// head_dim 128, windows that span whole grid rows (full attention above all): the ring design
-// of attn_ring_bf16 on 256-byte rows.  A workgroup holds 128 query slots (4 wavefronts x 32);
+// head_dim 128, windows whose key slots are a fixed-step walk through memory -- windows of whole
+// grid rows (full attention above all) and unpadded windows whose width divides the 32-key
+// stage (a stage is then 32 / ww whole window rows) --: the ring design of attn_ring_bf16 on
+// 256-byte rows.  A workgroup holds 128 query slots (4 wavefronts x 32);
 // the keys pass through a ring of three LDS stages of one tile each (32 keys: 8 KB of K rows,
 // 8 KB of V rows), filled from global memory straight into LDS two stages ahead (four load
 // instructions per stage and wavefront, one wait, one barrier).  Inside a tile: the eight

@@ -7,8 +7,6 @@
 //   pack_v_rows, dwc_token_add       (Tab. 1): the generator as two matrix products over all
 //                                    tokens, then every token's own filters on its neighbourhood
 //   token_hidden_f32, token_dwc_f32  the same variant for fp32 tensors, plain fp32 arithmetic
-#include <type_traits>
-
 #include "jv_linear.h"
 #include "jv_mfma.h"
 

@@ -9,6 +9,8 @@
 //   la_apply_bf16   sums the (few) partials, splits S and z into bf16 high and low parts held
 //                   in registers, and streams Q -> O:  O^T = S^T relu(Q)^T on the matrix
 //                   cores, the denominator relu(q).z as one more row block, fp32 divide.
+//   la_state_wide_bf16, la_apply_wide_bf16   the same two passes for heads of 128 channels: the
+//                   128 x 128 state as four 64 x 64 quadrants, one per wavefront of a workgroup.
 #include <type_traits>
 
 #include "jv_linear.h"
