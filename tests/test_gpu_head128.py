@@ -152,6 +152,24 @@ def test_vit_layer_size_elementwise():
     check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref)
 
 
+def test_long_sequences_sampled_rows():
+    """One image of 256 x 256 tokens (65 536): the state pass splits the tokens over many chunks,
+    window attention walks 256 windows per head through the ring; and full attention on 16 384
+    tokens (512 key stages).  Sampled rows against the oracle."""
+    B, heads, H, W = 1, 2, 256, 256
+    q, k, v = synth.qkv(68, B, heads, H * W, D, 0.125, True)
+    rows = synth.sample_rows(B, heads, H * W, 96, seed=5)
+    ref = oracle.linear_attn_rows(q, k, v, rows, 1e-6)
+    check_bf16_pair(_linear(q, k, v, H, W, torch.float32), _linear(q, k, v, H, W), ref, rows)
+    ref = oracle.window_attn_rows(q, k, v, H, W, 16, 16, rows)
+    check_bf16_pair(_window(q, k, v, H, W, (16, 16), torch.float32), _window(q, k, v, H, W, (16, 16)), ref, rows)
+    H = W = 128
+    q, k, v = synth.qkv(69, B, heads, H * W, D, 0.125, True)
+    rows = synth.sample_rows(B, heads, H * W, 96, seed=6)
+    ref = oracle.full_attn_rows(q, k, v, rows)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32), _full(q, k, v, H, W), ref, rows)
+
+
 def test_fp32_tensors_are_refused():
     q = torch.zeros(1, 1, 16, D, device="cuda")
     with pytest.raises(binding.JvError) as e:
