@@ -23,7 +23,10 @@ LinearPlan plan_linear(int B, int heads, int N) {
     chunk = ((chunk + 255) / 256) * 256;
     p.chunk = (int)chunk;
     p.n_split = (int)((N + chunk - 1) / chunk);
+    // token chunks of the apply pass: 1024 tokens, halved (down to 256) while that leaves less
+    // than two workgroups per compute unit
     p.apply_tokens = 1024;
+    while (p.apply_tokens > 256 && bh * ((N + p.apply_tokens - 1) / p.apply_tokens) < 512) p.apply_tokens /= 2;
     p.combine = p.n_split > 4;
     return p;
 }

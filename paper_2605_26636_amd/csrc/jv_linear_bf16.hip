@@ -901,6 +901,8 @@ la_state_wide_bf16(TensorArg kt, TensorArg vt, float *__restrict__ ws, float *__
 LinearPlan plan_linear_wide(int B, int heads, int N) {
     LinearPlan p = plan_linear(B, heads, N);
     p.combine = p.n_split > 1;  // the apply pass reads one state per quadrant
+    // (the token chunks of the apply pass follow from B * heads as in plan_linear; every workgroup
+    // loads its head's state once, 64 KB)
     return p;
 }
 size_t linear_wide_workspace_floats(int B, int heads, int N) {
