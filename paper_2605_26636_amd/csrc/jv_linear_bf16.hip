@@ -910,12 +910,12 @@ size_t linear_wide_workspace_floats(int B, int heads, int N) {
 }
 
 jv_status linear_wide_state(const Problem &pr, float *ws, float *vsum, hipStream_t stream) {
+    if (4ll * pr.B * pr.heads > 65535) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
     static LdsLimit lds_limit[2];
     jv_status st = ensure_lds_limit(lds_limit[0], (const void *)la_state_wide_bf16<false>, kStateWideLds);
     if (st == JV_OK) st = ensure_lds_limit(lds_limit[1], (const void *)la_state_wide_bf16<true>, kStateWideLds);
     if (st != JV_OK) return st;
     const LinearPlan plan = plan_linear_wide(pr.B, pr.heads, pr.N);
-    if (4ll * pr.B * pr.heads > 65535) return fail(JV_ERR_UNSUPPORTED, "head_dim 128: batch * heads above 16383");
     const dim3 grid(plan.n_split, (unsigned)(pr.B * pr.heads));
     if (vsum)
         hipLaunchKernelGGL(la_state_wide_bf16<true>, grid, dim3(256), kStateWideLds, stream, pr.k, pr.v, ws, vsum,

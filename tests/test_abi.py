@@ -127,6 +127,35 @@ def test_block_workspace_query_by_convolution_mode():
     assert binding.jv_linear_block_workspace_bytes(d, params(4)) == 0
 
 
+def test_block_workspace_query_for_wide_heads():
+    """The same query for heads of 128 channels (host only): four 64 x 64 quadrant states per head
+    and chunk plus their sums; static filters need nothing more, squeeze-dynamic filters the
+    partial token sums of V, the hidden layer and one filter bank per image; the token-wise
+    variant is not built for wide heads."""
+    B, heads, H, W = 2, 3, 40, 48
+    C, N, hidden, k = heads * 128, H * W, 32, 3
+    s = binding.JvStrides(heads * N * 128, N * 128, 128)
+    d = binding.JvAttnDesc(B, heads, H, W, 128, binding.JV_BF16, binding.JV_BF16, s, s, s, s, 0)
+    fake = ctypes.c_void_p(4096)
+
+    def params(mode, hid=hidden):
+        return binding.JvDwcParams(mode, k, hid, fake, fake, fake, fake, fake)
+
+    plain = binding.jv_linear_attn_workspace_bytes(d)
+    state = 4 * (64 * 64 + 64)                      # one quadrant state, bytes
+    assert plain >= 2 * 4 * B * heads * state        # at least one partial and the sum, four quadrants each
+    assert plain % (4 * B * heads * state) == 0      # (n_split + 1) of them
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_NONE)) == plain
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_STATIC)) == plain
+    squeeze = binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_SQUEEZE_DYNAMIC))
+    n_split = plain // (4 * B * heads * state) - 1
+    need = 4 * (n_split * B * C + B * hidden + B * C * k * k)
+    assert plain + need <= squeeze <= plain + need + 4 * 256
+    assert binding.jv_linear_block_workspace_bytes(d, params(binding.JV_DWC_TOKEN_DYNAMIC, hid=64)) == 0
+    d.dtype = d.o_dtype = binding.JV_F32             # wide heads are built for bf16 tensors
+    assert binding.jv_linear_attn_workspace_bytes(d) == 0
+
+
 def test_gemm_shape_limits_are_checked_on_the_host():
     """jv_gemm_bias_act refuses on the host what its kernel cannot address; large token counts
     (a 256 x 256 grid at batch 4 against a 4096-wide hidden layer) are inside the limits."""
