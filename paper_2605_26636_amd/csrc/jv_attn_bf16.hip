@@ -1422,15 +1422,10 @@ __device__ inline void raise_reference_wide(WideState<NT> &w, int nt, const f32x
     const float alpha = __builtin_amdgcn_exp2f(w.m[nt] - m_new);
     w.m[nt] = m_new;
     w.l[nt] *= alpha;
-    // One 32-channel block at a time: with NT = 2 the accumulators live in the accumulation
-    // registers, which the vector unit cannot scale in place, and the vector registers this rare
-    // path holds at once are taken from every tile's budget.
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int v = 0; v < 16; ++v) w.acc[mi][nt][v] *= alpha;
-        __builtin_amdgcn_sched_barrier(0);
-    }
 }
 
 // One tile of 32 keys: `ka` holds its K operands; V rows at vaddr + VOFF; KNEXT >= 0: the K
@@ -1483,16 +1478,14 @@ __device__ __forceinline__ void wide_ring_tile(WideState<NT> &w, const u32x4 (&q
             }
 }
 
-// NT = 1 (the build's choice): 128 query slots per workgroup, two workgroups per compute unit.
-// NT = 2: 256 query slots, one workgroup per compute unit with the whole register file
-// (accumulators and queries in the accumulation registers); every operand read from LDS feeds
-// two matrix instructions, but with one wavefront per SIMD nothing runs under its softmax
-// arithmetic: measured 27 % slower (4096 tokens x 64 heads: 687 us against 541 us).  The NT = 2
-// build is only correct while the compiler leaves the registers the assembly LDS reads write
-// alone until wide_reads_landed -- under register pressure it has copied them to accumulation
-// registers first, before the data had arrived; check the generated code when building it.
+// NT: blocks of 32 query columns per wavefront.  The kernel is built with NT = 1: 128 query slots
+// per workgroup, two workgroups per compute unit.  (NT = 2 -- 256 query slots, one workgroup per
+// compute unit with the whole register file, every operand read from LDS feeding two matrix
+// instructions -- was measured 27 % slower: with one wavefront per SIMD nothing runs under its
+// softmax arithmetic.)
 template <bool O_BF16, int NT>
-__global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
+__global__ void __launch_bounds__(256, 2) attn_ring_wide_bf16(AttnArgs a) {
+    static_assert(NT == 1, "two wavefronts per SIMD: the register budget holds one block of query columns");
     float c_log2 = a.c;
     asm volatile("" : "+s"(c_log2));  // fetched and waited for here, not inside the key loop
     __shared__ __align__(16) unsigned char smem[kWideRing * kStageWideBytes];
@@ -1512,12 +1505,8 @@ __global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
         const int tok = max(slot_token(a, wy, wx, q0 + 32 * nt + li), 0);
         const __bf16 *row = (const __bf16 *)a.q.ptr + qbase + (long long)tok * a.q.sn + g * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            // (NT = 2: straight into the accumulation registers, where the matrix instructions read them:
-            // the vector registers are left to the operands that change from tile to tile)
-            if (NT == 2) asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][ks]) : "v"(row), "n"(32 * ks));
-            else asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qreg[nt][ks]) : "v"(row), "n"(32 * ks));
-        }
+        for (int ks = 0; ks < 8; ++ks)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qreg[nt][ks]) : "v"(row), "n"(32 * ks));
     }
     WideState<NT> w;
 #pragma unroll
@@ -1606,10 +1595,7 @@ __global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {  // the queries, older than stage 0, have landed too
-            if (NT == 2) asm volatile("" : "+a"(qreg[nt][ks]));
-            else asm volatile("" : "+v"(qreg[nt][ks]));
-        }
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[nt][ks]));  // the queries, older than stage 0, have landed too
     wide_load_k<0>(ka, kaddr);
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(ka[4]), "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7]));
@@ -1679,13 +1665,6 @@ __global__ void __launch_bounds__(256, 3 - NT) attn_ring_wide_bf16(AttnArgs a) {
     }
 }
 
-#ifndef JV_WIDE_WINDOWS
-#define JV_WIDE_WINDOWS 1  // unpadded windows whose width divides 32 take the ring kernel too
-#endif
-#ifndef JV_WIDE_NT
-#define JV_WIDE_NT 1  // blocks of 32 query columns per wavefront of the wide ring kernel
-#endif
-
 jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_slots, hipStream_t stream) {
     AttnArgs a;
     a.q = pr.q; a.k = pr.k; a.v = pr.v; a.o = pr.o;
@@ -1696,18 +1675,17 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     a.c = scale * kLog2e;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
     if (pr.D == kHeadDimWide) {
-        // windows of whole grid rows with 32-bit byte offsets inside a (batch, head) slice: the ring kernel
+        dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
+        // windows of whole grid rows, and unpadded windows whose width divides a key stage, with 32-bit
+        // byte offsets inside a (batch, head) slice: the ring kernel
         const long long wide_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
         const bool whole_windows = g.H % g.wh == 0 && g.W % g.ww == 0 && kStageWide % g.ww == 0;
-        if ((a.contig || (JV_WIDE_WINDOWS && whole_windows)) &&
+        if ((a.contig || whole_windows) &&
             ((long long)pr.N + 2ll * kStageWide * g.W) * wide_sn * 2 + 512 < (1ll << 31)) {
-            constexpr int NT = JV_WIDE_NT;
-            dim3 ring_grid((a.q_slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
-            if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true, NT>), ring_grid, dim3(256), 0, stream, a);
-            else hipLaunchKernelGGL((attn_ring_wide_bf16<false, NT>), ring_grid, dim3(256), 0, stream, a);
+            if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true, 1>), grid, dim3(256), 0, stream, a);
+            else hipLaunchKernelGGL((attn_ring_wide_bf16<false, 1>), grid, dim3(256), 0, stream, a);
             return launch_status("attn_ring_wide_bf16");
         }
-        dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
         if (pr.o_bf16) hipLaunchKernelGGL((attn_wide_bf16<true>), grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((attn_wide_bf16<false>), grid, dim3(256), 0, stream, a);
         return launch_status("attn_wide_bf16");
