@@ -41,7 +41,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazySum = 256.0f;     // largest lane sum of a tile taken without a max pass
 constexpr float kMinusHuge = -1.0e30f; // finite stand-in for "no maximum yet"
 
-// Work items of the ring kernels: (query block, window, batch * head), query block fastest.  The
+// Work items of the streaming and ring kernels: (query block, window, batch * head), query block fastest.  The
 // hardware deals consecutive workgroups to the eight XCDs in turn; the launch is one-dimensional
 // (8 * ceil(items / 8) workgroups) and workgroup w takes item (w % 8) * ceil(items / 8) + w / 8,
 // so that an XCD walks a contiguous range of items: the query blocks that stream the same keys
@@ -340,7 +340,7 @@ __device__ inline void queries_landed(u32x4 (&qreg)[NT][4]) {
 // Streaming kernel: any window size, including the whole grid (full attention).
 // A workgroup holds 128*NT consecutive query slots of one window (4 waves x 32*NT) and streams
 // the window's keys through LDS in double-buffered stages of 64.
-// grid (ceil(slots/(128*NT)), n_win, B*heads), 256 threads.
+// grid ring_grid(a, 128 * NT): one workgroup per (block of 128 * NT query slots, window, batch * head); 256 threads.
 // ---------------------------------------------------------------------------------------
 constexpr int kStage = 64;
 constexpr int kStageBytes = 2 * kStage * 128;  // K rows then V rows
@@ -353,9 +353,11 @@ __global__ void __launch_bounds__(256, JV_ATTN_MINW) attn_stream_bf16(AttnArgs a
     __shared__ __align__(16) unsigned char smem[2 * kStageBytes];
     __shared__ __align__(16) float bias[2][kStage];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
-    const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
-    const int q0 = blockIdx.x * (128 * NT) + wave * (32 * NT);
+    RingItem it;
+    if (!ring_item(a, 128 * NT, it)) return;  // whole workgroup
+    const int bh = it.bh, b = bh / a.heads, h = bh % a.heads;
+    const int win = it.win, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
+    const int q0 = it.qblock * (128 * NT) + wave * (32 * NT);
     const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
     const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
     const bool wave_live = q0 < a.q_slots;
@@ -1178,7 +1180,7 @@ static jv_status launch_window8(const AttnArgs &a, int BH, hipStream_t stream) {
 // channels in steps of 16) and 8 for O^T += V^T P^T (four 32-channel blocks x two steps of 16
 // keys) around the same softmax arithmetic as for 64 channels on half as many columns: the
 // vector work per matrix instruction is half that of the 64-channel kernels.
-// grid (ceil(q_slots / 128), n_win, B*heads), 256 threads.
+// grid ring_grid(a, 128): one workgroup per (block of 128 query slots, window, batch * head); 256 threads.
 // ---------------------------------------------------------------------------------------
 constexpr int kStageWide = 32;
 constexpr int kTileWideBytes = kStageWide * 256;    // the K rows or the V rows of a stage
@@ -1214,9 +1216,11 @@ __global__ void __launch_bounds__(256, 2) attn_wide_bf16(AttnArgs a) {
     __shared__ __align__(16) unsigned char smem[2 * kStageWideBytes];
     __shared__ __align__(16) float bias[2][kStageWide];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
-    const int bh = blockIdx.z, b = bh / a.heads, h = bh % a.heads;
-    const int win = blockIdx.y, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
-    const int q0 = blockIdx.x * 128 + wave * 32;
+    RingItem it;
+    if (!ring_item(a, 128, it)) return;  // whole workgroup
+    const int bh = it.bh, b = bh / a.heads, h = bh % a.heads;
+    const int win = it.win, wy = win / a.g.wins_x, wx = win % a.g.wins_x;
+    const int q0 = it.qblock * 128 + wave * 32;
     const long long qbase = b * a.q.sb + h * a.q.sh, kbase = b * a.k.sb + h * a.k.sh;
     const long long vbase = b * a.v.sb + h * a.v.sh, obase = b * a.o.sb + h * a.o.sh;
     const bool wave_live = q0 < a.q_slots;
@@ -1705,22 +1709,22 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     a.c = scale * kLog2e;
     a.n_bh = pr.B * pr.heads;
     if (g.n_win > 65535) return fail(JV_ERR_UNSUPPORTED, "more than 65535 windows");
-    // the ring kernels number their work items (query block, window, batch * head) in 32 bits
-    const bool ring_items_fit = (long long)((a.q_slots + 127) / 128) * g.n_win * a.n_bh < (1ll << 28);
+    // the streaming and ring kernels number their work items (query block, window, batch * head) in 32 bits
+    if ((long long)((a.q_slots + 127) / 128) * g.n_win * a.n_bh >= (1ll << 28))
+        return fail(JV_ERR_UNSUPPORTED, "more than 2^28 blocks of 128 queries");
     if (pr.D == kHeadDimWide) {
-        dim3 grid((a.q_slots + 127) / 128, g.n_win, pr.B * pr.heads);
         // windows of whole grid rows, and unpadded windows whose width divides a key stage, with 32-bit
         // byte offsets inside a (batch, head) slice: the ring kernel
         const long long wide_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
         const bool whole_windows = g.H % g.wh == 0 && g.W % g.ww == 0 && kStageWide % g.ww == 0;
-        if ((a.contig || whole_windows) && ring_items_fit &&
+        if ((a.contig || whole_windows) &&
             ((long long)pr.N + 2ll * kStageWide * g.W) * wide_sn * 2 + 512 < (1ll << 31)) {
             if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_wide_bf16<true, 1>), ring_grid(a, 128), dim3(256), 0, stream, a);
             else hipLaunchKernelGGL((attn_ring_wide_bf16<false, 1>), ring_grid(a, 128), dim3(256), 0, stream, a);
             return launch_status("attn_ring_wide_bf16");
         }
-        if (pr.o_bf16) hipLaunchKernelGGL((attn_wide_bf16<true>), grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((attn_wide_bf16<false>), grid, dim3(256), 0, stream, a);
+        if (pr.o_bf16) hipLaunchKernelGGL((attn_wide_bf16<true>), ring_grid(a, 128), dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((attn_wide_bf16<false>), ring_grid(a, 128), dim3(256), 0, stream, a);
         return launch_status("attn_wide_bf16");
     }
     const bool all_queries = a.q_slots == g.slots;  // the window-resident kernels compute every slot
@@ -1740,7 +1744,6 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
         return pr.o_bf16 ? launch_window<true, 4>(a, pr.B * pr.heads, stream)
                          : launch_window<false, 4>(a, pr.B * pr.heads, stream);
     constexpr int NT = JV_ATTN_NT;
-    dim3 grid((a.q_slots + 128 * NT - 1) / (128 * NT), g.n_win, pr.B * pr.heads);
     // 32-bit byte offsets inside one (batch, head) slice?
     const long long max_sn = pr.k.sn > pr.v.sn ? pr.k.sn : pr.v.sn;
     const bool fast = a.contig && ((long long)pr.N + 2 * kStage) * max_sn * 2 + 256 < (1ll << 31);
@@ -1748,15 +1751,15 @@ jv_status attn_bf16(const Problem &pr, const WindowGeom &g, float scale, int q_s
     if (fast && !all_queries && a.q_slots <= 64 && g.n_win == 1)
         return pr.o_bf16 ? launch_prefix<true>(a, pr.B * pr.heads, stream)
                          : launch_prefix<false>(a, pr.B * pr.heads, stream);
-    if (fast && NT == 2 && ring_items_fit) {
+    if (fast && NT == 2) {
         if (pr.o_bf16) hipLaunchKernelGGL((attn_ring_bf16<true>), ring_grid(a, 256), dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((attn_ring_bf16<false>), ring_grid(a, 256), dim3(256), 0, stream, a);
         return launch_status("attn_ring_bf16");
     }
     if (pr.o_bf16)
-        hipLaunchKernelGGL((attn_stream_bf16<true, NT>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_stream_bf16<true, NT>), ring_grid(a, 128 * NT), dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((attn_stream_bf16<false, NT>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_stream_bf16<false, NT>), ring_grid(a, 128 * NT), dim3(256), 0, stream, a);
     return launch_status("attn_stream_bf16");
 }
 
