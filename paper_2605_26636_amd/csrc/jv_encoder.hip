@@ -13,7 +13,7 @@ namespace jv {
 // ---------------------------------------------------------------------------------------
 // LayerNorm: one wavefront per row, the row held in registers (16-byte pieces, lane-strided),
 // mean and variance in two register passes, fp32 statistics.
-// grid (ceil(rows / 4)), 256 threads.  NV = 16-byte pieces per lane (cols <= 256 * NV).
+// grid (8 * ceil(ceil(rows / 4) / 8)), 256 threads.  NV = 16-byte pieces per lane (cols <= 256 * NV).
 // ---------------------------------------------------------------------------------------
 template <bool IN_BF16, bool OUT_BF16, int NV>
 __global__ void __launch_bounds__(256)
@@ -21,8 +21,13 @@ layernorm_kernel(const void *__restrict__ xin, const float *__restrict__ gamma,
                  const float *__restrict__ beta, void *__restrict__ yout, long long rows, int cols,
                  float eps) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const long long row = (long long)blockIdx.x * 4 + wave;
-    if (row >= rows) return;
+    // workgroups in contiguous ranges per XCD (workgroup w of the launch takes range w % 8): an
+    // XCD then normalises the rows whose tiles it wrote in the product before and reads in the
+    // product after (their tiles are dealt the same way), which keeps part of them in its L2
+    const long long n_wg = (rows + 3) / 4, per_xcd = (n_wg + 7) / 8;
+    const long long wg = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const long long row = wg * 4 + wave;
+    if (wg >= n_wg || row >= rows) return;
     // piece p of a lane covers columns 4 * (lane + 64 p) .. + 3
     f32x4 v[NV];
     float sum = 0.f;
@@ -81,7 +86,7 @@ layernorm_kernel(const void *__restrict__ xin, const float *__restrict__ gamma,
 template <bool IN_BF16, bool OUT_BF16>
 static void launch_layernorm(const void *x, const float *gamma, const float *beta, void *y,
                              long long rows, int cols, float eps, hipStream_t stream) {
-    dim3 grid((unsigned)((rows + 3) / 4));
+    dim3 grid((unsigned)(8 * (((rows + 3) / 4 + 7) / 8)));
     const int nv = (cols + 255) / 256;
     if (nv <= 1)
         hipLaunchKernelGGL((layernorm_kernel<IN_BF16, OUT_BF16, 1>), grid, dim3(256), 0, stream, x, gamma, beta, y, rows, cols, eps);
