@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--fold-layernorm", action="store_true",
                     help="--encoder: fold the LayerNorms into the products behind them "
                          "(jv_encoder_fold_layernorm)")
+    ap.add_argument("--fuse-linear-projection", action="store_true",
+                    help="--encoder: fold the apply pass of the linear-attention blocks into their output "
+                         "projection (jv_encoder_fuse_linear_projection)")
     ap.add_argument("--gemm", action="store_true",
                     help="time the encoder's four GEMM shapes alone (this library, and the vendor "
                          "library's plain GEMM through torch as a reference point)")
@@ -138,7 +141,7 @@ def main():
         print(json.dumps(bench_paper_ratio(args.steps, args.warmup, args.model, args.graph)))
         return
     if args.encoder:
-        enc = bench_encoder(args.steps, args.warmup, args.stream_bf16, args.fold_layernorm)
+        enc = bench_encoder(args.steps, args.warmup, args.stream_bf16, args.fold_layernorm, args.fuse_linear_projection)
         print(json.dumps({
             "metric": "hybrid ViT-L encoder forward, tokens/s per encoder",
             "value": enc["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -289,7 +292,7 @@ def main():
     print(json.dumps(out))
 
 
-def bench_encoder(steps, warmup, stream_bf16=False, fold=False):
+def bench_encoder(steps, warmup, stream_bf16=False, fold=False, fuse_linear=False):
     """Config 5: 24 pre-LN blocks of width 1024 (16 heads, MLP 4096), batch 4 on a 64x64 grid;
     full attention at blocks 5, 11, 17, 23, window 16x16 at the other even blocks, linear
     attention at the rest.  Random-init (Xavier-normal, seeded) bf16 weights; the residual stream
@@ -306,6 +309,8 @@ def bench_encoder(steps, warmup, stream_bf16=False, fold=False):
                            else torch.from_numpy(v).cuda()) for k, v in wts.items()})
     sd = torch.bfloat16 if stream_bf16 else torch.float32
     enc = binding.Encoder(blocks, pattern, heads, hidden, window=(16, 16), stream_dtype=sd, fold_layernorm=fold)
+    if fuse_linear:
+        enc.fuse_linear_projection(True)
     x = torch.from_numpy(synth.normal((B, N, C), 5003)).cuda().to(sd)
     y = torch.empty_like(x)
     ws = torch.empty(enc.workspace_bytes(B, (H, W)), dtype=torch.uint8, device="cuda")

@@ -373,6 +373,23 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
  * ------------------------------------------------------------------------- */
 size_t jv_encoder_fold_bytes(const jv_encoder *enc);
 jv_status jv_encoder_fold_layernorm(jv_encoder *enc, void *buffer, size_t buffer_bytes, void *hip_stream);
+/* ---------------------------------------------------------------------------
+ * jv_encoder_fuse_linear_projection (optional): in the linear-attention blocks, fold the apply
+ * pass of Eq. 2 into the output projection the block inherits (Sec. 3.2.3).  With
+ * o_h = relu(q_h) S_h / den_h and den_h = relu(q_h) . z_h + eps,
+ *     concat_h(o_h) W_O^T = A' W'_b^T,   A'[t, 64 h + i] = relu(q_h[t, i]) / den_h[t],
+ *                                        W'_b[n, 64 h + i] = sum_c W_O[n, 64 h + c] S_bh[i, c],
+ * so a block runs the state pass, forms the per-image weights W'_b (bf16) and the scaled
+ * queries A' (bf16) and multiplies them in the projection's GEMM (bias and residual as before);
+ * the attention output itself is never written.  The block is unchanged as a function; the
+ * roundings differ (S enters through W'_b rounded to bf16 instead of as a high + low bf16 pair).
+ * Applies to blocks with 64-channel heads, the ReLU map and no convolution branch, with
+ * separate LayerNorm passes, on images of a multiple of 256 tokens (prefix tokens included);
+ * every other block runs as without the option.  enable != 0 switches it on, 0 off; afterwards
+ * jv_encoder_workspace_bytes also asks for the summed states and [batch][width][width] bf16.
+ * Host-only call: nothing is launched.  Returns JV_ERR_INVALID_ARG for a null encoder.
+ * ------------------------------------------------------------------------- */
+jv_status jv_encoder_fuse_linear_projection(jv_encoder *enc, int32_t enable);
 jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
                              int32_t grid_h, int32_t grid_w, void *workspace,
                              size_t workspace_bytes, void *hip_stream);

@@ -24,7 +24,7 @@ EXPORTS = [
     "jv_window_attn_fwd", "jv_full_attn_fwd",
     "jv_layernorm_fwd", "jv_gemm_bias_act",
     "jv_encoder_create", "jv_encoder_workspace_bytes", "jv_encoder_forward", "jv_encoder_forward_taps", "jv_encoder_destroy",
-    "jv_encoder_fold_bytes", "jv_encoder_fold_layernorm",
+    "jv_encoder_fold_bytes", "jv_encoder_fold_layernorm", "jv_encoder_fuse_linear_projection",
 ]
 JV_EPI_NONE, JV_EPI_GELU, JV_EPI_RESIDUAL, JV_EPI_SILU = 0, 1, 2, 3
 JV_DWC_NONE, JV_DWC_STATIC, JV_DWC_SQUEEZE_DYNAMIC, JV_DWC_TOKEN_DYNAMIC = 0, 1, 2, 3
@@ -120,6 +120,7 @@ def lib():
         L.jv_encoder_fold_bytes.restype = ctypes.c_size_t
         L.jv_encoder_fold_bytes.argtypes = [vp]
         L.jv_encoder_fold_layernorm.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.jv_encoder_fuse_linear_projection.argtypes = [vp, i32]
         L.jv_encoder_destroy.restype = None
         L.jv_encoder_destroy.argtypes = [vp]
         _lib = L
@@ -376,6 +377,11 @@ class Encoder:
         buf = torch.empty(max(need, 256), dtype=torch.uint8, device=self.blocks[0]["w_o"].device)
         _check(lib().jv_encoder_fold_layernorm(self._handle, buf.data_ptr(), buf.numel(), _stream(stream)))
         self._folded = buf
+
+    def fuse_linear_projection(self, enable=True):
+        """Fold the apply pass of the linear-attention blocks into their output projection
+        (jv_encoder_fuse_linear_projection)."""
+        _check(lib().jv_encoder_fuse_linear_projection(self._handle, 1 if enable else 0))
 
     def workspace_bytes(self, batch, grid):
         return int(lib().jv_encoder_workspace_bytes(self._handle, batch, grid[0], grid[1]))

@@ -202,6 +202,11 @@ struct GemmLn {
     void *xb_out;           // produce: [M][N] bf16 copy of y, or null
     int groups;             // consume: K / 64
     float eps;              // consume
+    // One weight matrix per group of rows (the fused projection of a linear-attention block:
+    // one matrix per image): rows m use w + (m / w_rows) * w_stride; w_rows = 0: one matrix.
+    // w_rows is a multiple of the tile height, so a tile never straddles two matrices.
+    int w_rows;
+    long long w_stride;     // elements
 };
 
 // Sum over the 16 lanes of a DPP row (the lanes that hold one token row of the fp32 tile).
@@ -237,7 +242,8 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     const int lrow = lane >> 3;
     // The tile's first rows are 64-bit bases (the same in every lane); the offsets inside the
     // tile, 255 rows at most, fit 32 bits (the launcher bounds lda and K).
-    const char *a_tile = (const char *)(A + (size_t)m0 * lda), *w_tile = (const char *)(W + (size_t)n0 * K);
+    const char *a_tile = (const char *)(A + (size_t)m0 * lda);
+    const char *w_tile = (const char *)(W + (size_t)n0 * K + (ln.w_rows ? (size_t)(m0 / ln.w_rows) * (size_t)ln.w_stride : (size_t)0));
     unsigned a_off[kPartLoads], w_off[kPartLoads];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
     for (int j = 0; j < kPartLoads; ++j) {
@@ -699,6 +705,7 @@ struct jv_encoder {
     jv_block_weights *blocks;
     jv_dwc_params *dwc;  // per block, a copy of the caller's parameters (mode none if absent)
     unsigned char *folded;  // caller's buffer with the LayerNorm-folded weights, or null (jv_encoder_fold_layernorm)
+    bool fuse_la;           // jv_encoder_fuse_linear_projection
 };
 
 namespace jv {
@@ -726,6 +733,19 @@ static size_t encoder_linear_workspace(const jv_encoder *enc, int batch, int N) 
         }
     }
     return need;
+}
+// The linear-attention blocks that run with the apply pass folded into the output projection
+// when jv_encoder_fuse_linear_projection is on: 64-channel heads, ReLU map, no convolution
+// branch, separate LayerNorm passes, and images of a multiple of 256 tokens (a GEMM tile then
+// lies inside one image).  The other blocks run the two passes and the plain projection.
+static bool encoder_block_fuses(const jv_encoder *enc, int l, int N) {
+    return enc->fuse_la && !enc->folded && enc->pattern[l] == 0 && encoder_head_dim(enc->cfg) == kHeadDim &&
+           enc->cfg.la_focus_p <= 1 && enc->dwc[l].mode == JV_DWC_NONE && N % kBM == 0;
+}
+static bool encoder_any_block_fuses(const jv_encoder *enc, int N) {
+    for (int l = 0; l < enc->cfg.n_blocks; ++l)
+        if (encoder_block_fuses(enc, l, N)) return true;
+    return false;
 }
 // Everything a forward pass over (batch, grid) would be refused for after its first launch,
 // checked on the host: the four GEMM shapes, the window partition, the token-count limits of
@@ -842,6 +862,7 @@ jv_status jv_encoder_create(const jv_encoder_config *config, const jv_block_weig
     }
     e->cfg.pattern = e->pattern;
     e->folded = nullptr;
+    e->fuse_la = false;
     *out = e;
     return JV_OK;
 }
@@ -873,6 +894,13 @@ static FoldLayout fold_layout(const jv_encoder_config &c) {
     return f;
 }
 }  // namespace jv
+
+jv_status jv_encoder_fuse_linear_projection(jv_encoder *enc, int32_t enable) {
+    jv::clear_error();
+    if (!enc) return jv::fail(JV_ERR_INVALID_ARG, "null encoder");
+    enc->fuse_la = enable != 0;
+    return JV_OK;
+}
 
 size_t jv_encoder_fold_bytes(const jv_encoder *enc) {
     jv::clear_error();
@@ -914,7 +942,8 @@ jv_status jv_encoder_fold_layernorm(jv_encoder *enc, void *buffer, size_t buffer
 // Workspace: [T, width] bf16 (LayerNorm output, later the mixer output), [T, max(3 width,
 // mlp_hidden)] bf16 (QKV, later the MLP hidden layer), then the linear-attention states; with
 // folded LayerNorms also a second [T, width] bf16 buffer and the row statistics
-// [T, width / 64, 2] fp32.
+// [T, width / 64, 2] fp32; with fused linear-attention projections the summed states
+// [batch * heads][64 * 64 + 64] fp32 and the per-image weights [batch][width][width] bf16.
 size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
                                   int32_t grid_w) {
     jv::clear_error();
@@ -922,8 +951,12 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
     const size_t T = (size_t)batch * (enc->cfg.n_prefix + (size_t)grid_h * grid_w), C = enc->cfg.width;
     const size_t wide = 3 * C > (size_t)enc->cfg.mlp_hidden ? 3 * C : (size_t)enc->cfg.mlp_hidden;
     const size_t fold = enc->folded ? jv::align256(T * C * 2) + jv::align256(T * (C / 64) * 8) : 0;
+    const int N = enc->cfg.n_prefix + grid_h * grid_w;
+    const size_t fuse = jv::encoder_any_block_fuses(enc, N)
+                            ? jv::align256((size_t)batch * enc->cfg.heads * jv::kStateFloats * 4) + jv::align256((size_t)batch * C * C * 2)
+                            : 0;
     return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
-           jv::align256(jv::encoder_linear_workspace(enc, batch, enc->cfg.n_prefix + grid_h * grid_w)) + fold;
+           jv::align256(jv::encoder_linear_workspace(enc, batch, N)) + fold + fuse;
 }
 
 jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
@@ -975,6 +1008,11 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
     __bf16 *stream16 = (__bf16 *)((unsigned char *)la_ws + la_ws_bytes);  // [T, C], the stream before LayerNorm 2
     float *row_stats = (float *)((unsigned char *)stream16 + jv::align256(T * C * 2));
     const jv::FoldLayout fl = jv::fold_layout(c);
+    // fused linear-attention projections (jv_encoder_fuse_linear_projection): behind the fold buffers
+    unsigned char *fuse_base = (unsigned char *)la_ws + la_ws_bytes +
+                               (fold ? jv::align256(T * C * 2) + jv::align256(T * (C / 64) * 8) : 0);
+    float *la_states = (float *)fuse_base;
+    __bf16 *w_fold = (__bf16 *)(fuse_base + jv::align256((size_t)batch * c.heads * jv::kStateFloats * 4));
     bool ln1_folded = false;  // the previous block's last product has left rows and statistics for LayerNorm 1
 
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
@@ -1003,10 +1041,14 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
             if ((st = jv::layernorm_forward(resid, b.ln1_g, b.ln1_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
             if ((st = jv::gemm_forward(narrow, b.w_qkv, b.b_qkv, nullptr, widebuf, T, 3 * C, C, JV_EPI_NONE, true, stream)) != JV_OK) return st;
         }
+        const bool fused = jv::encoder_block_fuses(enc, l, N);
         switch (enc->pattern[l]) {
             case 0:
-                st = jv::linear_block_forward(pr, c.la_eps, &enc->dwc[l], la_ws, la_ws_bytes, stream,
-                                              c.la_focus_p > 1 ? c.la_focus_p : 1);
+                if (fused)  // the scaled queries take the place of the mixer's output
+                    st = jv::linear_fused_projection_operands(pr, c.la_eps, (float *)la_ws, la_states, b.w_o, w_fold, narrow, stream);
+                else
+                    st = jv::linear_block_forward(pr, c.la_eps, &enc->dwc[l], la_ws, la_ws_bytes, stream,
+                                                  c.la_focus_p > 1 ? c.la_focus_p : 1);
                 break;
             case 1: st = jv::window_forward(pr, c.win_h, c.win_w, 0.f, stream); break;
             default: st = jv::full_forward(pr, 0.f, stream); break;
@@ -1018,7 +1060,16 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
                                      (const float *)(fw + fl.c2fc1), row_stats, c.ln_eps, widebuf, T, c.mlp_hidden, C, true, stream);
             if (st != JV_OK) return st;
         } else {
-            if ((st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
+            if (fused) {
+                jv::GemmLn per_image{};
+                per_image.w_rows = N;
+                per_image.w_stride = (long long)C * C;
+                st = s16 ? jv::launch_gemm<JV_EPI_RESIDUAL, true>(narrow, w_fold, b.b_o, resid, y, T, C, C, C, stream, per_image)
+                         : jv::launch_gemm<JV_EPI_RESIDUAL, false>(narrow, w_fold, b.b_o, resid, y, T, C, C, C, stream, per_image);
+            } else {
+                st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, s16, stream);
+            }
+            if (st != JV_OK) return st;
             if ((st = jv::layernorm_forward(y, b.ln2_g, b.ln2_b, narrow, T, C, c.ln_eps, s16, true, stream)) != JV_OK) return st;
             if ((st = jv::gemm_forward(narrow, b.w_fc1, b.b_fc1, nullptr, widebuf, T, c.mlp_hidden, C, JV_EPI_GELU, true, stream)) != JV_OK) return st;
         }

@@ -56,6 +56,11 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
 // head_dim 128 (bf16 tensors): launch plan and workspace floats of the states; the state pass
 // (with `vsum`, [n_split][B][C] floats, it also leaves the partial token sums of V), the apply
 // pass (with `cv` it adds the block's convolution, filters of ksize x ksize taps), and both.
+// Operands of a linear-attention block's output projection with the apply pass folded in
+// (jv_encoder_fuse_linear_projection): states [B*heads][kStateFloats] fp32, w_fold [B][C][C] bf16,
+// a_out [B*N][C] bf16; ws as for linear_bf16.
+jv_status linear_fused_projection_operands(const Problem &pr, float eps, float *ws, float *states,
+                                           const void *w_o, void *w_fold, void *a_out, hipStream_t stream);
 LinearPlan plan_linear_wide(int B, int heads, int N);
 size_t linear_wide_workspace_floats(int B, int heads, int N);
 jv_status linear_wide_state(const Problem &pr, float *ws, float *vsum, hipStream_t stream);

@@ -564,6 +564,104 @@ jv_status linear_bf16(const Problem &pr, const LinearPlan &plan, float eps, floa
 }
 
 // ---------------------------------------------------------------------------------------
+// The apply pass folded into the output projection that follows a linear-attention block
+// (Sec. 3.2.3: the block keeps the projection W_O it inherits).  With o_h = relu(q_h) S_h / den_h,
+// den_h = relu(q_h) . z_h + eps, the projected output of a token is
+//     sum_h o_h W_O[:, h]^T = sum_h (relu(q_h) / den_h) (W_O[:, h] S_h^T)^T,
+// i.e. one product of the scaled queries A'[t, 64 h + i] = relu(q_h[t, i]) / den_h[t] with a
+// weight matrix of the image, W'_b[n, 64 h + i] = sum_c W_O[n, 64 h + c] St_bh[c][i]  (St is the
+// state as la_state_bf16 stores it, St[c][i] = sum_t relu(k[t, i]) v[t, c]).  Both operands are
+// rounded to bf16 once; the product runs on the GEMM with one weight matrix per image.
+// ---------------------------------------------------------------------------------------
+
+// grid (C / 64, B*heads), 256 threads: 64 output features n x the 64 columns of head h of W'_b;
+// a thread forms a 4 x 4 block of them (two 16-byte LDS reads per 16 multiply-adds), in fp32.
+__global__ void __launch_bounds__(256)
+la_fold_projection(const float *__restrict__ states, const __bf16 *__restrict__ w_o,
+                   __bf16 *__restrict__ w_fold, int heads, int C) {
+    __shared__ __align__(16) float St[kHeadDim][kHeadDim + 4];   // [c][i]
+    __shared__ __align__(16) float Wt[kHeadDim][kHeadDim + 4];   // [c][n - n0]
+    const int tid = threadIdx.x, bh = blockIdx.y, b = bh / heads, h = bh % heads, n0 = blockIdx.x * 64;
+    const float *sp = states + (size_t)bh * kStateFloats;
+    for (int e = tid; e < kHeadDim * kHeadDim; e += 256) St[e >> 6][e & 63] = sp[e];
+    for (int e = tid; e < kHeadDim * kHeadDim; e += 256)
+        Wt[e & 63][e >> 6] = (float)w_o[(size_t)(n0 + (e >> 6)) * C + h * kHeadDim + (e & 63)];
+    __syncthreads();
+    const int nb = (tid >> 4) * 4, ib = (tid & 15) * 4;
+    float acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[a][i] = 0.f;
+#pragma unroll 8
+    for (int c = 0; c < kHeadDim; ++c) {
+        const f32x4 w4 = *(const f32x4 *)&Wt[c][nb], s4 = *(const f32x4 *)&St[c][ib];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[a][i] = fmaf(w4[a], s4[i], acc[a][i]);
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        u32x2 pk = {pack_bf16x2(acc[a][0], acc[a][1]), pack_bf16x2(acc[a][2], acc[a][3])};
+        *(u32x2 *)(w_fold + ((size_t)b * C + n0 + nb + a) * C + h * kHeadDim + ib) = pk;
+    }
+}
+
+// grid (ceil(B * N * heads / 32)), 256 threads: 8 lanes per (token, head) row of 64 channels, rows in
+// the order (batch, token, head), so that a workgroup writes 4 KB of consecutive bytes of a_out.
+__global__ void __launch_bounds__(256)
+la_scale_queries(TensorArg qt, const float *__restrict__ states, __bf16 *__restrict__ a_out, int heads,
+                 int N, long long rows, float eps) {
+    const long long row = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);
+    if (row >= rows) return;  // all eight lanes of a row together
+    const int l8 = threadIdx.x & 7;
+    const int h = (int)(row % heads);
+    const long long tn = row / heads;
+    const int n = (int)(tn % N), b = (int)(tn / N);
+    const u32x4 q = relu_bf16x8(ld_stream((const u32x4 *)((const __bf16 *)qt.ptr + b * qt.sb + h * qt.sh + (long long)n * qt.sn + l8 * 8)));
+    const float *zp = states + ((size_t)b * heads + h) * kStateFloats + kHeadDim * kHeadDim + l8 * 8;
+    const f32x4 z0 = *(const f32x4 *)zp, z1 = *(const f32x4 *)(zp + 4);
+    float r[8] = {bf16_lo(q[0]), bf16_hi(q[0]), bf16_lo(q[1]), bf16_hi(q[1]),
+                  bf16_lo(q[2]), bf16_hi(q[2]), bf16_lo(q[3]), bf16_hi(q[3])};
+    float den = r[0] * z0[0] + r[1] * z0[1] + r[2] * z0[2] + r[3] * z0[3] +
+                r[4] * z1[0] + r[5] * z1[1] + r[6] * z1[2] + r[7] * z1[3];
+    den += __shfl_xor(den, 1, 64);
+    den += __shfl_xor(den, 2, 64);
+    den += __shfl_xor(den, 4, 64);
+    const float inv = 1.0f / (den + eps);
+    u32x4 out = {pack_bf16x2(r[0] * inv, r[1] * inv), pack_bf16x2(r[2] * inv, r[3] * inv),
+                 pack_bf16x2(r[4] * inv, r[5] * inv), pack_bf16x2(r[6] * inv, r[7] * inv)};
+    st_stream((u32x4 *)(a_out + ((size_t)tn * heads + h) * kHeadDim + l8 * 8), out);
+}
+
+// State pass, sum of the partial states into `states` ([B*heads][kStateFloats], one per head),
+// then the two operands of the fused projection: w_fold [B][C][C] and a_out [B*N][C], C = 64 heads.
+// ws: the linear-attention workspace (the partial states).  64-channel heads, ReLU map, no
+// convolution branch (the caller checks).
+jv_status linear_fused_projection_operands(const Problem &pr, float eps, float *ws, float *states,
+                                           const void *w_o, void *w_fold, void *a_out, hipStream_t stream) {
+    static LdsLimit lds_limit;
+    jv_status st = ensure_lds_limit(lds_limit, (const void *)la_state_bf16<false, false>, kStateLds);
+    if (st != JV_OK) return st;
+    const LinearPlan plan = plan_linear(pr.B, pr.heads, pr.N);
+    const int BH = pr.B * pr.heads, C = pr.heads * kHeadDim;
+    hipLaunchKernelGGL((la_state_bf16<false, false>), dim3(8 * ((plan.n_split * BH + 7) / 8)), dim3(256), kStateLds, stream,
+                       pr.k, pr.v, ws, (float *)nullptr, pr.heads, pr.N, plan.chunk, 1, plan.n_split, BH);
+    if ((st = launch_status("la_state_bf16")) != JV_OK) return st;
+    hipLaunchKernelGGL(la_combine, dim3(8 * ((BH + 7) / 8), ((kStateFloats + kHeadDim) / 4 + 255) / 256), dim3(256), 0,
+                       stream, ws, states, (float *)nullptr, plan.n_split, BH, 1);
+    if ((st = launch_status("la_combine")) != JV_OK) return st;
+    hipLaunchKernelGGL(la_fold_projection, dim3(C / 64, BH), dim3(256), 0, stream, states, (const __bf16 *)w_o,
+                       (__bf16 *)w_fold, pr.heads, C);
+    if ((st = launch_status("la_fold_projection")) != JV_OK) return st;
+    const long long rows = (long long)pr.B * pr.N * pr.heads;
+    hipLaunchKernelGGL(la_scale_queries, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, stream, pr.q, states,
+                       (__bf16 *)a_out, pr.heads, pr.N, rows, eps);
+    return launch_status("la_scale_queries");
+}
+
+// ---------------------------------------------------------------------------------------
 // head_dim 128.  la_state_wide_bf16 (below) leaves four 64 x 64 quadrant states per head,
 // la_combine sums the partial ones; this is the apply pass:
 //   o[c2] = sum_i relu(q_i) S_ij[:, c2] / (sum_i relu(q_i) . z_i + eps),   j = c2 / 64,

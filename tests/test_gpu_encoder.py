@@ -151,6 +151,66 @@ def test_small_encoder_each_mixer_and_pattern(fold):
         enc.close()
 
 
+@pytest.mark.parametrize("stream_dtype", [torch.float32, torch.bfloat16], ids=["fp32 stream", "bf16 stream"])
+def test_encoder_fused_linear_projection(stream_dtype):
+    """The apply pass of the linear-attention blocks folded into their output projection
+    (jv_encoder_fuse_linear_projection): the same block as a function, so the same oracle and
+    the same bar; images of 256 and of 512 tokens (one and two GEMM row tiles per image), a
+    pattern with all three mixers, in place, and the blocks the option does not apply to (a
+    convolution branch; an image that is not a multiple of 256 tokens) unchanged by it."""
+    heads, hidden = 3, 256
+    C = heads * 64
+    blocks = [synth.block_weights(C, hidden, 910 + i) for i in range(3)]
+    for b in blocks:
+        for key in ("b_qkv", "b_o", "b_fc1", "b_fc2", "ln1_b", "ln2_b"):
+            b[key] = synth.normal(b[key].shape, 920 + len(key)) * 0.1
+        b["ln1_g"] = 1.0 + 0.1 * synth.normal((C,), 930)
+        b["ln2_g"] = 1.0 + 0.1 * synth.normal((C,), 931)
+    dev = _device_blocks(blocks)
+    # (a stream stored in bf16 is judged beyond the storage format's own rounding, as in its own test)
+    err = err_bf16 if stream_dtype == torch.float32 else err_bf16_stored
+    for (B, H, W), pattern in (((3, 16, 16), [0, 0, 0]), ((2, 16, 32), [0, 1, 0]), ((2, 16, 16), [2, 0, 1])):
+        if stream_dtype == torch.bfloat16:   # two blocks at a time: the error of a bf16 stream grows with depth
+            pattern = pattern[:2]
+        x = synth.normal((B, H * W, C), 900 + H * W)
+        dx = torch.from_numpy(x).cuda().to(stream_dtype)
+        ref = oracle.encoder_forward(dx.float().cpu().numpy().astype(np.float64), blocks[:len(pattern)], pattern, H, W, heads, window=(8, 8))
+        enc = binding.Encoder(dev[:len(pattern)], pattern, heads, hidden, window=(8, 8), stream_dtype=stream_dtype)
+        plain = torch.empty_like(dx)
+        enc.forward(dx, plain, (H, W))
+        ws_plain = enc.workspace_bytes(B, (H, W))
+        enc.fuse_linear_projection(True)
+        assert enc.workspace_bytes(B, (H, W)) > ws_plain
+        y = torch.empty_like(dx)
+        enc.forward(dx, y, (H, W))
+        e = err(to_host(y), ref)
+        print(f"fused projection, {B} x {H * W} tokens, pattern {pattern}: {e:.2e}")
+        check(e, BF16_TOL)
+        assert not torch.equal(y, plain)                 # the fused path did run
+        y2 = dx.clone()
+        enc.forward(y2, y2, (H, W))                      # in place
+        assert torch.equal(y, y2)
+        enc.fuse_linear_projection(False)
+        y3 = torch.empty_like(dx)
+        enc.forward(dx, y3, (H, W))
+        assert torch.equal(y3, plain)
+        enc.close()
+    # blocks the option does not apply to run as without it: 18 x 18 = 324 tokens per image
+    B, H, W = 2, 18, 18
+    x = synth.normal((B, H * W, C), 950)
+    dx = torch.from_numpy(x).cuda().to(stream_dtype)
+    enc = binding.Encoder(dev, [0, 0, 0], heads, hidden, window=(8, 8), stream_dtype=stream_dtype)
+    plain = torch.empty_like(dx)
+    enc.forward(dx, plain, (H, W))
+    ws_plain = enc.workspace_bytes(B, (H, W))
+    enc.fuse_linear_projection(True)
+    assert enc.workspace_bytes(B, (H, W)) == ws_plain
+    y = torch.empty_like(dx)
+    enc.forward(dx, y, (H, W))
+    assert torch.equal(y, plain)
+    enc.close()
+
+
 def test_vit_l_blocks_teacher_forced():
     """One ViT-L block per mixer type at the encoder workload's width (1024, 16 heads, MLP 4096)
     on a 32 x 32 grid, each fed the same input: per-block parity at full width."""
@@ -168,6 +228,13 @@ def test_vit_l_blocks_teacher_forced():
         check(err_bf16(to_host(y), ref), BF16_TOL)
         # the block's own contribution (output minus input) is what the kernels computed
         check(err_bf16(to_host(y) - x, ref - x), BF16_TOL)
+        if mixer == 0:  # the same block with the apply pass folded into the output projection
+            enc.fuse_linear_projection(True)
+            yf = torch.empty_like(dx)
+            enc.forward(dx, yf, (H, W))
+            assert not torch.equal(yf, y)
+            check(err_bf16(to_host(yf), ref), BF16_TOL)
+            check(err_bf16(to_host(yf) - x, ref - x), BF16_TOL)
         enc.close()
     # the same block with the stream carried in bf16 (input rounded first, output stored in bf16)
     xb = synth.round_to_bf16(x)
