@@ -167,3 +167,11 @@ def test_gemm_shape_limits_are_checked_on_the_host():
     assert call(0, 64, 64) == binding.JV_ERR_INVALID_ARG
     assert call(16, 64, 1 << 22) == binding.JV_ERR_UNSUPPORTED  # rows above 2^21 elements
     assert call((1 << 30) + 1, 64, 64) == binding.JV_ERR_UNSUPPORTED
+
+
+def test_encoder_options_refuse_a_null_encoder():
+    """Host-only entry points of the encoder object: a null handle is an argument error."""
+    L = binding.lib()
+    assert L.jv_encoder_fuse_linear_projection(None, 1) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_encoder_fold_layernorm(None, None, 0, None) == binding.JV_ERR_INVALID_ARG
+    assert L.jv_encoder_fold_bytes(None) == 0
