@@ -146,6 +146,18 @@ def test_config3_full_attention_16k_tokens_sampled_rows():
     check_bf16_pair(_full(q, k, v, H, W, torch.float32), o, ref, rows)
 
 
+def test_full_attention_65536_tokens_sampled_rows():
+    """The largest image of the token-count sweep (256 x 256 grid) through full attention: 2 048
+    key tiles per query block, 256 query blocks per head; two heads, sampled rows."""
+    B, heads, H, W = 1, 2, 256, 256
+    N = H * W
+    q, k, v = synth.qkv(3, B, heads, N, 64, 0.125, True)
+    rows = synth.sample_rows(B, heads, N, 96, seed=9)
+    o = _full(q, k, v, H, W)
+    ref = oracle.full_attn_rows(q, k, v, rows)
+    check_bf16_pair(_full(q, k, v, H, W, torch.float32), o, ref, rows)
+
+
 def test_padding_is_masked_not_merely_zero():
     # NaN around the tensors: padded key slots must never be read into the result
     B, heads, H, W = 1, 2, 13, 11
