@@ -207,6 +207,11 @@ struct GemmLn {
     // w_rows is a multiple of the tile height, so a tile never straddles two matrices.
     int w_rows;
     long long w_stride;     // elements
+    // K split over k_split workgroups per tile (0 or 1: none): workgroup (part, tile) multiplies
+    // columns part * K / k_split .. of a and w and writes its tile of partial part, y_split
+    // elements after the one before (plain epilogue, fp32 output; gemm_split_combine adds them up).
+    int k_split;
+    long long y_split;      // elements
 };
 
 // Sum over the 16 lanes of a DPP row (the lanes that hold one token row of the fp32 tile).
@@ -229,9 +234,14 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                  int K, int lda, int tiles_n, int n_tiles, GemmLn ln) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
-    const int per_xcd = (n_tiles + 7) / 8;
-    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= n_tiles) return;  // whole workgroup
+    const int k_split = ln.k_split > 1 ? ln.k_split : 1;
+    const int per_xcd = (n_tiles * k_split + 7) / 8;
+    int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles * k_split) return;  // whole workgroup
+    const int k_part = tile / n_tiles;  // which part of K (0 without a split)
+    tile -= k_part * n_tiles;
+    const int k_len = K / k_split;      // columns this workgroup multiplies
+    Y = (void *)((char *)Y + (size_t)k_part * (size_t)ln.y_split * (OUT_BF16 ? 2 : 4));
     const int m0 = (tile / tiles_n) * kBM, n0 = (tile % tiles_n) * kBN;
     const int wm = wave >> 2, wn = wave & 3;  // 128-token half, 64-feature quarter
     constexpr int kPartLoads = 4;             // load instructions per part and wavefront
@@ -242,8 +252,9 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     const int lrow = lane >> 3;
     // The tile's first rows are 64-bit bases (the same in every lane); the offsets inside the
     // tile, 255 rows at most, fit 32 bits (the launcher bounds lda and K).
-    const char *a_tile = (const char *)(A + (size_t)m0 * lda);
-    const char *w_tile = (const char *)(W + (size_t)n0 * K + (ln.w_rows ? (size_t)(m0 / ln.w_rows) * (size_t)ln.w_stride : (size_t)0));
+    const char *a_tile = (const char *)(A + (size_t)m0 * lda + (size_t)k_part * k_len);
+    const char *w_tile = (const char *)(W + (size_t)n0 * K + (size_t)k_part * k_len +
+                                        (ln.w_rows ? (size_t)(m0 / ln.w_rows) * (size_t)ln.w_stride : (size_t)0));
     unsigned a_off[kPartLoads], w_off[kPartLoads];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
     for (int j = 0; j < kPartLoads; ++j) {
@@ -253,7 +264,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
         a_off[j] = 2u * ((unsigned)ar * (unsigned)lda + gchunk * 8);  // rows of a are lda elements apart
         w_off[j] = 2u * ((unsigned)wr * (unsigned)K + gchunk * 8);
     }
-    const int n_b = K / kBK, n_parts = 2 * n_b;
+    const int n_b = k_len / kBK, n_parts = 2 * n_b;
     // part = 2 * block + (0: a, 1: w); it lives in slot part % 5.  Loads j0 .. j1-1 of a part:
     auto issue_loads = [&](int part, int slot, int j0, int j1) __attribute__((always_inline)) {
         unsigned char *base = smem + slot * kGemmPart + wave * 32 * 128;
@@ -573,11 +584,66 @@ static jv_status launch_gemm(const void *a, const void *w, const float *bias, co
     if (st != JV_OK) return st;
     const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (N + kBN - 1) / kBN;
     const int n_tiles = tiles_m * tiles_n;
-    dim3 grid(8 * ((n_tiles + 7) / 8));
+    dim3 grid(8 * ((n_tiles * (ln.k_split > 1 ? ln.k_split : 1) + 7) / 8));
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16, LN>), grid, dim3(512), kGemmLds, stream,
                        (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K, lda,
                        tiles_n, n_tiles, ln);
     return launch_status("gemm_bf16_kernel");
+}
+
+// Residual product with K split over several workgroups per tile, for launches that would leave
+// most compute units without a tile (fc2 of a ViT-L block on 8 192 tokens: 128 tiles of
+// 256 x 256 for 256 units, each with a K loop of 4096): k_split workgroups per tile multiply a
+// part of K each and write fp32 partial tiles; gemm_split_combine then forms
+//     y = sum of the partials + bias + residual
+// in a fixed order (no atomics: the same bits on every run).
+constexpr int kComputeUnits = 256;  // MI355X
+// k_split for a residual product of M x N x K, or 1: as many parts as fill the chip, at most 4,
+// each a multiple of the K block and at least 1024 long.
+static int gemm_k_split(long long M, int N, int K) {
+    const long long tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
+    int split = 1;
+    while (split < 4 && tiles * split * 2 <= kComputeUnits && K % (2 * split * kBK) == 0 && K / (2 * split) >= 1024) split *= 2;
+    return split;
+}
+// grid (ceil(M * N / 4 / 256)), 256 threads; N % 4 == 0; y may be the residual itself.
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(256)
+gemm_split_combine(const float *__restrict__ parts, long long part_stride, int n_parts,
+                   const float *__restrict__ bias, const void *residual, void *y, long long total4, int N) {
+    const long long i4 = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i4 >= total4) return;
+    const int col = (int)((i4 * 4) % N);
+    f32x4 sum = *(const f32x4 *)(parts + i4 * 4);
+    for (int p = 1; p < n_parts; ++p) sum += *(const f32x4 *)(parts + (size_t)p * part_stride + i4 * 4);
+    if (bias) sum += *(const f32x4 *)(bias + col);
+    if (OUT_BF16) {
+        const u32x2 rr = *(const u32x2 *)((const __bf16 *)residual + i4 * 4);
+        sum[0] += bf16_lo(rr[0]); sum[1] += bf16_hi(rr[0]);
+        sum[2] += bf16_lo(rr[1]); sum[3] += bf16_hi(rr[1]);
+        u32x2 pk = {pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+        *(u32x2 *)((__bf16 *)y + i4 * 4) = pk;
+    } else {
+        sum += *(const f32x4 *)((const float *)residual + i4 * 4);
+        *(f32x4 *)((float *)y + i4 * 4) = sum;
+    }
+}
+// y = a w^T + bias + residual with K split k_split ways; parts: k_split * M * N floats of scratch.
+static jv_status gemm_residual_split(const void *a, const void *w, const float *bias, const void *residual,
+                                     void *y, long long M, int N, int K, bool out_bf16, int k_split,
+                                     float *parts, hipStream_t stream) {
+    GemmLn ex{};
+    ex.k_split = k_split;
+    ex.y_split = M * N;
+    jv_status st = launch_gemm<JV_EPI_NONE, false>(a, w, nullptr, nullptr, parts, M, N, K, K, stream, ex);
+    if (st != JV_OK) return st;
+    const long long total4 = M * N / 4;
+    const dim3 grid((unsigned)((total4 + 255) / 256));
+    if (out_bf16)
+        hipLaunchKernelGGL(gemm_split_combine<true>, grid, dim3(256), 0, stream, parts, M * N, k_split, bias, residual, y, total4, N);
+    else
+        hipLaunchKernelGGL(gemm_split_combine<false>, grid, dim3(256), 0, stream, parts, M * N, k_split, bias, residual, y, total4, N);
+    return launch_status("gemm_split_combine");
 }
 
 // Shape limits of the GEMM (no pointers): what jv_gemm_bias_act documents.  The kernel addresses
@@ -943,7 +1009,9 @@ jv_status jv_encoder_fold_layernorm(jv_encoder *enc, void *buffer, size_t buffer
 // mlp_hidden)] bf16 (QKV, later the MLP hidden layer), then the linear-attention states; with
 // folded LayerNorms also a second [T, width] bf16 buffer and the row statistics
 // [T, width / 64, 2] fp32; with fused linear-attention projections the summed states
-// [batch * heads][64 * 64 + 64] fp32 and the per-image weights [batch][width][width] bf16.
+// [batch * heads][64 * 64 + 64] fp32 and the per-image weights [batch][width][width] bf16; for
+// small token counts (fc2 with fewer than 128 output tiles) the fp32 partial results of its
+// K split, [parts][T, width].
 size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t grid_h,
                                   int32_t grid_w) {
     jv::clear_error();
@@ -955,8 +1023,10 @@ size_t jv_encoder_workspace_bytes(const jv_encoder *enc, int32_t batch, int32_t 
     const size_t fuse = jv::encoder_any_block_fuses(enc, N)
                             ? jv::align256((size_t)batch * enc->cfg.heads * jv::kStateFloats * 4) + jv::align256((size_t)batch * C * C * 2)
                             : 0;
+    const int k_split = enc->folded ? 1 : jv::gemm_k_split((long long)T, (int)C, enc->cfg.mlp_hidden);
+    const size_t split = k_split > 1 ? jv::align256((size_t)k_split * T * C * 4) : 0;
     return jv::align256(T * C * 2) + jv::align256(T * wide * 2) +
-           jv::align256(jv::encoder_linear_workspace(enc, batch, N)) + fold + fuse;
+           jv::align256(jv::encoder_linear_workspace(enc, batch, N)) + fold + fuse + split;
 }
 
 jv_status jv_encoder_forward(const jv_encoder *enc, const void *x, void *y, int32_t batch,
@@ -1013,6 +1083,11 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
                                (fold ? jv::align256(T * C * 2) + jv::align256(T * (C / 64) * 8) : 0);
     float *la_states = (float *)fuse_base;
     __bf16 *w_fold = (__bf16 *)(fuse_base + jv::align256((size_t)batch * c.heads * jv::kStateFloats * 4));
+    // K split of fc2 when its tiles would leave most compute units idle (gemm_residual_split)
+    const int fc2_split = fold ? 1 : jv::gemm_k_split(T, C, c.mlp_hidden);
+    float *fc2_parts = (float *)(fuse_base + (jv::encoder_any_block_fuses(enc, N)
+                                                  ? jv::align256((size_t)batch * c.heads * jv::kStateFloats * 4) + jv::align256((size_t)batch * C * C * 2)
+                                                  : 0));
     bool ln1_folded = false;  // the previous block's last product has left rows and statistics for LayerNorm 1
 
     // Q, K, V as strided views of the [B, N, 3, heads, 64] projection output; O as [B, N, heads, 64].
@@ -1080,6 +1155,8 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
         ln1_folded = fold && l + 1 < c.n_blocks;
         if (ln1_folded) {  // (the bf16 rows go where the next block's LayerNorm 1 would have written)
             if ((st = jv::gemm_ln_produce(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, s16, narrow, row_stats, stream)) != JV_OK) return st;
+        } else if (fc2_split > 1) {
+            if ((st = jv::gemm_residual_split(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, s16, fc2_split, fc2_parts, stream)) != JV_OK) return st;
         } else {
             if ((st = jv::gemm_forward(widebuf, b.w_fc2, b.b_fc2, y, out, T, C, c.mlp_hidden, JV_EPI_RESIDUAL, s16, stream)) != JV_OK) return st;
         }

@@ -248,6 +248,32 @@ def test_vit_l_blocks_teacher_forced():
         enc.close()
 
 
+def test_vit_l_block_fc2_with_split_k():
+    """Few tokens leave fc2 (K = 4096, 1024 output features) with fewer output tiles than half
+    the compute units; the encoder then splits its K loop over two or four workgroups per tile
+    and adds the partial results in a second pass.  6 144 tokens (96 tiles: two parts) and 2 304
+    tokens (36 tiles: four parts), a linear-attention block at ViT-L width, both stream types;
+    a second run gives the same bits (the partial results are added in a fixed order)."""
+    heads, hidden = 16, 4096
+    C = heads * 64
+    wts = synth.block_weights(C, hidden, 830)
+    wts["b_fc2"] = synth.normal(wts["b_fc2"].shape, 831) * 0.1
+    dev = _device_blocks([wts])
+    for H, W in ((64, 96), (48, 48)):
+        x = synth.round_to_bf16(synth.normal((1, H * W, C), 832 + H))
+        ref = oracle.encoder_block(x.astype(np.float64), wts, 0, H, W, heads, (16, 16))
+        for sd in (torch.float32, torch.bfloat16):
+            dx = torch.from_numpy(x).cuda().to(sd)
+            enc = binding.Encoder(dev, [0], heads, hidden, window=(16, 16), stream_dtype=sd)
+            y = torch.empty_like(dx)
+            enc.forward(dx, y, (H, W))
+            check((err_bf16 if sd == torch.float32 else err_bf16_stored)(to_host(y), ref), BF16_TOL)
+            z = dx.clone()
+            enc.forward(z, z, (H, W))     # in place: the residual is the output
+            assert torch.equal(z, y)
+            enc.close()
+
+
 @pytest.mark.parametrize("fold", [False, True], ids=["layernorm passes", "layernorm folded"])
 def test_config5_first_six_blocks_full_size(fold):
     """The encoder workload at its real shape (64 x 64 grid, width 1024, 16 heads, MLP 4096),
