@@ -194,7 +194,7 @@ __device__ inline void wait_loads_and_barrier(int pending) {
 // that bf16 stream, w is (w gamma) rounded to bf16, `bias` is c2; every workgroup first merges
 // the group statistics of its 256 rows into mean and 1/sigma (pairwise update of mean and
 // squared deviations), and the epilogue applies the formula above.
-enum { kLnNone = 0, kLnConsume = 1, kLnProduce = 2 };
+enum { kLnNone = 0, kLnConsume = 1, kLnProduce = 2, kGemmExtras = 3 };  // kGemmExtras: w_rows / k_split below are read
 struct GemmLn {
     const float *c1;        // consume: [N]
     const float *stats_in;  // consume: [groups][M][2] (mean, sum of squared deviations) of 64 features each
@@ -234,14 +234,19 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
                  int K, int lda, int tiles_n, int n_tiles, GemmLn ln) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
-    const int k_split = ln.k_split > 1 ? ln.k_split : 1;
+    // (the per-image weights and the K split exist only in the kGemmExtras instances: the
+    // other instances pay nothing for them)
+    const int k_split = (LN == kGemmExtras && ln.k_split > 1) ? ln.k_split : 1;
     const int per_xcd = (n_tiles * k_split + 7) / 8;
     int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile >= n_tiles * k_split) return;  // whole workgroup
-    const int k_part = tile / n_tiles;  // which part of K (0 without a split)
-    tile -= k_part * n_tiles;
-    const int k_len = K / k_split;      // columns this workgroup multiplies
-    Y = (void *)((char *)Y + (size_t)k_part * (size_t)ln.y_split * (OUT_BF16 ? 2 : 4));
+    int k_part = 0, k_len = K;          // which part of K, and the columns this workgroup multiplies
+    if (LN == kGemmExtras) {
+        k_part = tile / n_tiles;
+        tile -= k_part * n_tiles;
+        k_len = K / k_split;
+        Y = (void *)((char *)Y + (size_t)k_part * (size_t)ln.y_split * (OUT_BF16 ? 2 : 4));
+    }
     const int m0 = (tile / tiles_n) * kBM, n0 = (tile % tiles_n) * kBN;
     const int wm = wave >> 2, wn = wave & 3;  // 128-token half, 64-feature quarter
     constexpr int kPartLoads = 4;             // load instructions per part and wavefront
@@ -254,7 +259,7 @@ gemm_bf16_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ W,
     // tile, 255 rows at most, fit 32 bits (the launcher bounds lda and K).
     const char *a_tile = (const char *)(A + (size_t)m0 * lda + (size_t)k_part * k_len);
     const char *w_tile = (const char *)(W + (size_t)n0 * K + (size_t)k_part * k_len +
-                                        (ln.w_rows ? (size_t)(m0 / ln.w_rows) * (size_t)ln.w_stride : (size_t)0));
+                                        ((LN == kGemmExtras && ln.w_rows) ? (size_t)(m0 / ln.w_rows) * (size_t)ln.w_stride : (size_t)0));
     unsigned a_off[kPartLoads], w_off[kPartLoads];  // byte offsets of this lane's 16 bytes, k = 0
 #pragma unroll
     for (int j = 0; j < kPartLoads; ++j) {
@@ -584,7 +589,7 @@ static jv_status launch_gemm(const void *a, const void *w, const float *bias, co
     if (st != JV_OK) return st;
     const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (N + kBN - 1) / kBN;
     const int n_tiles = tiles_m * tiles_n;
-    dim3 grid(8 * ((n_tiles * (ln.k_split > 1 ? ln.k_split : 1) + 7) / 8));
+    dim3 grid(8 * ((n_tiles * ((LN == kGemmExtras && ln.k_split > 1) ? ln.k_split : 1) + 7) / 8));
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, OUT_BF16, LN>), grid, dim3(512), kGemmLds, stream,
                        (const __bf16 *)a, (const __bf16 *)w, bias, residual, y, (int)M, N, K, lda,
                        tiles_n, n_tiles, ln);
@@ -635,7 +640,7 @@ static jv_status gemm_residual_split(const void *a, const void *w, const float *
     GemmLn ex{};
     ex.k_split = k_split;
     ex.y_split = M * N;
-    jv_status st = launch_gemm<JV_EPI_NONE, false>(a, w, nullptr, nullptr, parts, M, N, K, K, stream, ex);
+    jv_status st = launch_gemm<JV_EPI_NONE, false, kGemmExtras>(a, w, nullptr, nullptr, parts, M, N, K, K, stream, ex);
     if (st != JV_OK) return st;
     const long long total4 = M * N / 4;
     const dim3 grid((unsigned)((total4 + 255) / 256));
@@ -1139,8 +1144,8 @@ jv_status jv_encoder_forward_taps(const jv_encoder *enc, const void *x, void *y,
                 jv::GemmLn per_image{};
                 per_image.w_rows = N;
                 per_image.w_stride = (long long)C * C;
-                st = s16 ? jv::launch_gemm<JV_EPI_RESIDUAL, true>(narrow, w_fold, b.b_o, resid, y, T, C, C, C, stream, per_image)
-                         : jv::launch_gemm<JV_EPI_RESIDUAL, false>(narrow, w_fold, b.b_o, resid, y, T, C, C, C, stream, per_image);
+                st = s16 ? jv::launch_gemm<JV_EPI_RESIDUAL, true, jv::kGemmExtras>(narrow, w_fold, b.b_o, resid, y, T, C, C, C, stream, per_image)
+                         : jv::launch_gemm<JV_EPI_RESIDUAL, false, jv::kGemmExtras>(narrow, w_fold, b.b_o, resid, y, T, C, C, C, stream, per_image);
             } else {
                 st = jv::gemm_forward(narrow, b.w_o, b.b_o, resid, y, T, C, C, JV_EPI_RESIDUAL, s16, stream);
             }
