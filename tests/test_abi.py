@@ -175,3 +175,35 @@ def test_encoder_options_refuse_a_null_encoder():
     assert L.jv_encoder_fuse_linear_projection(None, 1) == binding.JV_ERR_INVALID_ARG
     assert L.jv_encoder_fold_layernorm(None, None, 0, None) == binding.JV_ERR_INVALID_ARG
     assert L.jv_encoder_fold_bytes(None) == 0
+
+
+def test_encoder_workspace_query_follows_the_options():
+    """jv_encoder_workspace_bytes is host arithmetic: the base buffers, plus the partial results
+    of fc2's K split when its output has fewer than 128 tiles (few tokens), plus the states and
+    per-image weights of the fused linear-attention projection when that option is on."""
+    import torch
+    heads, hidden, C = 16, 4096, 1024
+
+    def weights():   # host tensors: creating an encoder only records the pointers
+        z = lambda *s: torch.zeros(*s, dtype=torch.float32)
+        w = lambda *s: torch.zeros(*s, dtype=torch.bfloat16)
+        return {"ln1_g": z(C), "ln1_b": z(C), "w_qkv": w(3 * C, C), "b_qkv": z(3 * C), "w_o": w(C, C), "b_o": z(C),
+                "ln2_g": z(C), "ln2_b": z(C), "w_fc1": w(hidden, C), "b_fc1": z(hidden), "w_fc2": w(C, hidden), "b_fc2": z(C)}
+
+    a256 = lambda n: (n + 255) // 256 * 256
+    enc = binding.Encoder([weights(), weights()], [0, 2], heads, hidden)
+    base = lambda B, N: a256(B * N * C * 2) + a256(B * N * 3 * C * 2 if 3 * C > hidden else B * N * hidden * 2)
+    # 4 x 4096 tokens: 256 output tiles, no split; 1 x 8192: 128 tiles, two parts; 1 x 4096: 64 tiles, four parts
+    w_big, w_two, w_four = enc.workspace_bytes(4, (64, 64)), enc.workspace_bytes(1, (64, 128)), enc.workspace_bytes(1, (64, 64))
+    la = lambda B, N, total: total - base(B, N)     # what is left: linear-attention states (+ options)
+    la_big = la(4, 4096, w_big)
+    assert 0 < la_big < 64 << 20
+    assert la(1, 8192, w_two) - 2 * 8192 * C * 4 < 64 << 20 and la(1, 8192, w_two) > 2 * 8192 * C * 4
+    assert la(1, 4096, w_four) - 4 * 4096 * C * 4 < 64 << 20 and la(1, 4096, w_four) > 4 * 4096 * C * 4
+    enc.fuse_linear_projection(True)
+    extra = enc.workspace_bytes(4, (64, 64)) - w_big
+    assert extra == a256(4 * heads * (64 * 64 + 64) * 4) + a256(4 * C * C * 2)
+    with_option = enc.workspace_bytes(4, (18, 18))       # 324 tokens per image: no block fuses
+    enc.fuse_linear_projection(False)
+    assert enc.workspace_bytes(4, (18, 18)) == with_option
+    enc.close()
