@@ -308,7 +308,10 @@ jv_status jv_gemm_bias_act(const void *a, const void *w, const float *bias, cons
  * aligned.  About 8 launches per block, all on hip_stream, no synchronisation.  Every shape the
  * pass would launch (its four matrix products, the window partition, the token counts) is
  * checked before the first launch; jv_encoder_workspace_bytes returns 0 for a (batch, grid) that
- * jv_encoder_forward would refuse.
+ * jv_encoder_forward would refuse.  With few tokens (the output of the second MLP product has
+ * fewer than 128 tiles of 256 x 256) that product's K loop is split over two or four workgroups
+ * per tile, whose fp32 partial results are added, with bias and residual, in a pass of their
+ * own and in a fixed order; the workspace query accounts for the partial results.
  *
  * jv_encoder_forward_taps: the same forward pass that also hands out the residual stream after
  * chosen blocks, which is what a dense-prediction head attached to the encoder reads (the
